@@ -1,0 +1,172 @@
+/*
+ * s3kv - prediction-sized ragged KV cache and decode-step attention for AMD MI355X (gfx950).
+ *
+ * C ABI of libs3kv.so.  Plain pointers and sizes only.  Every pointer is marked
+ * HOST or DEVICE; DEVICE pointers are HIP device memory owned by the caller.
+ *
+ * The library implements the memory-management idea of the S3 paper (arXiv 2306.06000):
+ * every sequence reserves KV-cache room for its PREDICTED length instead of the
+ * maximum sequence length (sections 1, 2.2, 2.3), rows are filled append-only
+ * (section 2.2), each sequence attends to its own rows without padding
+ * (section 2.1 equation; section 3, scheduler paragraph on irregular batches), and
+ * a sequence that outgrows its reservation gets twice the room (section 3,
+ * supervisor paragraph).
+ *
+ * Units.  Slot offsets, capacities, lengths and positions are in TOKEN ROWS.  One
+ * token row holds, for every layer, one key and one value vector of
+ * n_heads*head_dim elements: bytes_per_token = 2*n_layers*n_heads*head_dim*elem
+ * (= the paper's 4*l*d_h bytes for two-byte elements, section 2.1).  How rows are
+ * placed inside the arena is private to the library.
+ *
+ * Conventions.  Every call returns an s3_status (or a non-negative count where
+ * stated).  Nothing aborts or throws.  No call synchronises the device unless
+ * stated.  Kernels are enqueued on the `stream` argument (a hipStream_t passed as
+ * void*; NULL is the default stream).  Host-side bookkeeping (slot table, free
+ * list) changes immediately; device work is ordered by the stream.  An arena is
+ * not thread-safe: serialise calls on one arena.
+ *
+ * Error behaviour of device arrays.  slot_off/pos/cur_len live in device memory
+ * and cannot be checked by the host without a sync, so the kernels themselves
+ * skip any entry that would address rows outside the arena (off < 0, len < 0,
+ * len > max_len or off+len > arena capacity): append writes nothing for such an
+ * entry, attention returns an all-zero row.  No access ever leaves the arena.
+ */
+#ifndef S3KV_H
+#define S3KV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct s3_arena s3_arena; /* opaque; host-side metadata owned by the library */
+
+typedef enum { S3_F16 = 0, S3_BF16 = 1, S3_F32 = 2 } s3_dtype;
+
+typedef enum {
+    S3_OK = 0,
+    S3_ERR_INVALID = -1,   /* null pointer, bad shape, unknown id, misaligned base, unsupported type */
+    S3_ERR_NOMEM = -2,     /* the arena cannot fit the request; state unchanged */
+    S3_ERR_SLOT_FULL = -3, /* append at pos == capacity; nothing written, nothing launched */
+    S3_ERR_MAXLEN = -4,    /* grow of a slot whose capacity already is max_len */
+    S3_ERR_HIP = -5        /* a HIP call failed; see s3_last_hip_error() */
+} s3_status;
+
+typedef struct {
+    int32_t n_layers;  /* l: transformer layers whose K and V the arena holds            */
+    int32_t n_heads;   /* H                                                              */
+    int32_t head_dim;  /* D: 64, 128 or 256                                              */
+    int32_t kv_dtype;  /* s3_dtype of q, K, V: S3_F16 or S3_BF16                         */
+    int32_t granule;   /* G: capacities are multiples of G tokens (> 0)                  */
+    int32_t max_len;   /* M: largest capacity, tokens; a multiple of G                   */
+} s3_kv_config;
+
+/* KV-cache bytes one token occupies: 2 * n_layers * n_heads * head_dim * sizeof(element)
+ * (section 2.1: 4*l*d_h bytes in half precision).  Returns the byte count, or
+ * S3_ERR_INVALID (< 0) for a bad config. */
+int64_t s3_kv_bytes_per_token(const s3_kv_config *cfg /*HOST*/);
+
+/* Create the bookkeeping for one arena over caller-owned device memory.
+ *   dev_base  DEVICE, 256-byte aligned, dev_bytes long; stays owned by the caller and must
+ *             outlive the arena.  NULL = metadata-only arena: alloc/free/grow/stats work
+ *             as integers (grow copies nothing), every call that touches rows returns
+ *             S3_ERR_INVALID.  No HIP call is made for a metadata-only arena.
+ *   capacity  = floor(dev_bytes / bytes_per_token) token rows.
+ * The arena contents are not cleared.  *out receives the handle. */
+int s3_kv_arena_init(s3_arena **out /*HOST*/, const s3_kv_config *cfg /*HOST*/, void *dev_base /*DEVICE*/,
+                     size_t dev_bytes);
+
+/* Frees host metadata and the library's own split-K scratch (synchronises the device
+ * if such scratch exists).  Never touches dev_base.  NULL is allowed. */
+void s3_kv_arena_destroy(s3_arena *a);
+
+/* Reserve a slot per sequence by predicted length (sections 1 and 2.3; admission loop of
+ * section 3, scheduler paragraph): in caller order, sequence i gets capacity
+ *   cap = min(M, max(G, round_up(predicted_len[i], G)))
+ * at the lowest-offset free extent that holds it (first fit), iff one exists; otherwise
+ * slot_id[i] = -1, slot_off[i] = -1, slot_cap[i] = 0 and the loop goes on to i+1.
+ *   predicted_len  HOST [n]  predicted TOTAL tokens (prompt + predicted output), >= 0
+ *   slot_id        HOST [n]  out: id (smallest unused non-negative integer) or -1
+ *   slot_off       HOST [n]  out: first token row of the slot
+ *   slot_cap       HOST [n]  out: capacity in tokens
+ * Returns the number admitted (>= 0), or S3_ERR_INVALID with state unchanged (n < 0, null
+ * pointer, a negative prediction). */
+int s3_kv_alloc(s3_arena *a, int32_t n, const int32_t *predicted_len, int32_t *slot_id, int64_t *slot_off,
+                int32_t *slot_cap);
+
+/* The sequence finished (iteration-level check of section 3): return its extent to the
+ * free list, merging with free neighbours.  S3_ERR_INVALID for an id that is not live. */
+int s3_kv_free(s3_arena *a, int32_t slot_id);
+
+/* Offset and capacity of a live slot.  S3_ERR_INVALID if not live. */
+int s3_kv_slot_info(const s3_arena *a, int32_t slot_id, int64_t *off /*HOST*/, int32_t *cap /*HOST*/);
+
+/* Append-only fill of the reserved rows (section 2.2): for b in [0, n), write the new token's key
+ * and value for `layer` into row pos[b] of the slot starting at slot_off[b].
+ *   slot_id   HOST [n] or NULL, pos_host HOST [n] or NULL: when both are given the host checks
+ *             BEFORE launching that every id is live, 0 <= pos_host[b], and pos_host[b] <
+ *             capacity; pos_host[b] == capacity gives S3_ERR_SLOT_FULL (the sequence used up
+ *             its reservation: call s3_kv_grow), anything else bad gives S3_ERR_INVALID; in
+ *             both cases nothing is written.  When NULL the caller vouches for the positions.
+ *   slot_off  DEVICE [n] int64, pos DEVICE [n] int32
+ *   k_new, v_new  DEVICE [n][H][D] elements of kv_dtype, 16-byte aligned */
+int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
+                 const int64_t *slot_off, const int32_t *pos, const void *k_new, const void *v_new,
+                 void *stream);
+
+/* Decode-step attention (section 2.1 equation, per head): for b in [0, n), h in [0, H)
+ *   out[b][h][:] = softmax_j( scale * q[b][h][:] . K_b[j][h][:] ) . V_b[:][h][:],  j in [0, cur_len[b])
+ * over the sequence's own rows only (no padding).  cur_len[b] == 0 gives a zero row.
+ * Arithmetic is fp32 (dot products, max-subtracted softmax, weighted sum); contexts are
+ * cut into chunks whose partial (max, sum, weighted sum) are merged by a second kernel.
+ *   q         DEVICE [n][H][D] kv_dtype, 16-byte aligned
+ *   slot_off  DEVICE [n] int64, cur_len DEVICE [n] int32
+ *   out       DEVICE [n][H][D] of out_dtype (S3_F32, S3_F16 or S3_BF16), 16-byte aligned
+ *   scale     <= 0 means 1/sqrt(D)
+ * May grow the library's scratch buffer with hipMalloc (which synchronises) the first time a
+ * larger batch is seen; n <= 16383. */
+int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
+                        const int32_t *cur_len, void *out, int32_t out_dtype, float scale, void *stream);
+
+/* A sequence used up its reservation and is not finished: double it (section 3, supervisor
+ * paragraph).  new capacity = min(2*cap, M); the new slot is placed first-fit while the old one is
+ * still reserved (they never overlap); rows [0, len) of K and V of every layer are copied on
+ * `stream`; the old extent is then released and the id keeps naming the sequence.
+ *   S3_ERR_MAXLEN if cap == M, S3_ERR_NOMEM if no extent fits (state unchanged in both),
+ *   S3_ERR_INVALID for a dead id or len outside [0, cap]. */
+int s3_kv_grow(s3_arena *a, int32_t slot_id, int32_t len, int64_t *new_off /*HOST*/,
+               int32_t *new_cap /*HOST*/, void *stream);
+
+/* The supervisor's report of available memory (section 3), in tokens.  Any out pointer may be NULL. */
+int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t *largest_free_tok,
+                int64_t *capacity_tok);
+
+/* Bulk write of rows [first_row, first_row+n_rows) of a live slot for one layer: the stand-in for
+ * the prompt phase.  k_rows, v_rows: DEVICE [n_rows][H][D] kv_dtype, 16-byte aligned.
+ * S3_ERR_SLOT_FULL if first_row + n_rows > capacity. */
+int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t first_row, int32_t n_rows,
+               const void *k_rows, const void *v_rows, void *stream);
+
+/* Copy rows [first_row, first_row+n_rows) of K (which = 0) or V (which = 1) of a live slot into
+ * dst, DEVICE [n_rows][H][D] kv_dtype, 16-byte aligned.  For bit-exact checks of append / grow. */
+int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,
+                    int32_t n_rows, void *dst, void *stream);
+
+/* Launch-shape knobs of the attention kernels, for measurement sweeps.  name is one of
+ *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default)
+ *   "grid_blocks"  workgroups launched (0 = library default)
+ *   "variant"      kernel variant index (see s3_kv_get_param "n_variants")
+ * Returns S3_ERR_INVALID for an unknown name or a value out of range. */
+int s3_kv_set_param(s3_arena *a, const char *name /*HOST*/, int64_t value);
+int s3_kv_get_param(const s3_arena *a, const char *name /*HOST*/, int64_t *value /*HOST*/);
+
+/* Text of the last HIP error seen by this thread's calls ("" if none), and of a status code. */
+const char *s3_last_hip_error(void);
+const char *s3_status_str(int status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* S3KV_H */

@@ -1,0 +1,154 @@
+/*
+ * CPU oracle for single-query (decode-step) attention.  TEST INFRASTRUCTURE ONLY:
+ * nothing in the product path may call, link or import this file.
+ *
+ * What it computes (paper section 2.1, the self-attention equation):
+ *     h_out = softmax(q . K^T / sqrt(d)) . V
+ * for one query row q against the L cached key/value rows of its own sequence,
+ * once per attention head (d = head dimension; with one head and d = model
+ * dimension this is the paper's formula verbatim).
+ *
+ * It is the definition written out: a dot product per cached row, the maximum,
+ * exponentials, their sum, the normalised weights, and a weighted sum of value
+ * rows.  No tiling, no running ("online") softmax, no reordering.
+ *
+ * Inputs are the values as stored in the KV cache: 16-bit patterns of IEEE
+ * binary16 (dtype 0) or bfloat16 (dtype 1).  They are widened to REAL before
+ * any arithmetic.  The file is compiled twice: REAL = float (the fp32 oracle)
+ * and REAL = double (its twin, used to bound the fp32 oracle's own error).
+ *
+ * Row addressing: element d of row j of a matrix is base[j * row_stride + d];
+ * the caller chooses row_stride so that per-head slices of [rows][H][D] storage
+ * can be addressed without copying.
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+#ifndef REAL
+#error "compile with -DREAL=float -DSUF=f32 or -DREAL=double -DSUF=f64"
+#endif
+#define CAT_(a, b) a##_##b
+#define CAT(a, b) CAT_(a, b)
+#define FN(name) CAT(name, SUF)
+
+/* IEEE binary16 -> REAL, exact (every binary16 value is a binary32 value).
+ * binary16 = 1 sign, 5 exponent (bias 15), 10 fraction bits;
+ * binary32 = 1 sign, 8 exponent (bias 127), 23 fraction bits. */
+static REAL widen_f16(uint16_t h)
+{
+    uint32_t sign = (uint32_t)(h >> 15) & 1u;
+    uint32_t e = (uint32_t)(h >> 10) & 0x1fu;
+    uint32_t f = (uint32_t)h & 0x3ffu;
+    float v;
+    if (e == 0) {
+        v = (float)f * 5.9604644775390625e-8f; /* zero or subnormal: f * 2^-24, exact */
+    } else {
+        /* normal: same fraction, exponent re-biased by 127 - 15; e == 31 is inf / NaN */
+        uint32_t bits = ((e == 31 ? 255u : e + 112u) << 23) | (f << 13);
+        memcpy(&v, &bits, sizeof v);
+    }
+    return (REAL)(sign ? -v : v);
+}
+
+/* bfloat16 -> REAL, exact: a bfloat16 is the upper half of a binary32. */
+static REAL widen_bf16(uint16_t h)
+{
+    uint32_t bits = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &bits, sizeof f);
+    return (REAL)f;
+}
+
+static REAL widen(uint16_t h, int dtype) { return dtype == 0 ? widen_f16(h) : widen_bf16(h); }
+
+/* Exposed so that tests can pin the widening against an independent library. */
+void FN(s3o_widen)(const uint16_t *src, int64_t n, int dtype, REAL *dst)
+{
+    for (int64_t i = 0; i < n; i++) dst[i] = widen(src[i], dtype);
+}
+
+/* Step 1: s_j = scale * sum_d q[d] * K[j][d],  j = 0..L-1. */
+void FN(s3o_scores)(const uint16_t *q, const uint16_t *K, int64_t row_stride, int L, int D,
+                    int dtype, REAL scale, REAL *s)
+{
+    for (int j = 0; j < L; j++) {
+        REAL dot = 0;
+        for (int d = 0; d < D; d++) dot += widen(q[d], dtype) * widen(K[(int64_t)j * row_stride + d], dtype);
+        s[j] = dot * scale;
+    }
+}
+
+/* Step 2: p = softmax(s): subtract the maximum, exponentiate, divide by the sum. */
+void FN(s3o_softmax)(const REAL *s, int L, REAL *p)
+{
+    if (L <= 0) return;
+    REAL m = s[0];
+    for (int j = 1; j < L; j++)
+        if (s[j] > m) m = s[j];
+    REAL Z = 0;
+    for (int j = 0; j < L; j++) {
+        p[j] = (REAL)(sizeof(REAL) == 4 ? expf((float)(s[j] - m)) : exp((double)(s[j] - m)));
+        Z += p[j];
+    }
+    for (int j = 0; j < L; j++) p[j] /= Z;
+}
+
+/* Step 3: o[d] = sum_j p_j * V[j][d]. */
+void FN(s3o_weighted_sum)(const REAL *p, const uint16_t *V, int64_t row_stride, int L, int D, int dtype,
+                          REAL *o)
+{
+    for (int d = 0; d < D; d++) o[d] = 0;
+    for (int j = 0; j < L; j++)
+        for (int d = 0; d < D; d++) o[d] += p[j] * widen(V[(int64_t)j * row_stride + d], dtype);
+}
+
+/* One (sequence, head): the three steps in order.  L == 0 (nothing cached) is
+ * defined as an all-zero output row.  Returns 0, or -1 if scratch allocation fails. */
+int FN(s3o_attend_one)(const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t row_stride, int L,
+                       int D, int dtype, REAL scale, REAL *o)
+{
+    if (L <= 0) {
+        for (int d = 0; d < D; d++) o[d] = 0;
+        return 0;
+    }
+    REAL *s = (REAL *)malloc(sizeof(REAL) * (size_t)L * 2);
+    if (!s) return -1;
+    REAL *p = s + L;
+    FN(s3o_scores)(q, K, row_stride, L, D, dtype, scale, s);
+    FN(s3o_softmax)(s, L, p);
+    FN(s3o_weighted_sum)(p, V, row_stride, L, D, dtype, o);
+    free(s);
+    return 0;
+}
+
+/* A ragged batch.  Sequence b has its own K and V storage, K_ptr[b] / V_ptr[b],
+ * laid out [rows][H][D]; it attends over its first len[b] rows only (no padding).
+ * q and out are [n][H][D].  The (sequence, head) pairs are independent, so they
+ * may be spread over `threads` OpenMP threads (1 = plain serial loops); the
+ * arithmetic of each pair is the same either way.  Returns the number of
+ * threads used, or -1 on allocation failure. */
+int FN(s3o_attention_batch)(int n, int H, int D, int dtype, const uint16_t *const *K_ptr,
+                            const uint16_t *const *V_ptr, const int32_t *len, const uint16_t *q,
+                            REAL scale, REAL *out, int threads)
+{
+    int used = 1, fail = 0;
+    int64_t pairs = (int64_t)n * H;
+#ifdef _OPENMP
+    if (threads < 1) threads = 1;
+    used = threads;
+#pragma omp parallel for schedule(dynamic, 1) num_threads(threads) reduction(| : fail)
+#endif
+    for (int64_t i = 0; i < pairs; i++) {
+        int b = (int)(i / H), h = (int)(i % H);
+        int rc = FN(s3o_attend_one)(q + ((int64_t)b * H + h) * D, K_ptr[b] + (int64_t)h * D,
+                                    V_ptr[b] + (int64_t)h * D, (int64_t)H * D, len[b], D, dtype, scale,
+                                    out + ((int64_t)b * H + h) * D);
+        if (rc) fail |= 1;
+    }
+    return fail ? -1 : used;
+}

@@ -1,0 +1,260 @@
+"""Pins of the CPU slot-allocator / KV-storage oracle.
+
+Pinned to: the paper's worked example of cache sizes (sections 2.1, 2.2; golden file),
+the doubling rule (section 3, supervisor paragraph), the admission loop (section 3,
+scheduler paragraph), structural invariants after every operation of random traces, and a
+second, bitmap-based first-fit allocator written here that must agree on every offset.
+"""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import kv_oracle as orc
+from paper_2306_06000_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def golden_bytes():
+    d = {}
+    for line in open(os.path.join(GOLDEN, "kv_bytes_worked_example.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        k, v = line.split()
+        d[k] = int(v)
+    return d
+
+
+def neox(arena_bytes, granule=64):
+    # 44 layers, hidden 6144 = 64 heads x 96 (table 1)
+    return orc.KVOracle(44, 64, 96, orc.F16, granule, 2048, arena_bytes, store=False)
+
+
+def test_bytes_per_token_and_max_length_reservation_match_the_paper():
+    g = golden_bytes()
+    o = neox(0)
+    assert o.bytes_per_token == g["bytes_per_token"] == 4 * g["n_layers"] * g["hidden"]
+    assert abs(o.bytes_per_token / 2**20 - 1.0) < 0.05  # "1MB per token"
+    assert o.bytes_per_token * g["max_len"] == g["bytes_per_max_reservation"]
+    assert round(g["bytes_per_max_reservation"] / 1e9, 1) == 2.2  # "2.2GB per sequence"
+
+
+@pytest.mark.parametrize("key_bytes,key_batch", [("free_bytes_decimal", "max_batch_decimal"),
+                                                 ("free_bytes_binary", "max_batch_binary")])
+def test_worst_case_reservation_admits_fewer_than_twenty(key_bytes, key_batch):
+    g = golden_bytes()
+    o = neox(g[key_bytes])
+    admitted, ids, offs, caps = o.alloc([2048] * 25)
+    assert admitted == g[key_batch] < 20
+    assert ids[:admitted] == list(range(admitted)) and all(i == -1 for i in ids[admitted:])
+    assert offs[:admitted] == [2048 * i for i in range(admitted)]
+    # the same memory holds many more 50-token sequences when each reserves what it needs
+    o2 = neox(g[key_bytes])
+    many, *_ = o2.alloc([50] * 1000)
+    assert many == min(1000, o2.N // 64) and many > 10 * admitted
+
+
+def test_capacity_rule():
+    o = orc.KVOracle(1, 2, 64, orc.F16, 64, 2048, 10**9, store=False)
+    assert [o.capacity_for(p) for p in (0, 1, 63, 64, 65, 128, 129, 2047, 2048, 2049, 10**6)] == \
+        [64, 64, 64, 64, 128, 128, 192, 2048, 2048, 2048, 2048]
+    o4 = orc.KVOracle(1, 2, 64, orc.F16, 128, 2048, 10**9, store=False)
+    assert [o4.capacity_for(p) for p in (1, 128, 129, 576 + 64)] == [128, 128, 256, 640]
+
+
+def test_c0_slots():
+    w = wl.c0()
+    o = orc.KVOracle(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len,
+                     512 * w.bytes_per_token, store=False)
+    n, ids, offs, caps = o.alloc([s.predicted for s in w.seqs])
+    assert n == 4 and ids == [0, 1, 2, 3]
+    assert caps == [64, 64, 128, 128] and offs == [0, 64, 128, 256]
+    assert o.stats() == (384, 128, 128, 512)
+
+
+def test_first_fit_lowest_offset_coalescing_and_id_reuse():
+    o = orc.KVOracle(1, 1, 64, orc.F16, 64, 2048, 1024 * 256, store=False)
+    assert o.N == 1024
+    n, ids, offs, caps = o.alloc([64, 128, 64, 256, 64])
+    assert offs == [0, 64, 192, 256, 512] and ids == [0, 1, 2, 3, 4]
+    assert o.free(1) == orc.OK and o.free(3) == orc.OK
+    assert o.free_list == [[64, 128], [256, 256], [576, 448]]
+    assert o.free(2) == orc.OK  # merges with both neighbours
+    assert o.free_list == [[64, 448], [576, 448]]
+    assert o.free(2) == orc.ERR_INVALID
+    sid, off, cap = o.alloc_one(200)  # 256 tokens, lowest extent that fits, smallest unused id
+    assert (sid, off, cap) == (1, 64, 256)
+    sid, off, cap = o.alloc_one(250)  # 256: the hole has 192 left, so the tail extent is used
+    assert (sid, off, cap) == (2, 576, 256)
+    sid, off, cap = o.alloc_one(192)
+    assert (sid, off, cap) == (3, 320, 192)
+    assert o.alloc_one(256) == (-1, -1, 0)  # 192 left at the tail: does not fit, state unchanged
+    assert o.free_list == [[832, 192]]
+    assert o.alloc([-1])[0] == orc.ERR_INVALID
+
+
+def test_grow_doubles_until_max_len_and_never_overlaps():
+    o = orc.KVOracle(2, 2, 8, orc.F16, 64, 256, 4096 * 2 * 2 * 2 * 8 * 2)
+    assert o.N == 4096
+    rng = np.random.default_rng(0)
+    sid, off, cap = o.alloc_one(10)
+    other, ooff, ocap = o.alloc_one(100)
+    k = wl.normal_bits(rng, (cap, 2, 8), orc.F16)
+    v = wl.normal_bits(rng, (cap, 2, 8), orc.F16)
+    for layer in range(2):
+        assert o.fill(sid, layer, k, v) == orc.OK
+        assert o.fill(other, layer, k[:50], v[:50]) == orc.OK
+    before_other = o.data[other].copy()
+    assert o.append(sid, 0, cap, k[0], v[0]) == orc.ERR_SLOT_FULL
+    st, noff, ncap = o.grow(sid, cap)
+    assert st == orc.OK and ncap == 2 * cap == 128
+    assert noff >= ooff + ocap  # placed while the old extent was still reserved
+    assert o.free_list[0] == [0, 64]  # old extent released afterwards
+    for layer in range(2):
+        assert np.array_equal(o.rows(sid, layer, 0, cap), k)
+        assert np.array_equal(o.rows(sid, layer, 1, cap), v)
+    assert np.array_equal(o.data[other], before_other)
+    st, _, ncap = o.grow(sid, 64)
+    assert st == orc.OK and ncap == 256
+    assert o.grow(sid, 64)[0] == orc.ERR_MAXLEN
+    assert o.grow(99, 1)[0] == orc.ERR_INVALID
+    assert o.grow(sid, 257)[0] == orc.ERR_INVALID
+    assert o.n_grows == 2
+
+
+def test_grow_cap_not_power_of_two_is_clipped_to_max_len():
+    o = orc.KVOracle(1, 1, 8, orc.F16, 64, 320, 10**6, store=False)
+    sid, off, cap = o.alloc_one(192)
+    st, noff, ncap = o.grow(sid, 192)
+    assert st == orc.OK and ncap == 320  # min(2 * 192, M)
+    assert o.grow(sid, 0)[0] == orc.ERR_MAXLEN
+
+
+def test_grow_nomem_leaves_state_unchanged():
+    o = orc.KVOracle(1, 1, 8, orc.F16, 64, 2048, 256 * 32, store=False)
+    assert o.N == 256
+    a = o.alloc_one(128)
+    b = o.alloc_one(64)
+    snap = ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()})
+    assert o.grow(a[0], 128)[0] == orc.ERR_NOMEM
+    assert ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()}) == snap
+    assert o.grow(b[0], 64)[0] == orc.ERR_NOMEM  # needs 128, only 64 free
+    assert o.free(a[0]) == orc.OK
+    assert o.grow(b[0], 64) == (orc.OK, 0, 128)
+
+
+def test_append_writes_exactly_one_row():
+    o = orc.KVOracle(2, 2, 8, orc.F16, 64, 128, 10**6)
+    rng = np.random.default_rng(1)
+    a, _, _ = o.alloc_one(64)
+    b, _, _ = o.alloc_one(64)
+    k = wl.normal_bits(rng, (2, 8), orc.F16)
+    v = wl.normal_bits(rng, (2, 8), orc.F16)
+    assert o.append(a, 1, 5, k, v) == orc.OK
+    assert np.array_equal(o.data[a][1, 0, 5], k) and np.array_equal(o.data[a][1, 1, 5], v)
+    mask = np.ones_like(o.data[a], bool)
+    mask[1, :, 5] = False
+    assert not o.data[a][mask].any() and not o.data[b].any()
+    snap = o.data[a].copy()
+    assert o.append(a, 0, 64, k, v) == orc.ERR_SLOT_FULL
+    assert o.append(a, 2, 0, k, v) == orc.ERR_INVALID
+    assert o.append(7, 0, 0, k, v) == orc.ERR_INVALID
+    assert np.array_equal(o.data[a], snap)
+
+
+# ---------------------------------------------------------------- random traces
+class BitmapAllocator:
+    """Brute force: one flag per granule, linear scan for the first run that fits."""
+
+    def __init__(self, n_tokens, granule, max_len):
+        self.G, self.M = granule, max_len
+        self.used = [False] * (n_tokens // granule)
+        self.slots = {}
+
+    def _find(self, cap):
+        need = cap // self.G
+        run = 0
+        for i, u in enumerate(self.used):
+            run = 0 if u else run + 1
+            if run == need:
+                return (i - need + 1) * self.G
+        return -1
+
+    def _mark(self, off, cap, val):
+        for i in range(off // self.G, (off + cap) // self.G):
+            assert self.used[i] != val
+            self.used[i] = val
+
+    def alloc(self, pred):
+        cap = min(self.M, max(self.G, (pred + self.G - 1) // self.G * self.G))
+        off = self._find(cap)
+        if off < 0:
+            return -1, -1, 0
+        sid = min(set(range(len(self.slots) + 1)) - set(self.slots))
+        self._mark(off, cap, True)
+        self.slots[sid] = (off, cap)
+        return sid, off, cap
+
+    def free(self, sid):
+        off, cap = self.slots.pop(sid)
+        self._mark(off, cap, False)
+
+    def grow(self, sid):
+        off, cap = self.slots[sid]
+        if cap >= self.M:
+            return orc.ERR_MAXLEN, -1, 0
+        ncap = min(2 * cap, self.M)
+        noff = self._find(ncap)
+        if noff < 0:
+            return orc.ERR_NOMEM, -1, 0
+        self._mark(noff, ncap, True)
+        self._mark(off, cap, False)
+        self.slots[sid] = (noff, ncap)
+        return orc.OK, noff, ncap
+
+
+def check_invariants(o):
+    fl = o.free_list
+    for i, (off, size) in enumerate(fl):
+        assert size > 0 and off >= 0 and off + size <= o.N
+        if i:
+            assert fl[i - 1][0] + fl[i - 1][1] < off  # sorted, disjoint and coalesced
+    ext = sorted((off, cap) for off, cap in o.slots.values())
+    for off, cap in ext:
+        assert cap % o.G == 0 and o.G <= cap <= o.M and off % o.G == 0 and off + cap <= o.N
+    allx = sorted(ext + [tuple(x) for x in fl])
+    for (o1, s1), (o2, _) in zip(allx, allx[1:]):
+        assert o1 + s1 <= o2
+    used, free, largest, N = o.stats()
+    assert used + free == N - N % o.G or used + free == N
+    assert largest == max([s for _, s in fl], default=0)
+
+
+@pytest.mark.parametrize("seed,granule,tokens", [(0, 64, 64 * 300), (1, 128, 128 * 97), (2, 64, 64 * 41)])
+def test_random_trace_agrees_with_bitmap_allocator(seed, granule, tokens):
+    rng = np.random.default_rng(seed)
+    M = 2048
+    o = orc.KVOracle(1, 1, 8, orc.F16, granule, M, tokens * 32, store=False)
+    assert o.N == tokens
+    bm = BitmapAllocator(tokens, granule, M)
+    live = []
+    n_ops = 10000 if seed == 0 else 3000
+    for _ in range(n_ops):
+        r = rng.random()
+        if r < 0.45 or not live:
+            pred = int(rng.integers(0, 2400)) if rng.random() < 0.5 else int(rng.integers(1, 300))
+            got = o.alloc_one(pred)
+            assert got == bm.alloc(pred)
+            if got[0] >= 0:
+                live.append(got[0])
+        elif r < 0.75:
+            sid = live.pop(int(rng.integers(len(live))))
+            assert o.free(sid) == orc.OK
+            bm.free(sid)
+        else:
+            sid = live[int(rng.integers(len(live)))]
+            length = int(rng.integers(0, o.slots[sid][1] + 1))
+            assert o.grow(sid, length) == bm.grow(sid)
+        check_invariants(o)
+        assert {k: tuple(v) for k, v in o.slots.items()} == bm.slots
