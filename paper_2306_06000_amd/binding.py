@@ -1,0 +1,182 @@
+"""Thin ctypes binding of libs3kv.so: same names as the C ABI, argument marshalling only.
+
+Device arrays are passed as torch tensors (their ``data_ptr()`` is used) or raw integer
+addresses; host arrays as numpy arrays / sequences.  Nothing here computes: every step of
+the hot path runs inside the library's kernels.  The library must have been built
+(``python -m paper_2306_06000_amd.build`` or ``__graft_entry__.build()``); loading fails
+loudly otherwise - there is no fallback.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+S3_F16, S3_BF16, S3_F32 = 0, 1, 2
+S3_OK, S3_ERR_INVALID, S3_ERR_NOMEM, S3_ERR_SLOT_FULL, S3_ERR_MAXLEN, S3_ERR_HIP = 0, -1, -2, -3, -4, -5
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libs3kv.so")
+_lib = None
+
+
+class s3_kv_config(ctypes.Structure):
+    _fields_ = [("n_layers", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+                ("kv_dtype", ctypes.c_int32), ("granule", ctypes.c_int32), ("max_len", ctypes.c_int32)]
+
+
+_vp, _i32, _i64, _f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
+_pi32, _pi64 = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+
+SIGNATURES = {
+    "s3_kv_bytes_per_token": (_i64, [ctypes.POINTER(s3_kv_config)]),
+    "s3_kv_arena_init": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(s3_kv_config), _vp, ctypes.c_size_t]),
+    "s3_kv_arena_destroy": (None, [_vp]),
+    "s3_kv_alloc": (ctypes.c_int, [_vp, _i32, _pi32, _pi32, _pi64, _pi32]),
+    "s3_kv_free": (ctypes.c_int, [_vp, _i32]),
+    "s3_kv_slot_info": (ctypes.c_int, [_vp, _i32, _pi64, _pi32]),
+    "s3_kv_append": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp]),
+    "s3_decode_attention": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _f32, _vp]),
+    "s3_kv_grow": (ctypes.c_int, [_vp, _i32, _i32, _pi64, _pi32, _vp]),
+    "s3_kv_stats": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64]),
+    "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "s3_kv_read_rows": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp]),
+    "s3_kv_set_param": (ctypes.c_int, [_vp, ctypes.c_char_p, _i64]),
+    "s3_kv_get_param": (ctypes.c_int, [_vp, ctypes.c_char_p, _pi64]),
+    "s3_last_hip_error": (ctypes.c_char_p, []),
+    "s3_status_str": (ctypes.c_char_p, [ctypes.c_int]),
+}
+
+
+def lib():
+    """Load libs3kv.so once.  Raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2306_06000_amd.build`; "
+                               "there is no CPU fallback")
+        handle = ctypes.CDLL(LIB_PATH)
+        for name, (res, args) in SIGNATURES.items():
+            fn = getattr(handle, name)
+            fn.restype, fn.argtypes = res, args
+        _lib = handle
+    return _lib
+
+
+def _ptr(x):
+    """Device/host address of a torch tensor, numpy array, int or None."""
+    if x is None:
+        return None
+    if isinstance(x, int):
+        return x
+    if hasattr(x, "data_ptr"):
+        return x.data_ptr()
+    if isinstance(x, np.ndarray):
+        return x.ctypes.data
+    raise TypeError(type(x))
+
+
+def _host_i32(x):
+    if x is None:
+        return None, None
+    arr = np.ascontiguousarray(x, np.int32)
+    return arr, arr.ctypes.data_as(_pi32)
+
+
+class S3Error(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        detail = lib().s3_last_hip_error().decode() if status == S3_ERR_HIP else ""
+        super().__init__(f"{where}: {lib().s3_status_str(status).decode()} {detail}".strip())
+
+
+def make_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len):
+    return s3_kv_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len)
+
+
+def s3_kv_bytes_per_token(cfg):
+    return int(lib().s3_kv_bytes_per_token(ctypes.byref(cfg)))
+
+
+def s3_kv_arena_init(cfg, dev_base, dev_bytes):
+    """-> (status, arena handle).  dev_base: torch uint8 tensor / address / None (metadata only)."""
+    h = _vp()
+    st = lib().s3_kv_arena_init(ctypes.byref(h), ctypes.byref(cfg), _ptr(dev_base), int(dev_bytes))
+    return st, (h if st == S3_OK else None)
+
+
+def s3_kv_arena_destroy(arena):
+    lib().s3_kv_arena_destroy(arena)
+
+
+def s3_kv_alloc(arena, predicted_len):
+    """-> (admitted or status, slot_id[n], slot_off[n], slot_cap[n]) as numpy arrays."""
+    pl, plp = _host_i32(predicted_len)
+    n = int(pl.size)
+    ids = np.full(n, -2, np.int32)
+    offs = np.full(n, -2, np.int64)
+    caps = np.full(n, -2, np.int32)
+    rc = lib().s3_kv_alloc(arena, n, plp, ids.ctypes.data_as(_pi32), offs.ctypes.data_as(_pi64),
+                           caps.ctypes.data_as(_pi32))
+    return rc, ids, offs, caps
+
+
+def s3_kv_free(arena, slot_id):
+    return lib().s3_kv_free(arena, int(slot_id))
+
+
+def s3_kv_slot_info(arena, slot_id):
+    off, cap = _i64(-1), _i32(0)
+    st = lib().s3_kv_slot_info(arena, int(slot_id), ctypes.byref(off), ctypes.byref(cap))
+    return st, off.value, cap.value
+
+
+def s3_kv_append(arena, layer, n, slot_off, pos, k_new, v_new, stream=0, slot_id=None, pos_host=None):
+    _a, idp = _host_i32(slot_id)
+    _b, php = _host_i32(pos_host)
+    return lib().s3_kv_append(arena, int(layer), int(n), idp, php, _ptr(slot_off), _ptr(pos), _ptr(k_new),
+                              _ptr(v_new), stream or None)
+
+
+def s3_decode_attention(arena, layer, n, q, slot_off, cur_len, out, out_dtype=S3_F32, scale=0.0, stream=0):
+    return lib().s3_decode_attention(arena, int(layer), int(n), _ptr(q), _ptr(slot_off), _ptr(cur_len), _ptr(out),
+                                     int(out_dtype), float(scale), stream or None)
+
+
+def s3_kv_grow(arena, slot_id, length, stream=0):
+    """-> (status, new_off, new_cap)."""
+    off, cap = _i64(-1), _i32(0)
+    st = lib().s3_kv_grow(arena, int(slot_id), int(length), ctypes.byref(off), ctypes.byref(cap), stream or None)
+    return st, off.value, cap.value
+
+
+def s3_kv_stats(arena):
+    """-> (status, used, free, largest_free, capacity) in tokens."""
+    v = [_i64(0) for _ in range(4)]
+    st = lib().s3_kv_stats(arena, *[ctypes.byref(x) for x in v])
+    return (st, *[x.value for x in v])
+
+
+def s3_kv_fill(arena, slot_id, layer, first_row, n_rows, k_rows, v_rows, stream=0):
+    return lib().s3_kv_fill(arena, int(slot_id), int(layer), int(first_row), int(n_rows), _ptr(k_rows), _ptr(v_rows),
+                            stream or None)
+
+
+def s3_kv_read_rows(arena, slot_id, layer, which, first_row, n_rows, dst, stream=0):
+    return lib().s3_kv_read_rows(arena, int(slot_id), int(layer), int(which), int(first_row), int(n_rows), _ptr(dst),
+                                 stream or None)
+
+
+def s3_kv_set_param(arena, name, value):
+    return lib().s3_kv_set_param(arena, name.encode(), int(value))
+
+
+def s3_kv_get_param(arena, name):
+    v = _i64(0)
+    st = lib().s3_kv_get_param(arena, name.encode(), ctypes.byref(v))
+    return st, v.value
+
+
+def check(status, where="s3kv"):
+    if status < 0:
+        raise S3Error(status, where)
+    return status

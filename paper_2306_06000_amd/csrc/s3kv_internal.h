@@ -1,0 +1,58 @@
+// Internal declarations shared by the host bookkeeping and the HIP launchers of libs3kv.
+#pragma once
+#include <stdint.h>
+
+#include <map>
+#include <set>
+#include <vector>
+
+#include "s3kv.h"
+
+struct s3_slot {
+    int64_t off = -1;
+    int32_t cap = 0;
+    bool live = false;
+};
+
+struct s3_arena {
+    s3_kv_config cfg{};
+    char *base = nullptr;      // device memory owned by the caller (nullptr: metadata only)
+    size_t dev_bytes = 0;
+    int64_t n_tokens = 0;      // N: token rows the arena holds
+    int64_t elem_bytes = 2;
+    int64_t row_bytes = 0;     // H * D * elem
+    int64_t plane_bytes = 0;   // N * row_bytes; plane p = 2*layer + (0: K, 1: V)
+
+    std::map<int64_t, int64_t> free_ext;  // offset -> size, disjoint, coalesced
+    std::vector<s3_slot> slots;           // indexed by id
+    std::set<int32_t> dead_ids;           // ids below slots.size() that are not live
+    int64_t used_tokens = 0;
+    int64_t n_grows = 0;
+
+    // split-K partials owned by the library
+    void *scratch = nullptr;
+    size_t scratch_bytes = 0;
+
+    // launch-shape knobs (0 = default)
+    int32_t chunk = 0;
+    int32_t grid_blocks = 0;
+    int32_t variant = -1;
+    int32_t num_cus = 0;
+
+    char *plane(int32_t layer, int32_t which) const {
+        return base + (int64_t)(2 * layer + which) * plane_bytes;
+    }
+};
+
+// host bookkeeping (s3kv_alloc.cpp)
+int32_t s3i_capacity_for(const s3_arena *a, int32_t predicted_len);
+int64_t s3i_carve(s3_arena *a, int64_t cap);          // first fit; -1 if nothing fits
+void s3i_release(s3_arena *a, int64_t off, int64_t cap);
+const s3_slot *s3i_live_slot(const s3_arena *a, int32_t id);
+void s3i_set_hip_error(const char *what, int code, const char *text);
+
+// device work (s3kv_kernels.hip); each returns an s3_status
+int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src_plane_stride,
+                           size_t dst_plane_stride, int planes, void *stream);
+int s3i_num_variants();
+int s3i_device_cus(int32_t *cus);

@@ -1,0 +1,108 @@
+"""Shared test plumbing: feed the same seeded inputs to the HIP engine and to the CPU oracle,
+replay the engine's event log on the oracle, and compare."""
+import numpy as np
+
+from oracle import kv_oracle as orc
+from paper_2306_06000_amd import workloads as wl
+
+MAX_ABS, REL_L2 = 2e-3, 1e-3  # attention tolerance against the fp32 oracle (fp16 / bf16 storage)
+
+
+def assert_close(got, want, what=""):
+    got = np.asarray(got, np.float64)
+    want = np.asarray(want, np.float64)
+    assert got.shape == want.shape, (got.shape, want.shape)
+    assert np.isfinite(got).all(), f"{what}: non-finite output"
+    max_abs = np.abs(got - want).max() if got.size else 0.0
+    denom = np.linalg.norm(want.ravel())
+    rel = np.linalg.norm((got - want).ravel()) / denom if denom > 0 else np.linalg.norm(got.ravel())
+    assert max_abs <= MAX_ABS and rel <= REL_L2, f"{what}: max-abs {max_abs:.3e} rel-L2 {rel:.3e}"
+    return max_abs, rel
+
+
+def device_bits(bits, torch_dtype, device):
+    """uint16 patterns (numpy) -> device tensor of the 16-bit float type, bit-preserving."""
+    import torch
+
+    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch_dtype)
+
+
+def make_sources(w, engine):
+    """prefill(serial, layer, rows) and tensors_for(step) closures that upload the seeded inputs."""
+    tdt = engine.kv_dtype_torch()
+
+    def prefill(serial, layer, rows):
+        k, v = wl.prefill_rows(w, serial, layer, rows)
+        return device_bits(k, tdt, engine.dev), device_bits(v, tdt, engine.dev)
+
+    def tensors_for(step):
+        def tensors(layer, n):
+            q, k, v = wl.step_tensors(w, step, layer, n)
+            return tuple(device_bits(x, tdt, engine.dev) for x in (q, k, v))
+
+        return tensors
+
+    return prefill, tensors_for
+
+
+class OracleReplay:
+    """Replays an engine event log on the CPU oracle; every integer the library returned must
+    equal the oracle's.  Keeps serial -> oracle id so that rows can be compared afterwards."""
+
+    def __init__(self, w, arena_tokens):
+        self.w = w
+        self.o = orc.KVOracle(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len,
+                              arena_tokens * w.bytes_per_token)
+        self.sid = {}   # serial -> slot id
+        self.len = {}   # serial -> rows cached
+        self.step_idx = 0
+
+    def replay(self, events, attend_steps=(), threads=8, precision="f32"):
+        """Returns {step index: (serials, lens, oracle attention output of the last layer)}."""
+        w, o = self.w, self.o
+        outs = {}
+        for ev in events:
+            kind = ev[0]
+            if kind == "alloc":
+                _, serial, pred, sid, off, cap = ev
+                got = o.alloc_one(pred)
+                assert got == (sid, off, cap), ("alloc", serial, got, (sid, off, cap))
+                if sid >= 0:
+                    self.sid[serial] = sid
+            elif kind == "fill":
+                _, serial, sid, rows = ev
+                for layer in range(w.n_layers):
+                    k, v = wl.prefill_rows(w, serial, layer, rows)
+                    assert o.fill(sid, layer, k, v) == orc.OK
+                self.len[serial] = rows
+            elif kind == "grow":
+                _, serial, sid, length, st, off, cap = ev
+                assert length == self.len[serial] == o.slots[sid][1]  # grown exactly when full
+                got = o.grow(sid, length)
+                assert got == (st, off, cap), ("grow", serial, got, (st, off, cap))
+            elif kind == "free":
+                _, serial, sid = ev
+                assert self.sid.pop(serial) == sid
+                assert o.free(sid) == orc.OK
+                self.len.pop(serial)
+            elif kind == "step":
+                _, serials, lens = ev
+                n = len(serials)
+                t = self.step_idx
+                last = None
+                for layer in range(w.n_layers):
+                    q, k, v = wl.step_tensors(w, t, layer, n)
+                    for b, serial in enumerate(serials):
+                        assert o.append(self.sid[serial], layer, self.len[serial], k[b], v[b]) == orc.OK
+                    if t in attend_steps and layer == w.n_layers - 1:
+                        ids = [self.sid[s] for s in serials]
+                        last = o.attention(layer, ids, lens, q, None, precision, threads)
+                for b, serial in enumerate(serials):
+                    self.len[serial] += 1
+                    assert self.len[serial] == lens[b]
+                if last is not None:
+                    outs[t] = (list(serials), list(lens), last)
+                self.step_idx += 1
+            else:
+                raise AssertionError(kind)
+        return outs

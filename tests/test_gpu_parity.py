@@ -1,0 +1,385 @@
+"""GPU parity: the HIP path, called through the C ABI, against the CPU oracle on the same
+seeded inputs.  Integers (ids, offsets, capacities) and stored rows must be bit-exact;
+attention must be within max-abs 2e-3 and relative L2 1e-3 of the fp32 oracle."""
+import os
+
+import numpy as np
+import pytest
+
+from oracle import kv_oracle as orc
+from paper_2306_06000_amd import binding as s3
+from paper_2306_06000_amd import workloads as wl
+from tests.harness import OracleReplay, assert_close, device_bits, make_sources
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+DEV = "cuda:0"
+TDT = {0: torch.float16, 1: torch.bfloat16}
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the GPU box"
+    assert os.path.exists(s3.LIB_PATH), "libs3kv.so must be built before the GPU tests run"
+    s3.lib()
+
+
+class Rig:
+    """A small arena with hand-placed sequences, mirrored in the oracle."""
+
+    def __init__(self, n_layers, H, D, dtype, G, M, preds, seed, arena_tokens=None):
+        self.n_layers, self.H, self.D, self.dtype = n_layers, H, D, dtype
+        self.cfg = s3.make_config(n_layers, H, D, dtype, G, M)
+        bpt = s3.s3_kv_bytes_per_token(self.cfg)
+        caps = [min(M, max(G, -(-p // G) * G)) for p in preds]
+        self.N = arena_tokens or (sum(caps) + 3 * M)
+        self.mem = torch.zeros(self.N * bpt, dtype=torch.uint8, device=DEV)
+        st, self.a = s3.s3_kv_arena_init(self.cfg, self.mem, self.mem.numel())
+        assert st == 0
+        self.o = orc.KVOracle(n_layers, H, D, dtype, G, M, self.N * bpt)
+        rc, self.ids, self.offs, self.caps = s3.s3_kv_alloc(self.a, preds)
+        n_o, ids_o, offs_o, caps_o = self.o.alloc(preds)
+        assert rc == n_o == len(preds)
+        assert self.ids.tolist() == ids_o and self.offs.tolist() == offs_o and self.caps.tolist() == caps_o
+        self.rng = np.random.default_rng(seed)
+        self.stream = torch.cuda.current_stream().cuda_stream
+
+    def fill(self, lens, layer=0):
+        for sid, L in zip(self.ids.tolist(), lens):
+            if L == 0:
+                continue
+            k = wl.normal_bits(self.rng, (L, self.H, self.D), self.dtype)
+            v = wl.normal_bits(self.rng, (L, self.H, self.D), self.dtype)
+            assert self.o.fill(sid, layer, k, v) == 0
+            st = s3.s3_kv_fill(self.a, sid, layer, 0, L, device_bits(k, TDT[self.dtype], DEV),
+                               device_bits(v, TDT[self.dtype], DEV), self.stream)
+            assert st == 0
+
+    def attend(self, lens, layer=0, out_dtype=s3.S3_F32, scale=0.0, offs=None, q=None):
+        n = len(lens)
+        if q is None:
+            q = wl.normal_bits(self.rng, (n, self.H, self.D), self.dtype)
+        qd = device_bits(q, TDT[self.dtype], DEV)
+        off_d = torch.tensor(self.offs.tolist() if offs is None else offs, dtype=torch.int64, device=DEV)
+        len_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+        odt = {s3.S3_F32: torch.float32, s3.S3_F16: torch.float16, s3.S3_BF16: torch.bfloat16}[out_dtype]
+        out = torch.full((n, self.H, self.D), float("nan"), dtype=odt, device=DEV)
+        st = s3.s3_decode_attention(self.a, layer, n, qd, off_d, len_d, out, out_dtype, scale, self.stream)
+        assert st == 0, st
+        torch.cuda.synchronize()
+        return q, out.float().cpu().numpy()
+
+    def oracle_attend(self, q, lens, layer=0, scale=None):
+        return self.o.attention(layer, self.ids.tolist(), lens, q, scale, "f32", threads=8)
+
+    def close(self):
+        torch.cuda.synchronize()
+        s3.s3_kv_arena_destroy(self.a)
+
+
+def n_variants(a):
+    return s3.s3_kv_get_param(a, "n_variants")[1]
+
+
+# ---------------------------------------------------------------- C0, the whole config
+def test_c0_one_append_and_attention_step():
+    from paper_2306_06000_amd.engine import DecodeEngine
+
+    w = wl.c0()
+    eng = DecodeEngine(w, arena_tokens=512)
+    prefill, tensors_for = make_sources(w, eng)
+    eng.start(prefill)
+    assert [a.cap for a in eng.active] == [64, 64, 128, 128] and [a.off for a in eng.active] == [0, 64, 128, 256]
+    out = eng.step(tensors_for(0), prefill, check_host=True)
+    got = out.float().cpu().numpy()
+    rep = OracleReplay(w, 512)
+    outs = rep.replay(eng.events, attend_steps={0})
+    serials, lens, want = outs[0]
+    assert lens == [17, 64, 100, 128]
+    assert_close(got, want, "C0")
+    # the step retired all four sequences (each generated its one token); rows were checked by replay
+    assert eng.active == [] and s3.s3_kv_stats(eng.arena)[1] == 0
+    eng.close()
+
+
+def test_c0_read_as_pre_append_lengths_needs_two_grows():
+    """Other reading of the config: {17,64,100,128} rows are cached BEFORE the step with capacities
+    {64,64,128,128}: sequences 1 and 3 are full, append reports it, grow doubles them."""
+    rig = Rig(1, 16, 256, s3.S3_F16, 64, 2048, [17, 64, 100, 128], seed=5)
+    lens = [17, 64, 100, 128]
+    rig.fill(lens)
+    n = 4
+    k = wl.normal_bits(rig.rng, (n, 16, 256), 0)
+    v = wl.normal_bits(rig.rng, (n, 16, 256), 0)
+    kd, vd = device_bits(k, torch.float16, DEV), device_bits(v, torch.float16, DEV)
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    before = [rig_read(rig, sid, 0, w_, c) for sid, c in zip(rig.ids.tolist(), rig.caps.tolist()) for w_ in (0, 1)]
+    st = s3.s3_kv_append(rig.a, 0, n, off_d, pos_d, kd, vd, rig.stream, slot_id=rig.ids, pos_host=lens)
+    assert st == s3.S3_ERR_SLOT_FULL
+    after = [rig_read(rig, sid, 0, w_, c) for sid, c in zip(rig.ids.tolist(), rig.caps.tolist()) for w_ in (0, 1)]
+    assert all(np.array_equal(x, y) for x, y in zip(before, after))  # nothing was written
+    for b in (1, 3):
+        sid = int(rig.ids[b])
+        assert rig.o.append(sid, 0, lens[b], k[b], v[b]) == orc.ERR_SLOT_FULL
+        got = s3.s3_kv_grow(rig.a, sid, lens[b], rig.stream)
+        assert got == rig.o.grow(sid, lens[b])
+        rig.offs[b], rig.caps[b] = got[1], got[2]
+    assert rig.caps.tolist() == [64, 128, 128, 256]
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    st = s3.s3_kv_append(rig.a, 0, n, off_d, pos_d, kd, vd, rig.stream, slot_id=rig.ids, pos_host=lens)
+    assert st == 0
+    for b, sid in enumerate(rig.ids.tolist()):
+        assert rig.o.append(sid, 0, lens[b], k[b], v[b]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, sid, 0, which, rig.caps[b]), rig.o.data[sid][0, which])
+    lens1 = [L + 1 for L in lens]
+    q, got = rig.attend(lens1)
+    assert_close(got, rig.oracle_attend(q, lens1), "C0 pre-append reading")
+    rig.close()
+
+
+def rig_read(rig, sid, layer, which, rows):
+    dst = torch.empty((int(rows), rig.H, rig.D), dtype=torch.int16, device=DEV)
+    assert s3.s3_kv_read_rows(rig.a, sid, layer, which, 0, int(rows), dst, rig.stream) == 0
+    return dst.cpu().numpy().view(np.uint16)
+
+
+# ---------------------------------------------------------------- kernel variants, chunk sizes, shapes
+RAGGED = [1, 2, 31, 32, 33, 63, 64, 65, 127, 128, 129, 200, 255, 256, 257, 300, 511, 777, 1000, 1, 5, 64]
+
+
+def test_every_variant_and_chunk_size_on_a_ragged_batch():
+    rig = Rig(1, 16, 256, s3.S3_F16, 64, 2048, RAGGED, seed=11)
+    rig.fill(RAGGED)
+    q = wl.normal_bits(rig.rng, (len(RAGGED), 16, 256), 0)
+    want = rig.oracle_attend(q, RAGGED)
+    for variant in range(n_variants(rig.a)):
+        for chunk in (32, 64, 128, 256, 1024):
+            assert s3.s3_kv_set_param(rig.a, "variant", variant) == 0
+            assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+            _, got = rig.attend(RAGGED, q=q)
+            assert_close(got, want, f"variant {variant} chunk {chunk}")
+    # a grid much smaller than the work list (every workgroup walks many items) and a huge one
+    s3.s3_kv_set_param(rig.a, "variant", 1)
+    s3.s3_kv_set_param(rig.a, "chunk", 64)
+    for blocks in (1, 7, 100000):
+        s3.s3_kv_set_param(rig.a, "grid_blocks", blocks)
+        _, got = rig.attend(RAGGED, q=q)
+        assert_close(got, want, f"grid {blocks}")
+    rig.close()
+
+
+@pytest.mark.parametrize("dtype", [s3.S3_F16, s3.S3_BF16])
+@pytest.mark.parametrize("D", [64, 128, 256])
+@pytest.mark.parametrize("H", [1, 3, 12, 16])
+def test_shapes_and_types(dtype, D, H):
+    lens = [1, 17, 64, 100, 128, 129, 515, 40]
+    rig = Rig(1, H, D, dtype, 64, 1024, lens, seed=100 * D + 10 * H + dtype)
+    rig.fill(lens)
+    q = wl.normal_bits(rig.rng, (len(lens), H, D), dtype)
+    want = rig.oracle_attend(q, lens)
+    for variant in (0, 1, 3, 6):
+        s3.s3_kv_set_param(rig.a, "variant", variant)
+        _, got = rig.attend(lens, q=q)
+        assert_close(got, want, f"H{H} D{D} dt{dtype} v{variant}")
+    rig.close()
+
+
+def test_multi_layer_planes_are_independent():
+    lens = [70, 130, 5]
+    rig = Rig(3, 4, 128, s3.S3_BF16, 64, 512, lens, seed=3)
+    for layer in range(3):
+        rig.fill(lens, layer)
+    for layer in range(3):
+        q, got = rig.attend(lens, layer)
+        assert_close(got, rig.oracle_attend(q, lens, layer), f"layer {layer}")
+    rig.close()
+
+
+def test_explicit_scale_and_output_types():
+    lens = [9, 150, 64]
+    rig = Rig(1, 2, 128, s3.S3_F16, 64, 512, lens, seed=4)
+    rig.fill(lens)
+    q, got = rig.attend(lens, scale=0.05)
+    assert_close(got, rig.oracle_attend(q, lens, scale=0.05), "scale 0.05")
+    want = rig.oracle_attend(q, lens)
+    _, got16 = rig.attend(lens, out_dtype=s3.S3_F16, q=q)
+    assert_close(got16, want, "fp16 output")
+    # a bfloat16 output cannot meet 2e-3 by rounding alone (half an ulp is 3.9e-3 in [1, 2)):
+    # it must equal the fp32 result rounded once
+    _, got32 = rig.attend(lens, q=q)
+    _, gotbf = rig.attend(lens, out_dtype=s3.S3_BF16, q=q)
+    rounded = torch.from_numpy(got32).to(torch.bfloat16).float().numpy()
+    assert np.array_equal(gotbf, rounded)
+    rig.close()
+
+
+# ---------------------------------------------------------------- edge cases
+def test_empty_context_length_one_and_max_length():
+    M = 2048
+    lens = [0, 1, M, 0, 2047]
+    rig = Rig(1, 16, 256, s3.S3_F16, 64, M, [64, 64, M, 64, M], seed=6)
+    rig.fill(lens)
+    for chunk in (128, 2048, 32):
+        s3.s3_kv_set_param(rig.a, "chunk", chunk)
+        q, got = rig.attend(lens)
+        want = rig.oracle_attend(q, lens)
+        assert_close(got, want, f"edges chunk {chunk}")
+        assert not got[0].any() and not got[3].any()  # empty context: zero row
+        v0 = rig.o.rows(int(rig.ids[1]), 0, 1, 1)[0].view(np.float16).astype(np.float32)
+        assert np.array_equal(got[1], v0)  # one cached row: the output is that value row exactly
+    rig.close()
+
+
+def test_identical_keys_give_the_mean_value_and_permutation_invariance():
+    H, D, L = 16, 256, 333
+    rig = Rig(1, H, D, s3.S3_F16, 64, 2048, [L, L], seed=8)
+    rng = rig.rng
+    krow = wl.normal_bits(rng, (1, H, D), 0)
+    k = np.repeat(krow, L, axis=0)
+    v = wl.normal_bits(rng, (L, H, D), 0)
+    perm = rng.permutation(L)
+    k2 = wl.normal_bits(rng, (L, H, D), 0)
+    for sid, (kk, vv) in zip(rig.ids.tolist(), [(k, v), (k2, v)]):
+        s3.s3_kv_fill(rig.a, sid, 0, 0, L, device_bits(kk, torch.float16, DEV), device_bits(vv, torch.float16, DEV),
+                      rig.stream)
+    q, got = rig.attend([L, L])
+    mean = v.view(np.float16).astype(np.float64).mean(axis=0)
+    assert np.abs(got[0] - mean).max() < 1e-4
+    s3.s3_kv_fill(rig.a, int(rig.ids[0]), 0, 0, L, device_bits(k2[perm], torch.float16, DEV),
+                  device_bits(v[perm], torch.float16, DEV), rig.stream)
+    q2 = np.stack([q[1], q[1]])
+    _, got2 = rig.attend([L, L], q=q2)
+    assert np.abs(got2[0] - got2[1]).max() < 1e-5  # same rows in another order
+    rig.close()
+
+
+def test_bad_device_entries_are_skipped_not_followed():
+    """Offsets / lengths that would address rows outside the arena are refused inside the
+    kernels: attention returns a zero row, append writes nothing."""
+    lens = [50, 60, 70, 80]
+    rig = Rig(1, 4, 128, s3.S3_F16, 64, 256, lens, seed=9, arena_tokens=1024)
+    rig.fill(lens)
+    offs = rig.offs.tolist()
+    bad_offs = [offs[0], -64, rig.N - 10, offs[3]]
+    bad_lens = [50, 60, 70, 257]  # 1: negative offset, 2: runs past the arena, 3: longer than max_len
+    q, got = rig.attend(bad_lens, offs=bad_offs)
+    want = rig.oracle_attend(q, lens)
+    assert_close(got[0], want[0], "good row beside bad ones")
+    assert not got[1].any() and not got[2].any() and not got[3].any()
+    snap = rig.mem.clone()
+    k = device_bits(wl.normal_bits(rig.rng, (4, 4, 128), 0), torch.float16, DEV)
+    off_d = torch.tensor([-1, rig.N, rig.N - 1, offs[0]], dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor([0, 0, 5, 256], dtype=torch.int32, device=DEV)
+    assert s3.s3_kv_append(rig.a, 0, 4, off_d, pos_d, k, k, rig.stream) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(snap, rig.mem)
+    rig.close()
+
+
+def test_append_writes_exactly_the_addressed_rows():
+    lens = [10, 64, 127]
+    rig = Rig(2, 12, 128, s3.S3_BF16, 64, 512, [64, 128, 128], seed=10)
+    for layer in range(2):
+        rig.fill(lens, layer)
+    n = 3
+    k = wl.normal_bits(rig.rng, (n, 12, 128), 1)
+    v = wl.normal_bits(rig.rng, (n, 12, 128), 1)
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    st = s3.s3_kv_append(rig.a, 1, n, off_d, pos_d, device_bits(k, torch.bfloat16, DEV),
+                         device_bits(v, torch.bfloat16, DEV), rig.stream, slot_id=rig.ids, pos_host=lens)
+    assert st == 0
+    for b, sid in enumerate(rig.ids.tolist()):
+        assert rig.o.append(sid, 1, lens[b], k[b], v[b]) == 0
+    for b, sid in enumerate(rig.ids.tolist()):
+        for layer in range(2):
+            for which in (0, 1):
+                assert np.array_equal(rig_read(rig, sid, layer, which, rig.caps[b]), rig.o.data[sid][layer, which])
+    # host-side refusal: unknown id, negative position
+    assert s3.s3_kv_append(rig.a, 0, n, off_d, pos_d, device_bits(k, torch.bfloat16, DEV),
+                           device_bits(v, torch.bfloat16, DEV), rig.stream, slot_id=[0, 1, 9], pos_host=lens) == -1
+    rig.close()
+
+
+def test_grow_moves_rows_bit_exactly_and_leaves_other_slots_alone():
+    lens = [64, 100, 128, 30]
+    rig = Rig(2, 16, 256, s3.S3_F16, 64, 2048, [64, 100, 128, 30], seed=12)
+    for layer in range(2):
+        rig.fill(lens, layer)
+    for b in (0, 2):
+        sid = int(rig.ids[b])
+        got = s3.s3_kv_grow(rig.a, sid, lens[b], rig.stream)
+        assert got == rig.o.grow(sid, lens[b]) and got[2] == 2 * rig.caps[b]
+        rig.offs[b], rig.caps[b] = got[1], got[2]
+    for b, sid in enumerate(rig.ids.tolist()):
+        for layer in range(2):
+            for which in (0, 1):
+                assert np.array_equal(rig_read(rig, sid, layer, which, lens[b]), rig.o.rows(sid, layer, which, lens[b]))
+    q, got = rig.attend(lens, layer=1)
+    assert_close(got, rig.oracle_attend(q, lens, layer=1), "after grow")
+    assert s3.s3_kv_stats(rig.a) == (0, *rig.o.stats())
+    rig.close()
+
+
+# ---------------------------------------------------------------- traces
+def run_trace(w, steps, attend_steps, arena_tokens=None, variant=None, chunk=None, sample=None):
+    from paper_2306_06000_amd.engine import DecodeEngine
+
+    eng = DecodeEngine(w, arena_tokens=arena_tokens)
+    if variant is not None:
+        s3.s3_kv_set_param(eng.arena, "variant", variant)
+    if chunk is not None:
+        s3.s3_kv_set_param(eng.arena, "chunk", chunk)
+    prefill, tensors_for = make_sources(w, eng)
+    eng.start(prefill)
+    got = {}
+    for t in range(steps):
+        out = eng.step(tensors_for(t), prefill, check_host=True)
+        if t in attend_steps:
+            got[t] = out.float().cpu().numpy()
+    rep = OracleReplay(w, eng.arena_tokens)
+    outs = rep.replay(eng.events, attend_steps=set(attend_steps))
+    for t in attend_steps:
+        serials, lens, want = outs[t]
+        assert_close(got[t], want, f"{w.name} step {t}")
+    # every live slot holds exactly the rows the oracle holds
+    live = eng.active if sample is None else eng.active[:sample]
+    for a in live:
+        sid = rep.sid[a.serial]
+        assert sid == a.slot and rep.o.slots[sid] == [a.off, a.cap] and rep.len[a.serial] == a.len
+        for layer in range(w.n_layers):
+            for which in (0, 1):
+                assert np.array_equal(eng.read_slot(a, layer, which), rep.o.rows(sid, layer, which, a.len))
+    assert s3.s3_kv_stats(eng.arena) == (0, *rep.o.stats())
+    stats = dict(grows=s3.s3_kv_get_param(eng.arena, "n_grows")[1], frees=sum(e[0] == "free" for e in eng.events),
+                 evicted=eng.n_evicted)
+    assert stats["grows"] == rep.o.n_grows
+    eng.close()
+    return stats
+
+
+def test_c1_trace_128_steps_with_grow_free_and_refill():
+    w = wl.c1()
+    stats = run_trace(w, w.steps, attend_steps=[0, 1, 40, 127])
+    assert stats["grows"] >= 1 and stats["frees"] >= 1 and stats["evicted"] == 0
+
+
+def test_c2_shape_shortened_trace_with_mispredictions():
+    w = wl.c2(batch=192, steps=40)
+    stats = run_trace(w, w.steps, attend_steps=[0, 39], sample=48)
+    assert stats["grows"] >= 1
+
+
+def test_c4_shape_long_contexts_bf16():
+    w = wl.c4(batch=24, steps=6)
+    run_trace(w, w.steps, attend_steps=[0, 5], sample=6)
+
+
+def test_c3_shape_small_arena_28_layers():
+    w = wl.c3(target_bytes=0)
+    w.seqs = w.seqs[:6]
+    w.arena_bytes = 0
+    run_trace(w, 1, attend_steps=[0])

@@ -1,0 +1,156 @@
+"""CPU-side checks of libs3kv.so: it loads, exports every declared symbol, and its host
+bookkeeping (slot table, first fit, doubling) agrees bit for bit with the oracle on random
+traces.  A metadata-only arena (no device memory) is used, so no GPU call is made."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import kv_oracle as orc
+from paper_2306_06000_amd import binding as s3
+from paper_2306_06000_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module", autouse=True)
+def built():
+    if not os.path.exists(s3.LIB_PATH):
+        from paper_2306_06000_amd.build import build_lib
+
+        build_lib()
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "s3kv.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(s3_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_symbols()
+    assert {"s3_kv_arena_init", "s3_kv_alloc", "s3_kv_append", "s3_decode_attention", "s3_kv_grow", "s3_kv_free",
+            "s3_kv_stats"} <= set(names)
+    lib = s3.lib()
+    for n in names:
+        assert hasattr(lib, n), n
+        assert n in s3.SIGNATURES, n
+    assert sorted(s3.SIGNATURES) == names
+
+
+def meta_arena(n_layers, H, D, dtype, G, M, nbytes):
+    cfg = s3.make_config(n_layers, H, D, dtype, G, M)
+    st, a = s3.s3_kv_arena_init(cfg, None, nbytes)
+    assert st == s3.S3_OK
+    return cfg, a
+
+
+def test_bytes_per_token_matches_the_paper_example():
+    cfg = s3.make_config(44, 64, 64, s3.S3_F16, 64, 2048)  # hidden 4096: 4*44*4096
+    assert s3.s3_kv_bytes_per_token(cfg) == 4 * 44 * 4096
+    bad = s3.make_config(44, 64, 96, s3.S3_F16, 64, 2048)  # head_dim 96 is not supported by the kernels
+    assert s3.s3_kv_bytes_per_token(bad) == s3.S3_ERR_INVALID
+    gptj = s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048)
+    assert s3.s3_kv_bytes_per_token(gptj) == 458752
+
+
+def test_config_validation():
+    for bad in [(0, 16, 256, 0, 64, 2048), (1, 0, 256, 0, 64, 2048), (1, 16, 100, 0, 64, 2048),
+                (1, 16, 256, 2, 64, 2048), (1, 16, 256, 0, 0, 2048), (1, 16, 256, 0, 64, 2000)]:
+        st, a = s3.s3_kv_arena_init(s3.make_config(*bad), None, 1 << 20)
+        assert st == s3.S3_ERR_INVALID and a is None
+
+
+def test_status_strings():
+    assert s3.lib().s3_status_str(0) == b"S3_OK"
+    assert s3.lib().s3_status_str(-3) == b"S3_ERR_SLOT_FULL"
+    assert s3.lib().s3_last_hip_error() == b""
+
+
+def test_c0_slots_and_stats():
+    w = wl.c0()
+    cfg, a = meta_arena(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len, 512 * w.bytes_per_token)
+    rc, ids, offs, caps = s3.s3_kv_alloc(a, [s.predicted for s in w.seqs])
+    assert rc == 4 and ids.tolist() == [0, 1, 2, 3]
+    assert caps.tolist() == [64, 64, 128, 128] and offs.tolist() == [0, 64, 128, 256]
+    assert s3.s3_kv_stats(a) == (0, 384, 128, 128, 512)
+    assert s3.s3_kv_slot_info(a, 2) == (0, 128, 128)
+    assert s3.s3_kv_slot_info(a, 9)[0] == s3.S3_ERR_INVALID
+    s3.s3_kv_arena_destroy(a)
+
+
+def test_errors_leave_state_unchanged():
+    cfg, a = meta_arena(1, 1, 64, 0, 64, 256, 256 * 256)  # 256 tokens
+    rc, ids, offs, caps = s3.s3_kv_alloc(a, [128, 64])
+    assert rc == 2
+    before = s3.s3_kv_stats(a)
+    assert s3.s3_kv_alloc(a, [5, -1])[0] == s3.S3_ERR_INVALID
+    assert s3.s3_kv_grow(a, 0, 128)[0] == s3.S3_ERR_NOMEM
+    assert s3.s3_kv_grow(a, 0, 129)[0] == s3.S3_ERR_INVALID
+    assert s3.s3_kv_grow(a, 5, 1)[0] == s3.S3_ERR_INVALID
+    assert s3.s3_kv_free(a, 7) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_stats(a) == before
+    rc, ids2, offs2, caps2 = s3.s3_kv_alloc(a, [64, 64, 64])  # only one more fits
+    assert rc == 1 and ids2.tolist() == [2, -1, -1] and offs2.tolist() == [192, -1, -1] and caps2.tolist() == [64, 0, 0]
+    assert s3.s3_kv_free(a, 0) == s3.S3_OK
+    assert s3.s3_kv_grow(a, 1, 64) == (s3.S3_OK, 0, 128)
+    assert s3.s3_kv_grow(a, 1, 10)[0] == s3.S3_ERR_NOMEM  # 256 needed, 64 free
+    s3.s3_kv_arena_destroy(a)
+
+
+def test_grow_to_max_len_then_maxlen_error():
+    cfg, a = meta_arena(1, 1, 64, 0, 64, 320, 4096 * 256)
+    rc, ids, offs, caps = s3.s3_kv_alloc(a, [192])
+    assert s3.s3_kv_grow(a, 0, 192)[2] == 320  # min(2*192, M)
+    assert s3.s3_kv_grow(a, 0, 0)[0] == s3.S3_ERR_MAXLEN
+    # rows cannot be touched through a metadata-only arena
+    assert s3.s3_kv_fill(a, 0, 0, 0, 1, 16, 16) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_append(a, 0, 1, 16, 16, 16, 16) == s3.S3_ERR_INVALID
+    assert s3.s3_decode_attention(a, 0, 1, 16, 16, 16, 16) == s3.S3_ERR_INVALID
+    s3.s3_kv_arena_destroy(a)
+
+
+def test_set_param_validation():
+    cfg, a = meta_arena(1, 1, 64, 0, 64, 256, 1 << 20)
+    assert s3.s3_kv_set_param(a, "chunk", 128) == s3.S3_OK
+    assert s3.s3_kv_get_param(a, "chunk") == (0, 128)
+    assert s3.s3_kv_set_param(a, "chunk", 100) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_set_param(a, "nonsense", 1) == s3.S3_ERR_INVALID
+    st, nv = s3.s3_kv_get_param(a, "n_variants")
+    assert st == 0 and nv >= 1
+    assert s3.s3_kv_set_param(a, "variant", nv) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_set_param(a, "variant", nv - 1) == s3.S3_OK
+    s3.s3_kv_arena_destroy(a)
+
+
+@pytest.mark.parametrize("seed,granule,tokens", [(0, 64, 64 * 300), (1, 128, 128 * 97), (2, 64, 64 * 41)])
+def test_random_trace_bit_exact_against_oracle(seed, granule, tokens):
+    rng = np.random.default_rng(100 + seed)
+    M = 2048
+    bpt = 2 * 1 * 1 * 64 * 2
+    o = orc.KVOracle(1, 1, 64, orc.F16, granule, M, tokens * bpt + 17, store=False)
+    cfg, a = meta_arena(1, 1, 64, 0, granule, M, tokens * bpt + 17)
+    live = []
+    for step in range(10000 if seed == 0 else 3000):
+        r = rng.random()
+        if r < 0.45 or not live:
+            k = int(rng.integers(1, 5))
+            preds = [int(rng.integers(0, 2400)) if rng.random() < 0.5 else int(rng.integers(1, 300)) for _ in range(k)]
+            n_o, ids_o, offs_o, caps_o = o.alloc(preds)
+            rc, ids, offs, caps = s3.s3_kv_alloc(a, preds)
+            assert rc == n_o and ids.tolist() == ids_o and offs.tolist() == offs_o and caps.tolist() == caps_o
+            live += [i for i in ids_o if i >= 0]
+        elif r < 0.75:
+            sid = live.pop(int(rng.integers(len(live))))
+            assert s3.s3_kv_free(a, sid) == o.free(sid) == 0
+        else:
+            sid = live[int(rng.integers(len(live)))]
+            length = int(rng.integers(0, o.slots[sid][1] + 1))
+            assert s3.s3_kv_grow(a, sid, length) == o.grow(sid, length)
+        assert s3.s3_kv_stats(a) == (0, *o.stats())
+        if step % 97 == 0:
+            for sid in live:
+                assert s3.s3_kv_slot_info(a, sid) == (0, *o.slots[sid])
+    assert s3.s3_kv_get_param(a, "n_grows") == (0, o.n_grows)
+    s3.s3_kv_arena_destroy(a)
