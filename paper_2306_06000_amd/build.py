@@ -25,6 +25,9 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
     cmd = [_hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
            # keep the compiler from forming packed-fp32 instructions
            "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+           # fuse a*b+c only inside one expression: the max-subtracted exponent s - max(s) must stay
+           # an exact zero for the largest score (cross-statement fusing would turn it into a residual)
+           "-ffp-contract=on",
            "-Wall", "-Wno-unused-function",
            "-I", os.path.join(ROOT, "include"), "-I", CSRC]
     for s in srcs:

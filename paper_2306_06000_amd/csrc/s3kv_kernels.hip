@@ -117,7 +117,8 @@ __device__ __forceinline__ int checked_len(const AttnArgs &a, int b) {
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_sum_step(float v) {
-    const int moved = __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true);
+    const int bits = __builtin_bit_cast(int, v);
+    const int moved = __builtin_amdgcn_update_dpp(0, bits, CTRL, 0xF, 0xF, true);
     return v + __builtin_bit_cast(float, moved);
 }
 
@@ -129,24 +130,28 @@ __device__ __forceinline__ float group_sum(float v) {
     v = dpp_sum_step<0x141>(v);  // row_half_mirror: the other quad of each 8
     if (LANES >= 16) v = dpp_sum_step<0x140>(v);  // row_mirror: the other 8 of each 16
     if (LANES >= 32)
-        v += __builtin_bit_cast(float, __builtin_amdgcn_ds_swizzle(__builtin_bit_cast(int, v), 0x401F));  // lane ^ 16
+    {
+        const int bits = __builtin_bit_cast(int, v);
+        const int other = __builtin_amdgcn_ds_swizzle(bits, 0x401F);  // lane ^ 16
+        v += __builtin_bit_cast(float, other);
+    }
     return v;
 }
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
+// Note: __builtin_bit_cast applied directly to a vector-element expression (v[i]) reads element 0
+// with this compiler, so elements are always copied into a scalar first.
 template <int DT>
 __device__ __forceinline__ float dot8(const u32x4 a, const u32x4 b) {
     float s = 0.f;
-    if (DT == S3_F16) {
 #pragma unroll
-        for (int i = 0; i < 4; i++)
-            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, a[i]), __builtin_bit_cast(f16x2, b[i]), s, false);
-    } else {
-#pragma unroll
-        for (int i = 0; i < 4; i++)
-            s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, a[i]), __builtin_bit_cast(bf16x2, b[i]), s,
-                                                false);
+    for (int i = 0; i < 4; i++) {
+        const unsigned ai = a[i], bi = b[i];
+        if (DT == S3_F16)
+            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, ai), __builtin_bit_cast(f16x2, bi), s, false);
+        else
+            s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, ai), __builtin_bit_cast(bf16x2, bi), s, false);
     }
     return s;
 }
@@ -156,13 +161,15 @@ __device__ __forceinline__ void axpy8(float (&acc)[8], const float p, const u32x
 #pragma unroll
     for (int i = 0; i < 4; i++) {
         float lo, hi;
+        const unsigned vi = v[i];
         if (DT == S3_F16) {
-            const f16x2 h = __builtin_bit_cast(f16x2, v[i]);
+            const f16x2 h = __builtin_bit_cast(f16x2, vi);
             lo = (float)h[0];
             hi = (float)h[1];
         } else {
-            lo = __builtin_bit_cast(float, v[i] << 16);
-            hi = __builtin_bit_cast(float, v[i] & 0xFFFF0000u);
+            const unsigned lo_bits = vi << 16, hi_bits = vi & 0xFFFF0000u;
+            lo = __builtin_bit_cast(float, lo_bits);
+            hi = __builtin_bit_cast(float, hi_bits);
         }
         acc[2 * i] = fmaf(p, lo, acc[2 * i]);
         acc[2 * i + 1] = fmaf(p, hi, acc[2 * i + 1]);
@@ -187,7 +194,8 @@ __device__ __forceinline__ void store_out8(void *out, int out_dtype, int64_t e, 
         for (int i = 0; i < 4; i++) {
             if (out_dtype == S3_F16) {
                 const f16x2 h = {(_Float16)v[2 * i], (_Float16)v[2 * i + 1]};
-                w[i] = __builtin_bit_cast(unsigned, h);
+                const unsigned packed = __builtin_bit_cast(unsigned, h);
+                w[i] = packed;
             } else {
                 w[i] = f32_to_bf16_rne(v[2 * i]) | (f32_to_bf16_rne(v[2 * i + 1]) << 16);
             }

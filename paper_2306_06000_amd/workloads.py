@@ -106,17 +106,15 @@ def _refill_pool(rng, n, draw):
 
 def c1(batch: int = 64, steps: int = 128) -> Workload:
     """GPT-J-shaped single layer, batch 64, 128 decode steps.  Prompt ~ U{32..512}, output ~
-    U{1..512}; the prediction multiplies the OUTPUT part by lognormal(0, 0.2) (the prompt is
-    known exactly), so under-predictions outgrow their slot mid-run."""
+    U{1..512}; the prediction is the true total length times lognormal(0, 0.2), never below
+    prompt + 1, so under-predicted sequences outgrow their slot mid-run."""
     rng = np.random.default_rng(SEED_BASE + 1)
 
     def draw(r):
         p = int(r.integers(32, 513))
         g = int(r.integers(1, 513))
         f = float(r.lognormal(0.0, 0.2))
-        pred = min(2048, p + max(1, int(round(g * f))))
-        if p + g > 2048:
-            g = 2048 - p
+        pred = min(2048, max(p + 1, int(round((p + g) * f))))
         return Seq(p, g, pred)
 
     seqs = [draw(rng) for _ in range(batch)]
@@ -155,7 +153,7 @@ def c3(target_bytes: int = 200 * 10**9, n_layers: int = 28, max_seqs: int = 4096
         g = int(rng.integers(1, 513))
         f = float(rng.lognormal(0.0, 0.2))
         u = float(rng.random())
-        pred = min(2048, p + max(1, int(round(g * f))))
+        pred = min(2048, max(p + 1, int(round((p + g) * f))))
         pred = max(pred, p + int(u * g) + 1)  # the row written by the timed step must fit
         seqs.append(Seq(p, g, pred, start=p + int(u * g)))
     w = Workload("C3-gptj-28layers", 3, n_layers, 16, 256, BF16, 64, 2048, 0, 1, seqs)
