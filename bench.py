@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the decode hot path (grow check, append, ragged attention, retire/refill) on ONE
+MI355X, through the C ABI of libs3kv.so, on the synthetic workload C1 of the benchmark spec
+(GPT-J-shaped layer, batch 64, 128 consecutive decode steps) unless --workload says otherwise.
+
+Prints ONE JSON line.  `value` is algorithmic bytes moved per second over the whole timed
+region (all kernels, host bookkeeping included), inputs resident in HBM.  `roofline` is for the
+dominant kernel (the split attention kernel), timed with HIP events on the launch stream inside
+the same timed region.  `cpu_baseline` is the CPU oracle timed on this machine's host cores on a
+bounded sample of the same workload.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+PEAK_HBM_GBPS = 8000.0
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=128)
+    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--variant", type=int, default=-1)
+    ap.add_argument("--chunk", type=int, default=0)
+    ap.add_argument("--grid-blocks", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-kernel-events", action="store_true", help="do not time the attention kernel with events")
+    ap.add_argument("--c3-bytes", type=float, default=200e9)
+    return ap.parse_args()
+
+
+def make_device_sources(w, eng, torch, ring=8):
+    """Inputs resident in HBM before the timed region: a ring of N(0,1) q/k/v tensors and a pool
+    of prompt rows that newcomers are filled from.  Seeded torch generator on the device."""
+    gen = torch.Generator(device=eng.dev)
+    gen.manual_seed(w.seed)
+    tdt = eng.kv_dtype_torch()
+    bmax = max(len(w.seqs), 1)
+    qkv = torch.randn((ring, 3, bmax, w.n_heads, w.head_dim), generator=gen, device=eng.dev, dtype=torch.float32).to(tdt)
+    rows = torch.randn((2, w.max_len, w.n_heads, w.head_dim), generator=gen, device=eng.dev,
+                       dtype=torch.float32).to(tdt)
+    state = {"i": 0}
+
+    def prefill(serial, layer, n_rows):
+        return rows[0, :n_rows], rows[1, :n_rows]
+
+    def tensors(layer, n):
+        t = qkv[state["i"] % ring]
+        state["i"] += 1
+        return t[0, :n], t[1, :n], t[2, :n]
+
+    return prefill, tensors, (qkv, rows)
+
+
+def cpu_baseline(w, eng, torch, budget_s=12.0):
+    """Time the oracle as it stands (fp32 attention, OpenMP over (sequence, head) on all host
+    cores) on the final batch state of the run: whole-batch passes over one layer are repeated
+    until the time budget is used (at least one pass; a pass that would not fit the budget is cut
+    to a prefix of the batch).  K/V values are N(0,1) like the GPU's; the oracle's run time does
+    not depend on them."""
+    import numpy as np
+
+    from oracle import kv_oracle as orc
+    from paper_2306_06000_amd import workloads as wl
+
+    cores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+    omp = int(os.environ.get("OMP_NUM_THREADS", "0") or 0)
+    if omp > 0:
+        cores = min(cores, omp)
+    H, D = w.n_heads, w.head_dim
+    rng = np.random.default_rng(w.seed)
+    lens = eng.len.copy()
+    kv = wl.normal_bits(rng, (2, int(w.max_len), H, D), w.dtype)
+    done_bytes, done_seqs, t_used, used = 0, 0, 0.0, cores
+    n_take = min(lens.size, 16)  # first a small probe to size the passes
+    passes = 0
+    while t_used < budget_s:
+        idx = np.arange(n_take)
+        q = wl.normal_bits(rng, (idx.size, H, D), w.dtype)
+        t0 = time.perf_counter()
+        _, used = orc.attention_ragged(q, [kv[0]] * idx.size, [kv[1]] * idx.size, lens[idx], w.dtype, None, "f32",
+                                       threads=cores)
+        dt = time.perf_counter() - t0
+        t_used += dt
+        done_bytes += int(2 * H * D * 2 * lens[idx].sum() + idx.size * H * D * (2 + 4))
+        done_seqs += int(idx.size)
+        passes += 1
+        rate = idx.size / dt
+        n_take = int(max(1, min(lens.size, rate * min(budget_s - t_used, 4.0))))
+        if budget_s - t_used < 0.05:
+            break
+    return {"value": round(done_bytes / t_used / 1e9, 4), "unit": "GB/s", "cores": int(used), "kind": "oracle",
+            "seq_steps_per_s": round(done_seqs / t_used, 2),
+            "sample": f"one layer of oracle attention over prefixes of the final batch state ({lens.size} sequences), "
+                      f"{passes} passes, {done_seqs} sequence-steps, {t_used:.1f} s of CPU work, OpenMP over "
+                      "(sequence, head)"}
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build measures ONE GPU (no collectives, no sharding); run with --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+
+    from paper_2306_06000_amd import binding as s3
+    from paper_2306_06000_amd import workloads as wl
+    from paper_2306_06000_amd.engine import DecodeEngine
+
+    assert torch.cuda.is_available(), "bench.py needs the GPU"
+    s3.lib()
+    w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4}[args.workload]() if args.workload != "c3" else wl.c3(
+        target_bytes=int(args.c3_bytes))
+    eng = DecodeEngine(w, log_events=False)
+    if args.variant >= 0:
+        s3.check(s3.s3_kv_set_param(eng.arena, "variant", args.variant))
+    if args.chunk:
+        s3.check(s3.s3_kv_set_param(eng.arena, "chunk", args.chunk))
+    if args.grid_blocks:
+        s3.check(s3.s3_kv_set_param(eng.arena, "grid_blocks", args.grid_blocks))
+    prefill, tensors, _keep = make_device_sources(w, eng, torch)
+    eng.start(prefill, stop_when_full=(args.workload == "c3"))
+    torch.cuda.synchronize()
+
+    for _ in range(args.warmup):
+        eng.step(tensors, prefill)
+    torch.cuda.synchronize()
+    if not args.no_kernel_events:
+        s3.check(s3.s3_kv_set_param(eng.arena, "profile", 1))
+    grown0, retired0 = eng.n_grown, eng.n_retired
+    total_bytes, seq_steps, attn_bytes = 0, 0, 0
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        eng.step(tensors, prefill)
+        total_bytes += eng.last_step_bytes
+        seq_steps += eng.last_step_seqs
+    torch.cuda.synchronize()
+    dt = time.perf_counter() - t0
+
+    res = {
+        "metric": "decode-attention achieved HBM GB/s", "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "f16" if w.dtype == 0 else "bf16", "data": "synthetic",
+        "pct_of_peak_hbm": round(100 * total_bytes / dt / 1e9 / PEAK_HBM_GBPS, 2),
+        "seq_steps_per_s": round(seq_steps / dt, 1),
+        "config": {"workload": w.name, "batch": eng.n_active, "n_layers": w.n_layers, "n_heads": w.n_heads,
+                   "head_dim": w.head_dim, "mean_context": round(float(eng.len.mean()), 1),
+                   "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,
+                   "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
+                   "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
+                   "variant": s3.s3_kv_get_param(eng.arena, "variant")[1],
+                   "chunk": s3.s3_kv_get_param(eng.arena, "chunk")[1]},
+    }
+    if not args.no_kernel_events:
+        launches = s3.s3_kv_get_param(eng.arena, "profile_launches")[1]
+        part_ns = s3.s3_kv_get_param(eng.arena, "profile_partial_ns")[1]
+        merge_ns = s3.s3_kv_get_param(eng.arena, "profile_merge_ns")[1]
+        per_launch_bytes = total_bytes / max(launches, 1)
+        avg_us = part_ns / max(launches, 1) / 1e3
+        achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if avg_us > 0 else 0.0
+        res["roofline"] = {"bound": "hbm", "kernel": "attn_partial_kernel", "achieved": round(achieved, 1),
+                           "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
+                           "traffic": None, "avg_kernel_us": round(avg_us, 2),
+                           "avg_merge_kernel_us": round(merge_ns / max(launches, 1) / 1e3, 2), "launches": launches,
+                           "algorithmic_bytes_per_launch": int(per_launch_bytes)}
+    if not args.no_cpu_baseline:
+        res["cpu_baseline"] = cpu_baseline(w, eng, torch)
+    eng.close()
+    print(json.dumps(res))
+
+
+if __name__ == "__main__":
+    main()

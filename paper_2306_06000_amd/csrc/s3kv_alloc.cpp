@@ -230,6 +230,13 @@ extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
         a->variant = (int32_t)value;
         return S3_OK;
     }
+    if (!strcmp(name, "profile")) {  // 1: time every attention launch with events; 0: off (and reset)
+        if (value != 0 && value != 1) return S3_ERR_INVALID;
+        if (!a->base) return S3_ERR_INVALID;
+        s3i_profile_reset(a);
+        a->profile = value != 0;
+        return S3_OK;
+    }
     return S3_ERR_INVALID;
 }
 
@@ -243,6 +250,14 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
     else if (!strcmp(name, "live_slots")) *value = (int64_t)a->slots.size() - (int64_t)a->dead_ids.size();
     else if (!strcmp(name, "scratch_bytes")) *value = (int64_t)a->scratch_bytes;
     else if (!strcmp(name, "num_cus")) *value = a->num_cus;
+    else if (!strncmp(name, "profile_", 8)) {
+        const int rc = s3i_profile_collect(const_cast<s3_arena *>(a));
+        if (rc != S3_OK) return rc;
+        if (!strcmp(name, "profile_launches")) *value = a->prof_launches;
+        else if (!strcmp(name, "profile_partial_ns")) *value = (int64_t)(a->prof_partial_ms * 1e6);
+        else if (!strcmp(name, "profile_merge_ns")) *value = (int64_t)(a->prof_merge_ms * 1e6);
+        else return S3_ERR_INVALID;
+    }
     else return S3_ERR_INVALID;
     return S3_OK;
 }

@@ -33,6 +33,13 @@ struct s3_arena {
     void *scratch = nullptr;
     size_t scratch_bytes = 0;
 
+    // optional timing of the attention kernels with events on the launch stream
+    bool profile = false;
+    std::vector<void *> prof_events;  // triples: before partial, after partial, after merge
+    size_t prof_used = 0;             // events handed out since the last collect
+    double prof_partial_ms = 0.0, prof_merge_ms = 0.0;
+    int64_t prof_launches = 0;
+
     // launch-shape knobs (0 = default)
     int32_t chunk = 0;
     int32_t grid_blocks = 0;
@@ -55,4 +62,6 @@ void s3i_set_hip_error(const char *what, int code, const char *text);
 int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src_plane_stride,
                            size_t dst_plane_stride, int planes, void *stream);
 int s3i_num_variants();
+int s3i_profile_collect(s3_arena *a);  // synchronises on the recorded events and accumulates the sums
+void s3i_profile_reset(s3_arena *a);
 int s3i_device_cus(int32_t *cus);

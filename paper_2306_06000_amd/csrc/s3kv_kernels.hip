@@ -466,8 +466,45 @@ static int ensure_scratch(s3_arena *a, size_t need) {
     return S3_OK;
 }
 
+// ---- optional event timing of the attention kernels -------------------------------------
+static int prof_next_event(s3_arena *a, hipEvent_t *ev) {
+    if (a->prof_used == a->prof_events.size()) {
+        hipEvent_t e;
+        HIP_TRY(hipEventCreate(&e));
+        a->prof_events.push_back((void *)e);
+    }
+    *ev = (hipEvent_t)a->prof_events[a->prof_used++];
+    return S3_OK;
+}
+
+int s3i_profile_collect(s3_arena *a) {
+    for (size_t i = 0; i + 2 < a->prof_used; i += 3) {
+        hipEvent_t e0 = (hipEvent_t)a->prof_events[i], e1 = (hipEvent_t)a->prof_events[i + 1],
+                   e2 = (hipEvent_t)a->prof_events[i + 2];
+        HIP_TRY(hipEventSynchronize(e2));
+        float p = 0.f, m = 0.f;
+        HIP_TRY(hipEventElapsedTime(&p, e0, e1));
+        HIP_TRY(hipEventElapsedTime(&m, e1, e2));
+        a->prof_partial_ms += p;
+        a->prof_merge_ms += m;
+        a->prof_launches++;
+    }
+    a->prof_used = 0;
+    return S3_OK;
+}
+
+void s3i_profile_reset(s3_arena *a) {
+    (void)s3i_profile_collect(a);
+    a->prof_partial_ms = a->prof_merge_ms = 0.0;
+    a->prof_launches = 0;
+}
+
 extern "C" void s3_kv_arena_destroy(s3_arena *a) {
     if (!a) return;
+    if (!a->prof_events.empty()) {
+        (void)hipDeviceSynchronize();
+        for (void *e : a->prof_events) (void)hipEventDestroy((hipEvent_t)e);
+    }
     if (a->scratch) {
         (void)hipDeviceSynchronize();
         (void)hipFree(a->scratch);
@@ -542,8 +579,17 @@ extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const 
     const int cus = a->num_cus > 0 ? a->num_cus : 256;
     int blocks = a->grid_blocks > 0 ? a->grid_blocks : cus * (32 / nw);
     const size_t dyn_lds = (size_t)(n + 1) * sizeof(int);
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    if (a->profile) {
+        for (int i = 0; i < 3; i++) {
+            const int prc = prof_next_event(a, &ev[i]);
+            if (prc != S3_OK) return prc;
+        }
+        HIP_TRY(hipEventRecord(ev[0], (hipStream_t)stream));
+    }
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)(nw * 64)), dyn_lds, (hipStream_t)stream, args);
     HIP_TRY(hipGetLastError());
+    if (a->profile) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
 
     const int GH = 512 / D;
     const int n_hg = (H + GH - 1) / GH;
@@ -551,6 +597,7 @@ extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const 
     void (*mfn)(const AttnArgs) = D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
     hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, args);
     HIP_TRY(hipGetLastError());
+    if (a->profile) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
     return S3_OK;
 }
 

@@ -9,21 +9,17 @@ Per decode step (iteration-level scheduling, section 3 of the S3 paper):
   4. sequences that reached their true total length are freed; with refill on, the next
      candidate of the pool is admitted into the freed room and its prompt rows are written.
 The event log lets a test replay the same decisions on the CPU oracle and compare every id,
-offset and capacity bit for bit.
+offset and capacity bit for bit.  Host-side state is kept in numpy arrays so that a step costs
+a few vector operations however large the batch is.
 """
+from types import SimpleNamespace
+
 import numpy as np
 import torch
 
 from . import binding as s3
 
 _TORCH_DT = {s3.S3_F16: torch.float16, s3.S3_BF16: torch.bfloat16, s3.S3_F32: torch.float32}
-
-
-class Active:
-    __slots__ = ("serial", "seq", "slot", "off", "cap", "len")
-
-    def __init__(self, serial, seq, slot, off, cap, length):
-        self.serial, self.seq, self.slot, self.off, self.cap, self.len = serial, seq, slot, off, cap, length
 
 
 class DecodeEngine:
@@ -43,16 +39,24 @@ class DecodeEngine:
         st, self.arena = s3.s3_kv_arena_init(self.cfg, self.arena_mem, self.arena_mem.numel())
         s3.check(st, "s3_kv_arena_init")
         self.out_dtype = out_dtype
-        self.active = []
         self.events = [] if log_events else None
         self.next_serial = 0
         self.pool_pos = 0
         self.n_evicted = 0
+        self.n_grown = 0
+        self.n_retired = 0
+        # per active sequence, batch order
+        self.serial = np.zeros(0, np.int64)
+        self.slot = np.zeros(0, np.int32)
+        self.off = np.zeros(0, np.int64)
+        self.cap = np.zeros(0, np.int32)
+        self.len = np.zeros(0, np.int32)
+        self.total = np.zeros(0, np.int32)
         self.slot_off_dev = None
         self.len_dev = None
+        self.len_next = None
         self._dirty = True
         self.out = None
-        self.stream = 0  # torch's current (default) stream
 
     # -- helpers ----------------------------------------------------------
     def close(self):
@@ -71,27 +75,48 @@ class DecodeEngine:
     def kv_dtype_torch(self):
         return _TORCH_DT[self.w.dtype]
 
-    def _upload(self, values, dtype):
+    @property
+    def n_active(self):
+        return int(self.slot.size)
+
+    @property
+    def active(self):
+        """Read-only view of the batch as records (for tests and reports)."""
+        return [SimpleNamespace(serial=int(self.serial[i]), slot=int(self.slot[i]), off=int(self.off[i]),
+                                cap=int(self.cap[i]), len=int(self.len[i]), total=int(self.total[i]))
+                for i in range(self.n_active)]
+
+    def _upload(self, arr):
         # torch's pinned-memory allocator does not reuse a block before the copy that reads it has
         # completed, so the staging tensor needs no lifetime management here
-        host = torch.tensor(values, dtype=dtype).pin_memory()
+        host = torch.from_numpy(arr.copy()).pin_memory()
         return host.to(self.dev, non_blocking=True)
 
     def _sync_arrays(self):
         if self._dirty:
-            self.slot_off_dev = self._upload([a.off for a in self.active], torch.int64)
-            self.len_dev = self._upload([a.len for a in self.active], torch.int32)
-            n = len(self.active)
-            odt = _TORCH_DT[self.out_dtype]
+            self.slot_off_dev = self._upload(self.off)
+            self.len_dev = self._upload(self.len)
+            self.len_next = torch.empty_like(self.len_dev)
+            n = self.n_active
             if self.out is None or self.out.shape[0] != n:
-                self.out = torch.empty((n, self.w.n_heads, self.w.head_dim), dtype=odt, device=self.dev)
+                self.out = torch.empty((n, self.w.n_heads, self.w.head_dim), dtype=_TORCH_DT[self.out_dtype],
+                                       device=self.dev)
             self._dirty = False
+
+    def _set_batch(self, recs):
+        self.serial = np.array([r[0] for r in recs], np.int64)
+        self.slot = np.array([r[1] for r in recs], np.int32)
+        self.off = np.array([r[2] for r in recs], np.int64)
+        self.cap = np.array([r[3] for r in recs], np.int32)
+        self.len = np.array([r[4] for r in recs], np.int32)
+        self.total = np.array([r[5] for r in recs], np.int32)
+        self._dirty = True
 
     # -- admission --------------------------------------------------------
     def admit(self, seqs, prefill):
         """Reserve slots for `seqs` in order (one s3_kv_alloc call) and write their cached rows.
         prefill(serial, layer, rows) -> (k_rows, v_rows) device tensors [rows][H][D].
-        Returns the Active records of the admitted ones."""
+        Returns (serial, slot, off, cap, len, total) of the admitted ones."""
         preds = [s.predicted for s in seqs]
         rc, ids, offs, caps = s3.s3_kv_alloc(self.arena, preds)
         s3.check(rc, "s3_kv_alloc")
@@ -108,102 +133,114 @@ class DecodeEngine:
                 s3.check(s3.s3_kv_fill(self.arena, sid, layer, 0, rows, k_rows, v_rows, self._stream_ptr()),
                          "s3_kv_fill")
             self._log("fill", serial, sid, rows)
-            admitted.append(Active(serial, s, sid, off, cap, rows))
+            admitted.append((serial, sid, off, cap, rows, s.total))
         return admitted
 
     def start(self, prefill, stop_when_full=False):
+        recs = []
         if stop_when_full:  # admit candidates one by one until the arena refuses one
             for s in self.w.seqs:
                 got = self.admit([s], prefill)
                 if not got:
                     break
-                self.active += got
+                recs += got
         else:
-            self.active = self.admit(self.w.seqs, prefill)
-        self._dirty = True
+            recs = self.admit(self.w.seqs, prefill)
+        self._set_batch(recs)
 
     # -- one decode step --------------------------------------------------
     def grow_full_slots(self):
-        for a in self.active:
-            if a.len == a.cap:
-                st, off, cap = s3.s3_kv_grow(self.arena, a.slot, a.len, self._stream_ptr())
-                self._log("grow", a.serial, a.slot, a.len, st, off, cap)
-                if st == s3.S3_OK:
-                    a.off, a.cap = off, cap
-                    self._dirty = True
-                elif st in (s3.S3_ERR_NOMEM, s3.S3_ERR_MAXLEN):
-                    a.len = -1  # cannot continue on the device: dropped (the paper evicts to the host)
-                else:
-                    s3.check(st, "s3_kv_grow")
-        if any(a.len < 0 for a in self.active):
-            for a in self.active:
-                if a.len < 0:
-                    s3.check(s3.s3_kv_free(self.arena, a.slot), "s3_kv_free")
-                    self._log("free", a.serial, a.slot)
-                    self.n_evicted += 1
-            self.active = [a for a in self.active if a.len >= 0]
-            self._dirty = True
+        full = np.nonzero(self.len == self.cap)[0]
+        if full.size == 0:
+            return
+        drop = []
+        for i in full.tolist():
+            st, off, cap = s3.s3_kv_grow(self.arena, int(self.slot[i]), int(self.len[i]), self._stream_ptr())
+            self._log("grow", int(self.serial[i]), int(self.slot[i]), int(self.len[i]), st, off, cap)
+            if st == s3.S3_OK:
+                self.off[i], self.cap[i] = off, cap
+                self.n_grown += 1
+            elif st in (s3.S3_ERR_NOMEM, s3.S3_ERR_MAXLEN):
+                drop.append(i)  # cannot continue on the device (the paper evicts such a sequence to the host)
+            else:
+                s3.check(st, "s3_kv_grow")
+        for i in drop:
+            s3.check(s3.s3_kv_free(self.arena, int(self.slot[i])), "s3_kv_free")
+            self._log("free", int(self.serial[i]), int(self.slot[i]))
+            self.n_evicted += 1
+        if drop:
+            keep = np.ones(self.n_active, bool)
+            keep[drop] = False
+            self._keep(keep)
+        self._dirty = True
+
+    def _keep(self, mask):
+        for name in ("serial", "slot", "off", "cap", "len", "total"):
+            setattr(self, name, getattr(self, name)[mask])
+        self._dirty = True
 
     def launch_step(self, tensors, check_host=False):
         """append + attention for every layer on the current batch.  tensors(layer, n) ->
         (q, k_new, v_new) device tensors.  Returns the output tensor of the LAST layer."""
         self._sync_arrays()
-        n = len(self.active)
+        n = self.n_active
         if n == 0:
             return None
         st = self._stream_ptr()
-        ids = [a.slot for a in self.active] if check_host else None
-        pos = [a.len for a in self.active] if check_host else None
+        ids = self.slot if check_host else None
+        pos = self.len if check_host else None
+        torch.add(self.len_dev, 1, out=self.len_next)
         for layer in range(self.w.n_layers):
             q, k_new, v_new = tensors(layer, n)
             s3.check(s3.s3_kv_append(self.arena, layer, n, self.slot_off_dev, self.len_dev, k_new, v_new, st,
                                      slot_id=ids, pos_host=pos), "s3_kv_append")
-            if layer == 0:
-                self.len_plus1 = self.len_dev + 1
-            s3.check(s3.s3_decode_attention(self.arena, layer, n, q, self.slot_off_dev, self.len_plus1, self.out,
+            s3.check(s3.s3_decode_attention(self.arena, layer, n, q, self.slot_off_dev, self.len_next, self.out,
                                             self.out_dtype, 0.0, st), "s3_decode_attention")
-        self.len_dev = self.len_plus1
-        for a in self.active:
-            a.len += 1
+        self.len_dev, self.len_next = self.len_next, self.len_dev
+        self.len += 1
         return self.out
 
     def retire_and_refill(self, prefill):
-        done = [i for i, a in enumerate(self.active) if a.len >= a.seq.total]
-        if not done:
+        done = np.nonzero(self.len >= self.total)[0]
+        if done.size == 0:
             return
-        for i in done:
-            a = self.active[i]
-            s3.check(s3.s3_kv_free(self.arena, a.slot), "s3_kv_free")
-            self._log("free", a.serial, a.slot)
-            self.active[i] = None
+        keep = np.ones(self.n_active, bool)
+        for i in done.tolist():
+            s3.check(s3.s3_kv_free(self.arena, int(self.slot[i])), "s3_kv_free")
+            self._log("free", int(self.serial[i]), int(self.slot[i]))
+            self.n_retired += 1
+            keep[i] = False
         if self.w.refill:
-            for i in done:
+            for i in done.tolist():
                 if self.pool_pos >= len(self.w.pool):
                     break
                 got = self.admit([self.w.pool[self.pool_pos]], prefill)
                 self.pool_pos += 1
                 if got:
-                    self.active[i] = got[0]
-        self.active = [a for a in self.active if a is not None]
-        self._dirty = True
+                    (self.serial[i], self.slot[i], self.off[i], self.cap[i], self.len[i], self.total[i]) = got[0]
+                    keep[i] = True
+        self._keep(keep)
 
     def step(self, tensors, prefill, check_host=False):
         self.grow_full_slots()
         out = self.launch_step(tensors, check_host)
-        self._log("step", [a.serial for a in self.active], [a.len for a in self.active])
+        self.last_step_bytes = self.algorithmic_bytes() * self.w.n_layers
+        self.last_step_seqs = self.n_active
+        if self.events is not None:
+            self._log("step", self.serial.tolist(), self.len.tolist())
         self.retire_and_refill(prefill)
         return out
 
     # -- accounting -------------------------------------------------------
     def algorithmic_bytes(self):
-        """Bytes one layer-step of the CURRENT batch must move (lengths before the append):
-        K and V rows read once, q read, out written, new k/v read and written."""
+        """Bytes one layer-step of the CURRENT batch must move, counted after the append (the
+        lengths attention sees): K and V rows read once, q read, out written, new k/v read and
+        written."""
         e = 2
         e_out = {s3.S3_F32: 4, s3.S3_F16: 2, s3.S3_BF16: 2}[self.out_dtype]
         hd = self.w.n_heads * self.w.head_dim
-        B = len(self.active)
-        sum_len = sum(a.len + 1 for a in self.active)
-        return 2 * hd * e * sum_len + B * hd * e + B * hd * e_out + 4 * B * hd * e
+        B = self.n_active
+        return 2 * hd * e * int(self.len.sum()) + B * hd * e + B * hd * e_out + 4 * B * hd * e
 
     def read_slot(self, a, layer, which, n_rows=None):
         n_rows = a.len if n_rows is None else n_rows
