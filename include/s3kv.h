@@ -126,9 +126,20 @@ int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, 
  *   out       DEVICE [n][H][D] of out_dtype (S3_F32, S3_F16 or S3_BF16), 16-byte aligned
  *   scale     <= 0 means 1/sqrt(D)
  * May grow the library's scratch buffer with hipMalloc (which synchronises) the first time a
- * larger batch is seen; n <= 16383. */
+ * larger batch is seen; n <= 4095. */
 int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
                         const int32_t *cur_len, void *out, int32_t out_dtype, float scale, void *stream);
+
+/* One layer-step in ONE kernel launch: exactly s3_kv_append(pos) followed by s3_decode_attention over
+ * cur_len[b] = pos[b] + 1 rows (the new token attends to itself as well; section 2.1), same results,
+ * same host-side checks (slot_id / pos_host as in s3_kv_append), same treatment of bad device entries.
+ * The wave that owns the new row takes it from k_new / v_new and writes it into the arena; the
+ * workgroup that delivers the last chunk of a context merges the chunks, so no second kernel runs.
+ *   len_out   DEVICE [n] int32 or NULL: receives pos[b] + 1, the positions of the next step; must not
+ *             be the same array as pos (S3_ERR_INVALID) - alternate between two arrays. */
+int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
+                   const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
+                   const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out, void *stream);
 
 /* A sequence used up its reservation and is not finished: double it (section 3, supervisor
  * paragraph).  new capacity = min(2*cap, M); the new slot is placed first-fit while the old one is
@@ -154,10 +165,14 @@ int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t first_row, i
 int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,
                     int32_t n_rows, void *dst, void *stream);
 
-/* Launch-shape knobs of the attention kernels, for measurement sweeps.  name is one of
+/* Launch-shape knobs of the attention kernels and measurement switches.  set names:
  *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default)
  *   "grid_blocks"  workgroups launched (0 = library default)
- *   "variant"      kernel variant index (see s3_kv_get_param "n_variants")
+ *   "variant"      kernel variant index, -1 = default (see get "n_variants")
+ *   "profile"      1: bracket every attention launch with HIP events on its stream; 0: off + reset
+ * get names: the above plus "n_variants", "n_grows", "live_slots", "scratch_bytes", "num_cus" and,
+ * after "profile" 1, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
+ * launches since the last reset; reading them waits for the recorded events).
  * Returns S3_ERR_INVALID for an unknown name or a value out of range. */
 int s3_kv_set_param(s3_arena *a, const char *name /*HOST*/, int64_t value);
 int s3_kv_get_param(const s3_arena *a, const char *name /*HOST*/, int64_t *value /*HOST*/);

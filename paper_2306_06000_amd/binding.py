@@ -36,6 +36,7 @@ SIGNATURES = {
     "s3_kv_slot_info": (ctypes.c_int, [_vp, _i32, _pi64, _pi32]),
     "s3_kv_append": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp]),
     "s3_decode_attention": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _f32, _vp]),
+    "s3_decode_step": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]),
     "s3_kv_grow": (ctypes.c_int, [_vp, _i32, _i32, _pi64, _pi32, _vp]),
     "s3_kv_stats": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64]),
     "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
@@ -140,6 +141,14 @@ def s3_kv_append(arena, layer, n, slot_off, pos, k_new, v_new, stream=0, slot_id
 def s3_decode_attention(arena, layer, n, q, slot_off, cur_len, out, out_dtype=S3_F32, scale=0.0, stream=0):
     return lib().s3_decode_attention(arena, int(layer), int(n), _ptr(q), _ptr(slot_off), _ptr(cur_len), _ptr(out),
                                      int(out_dtype), float(scale), stream or None)
+
+
+def s3_decode_step(arena, layer, n, slot_off, pos, q, k_new, v_new, out, out_dtype=S3_F32, scale=0.0, len_out=None,
+                   stream=0, slot_id=None, pos_host=None):
+    _a, idp = _host_i32(slot_id)
+    _b, php = _host_i32(pos_host)
+    return lib().s3_decode_step(arena, int(layer), int(n), idp, php, _ptr(slot_off), _ptr(pos), _ptr(q), _ptr(k_new),
+                                _ptr(v_new), _ptr(out), int(out_dtype), float(scale), _ptr(len_out), stream or None)
 
 
 def s3_kv_grow(arena, slot_id, length, stream=0):

@@ -95,24 +95,31 @@ __global__ void __launch_bounds__(256) append_kernel(char *kplane, char *vplane,
 // attention
 // ------------------------------------------------------------------------------------------
 struct AttnArgs {
-    const char *kplane;
-    const char *vplane;
+    char *kplane;
+    char *vplane;
     const char *q;
     const int64_t *slot_off;
-    const int32_t *cur_len;
+    const int32_t *cur_len;  // rows to attend minus len_add
     void *out;
     float *part_acc;   // [n][max_chunks][H][D]
     float2 *part_ml;   // [n][max_chunks][H]  (running max in log2 units, sum)
     int64_t n_tokens;  // arena capacity N
     int32_t n, H, chunk, max_chunks, out_dtype, max_len;
+    int32_t len_add;    // 0: cur_len is the context length; 1 (fused step): cur_len is the append position
     float scale_log2e;  // scale * log2(e): scores are kept in log2 units so that exp is v_exp_f32
+    // fused step only
+    const char *k_new;
+    const char *v_new;
+    int32_t *len_out;        // may be null
+    unsigned int *arrivals;  // [n][n_hgb] chunk-arrival counters, zero between launches
 };
 
 __device__ __forceinline__ int checked_len(const AttnArgs &a, int b) {
     const int64_t off = a.slot_off[b];
-    const int32_t len = a.cur_len[b];
-    const bool ok = off >= 0 && len >= 0 && len <= a.max_len && off + (int64_t)len <= a.n_tokens;
-    return ok ? len : 0;
+    const int32_t raw = a.cur_len[b];
+    const int64_t len = (int64_t)raw + a.len_add;
+    const bool ok = off >= 0 && raw >= 0 && len <= a.max_len && off + len <= a.n_tokens;
+    return ok ? (int)len : 0;
 }
 
 template <int CTRL>
@@ -236,15 +243,49 @@ __device__ __forceinline__ void scan_chunks(const AttnArgs &a, int *cum, int *wa
     __syncthreads();
 }
 
+// Merge the chunk partials of (sequence b, head h) for this lane's 8-element slice and store the
+// final output row slice.  nchunks >= 2.
+template <int D>
+__device__ __forceinline__ void merge_chunks(const AttnArgs &a, int b, int h, int dl, int nchunks) {
+    const int64_t p0 = ((int64_t)b * a.max_chunks) * a.H + h;
+    float mm = -INFINITY;
+    for (int c = 0; c < nchunks; c++) mm = fmaxf(mm, a.part_ml[p0 + (int64_t)c * a.H].x);
+    float l = 0.f;
+    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    for (int c = 0; c < nchunks; c++) {
+        const int64_t pi = p0 + (int64_t)c * a.H;
+        const float2 ml = a.part_ml[pi];
+        const float wgt = fast_exp2(ml.x - mm);
+        l += wgt * ml.y;
+        const f32x4 *pa = (const f32x4 *)(a.part_acc + pi * D + dl * 8);
+        const f32x4 x = pa[0], y = pa[1];
+#pragma unroll
+        for (int i = 0; i < 4; i++) {
+            o[i] += wgt * x[i];
+            o[4 + i] += wgt * y[i];
+        }
+    }
+    const float inv = 1.f / l;
+#pragma unroll
+    for (int i = 0; i < 8; i++) o[i] *= inv;
+    store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, o);
+}
+
 // DT: element type of q/K/V.  D: head_dim.  TS: waves splitting a chunk's tokens.  HS: head groups
 // per workgroup.  U: tokens per load batch.  NT: non-temporal loads of K/V.
-template <int DT, int D, int TS, int HS, int U, bool NT>
+// FUSED: one launch does the whole layer-step: the token at row cur_len[b] (the append position) is
+// taken from k_new/v_new instead of the arena and written into the arena by the wave that owns it,
+// attention runs over cur_len[b]+1 rows, the workgroup that delivers the last chunk of a (sequence,
+// head block) merges the chunks (arrival counter), empty contexts get their zero row, and
+// len_out[b] = cur_len[b]+1 is published for the next step.
+template <int DT, int D, int TS, int HS, int U, bool NT, bool FUSED>
 __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArgs a) {
     constexpr int LPH = D / 8;    // lanes per head
     constexpr int GH = 64 / LPH;  // heads per wave
     constexpr int NW = TS * HS;
     extern __shared__ int cum[];  // [n + 1]
     __shared__ int wave_sums[NW];
+    __shared__ int last_flag;
     __shared__ float comb[TS > 1 ? NW : 1][10][64];
 
     scan_chunks(a, cum, wave_sums);
@@ -257,6 +298,18 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
     const int64_t total = (int64_t)cum[a.n] * n_hgb;
     const int64_t rstride = (int64_t)a.H * D * 2;
     const int tok_per_wave = a.chunk / TS;
+
+    if (FUSED && blockIdx.x == 0) {
+        for (int b = threadIdx.x; b < a.n; b += NW * 64) {
+            if (a.len_out) a.len_out[b] = a.cur_len[b] + 1;
+            if (cum[b + 1] == cum[b]) {  // empty or refused context: zero output row
+                for (int e = 0; e < a.H * D; e += 8) {
+                    const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                    store_out8(a.out, a.out_dtype, (int64_t)b * a.H * D + e, z);
+                }
+            }
+        }
+    }
 
     for (int64_t item = blockIdx.x; item < total; item += gridDim.x) {
         const int w = (int)(item / n_hgb);
@@ -280,16 +333,28 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
         const int64_t lane_byte = ((int64_t)hc * D + dl * 8) * 2;
         const char *kp = a.kplane + off * rstride + lane_byte;
         const char *vp = a.vplane + off * rstride + lane_byte;
-        const u32x4 qv = *(const u32x4 *)(a.q + ((int64_t)b * a.H * D) * 2 + lane_byte);
+        const int64_t in_byte = ((int64_t)b * a.H * D) * 2 + lane_byte;  // this lane's slice of row b of q/k_new/v_new
+        const u32x4 qv = *(const u32x4 *)(a.q + in_byte);
+        const int jnew = FUSED ? len - 1 : -1;  // the row that is still only in k_new / v_new
 
         float m = -INFINITY, l = 0.f;
         float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
         for (int j = j0; j < j1; j += U) {
             u32x4 kk[U], vv[U];
 #pragma unroll
-            for (int u = 0; u < U; u++) kk[u] = load16<NT>(kp + (int64_t)min(j + u, j1 - 1) * rstride);
+            for (int u = 0; u < U; u++) {
+                const int jj = min(j + u, j1 - 1);
+                const char *src = kp + (int64_t)jj * rstride;
+                if (FUSED) src = (jj == jnew) ? a.k_new + in_byte : src;
+                kk[u] = load16<NT>(src);
+            }
 #pragma unroll
-            for (int u = 0; u < U; u++) vv[u] = load16<NT>(vp + (int64_t)min(j + u, j1 - 1) * rstride);
+            for (int u = 0; u < U; u++) {
+                const int jj = min(j + u, j1 - 1);
+                const char *src = vp + (int64_t)jj * rstride;
+                if (FUSED) src = (jj == jnew) ? a.v_new + in_byte : src;
+                vv[u] = load16<NT>(src);
+            }
             float s[U];
 #pragma unroll
             for (int u = 0; u < U; u++) s[u] = dot8<DT>(qv, kk[u]);
@@ -313,6 +378,10 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
                 axpy8<DT>(acc, p, vv[u]);
             }
             m = mn;
+        }
+        if (FUSED && h_ok && j0 <= jnew && jnew < j1) {  // the append: this wave owns the new row's slice
+            *(u32x4 *)(a.kplane + (off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.k_new + in_byte);
+            *(u32x4 *)(a.vplane + (off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.v_new + in_byte);
         }
 
         if (TS > 1) {  // merge the TS token splits of this head group through LDS
@@ -352,7 +421,23 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
                 pa[1] = (f32x4){acc[4], acc[5], acc[6], acc[7]};
             }
         }
-        if (TS > 1) __syncthreads();  // comb is reused by the next item
+        if (FUSED && nchunks > 1) {  // uniform over the workgroup: b is
+            __threadfence();         // this wave's partials are visible device-wide ...
+            __syncthreads();         // ... before thread 0 announces the chunk
+            if (threadIdx.x == 0) {
+                unsigned int *cnt = a.arrivals + (int64_t)b * n_hgb + hgb;
+                const unsigned int old = atomicAdd(cnt, 1u);
+                const int last = old == (unsigned int)(nchunks - 1);
+                if (last) atomicExch(cnt, 0u);  // every chunk has arrived: leave the counter clean
+                last_flag = last;
+            }
+            __syncthreads();
+            if (last_flag) {
+                __threadfence();  // see the other workgroups' partials
+                if (ts == 0 && h_ok) merge_chunks<D>(a, b, h, dl, nchunks);
+            }
+        }
+        if (TS > 1 || FUSED) __syncthreads();  // comb / last_flag are reused by the next item
     }
 }
 
@@ -371,30 +456,12 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     if (h >= a.H) return;
     const int nchunks = (checked_len(a, b) + a.chunk - 1) / a.chunk;
     if (nchunks == 1) return;
-    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     if (nchunks > 1) {
-        const int64_t p0 = ((int64_t)b * a.max_chunks) * a.H + h;
-        float mm = -INFINITY;
-        for (int c = 0; c < nchunks; c++) mm = fmaxf(mm, a.part_ml[p0 + (int64_t)c * a.H].x);
-        float l = 0.f;
-        for (int c = 0; c < nchunks; c++) {
-            const int64_t pi = p0 + (int64_t)c * a.H;
-            const float2 ml = a.part_ml[pi];
-            const float wgt = fast_exp2(ml.x - mm);
-            l += wgt * ml.y;
-            const f32x4 *pa = (const f32x4 *)(a.part_acc + pi * D + dl * 8);
-            const f32x4 x = pa[0], y = pa[1];
-#pragma unroll
-            for (int i = 0; i < 4; i++) {
-                o[i] += wgt * x[i];
-                o[4 + i] += wgt * y[i];
-            }
-        }
-        const float inv = 1.f / l;
-#pragma unroll
-        for (int i = 0; i < 8; i++) o[i] *= inv;
+        merge_chunks<D>(a, b, h, dl, nchunks);
+        return;
     }
-    store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, o);
+    const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, z);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -421,34 +488,35 @@ int s3i_num_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0]));
 
 typedef void (*attn_fn)(const AttnArgs);
 
-template <int DT, int D>
+template <int DT, int D, bool FUSED>
 static attn_fn pick_variant(int v) {
     switch (v) {
-        case 0: return attn_partial_kernel<DT, D, 4, 1, 4, true>;
-        case 1: return attn_partial_kernel<DT, D, 8, 1, 4, true>;
-        case 2: return attn_partial_kernel<DT, D, 4, 2, 4, true>;
-        case 3: return attn_partial_kernel<DT, D, 1, 4, 4, true>;
-        case 4: return attn_partial_kernel<DT, D, 8, 1, 8, true>;
-        case 5: return attn_partial_kernel<DT, D, 16, 1, 4, true>;
-        case 6: return attn_partial_kernel<DT, D, 2, 8, 4, true>;
-        case 7: return attn_partial_kernel<DT, D, 4, 1, 2, true>;
-        case 8: return attn_partial_kernel<DT, D, 4, 1, 4, false>;
-        case 9: return attn_partial_kernel<DT, D, 8, 1, 4, false>;
-        case 10: return attn_partial_kernel<DT, D, 4, 1, 8, true>;
-        case 11: return attn_partial_kernel<DT, D, 2, 2, 4, true>;
+        case 0: return attn_partial_kernel<DT, D, 4, 1, 4, true, FUSED>;
+        case 1: return attn_partial_kernel<DT, D, 8, 1, 4, true, FUSED>;
+        case 2: return attn_partial_kernel<DT, D, 4, 2, 4, true, FUSED>;
+        case 3: return attn_partial_kernel<DT, D, 1, 4, 4, true, FUSED>;
+        case 4: return attn_partial_kernel<DT, D, 8, 1, 8, true, FUSED>;
+        case 5: return attn_partial_kernel<DT, D, 16, 1, 4, true, FUSED>;
+        case 6: return attn_partial_kernel<DT, D, 2, 8, 4, true, FUSED>;
+        case 7: return attn_partial_kernel<DT, D, 4, 1, 2, true, FUSED>;
+        case 8: return attn_partial_kernel<DT, D, 4, 1, 4, false, FUSED>;
+        case 9: return attn_partial_kernel<DT, D, 8, 1, 4, false, FUSED>;
+        case 10: return attn_partial_kernel<DT, D, 4, 1, 8, true, FUSED>;
+        case 11: return attn_partial_kernel<DT, D, 2, 2, 4, true, FUSED>;
         default: return nullptr;
     }
 }
 
+template <bool FUSED>
 static attn_fn pick_kernel(int dt, int d, int v) {
     if (dt == S3_F16) {
-        if (d == 64) return pick_variant<S3_F16, 64>(v);
-        if (d == 128) return pick_variant<S3_F16, 128>(v);
-        if (d == 256) return pick_variant<S3_F16, 256>(v);
+        if (d == 64) return pick_variant<S3_F16, 64, FUSED>(v);
+        if (d == 128) return pick_variant<S3_F16, 128, FUSED>(v);
+        if (d == 256) return pick_variant<S3_F16, 256, FUSED>(v);
     } else if (dt == S3_BF16) {
-        if (d == 64) return pick_variant<S3_BF16, 64>(v);
-        if (d == 128) return pick_variant<S3_BF16, 128>(v);
-        if (d == 256) return pick_variant<S3_BF16, 256>(v);
+        if (d == 64) return pick_variant<S3_BF16, 64, FUSED>(v);
+        if (d == 128) return pick_variant<S3_BF16, 128, FUSED>(v);
+        if (d == 256) return pick_variant<S3_BF16, 256, FUSED>(v);
     }
     return nullptr;
 }
@@ -463,6 +531,7 @@ static int ensure_scratch(s3_arena *a, size_t need) {
     }
     HIP_TRY(hipMalloc(&a->scratch, need));
     a->scratch_bytes = need;
+    HIP_TRY(hipMemset(a->scratch, 0, need));  // the arrival counters at its head must start at zero
     return S3_OK;
 }
 
@@ -513,6 +582,7 @@ extern "C" void s3_kv_arena_destroy(s3_arena *a) {
 }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+static int check_slots_host(const s3_arena *a, int32_t n, const int32_t *slot_id, const int32_t *pos_host);
 
 extern "C" int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
                             const int64_t *slot_off, const int32_t *pos, const void *k_new, const void *v_new,
@@ -520,15 +590,8 @@ extern "C" int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t
     if (!a || !a->base || layer < 0 || layer >= a->cfg.n_layers || n < 0) return S3_ERR_INVALID;
     if (n == 0) return S3_OK;
     if (!slot_off || !pos || !k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return S3_ERR_INVALID;
-    if (slot_id && pos_host) {
-        bool full = false;
-        for (int32_t b = 0; b < n; b++) {
-            const s3_slot *s = s3i_live_slot(a, slot_id[b]);
-            if (!s || pos_host[b] < 0 || pos_host[b] > s->cap) return S3_ERR_INVALID;
-            if (pos_host[b] == s->cap) full = true;
-        }
-        if (full) return S3_ERR_SLOT_FULL;
-    }
+    const int rc = check_slots_host(a, n, slot_id, pos_host);
+    if (rc != S3_OK) return rc;
     hipLaunchKernelGGL(append_kernel, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
                        a->plane(layer, 1), slot_off, pos, (const char *)k_new, (const char *)v_new, a->row_bytes,
                        a->n_tokens, a->cfg.max_len);
@@ -536,26 +599,38 @@ extern "C" int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t
     return S3_OK;
 }
 
-extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
-                                   const int32_t *cur_len, void *out, int32_t out_dtype, float scale, void *stream) {
-    if (!a || !a->base || layer < 0 || layer >= a->cfg.n_layers || n < 0 || n > S3_MAX_BATCH) return S3_ERR_INVALID;
-    if (n == 0) return S3_OK;
-    if (!q || !slot_off || !cur_len || !out || !aligned16(q) || !aligned16(out)) return S3_ERR_INVALID;
-    if (out_dtype != S3_F32 && out_dtype != S3_F16 && out_dtype != S3_BF16) return S3_ERR_INVALID;
+static int check_slots_host(const s3_arena *a, int32_t n, const int32_t *slot_id, const int32_t *pos_host) {
+    if (!slot_id || !pos_host) return S3_OK;  // the caller vouches for the positions
+    bool full = false;
+    for (int32_t b = 0; b < n; b++) {
+        const s3_slot *s = s3i_live_slot(a, slot_id[b]);
+        if (!s || pos_host[b] < 0 || pos_host[b] > s->cap) return S3_ERR_INVALID;
+        if (pos_host[b] == s->cap) full = true;
+    }
+    return full ? S3_ERR_SLOT_FULL : S3_OK;
+}
+
+// Shared by s3_decode_attention (fused = false: partial kernel + merge kernel) and s3_decode_step
+// (fused = true: one kernel that also appends, merges and publishes the new lengths).
+static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
+                            const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
+                            bool fused, const void *k_new, const void *v_new, int32_t *len_out) {
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     const int variant = a->variant >= 0 ? a->variant : 1;
     const Variant &vr = kVariants[variant];
-    int chunk = a->chunk > 0 ? a->chunk : 128;
+    const int chunk = a->chunk > 0 ? a->chunk : 128;
     if (chunk % vr.ts) return S3_ERR_INVALID;
-    attn_fn fn = pick_kernel(a->cfg.kv_dtype, D, variant);
+    attn_fn fn = fused ? pick_kernel<true>(a->cfg.kv_dtype, D, variant) : pick_kernel<false>(a->cfg.kv_dtype, D, variant);
     if (!fn) return S3_ERR_INVALID;
+    const int GH = 512 / D;
+    const int n_hg = (H + GH - 1) / GH;
 
     AttnArgs args;
     args.kplane = a->plane(layer, 0);
     args.vplane = a->plane(layer, 1);
     args.q = (const char *)q;
     args.slot_off = slot_off;
-    args.cur_len = cur_len;
+    args.cur_len = len_or_pos;
     args.out = out;
     args.n_tokens = a->n_tokens;
     args.n = n;
@@ -564,20 +639,27 @@ extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const 
     args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
     args.out_dtype = out_dtype;
     args.max_len = a->cfg.max_len;
+    args.len_add = fused ? 1 : 0;
     if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
     args.scale_log2e = scale * 1.4426950408889634f;
+    args.k_new = (const char *)k_new;
+    args.v_new = (const char *)v_new;
+    args.len_out = len_out;
 
+    // scratch: [arrival counters, fixed size][partial sums][partial (max, sum)]
+    const size_t cnt_bytes = (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;
     const size_t n_part = (size_t)n * args.max_chunks * H;
     const size_t acc_bytes = n_part * D * sizeof(float);
-    const size_t need = acc_bytes + n_part * sizeof(float2);
+    const size_t need = cnt_bytes + acc_bytes + n_part * sizeof(float2);
     const int rc = ensure_scratch(a, need);
     if (rc != S3_OK) return rc;
-    args.part_acc = (float *)a->scratch;
-    args.part_ml = (float2 *)((char *)a->scratch + acc_bytes);
+    args.arrivals = (unsigned int *)a->scratch;
+    args.part_acc = (float *)((char *)a->scratch + cnt_bytes);
+    args.part_ml = (float2 *)((char *)a->scratch + cnt_bytes + acc_bytes);
 
     const int nw = vr.ts * vr.hs;
     const int cus = a->num_cus > 0 ? a->num_cus : 256;
-    int blocks = a->grid_blocks > 0 ? a->grid_blocks : cus * (32 / nw);
+    const int blocks = a->grid_blocks > 0 ? a->grid_blocks : cus * (32 / nw);
     const size_t dyn_lds = (size_t)(n + 1) * sizeof(int);
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     if (a->profile) {
@@ -590,15 +672,40 @@ extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const 
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)(nw * 64)), dyn_lds, (hipStream_t)stream, args);
     HIP_TRY(hipGetLastError());
     if (a->profile) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
-
-    const int GH = 512 / D;
-    const int n_hg = (H + GH - 1) / GH;
-    const unsigned mblocks = (unsigned)(((int64_t)n * n_hg + 3) / 4);
-    void (*mfn)(const AttnArgs) = D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
-    hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, args);
-    HIP_TRY(hipGetLastError());
+    if (!fused) {
+        const unsigned mblocks = (unsigned)(((int64_t)n * n_hg + 3) / 4);
+        void (*mfn)(const AttnArgs) =
+            D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
+        hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, args);
+        HIP_TRY(hipGetLastError());
+    }
     if (a->profile) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
     return S3_OK;
+}
+
+extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
+                                   const int32_t *cur_len, void *out, int32_t out_dtype, float scale, void *stream) {
+    if (!a || !a->base || layer < 0 || layer >= a->cfg.n_layers || n < 0 || n > S3_MAX_BATCH) return S3_ERR_INVALID;
+    if (n == 0) return S3_OK;
+    if (!q || !slot_off || !cur_len || !out || !aligned16(q) || !aligned16(out)) return S3_ERR_INVALID;
+    if (out_dtype != S3_F32 && out_dtype != S3_F16 && out_dtype != S3_BF16) return S3_ERR_INVALID;
+    return launch_attention(a, layer, n, q, slot_off, cur_len, out, out_dtype, scale, stream, false, nullptr, nullptr,
+                            nullptr);
+}
+
+extern "C" int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
+                              const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
+                              const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out,
+                              void *stream) {
+    if (!a || !a->base || layer < 0 || layer >= a->cfg.n_layers || n < 0 || n > S3_MAX_BATCH) return S3_ERR_INVALID;
+    if (n == 0) return S3_OK;
+    if (!q || !k_new || !v_new || !slot_off || !pos || !out) return S3_ERR_INVALID;
+    if (!aligned16(q) || !aligned16(k_new) || !aligned16(v_new) || !aligned16(out)) return S3_ERR_INVALID;
+    if (len_out == pos) return S3_ERR_INVALID;  // other workgroups still read pos while len_out is written
+    if (out_dtype != S3_F32 && out_dtype != S3_F16 && out_dtype != S3_BF16) return S3_ERR_INVALID;
+    const int rc = check_slots_host(a, n, slot_id, pos_host);
+    if (rc != S3_OK) return rc;
+    return launch_attention(a, layer, n, q, slot_off, pos, out, out_dtype, scale, stream, true, k_new, v_new, len_out);
 }
 
 extern "C" int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t first_row, int32_t n_rows,

@@ -23,8 +23,9 @@ _TORCH_DT = {s3.S3_F16: torch.float16, s3.S3_BF16: torch.bfloat16, s3.S3_F32: to
 
 
 class DecodeEngine:
-    def __init__(self, w, arena_tokens=None, device="cuda:0", out_dtype=s3.S3_F32, log_events=True):
+    def __init__(self, w, arena_tokens=None, device="cuda:0", out_dtype=s3.S3_F32, log_events=True, fused=True):
         self.w = w
+        self.fused = fused  # True: one s3_decode_step launch per layer; False: append + attention calls
         self.dev = torch.device(device)
         self.cfg = s3.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len)
         self.bpt = s3.s3_kv_bytes_per_token(self.cfg)
@@ -189,13 +190,19 @@ class DecodeEngine:
         st = self._stream_ptr()
         ids = self.slot if check_host else None
         pos = self.len if check_host else None
-        torch.add(self.len_dev, 1, out=self.len_next)
+        if not self.fused:
+            torch.add(self.len_dev, 1, out=self.len_next)
         for layer in range(self.w.n_layers):
             q, k_new, v_new = tensors(layer, n)
-            s3.check(s3.s3_kv_append(self.arena, layer, n, self.slot_off_dev, self.len_dev, k_new, v_new, st,
-                                     slot_id=ids, pos_host=pos), "s3_kv_append")
-            s3.check(s3.s3_decode_attention(self.arena, layer, n, q, self.slot_off_dev, self.len_next, self.out,
-                                            self.out_dtype, 0.0, st), "s3_decode_attention")
+            if self.fused:
+                s3.check(s3.s3_decode_step(self.arena, layer, n, self.slot_off_dev, self.len_dev, q, k_new, v_new,
+                                           self.out, self.out_dtype, 0.0, self.len_next, st, slot_id=ids,
+                                           pos_host=pos), "s3_decode_step")
+            else:
+                s3.check(s3.s3_kv_append(self.arena, layer, n, self.slot_off_dev, self.len_dev, k_new, v_new, st,
+                                         slot_id=ids, pos_host=pos), "s3_kv_append")
+                s3.check(s3.s3_decode_attention(self.arena, layer, n, q, self.slot_off_dev, self.len_next, self.out,
+                                                self.out_dtype, 0.0, st), "s3_decode_attention")
         self.len_dev, self.len_next = self.len_next, self.len_dev
         self.len += 1
         return self.out

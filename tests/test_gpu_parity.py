@@ -83,11 +83,12 @@ def n_variants(a):
 
 
 # ---------------------------------------------------------------- C0, the whole config
-def test_c0_one_append_and_attention_step():
+@pytest.mark.parametrize("fused", [True, False])
+def test_c0_one_append_and_attention_step(fused):
     from paper_2306_06000_amd.engine import DecodeEngine
 
     w = wl.c0()
-    eng = DecodeEngine(w, arena_tokens=512)
+    eng = DecodeEngine(w, arena_tokens=512, fused=fused)
     prefill, tensors_for = make_sources(w, eng)
     eng.start(prefill)
     assert [a.cap for a in eng.active] == [64, 64, 128, 128] and [a.off for a in eng.active] == [0, 64, 128, 256]
@@ -324,11 +325,75 @@ def test_grow_moves_rows_bit_exactly_and_leaves_other_slots_alone():
     rig.close()
 
 
+def test_fused_step_equals_append_then_attention_bit_for_bit():
+    """s3_decode_step is defined as s3_kv_append + s3_decode_attention over pos+1 rows: same output
+    bits, same arena rows, len_out = pos + 1; for every variant and a few chunk sizes."""
+    pos = [0, 1, 30, 31, 63, 64, 127, 128, 255, 256, 700, 1023, 5, 64]
+    caps = [p + 1 for p in pos]
+    H, D, dt = 16, 256, s3.S3_F16
+    n = len(pos)
+    rigs = [Rig(1, H, D, dt, 64, 1024, caps, seed=21) for _ in range(2)]  # same seed: same contents
+    for r in rigs:
+        r.fill(pos)
+    rng = np.random.default_rng(22)
+    for variant in range(n_variants(rigs[0].a)):
+        for chunk in (64, 128, 512):
+            q, k, v = (device_bits(wl.normal_bits(rng, (n, H, D), dt), torch.float16, DEV) for _ in range(3))
+            outs, rows = [], []
+            for r, fused in zip(rigs, (False, True)):
+                s3.s3_kv_set_param(r.a, "variant", variant)
+                s3.s3_kv_set_param(r.a, "chunk", chunk)
+                off_d = torch.tensor(r.offs.tolist(), dtype=torch.int64, device=DEV)
+                pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+                out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+                if fused:
+                    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+                    assert s3.s3_decode_step(r.a, 0, n, off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, len_out, r.stream,
+                                             slot_id=r.ids, pos_host=pos) == 0
+                    assert len_out.cpu().tolist() == [p + 1 for p in pos]
+                    assert s3.s3_decode_step(r.a, 0, n, off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, pos_d,
+                                             r.stream) == s3.S3_ERR_INVALID  # len_out must not alias pos
+                else:
+                    assert s3.s3_kv_append(r.a, 0, n, off_d, pos_d, k, v, r.stream, slot_id=r.ids, pos_host=pos) == 0
+                    assert s3.s3_decode_attention(r.a, 0, n, q, off_d, pos_d + 1, out, s3.S3_F32, 0.0, r.stream) == 0
+                torch.cuda.synchronize()
+                outs.append(out.cpu().numpy())
+                rows.append([rig_read(r, sid, 0, w_, c) for sid, c in zip(r.ids.tolist(), caps) for w_ in (0, 1)])
+            assert np.array_equal(outs[0], outs[1]), (variant, chunk)
+            assert all(np.array_equal(x, y) for x, y in zip(rows[0], rows[1])), (variant, chunk)
+    for r in rigs:
+        r.close()
+
+
+def test_fused_step_refuses_full_slots_and_skips_bad_entries():
+    lens = [64, 10]
+    rig = Rig(1, 4, 128, s3.S3_F16, 64, 256, [64, 64], seed=23, arena_tokens=1024)
+    rig.fill(lens)
+    n = 2
+    q, k, v = (device_bits(wl.normal_bits(rig.rng, (n, 4, 128), 0), torch.float16, DEV) for _ in range(3))
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.zeros((n, 4, 128), dtype=torch.float32, device=DEV)
+    snap = rig.mem.clone()
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, None, rig.stream,
+                             slot_id=rig.ids, pos_host=lens) == s3.S3_ERR_SLOT_FULL
+    torch.cuda.synchronize()
+    assert torch.equal(snap, rig.mem)
+    # device entries that would leave the arena: zero row, nothing written, neighbours unaffected
+    bad_off = torch.tensor([rig.N - 5, int(rig.offs[1])], dtype=torch.int64, device=DEV)
+    out.fill_(float("nan"))
+    assert s3.s3_decode_step(rig.a, 0, n, bad_off, pos_d, q, k, v, out, s3.S3_F32, 0.0, None, rig.stream) == 0
+    torch.cuda.synchronize()
+    got = out.cpu().numpy()
+    assert not got[0].any() and np.isfinite(got[1]).all()
+    rig.close()
+
+
 # ---------------------------------------------------------------- traces
-def run_trace(w, steps, attend_steps, arena_tokens=None, variant=None, chunk=None, sample=None):
+def run_trace(w, steps, attend_steps, arena_tokens=None, variant=None, chunk=None, sample=None, fused=True):
     from paper_2306_06000_amd.engine import DecodeEngine
 
-    eng = DecodeEngine(w, arena_tokens=arena_tokens)
+    eng = DecodeEngine(w, arena_tokens=arena_tokens, fused=fused)
     if variant is not None:
         s3.s3_kv_set_param(eng.arena, "variant", variant)
     if chunk is not None:
@@ -361,15 +426,17 @@ def run_trace(w, steps, attend_steps, arena_tokens=None, variant=None, chunk=Non
     return stats
 
 
-def test_c1_trace_128_steps_with_grow_free_and_refill():
+@pytest.mark.parametrize("fused", [True, False])
+def test_c1_trace_128_steps_with_grow_free_and_refill(fused):
     w = wl.c1()
-    stats = run_trace(w, w.steps, attend_steps=[0, 1, 40, 127])
+    stats = run_trace(w, w.steps, attend_steps=[0, 1, 40, 127], fused=fused)
     assert stats["grows"] >= 1 and stats["frees"] >= 1 and stats["evicted"] == 0
 
 
-def test_c2_shape_shortened_trace_with_mispredictions():
+@pytest.mark.parametrize("fused", [True, False])
+def test_c2_shape_shortened_trace_with_mispredictions(fused):
     w = wl.c2(batch=192, steps=40)
-    stats = run_trace(w, w.steps, attend_steps=[0, 39], sample=48)
+    stats = run_trace(w, w.steps, attend_steps=[0, 39], sample=48, fused=fused)
     assert stats["grows"] >= 1
 
 
