@@ -34,6 +34,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time the attention kernel with events")
     ap.add_argument("--c3-bytes", type=float, default=200e9)
+    ap.add_argument("--unfused", action="store_true", help="append + attention + merge kernels instead of one")
     return ap.parse_args()
 
 
@@ -120,7 +121,7 @@ def main():
     s3.lib()
     w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4}[args.workload]() if args.workload != "c3" else wl.c3(
         target_bytes=int(args.c3_bytes))
-    eng = DecodeEngine(w, log_events=False)
+    eng = DecodeEngine(w, log_events=False, fused=not args.unfused)
     if args.variant >= 0:
         s3.check(s3.s3_kv_set_param(eng.arena, "variant", args.variant))
     if args.chunk:
@@ -144,6 +145,7 @@ def main():
         eng.step(tensors, prefill)
         total_bytes += eng.last_step_bytes
         seq_steps += eng.last_step_seqs
+    t_enqueue = time.perf_counter() - t0  # host time to enqueue every step (no device wait in it)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
 
@@ -154,6 +156,7 @@ def main():
         "dtype": "f16" if w.dtype == 0 else "bf16", "data": "synthetic",
         "pct_of_peak_hbm": round(100 * total_bytes / dt / 1e9 / PEAK_HBM_GBPS, 2),
         "seq_steps_per_s": round(seq_steps / dt, 1),
+        "host_enqueue_ms_per_step": round(t_enqueue / args.steps * 1e3, 5),
         "config": {"workload": w.name, "batch": eng.n_active, "n_layers": w.n_layers, "n_heads": w.n_heads,
                    "head_dim": w.head_dim, "mean_context": round(float(eng.len.mean()), 1),
                    "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,

@@ -160,13 +160,25 @@ int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t
 int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t first_row, int32_t n_rows,
                const void *k_rows, const void *v_rows, void *stream);
 
+/* For callers that keep slot_off[] / len[] of the running batch in device memory: rewrite n_updates
+ * entries (a grown slot's new offset, a newcomer that took a finished sequence's place) without a
+ * host-to-device copy; the values travel as kernel arguments.  Stream-ordered like everything else.
+ *   slot_off DEVICE [n] int64 or NULL, len DEVICE [n] int32 or NULL (at least one given)
+ *   idx HOST [n_updates] entries in [0, n); new_off / new_len HOST [n_updates] (needed for the array given) */
+int s3_kv_batch_patch(int32_t n, int64_t *slot_off, int32_t *len, int32_t n_updates, const int32_t *idx,
+                      const int64_t *new_off, const int32_t *new_len, void *stream);
+
 /* Copy rows [first_row, first_row+n_rows) of K (which = 0) or V (which = 1) of a live slot into
  * dst, DEVICE [n_rows][H][D] kv_dtype, 16-byte aligned.  For bit-exact checks of append / grow. */
 int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,
                     int32_t n_rows, void *dst, void *stream);
 
 /* Launch-shape knobs of the attention kernels and measurement switches.  set names:
- *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default)
+ *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default); for
+ *                  s3_decode_step the upper bound of the chunk the kernel picks itself
+ *   "chunk_min"    lower bound of that pick (multiple of 32; 0 = library default)
+ *   "target_items" > 0: s3_decode_step picks its chunk on the device so that the batch's total rows make
+ *                  about this many work items; 0 or -1 (default): use "chunk" as is
  *   "grid_blocks"  workgroups launched (0 = library default)
  *   "variant"      kernel variant index, -1 = default (see get "n_variants")
  *   "profile"      1: bracket every attention launch with HIP events on its stream; 0: off + reset

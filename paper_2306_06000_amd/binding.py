@@ -40,6 +40,7 @@ SIGNATURES = {
     "s3_kv_grow": (ctypes.c_int, [_vp, _i32, _i32, _pi64, _pi32, _vp]),
     "s3_kv_stats": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64]),
     "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
+    "s3_kv_batch_patch": (ctypes.c_int, [_i32, _vp, _vp, _i32, _pi32, _pi64, _pi32, _vp]),
     "s3_kv_read_rows": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp]),
     "s3_kv_set_param": (ctypes.c_int, [_vp, ctypes.c_char_p, _i64]),
     "s3_kv_get_param": (ctypes.c_int, [_vp, ctypes.c_char_p, _pi64]),
@@ -168,6 +169,14 @@ def s3_kv_stats(arena):
 def s3_kv_fill(arena, slot_id, layer, first_row, n_rows, k_rows, v_rows, stream=0):
     return lib().s3_kv_fill(arena, int(slot_id), int(layer), int(first_row), int(n_rows), _ptr(k_rows), _ptr(v_rows),
                             stream or None)
+
+
+def s3_kv_batch_patch(n, slot_off, length, idx, new_off, new_len, stream=0):
+    i_arr, ip = _host_i32(idx)
+    o_arr = np.ascontiguousarray(new_off, np.int64) if new_off is not None else None
+    l_arr, lp = _host_i32(new_len)
+    op = o_arr.ctypes.data_as(_pi64) if o_arr is not None else None
+    return lib().s3_kv_batch_patch(int(n), _ptr(slot_off), _ptr(length), int(i_arr.size), ip, op, lp, stream or None)
 
 
 def s3_kv_read_rows(arena, slot_id, layer, which, first_row, n_rows, dst, stream=0):

@@ -60,6 +60,52 @@ __global__ void __launch_bounds__(256) copy_planes_kernel(const char *src, char 
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) d[i] = s[i];
 }
 
+// Two independent copies in one launch (blockIdx.y picks the pair): the K and V rows of a fill.
+__global__ void __launch_bounds__(256) copy_pair_kernel(const char *src0, char *dst0, const char *src1, char *dst1,
+                                                        size_t n16) {
+    const u32x4 *s = (const u32x4 *)(blockIdx.y ? src1 : src0);
+    u32x4 *d = (u32x4 *)(blockIdx.y ? dst1 : dst0);
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) d[i] = s[i];
+}
+
+// Rewrite a few entries of the per-batch device arrays; the new values travel as kernel arguments.
+#define S3_PATCH_MAX 32
+struct PatchArgs {
+    int64_t off[S3_PATCH_MAX];
+    int32_t idx[S3_PATCH_MAX];
+    int32_t len[S3_PATCH_MAX];
+    int32_t count;
+};
+__global__ void __launch_bounds__(64) batch_patch_kernel(int64_t *slot_off, int32_t *len, const PatchArgs p) {
+    const int i = threadIdx.x;
+    if (i < p.count) {
+        if (slot_off) slot_off[p.idx[i]] = p.off[i];
+        if (len) len[p.idx[i]] = p.len[i];
+    }
+}
+
+extern "C" int s3_kv_batch_patch(int32_t n, int64_t *slot_off, int32_t *len, int32_t n_updates, const int32_t *idx,
+                                 const int64_t *new_off, const int32_t *new_len, void *stream) {
+    if (n < 0 || n_updates < 0 || (!slot_off && !len)) return S3_ERR_INVALID;
+    if (n_updates == 0) return S3_OK;
+    if (!idx || (slot_off && !new_off) || (len && !new_len)) return S3_ERR_INVALID;
+    for (int32_t i = 0; i < n_updates; i++)
+        if (idx[i] < 0 || idx[i] >= n) return S3_ERR_INVALID;
+    for (int32_t first = 0; first < n_updates; first += S3_PATCH_MAX) {
+        PatchArgs p;
+        p.count = n_updates - first < S3_PATCH_MAX ? n_updates - first : S3_PATCH_MAX;
+        for (int32_t i = 0; i < p.count; i++) {
+            p.idx[i] = idx[first + i];
+            p.off[i] = new_off ? new_off[first + i] : 0;
+            p.len[i] = new_len ? new_len[first + i] : 0;
+        }
+        hipLaunchKernelGGL(batch_patch_kernel, dim3(1), dim3(64), 0, (hipStream_t)stream, slot_off, len, p);
+        HIP_TRY(hipGetLastError());
+    }
+    return S3_OK;
+}
+
 int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src_plane_stride,
                            size_t dst_plane_stride, int planes, void *stream) {
     if (nbytes == 0 || planes <= 0) return S3_OK;
@@ -105,6 +151,8 @@ struct AttnArgs {
     float2 *part_ml;   // [n][max_chunks][H]  (running max in log2 units, sum)
     int64_t n_tokens;  // arena capacity N
     int32_t n, H, chunk, max_chunks, out_dtype, max_len;
+    int32_t chunk_min;     // smallest chunk the launch may choose (sizes max_chunks)
+    int32_t target_items;  // > 0: pick the chunk so that about this many (chunk, head block) items exist
     int32_t len_add;    // 0: cur_len is the context length; 1 (fused step): cur_len is the append position
     float scale_log2e;  // scale * log2(e): scores are kept in log2 units so that exp is v_exp_f32
     // fused step only
@@ -216,54 +264,128 @@ __device__ __forceinline__ u32x4 load16(const char *p) {
     return NT ? __builtin_nontemporal_load((const u32x4 *)p) : *(const u32x4 *)p;
 }
 
-// Exclusive prefix sum of per-sequence chunk counts into cum[0..n] (LDS), by the whole workgroup.
-__device__ __forceinline__ void scan_chunks(const AttnArgs &a, int *cum, int *wave_sums) {
+// Work order of a launch.  Contexts of two or more chunks come first (their chunks in batch order),
+// single-chunk contexts after them: the cross-workgroup merges of the long contexts then overlap with
+// the streaming of the short ones instead of forming the tail of the kernel.  The whole workgroup
+// builds two exclusive prefix sums in LDS: multi[0..n] counts chunks of multi-chunk contexts,
+// single[0..n] counts single-chunk contexts (layout: multi at cum[0], single at cum[n+1]).
+__device__ __forceinline__ int chunks_of(const AttnArgs &a, int b, int chunk) {
+    return (checked_len(a, b) + chunk - 1) / chunk;
+}
+
+// Returns the chunk size of this launch: a.chunk, or (target_items > 0) the size that cuts the
+// batch's total rows into about target_items (chunk, head block) items, within [chunk_min, a.chunk],
+// so that every resident workgroup gets one item of similar size whatever the length mix is.
+__device__ __forceinline__ int scan_chunks(const AttnArgs &a, int *cum, int *wave_sums, int n_hgb) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nthreads = blockDim.x;
+    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
+    int *multi = cum, *single = cum + a.n + 1;
     const int per = (a.n + nthreads - 1) / nthreads;
     const int b0 = min(a.n, tid * per), b1 = min(a.n, b0 + per);
-    int sum = 0;
-    for (int b = b0; b < b1; b++) sum += (checked_len(a, b) + a.chunk - 1) / a.chunk;
-    int incl = sum;
+    int chunk = a.chunk;
+    if (a.target_items > 0) {
+        int rows = 0;
+        for (int b = b0; b < b1; b++) rows += checked_len(a, b);
+#pragma unroll
+        for (int d = 32; d >= 1; d >>= 1) rows += __shfl_xor(rows, d);
+        if (lane == 0) wave_sums[wave] = rows;
+        __syncthreads();
+        int64_t total_rows = 0;
+        for (int i = 0; i < nwaves; i++) total_rows += wave_sums[i];
+        __syncthreads();  // wave_sums is reused below
+        const int64_t want = (total_rows * n_hgb + a.target_items - 1) / a.target_items;
+        chunk = (int)min((int64_t)a.chunk, max((int64_t)a.chunk_min, (want + 31) / 32 * 32));
+    }
+    int sum_m = 0, sum_s = 0;
+    for (int b = b0; b < b1; b++) {
+        const int k = chunks_of(a, b, chunk);
+        sum_m += k >= 2 ? k : 0;
+        sum_s += k == 1;
+    }
+    int incl_m = sum_m, incl_s = sum_s;
 #pragma unroll
     for (int d = 1; d < 64; d <<= 1) {
-        const int t = __shfl_up(incl, d);
-        if (lane >= d) incl += t;
+        const int tm = __shfl_up(incl_m, d), tsn = __shfl_up(incl_s, d);
+        if (lane >= d) {
+            incl_m += tm;
+            incl_s += tsn;
+        }
     }
-    if (lane == 63) wave_sums[wave] = incl;
+    if (lane == 63) {
+        wave_sums[wave] = incl_m;
+        wave_sums[nwaves + wave] = incl_s;
+    }
     __syncthreads();
-    int base = 0;
-    for (int i = 0; i < wave; i++) base += wave_sums[i];
-    int run = base + incl - sum;
+    int base_m = 0, base_s = 0;
+    for (int i = 0; i < wave; i++) {
+        base_m += wave_sums[i];
+        base_s += wave_sums[nwaves + i];
+    }
+    int run_m = base_m + incl_m - sum_m, run_s = base_s + incl_s - sum_s;
     for (int b = b0; b < b1; b++) {
-        cum[b] = run;
-        run += (checked_len(a, b) + a.chunk - 1) / a.chunk;
+        const int k = chunks_of(a, b, chunk);
+        multi[b] = run_m;
+        single[b] = run_s;
+        run_m += k >= 2 ? k : 0;
+        run_s += k == 1;
     }
-    if (tid == nthreads - 1) cum[a.n] = run;
+    if (tid == nthreads - 1) {
+        multi[a.n] = run_m;
+        single[a.n] = run_s;
+    }
     __syncthreads();
+    return chunk;
+}
+
+// Partials that cross workgroups inside ONE launch (fused step) must not sit in a cache that
+// another XCD cannot see: they are written and read with device-scope relaxed atomics, which on
+// gfx950 are plain 32-bit stores / loads that go through to memory-side coherence.  No cache
+// write-back or invalidate is needed then (those cost far more than the partials themselves).
+template <bool COHERENT>
+__device__ __forceinline__ void put_partial(float *p, float v) {
+    if (COHERENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else *p = v;
+}
+template <bool COHERENT>
+__device__ __forceinline__ float get_partial(const float *p) {
+    return COHERENT ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
 }
 
 // Merge the chunk partials of (sequence b, head h) for this lane's 8-element slice and store the
-// final output row slice.  nchunks >= 2.
-template <int D>
+// final output row slice.  nchunks >= 2.  Four chunks are loaded per round so that the (cache
+// bypassing) loads of a round are in flight together.
+template <int D, bool COHERENT>
 __device__ __forceinline__ void merge_chunks(const AttnArgs &a, int b, int h, int dl, int nchunks) {
     const int64_t p0 = ((int64_t)b * a.max_chunks) * a.H + h;
-    float mm = -INFINITY;
-    for (int c = 0; c < nchunks; c++) mm = fmaxf(mm, a.part_ml[p0 + (int64_t)c * a.H].x);
-    float l = 0.f;
+    const float *ml = (const float *)a.part_ml;
+    float mm = -INFINITY, l = 0.f;
     float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int c = 0; c < nchunks; c++) {
-        const int64_t pi = p0 + (int64_t)c * a.H;
-        const float2 ml = a.part_ml[pi];
-        const float wgt = fast_exp2(ml.x - mm);
-        l += wgt * ml.y;
-        const f32x4 *pa = (const f32x4 *)(a.part_acc + pi * D + dl * 8);
-        const f32x4 x = pa[0], y = pa[1];
+    for (int c0 = 0; c0 < nchunks; c0 += 4) {
+        float mv[4], lv[4], av[4][8];
 #pragma unroll
-        for (int i = 0; i < 4; i++) {
-            o[i] += wgt * x[i];
-            o[4 + i] += wgt * y[i];
+        for (int u = 0; u < 4; u++) {
+            const int64_t pi = p0 + (int64_t)min(c0 + u, nchunks - 1) * a.H;
+            mv[u] = get_partial<COHERENT>(ml + 2 * pi);
+            lv[u] = get_partial<COHERENT>(ml + 2 * pi + 1);
+            const float *pa = a.part_acc + pi * D + dl * 8;
+#pragma unroll
+            for (int i = 0; i < 8; i++) av[u][i] = get_partial<COHERENT>(pa + i);
         }
+        float mn = mm;
+#pragma unroll
+        for (int u = 0; u < 4; u++) mn = fmaxf(mn, mv[u]);  // repeats of the last chunk do not change the max
+        const float alpha = fast_exp2(mm - mn);
+        l *= alpha;
+#pragma unroll
+        for (int i = 0; i < 8; i++) o[i] *= alpha;
+#pragma unroll
+        for (int u = 0; u < 4; u++) {
+            const float wgt = (c0 + u < nchunks) ? fast_exp2(mv[u] - mn) : 0.f;
+            l += wgt * lv[u];
+#pragma unroll
+            for (int i = 0; i < 8; i++) o[i] += wgt * av[u][i];
+        }
+        mm = mn;
     }
     const float inv = 1.f / l;
 #pragma unroll
@@ -271,173 +393,287 @@ __device__ __forceinline__ void merge_chunks(const AttnArgs &a, int b, int h, in
     store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, o);
 }
 
-// DT: element type of q/K/V.  D: head_dim.  TS: waves splitting a chunk's tokens.  HS: head groups
-// per workgroup.  U: tokens per load batch.  NT: non-temporal loads of K/V.
-// FUSED: one launch does the whole layer-step: the token at row cur_len[b] (the append position) is
-// taken from k_new/v_new instead of the arena and written into the arena by the wave that owns it,
-// attention runs over cur_len[b]+1 rows, the workgroup that delivers the last chunk of a (sequence,
-// head block) merges the chunks (arrival counter), empty contexts get their zero row, and
-// len_out[b] = cur_len[b]+1 is published for the next step.
-template <int DT, int D, int TS, int HS, int U, bool NT, bool FUSED>
-__global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArgs a) {
+// What a workgroup item is: chunk c of sequence b for head block hgb.
+struct Item {
+    int b, c, nchunks, len, hgb;
+    int clen;  // rows per chunk of this context: the context is cut into nchunks near-equal pieces
+    int64_t off;
+};
+
+// Rows per chunk when a context of len rows is cut into nchunks pieces: near-equal pieces; falls
+// back to `chunk` if rounding would leave the last piece empty.
+__device__ __forceinline__ int balanced_chunk_len(int len, int nchunks, int chunk) {
+    if (nchunks <= 1) return chunk;
+    const int clen = (len + nchunks - 1) / nchunks;
+    return (nchunks - 1) * clen < len ? clen : chunk;
+}
+
+// Rows [j0, j1) of item `it` that token split ts of TS takes: the item's rows are divided evenly
+// (split 0 is never empty; trailing splits may be).
+__device__ __forceinline__ void split_rows(const Item &it, int ts, int TS, int &j0, int &j1) {
+    const int start = it.c * it.clen;
+    const int end = min(it.len, start + it.clen);
+    const int per = (end - start + TS - 1) / TS;
+    j0 = min(end, start + ts * per);
+    j1 = min(end, j0 + per);
+}
+
+__device__ __forceinline__ Item decode_item(const AttnArgs &a, const int *cum, int64_t item, int n_hgb, int chunk) {
+    Item it;
+    int w = (int)(item / n_hgb);
+    it.hgb = (int)(item - (int64_t)w * n_hgb);
+    const int *pre = cum;  // multi-chunk contexts first
+    const bool is_single = w >= cum[a.n];
+    if (is_single) {
+        w -= cum[a.n];
+        pre = cum + a.n + 1;
+    }
+    int lo = 0, hi = a.n - 1;
+    while (lo < hi) {  // first b with pre[b+1] > w
+        const int mid = (lo + hi) >> 1;
+        if (pre[mid + 1] > w) hi = mid; else lo = mid + 1;
+    }
+    it.b = lo;
+    it.c = is_single ? 0 : w - pre[lo];
+    it.nchunks = is_single ? 1 : pre[lo + 1] - pre[lo];
+    it.len = checked_len(a, lo);
+    it.off = a.slot_off[lo];
+    it.clen = balanced_chunk_len(it.len, it.nchunks, chunk);
+    return it;
+}
+
+// One wave's share of an item: tokens [j0, j1) of head group hg, online softmax in fp32.
+// DT: element type of q/K/V.  D: head_dim.  U: tokens per load batch.  NT: non-temporal loads.
+// FUSED: row len-1 is still only in k_new / v_new: it is taken from there and, by the wave whose
+// range holds it, written into the arena (the append).
+template <int DT, int D, int U, bool NT, bool FUSED>
+__device__ __forceinline__ void wave_tokens(const AttnArgs &a, const Item &it, int hg, int j0, int j1, float &m,
+                                            float &l, float (&acc)[8]) {
     constexpr int LPH = D / 8;    // lanes per head
     constexpr int GH = 64 / LPH;  // heads per wave
-    constexpr int NW = TS * HS;
-    extern __shared__ int cum[];  // [n + 1]
-    __shared__ int wave_sums[NW];
-    __shared__ int last_flag;
-    __shared__ float comb[TS > 1 ? NW : 1][10][64];
+    const int lane = threadIdx.x & 63;
+    const int g = lane / LPH, dl = lane % LPH;
+    const int h = hg * GH + g;
+    const bool h_ok = h < a.H;
+    const int hc = h_ok ? h : a.H - 1;
+    const int64_t rstride = (int64_t)a.H * D * 2;
+    const int64_t lane_byte = ((int64_t)hc * D + dl * 8) * 2;
+    const char *kp = a.kplane + it.off * rstride + lane_byte;
+    const char *vp = a.vplane + it.off * rstride + lane_byte;
+    const int64_t in_byte = ((int64_t)it.b * a.H * D) * 2 + lane_byte;  // this lane's slice of row b of q/k_new/v_new
+    const u32x4 qv = *(const u32x4 *)(a.q + in_byte);
+    const int jnew = FUSED ? it.len - 1 : -1;
 
-    scan_chunks(a, cum, wave_sums);
+    m = -INFINITY;
+    l = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] = 0.f;
+    for (int j = j0; j < j1; j += U) {
+        u32x4 kk[U], vv[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int jj = min(j + u, j1 - 1);
+            const char *src = kp + (int64_t)jj * rstride;
+            if (FUSED) src = (jj == jnew) ? a.k_new + in_byte : src;
+            kk[u] = load16<NT>(src);
+        }
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const int jj = min(j + u, j1 - 1);
+            const char *src = vp + (int64_t)jj * rstride;
+            if (FUSED) src = (jj == jnew) ? a.v_new + in_byte : src;
+            vv[u] = load16<NT>(src);
+        }
+        float s[U];
+#pragma unroll
+        for (int u = 0; u < U; u++) s[u] = dot8<DT>(qv, kk[u]);
+#pragma unroll
+        for (int u = 0; u < U; u++) s[u] = group_sum<LPH>(s[u]);
+        float mb = -INFINITY;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            s[u] = (j + u < j1) ? s[u] * a.scale_log2e : -INFINITY;
+            mb = fmaxf(mb, s[u]);
+        }
+        const float mn = fmaxf(m, mb);  // finite: the batch holds at least one real token
+        const float alpha = fast_exp2(m - mn);
+        l *= alpha;
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[i] *= alpha;
+#pragma unroll
+        for (int u = 0; u < U; u++) {
+            const float p = fast_exp2(s[u] - mn);
+            l += p;
+            axpy8<DT>(acc, p, vv[u]);
+        }
+        m = mn;
+    }
+    if (FUSED && h_ok && j0 <= jnew && jnew < j1) {  // the append: this wave owns the new row's slice
+        *(u32x4 *)(a.kplane + (it.off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.k_new + in_byte);
+        *(u32x4 *)(a.vplane + (it.off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.v_new + in_byte);
+    }
+}
+
+// Merge TS token splits (rows first..first+TS-1 of comb) lane by lane.
+template <int TS>
+__device__ __forceinline__ void combine_splits(const float (*comb)[10][64], int first, int lane, float &m, float &l,
+                                               float (&acc)[8]) {
+    m = comb[first][0][lane];
+    for (int t = 1; t < TS; t++) m = fmaxf(m, comb[first + t][0][lane]);
+    l = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] = 0.f;
+    for (int t = 0; t < TS; t++) {  // split 0 is never empty, so m is finite; empty splits weigh exp2(-inf) = 0
+        const float wt = fast_exp2(comb[first + t][0][lane] - m);
+        l += wt * comb[first + t][1][lane];
+#pragma unroll
+        for (int i = 0; i < 8; i++) acc[i] += wt * comb[first + t][2 + i][lane];
+    }
+}
+
+// Write one (chunk, head) result: the final output row slice if the context has a single chunk,
+// else the partial (max, sum, weighted sum).
+template <int D, bool COHERENT>
+__device__ __forceinline__ void emit_chunk(const AttnArgs &a, const Item &it, int h, int dl, float m, float l,
+                                           const float (&acc)[8]) {
+    if (it.nchunks == 1) {
+        const float inv = 1.f / l;
+        float o[8];
+#pragma unroll
+        for (int i = 0; i < 8; i++) o[i] = acc[i] * inv;
+        store_out8(a.out, a.out_dtype, ((int64_t)it.b * a.H + h) * D + dl * 8, o);
+        return;
+    }
+    const int64_t pi = ((int64_t)it.b * a.max_chunks + it.c) * a.H + h;
+    float *pml = (float *)a.part_ml + 2 * pi;
+    float *pa = a.part_acc + pi * D + dl * 8;
+    if (COHERENT) {
+        if (dl == 0) {
+            put_partial<true>(pml, m);
+            put_partial<true>(pml + 1, l);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; i++) put_partial<true>(pa + i, acc[i]);
+    } else {
+        if (dl == 0) a.part_ml[pi] = make_float2(m, l);
+        ((f32x4 *)pa)[0] = (f32x4){acc[0], acc[1], acc[2], acc[3]};
+        ((f32x4 *)pa)[1] = (f32x4){acc[4], acc[5], acc[6], acc[7]};
+    }
+}
+
+// Attention only (s3_decode_attention): TS*HS waves; the TS waves of a head group split the chunk's
+// tokens and merge through LDS; multi-chunk contexts are finished by attn_merge_kernel.
+template <int DT, int D, int TS, int HS, int U, bool NT>
+__global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArgs a) {
+    constexpr int LPH = D / 8;
+    constexpr int GH = 64 / LPH;
+    constexpr int NW = TS * HS;
+    extern __shared__ int cum[];  // [2][n + 1]
+    __shared__ int wave_sums[2 * NW];
+    __shared__ float comb[TS > 1 ? NW : 1][10][64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ts = wave % TS, hs = wave / TS;
-    const int g = lane / LPH, dl = lane % LPH;
     const int n_hg = (a.H + GH - 1) / GH;
     const int n_hgb = (n_hg + HS - 1) / HS;
-    const int64_t total = (int64_t)cum[a.n] * n_hgb;
-    const int64_t rstride = (int64_t)a.H * D * 2;
-    const int tok_per_wave = a.chunk / TS;
-
-    if (FUSED && blockIdx.x == 0) {
-        for (int b = threadIdx.x; b < a.n; b += NW * 64) {
-            if (a.len_out) a.len_out[b] = a.cur_len[b] + 1;
-            if (cum[b + 1] == cum[b]) {  // empty or refused context: zero output row
-                for (int e = 0; e < a.H * D; e += 8) {
-                    const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                    store_out8(a.out, a.out_dtype, (int64_t)b * a.H * D + e, z);
-                }
-            }
-        }
-    }
+    const int chunk = scan_chunks(a, cum, wave_sums, n_hgb);
+    const int64_t total = (int64_t)(cum[a.n] + cum[2 * a.n + 1]) * n_hgb;
 
     for (int64_t item = blockIdx.x; item < total; item += gridDim.x) {
-        const int w = (int)(item / n_hgb);
-        const int hgb = (int)(item - (int64_t)w * n_hgb);
-        int lo = 0, hi = a.n - 1;
-        while (lo < hi) {  // first b with cum[b+1] > w
-            const int mid = (lo + hi) >> 1;
-            if (cum[mid + 1] > w) hi = mid; else lo = mid + 1;
-        }
-        const int b = lo;
-        const int c = w - cum[b];
-        const int nchunks = cum[b + 1] - cum[b];
-        const int len = checked_len(a, b);
-        const int64_t off = a.slot_off[b];
-        const int h = (hgb * HS + hs) * GH + g;
-        const bool h_ok = h < a.H;
-        const int hc = h_ok ? h : a.H - 1;
-
-        const int j0 = c * a.chunk + ts * tok_per_wave;
-        const int j1 = min(len, j0 + tok_per_wave);
-        const int64_t lane_byte = ((int64_t)hc * D + dl * 8) * 2;
-        const char *kp = a.kplane + off * rstride + lane_byte;
-        const char *vp = a.vplane + off * rstride + lane_byte;
-        const int64_t in_byte = ((int64_t)b * a.H * D) * 2 + lane_byte;  // this lane's slice of row b of q/k_new/v_new
-        const u32x4 qv = *(const u32x4 *)(a.q + in_byte);
-        const int jnew = FUSED ? len - 1 : -1;  // the row that is still only in k_new / v_new
-
-        float m = -INFINITY, l = 0.f;
-        float acc[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-        for (int j = j0; j < j1; j += U) {
-            u32x4 kk[U], vv[U];
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const int jj = min(j + u, j1 - 1);
-                const char *src = kp + (int64_t)jj * rstride;
-                if (FUSED) src = (jj == jnew) ? a.k_new + in_byte : src;
-                kk[u] = load16<NT>(src);
-            }
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const int jj = min(j + u, j1 - 1);
-                const char *src = vp + (int64_t)jj * rstride;
-                if (FUSED) src = (jj == jnew) ? a.v_new + in_byte : src;
-                vv[u] = load16<NT>(src);
-            }
-            float s[U];
-#pragma unroll
-            for (int u = 0; u < U; u++) s[u] = dot8<DT>(qv, kk[u]);
-#pragma unroll
-            for (int u = 0; u < U; u++) s[u] = group_sum<LPH>(s[u]);
-            float mb = -INFINITY;
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                s[u] = (j + u < j1) ? s[u] * a.scale_log2e : -INFINITY;
-                mb = fmaxf(mb, s[u]);
-            }
-            const float mn = fmaxf(m, mb);  // finite: the batch holds at least one real token
-            const float alpha = fast_exp2(m - mn);
-            l *= alpha;
-#pragma unroll
-            for (int i = 0; i < 8; i++) acc[i] *= alpha;
-#pragma unroll
-            for (int u = 0; u < U; u++) {
-                const float p = fast_exp2(s[u] - mn);
-                l += p;
-                axpy8<DT>(acc, p, vv[u]);
-            }
-            m = mn;
-        }
-        if (FUSED && h_ok && j0 <= jnew && jnew < j1) {  // the append: this wave owns the new row's slice
-            *(u32x4 *)(a.kplane + (off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.k_new + in_byte);
-            *(u32x4 *)(a.vplane + (off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.v_new + in_byte);
-        }
-
-        if (TS > 1) {  // merge the TS token splits of this head group through LDS
+        const Item it = decode_item(a, cum, item, n_hgb, chunk);
+        const int hg = it.hgb * HS + hs;
+        int j0, j1;
+        split_rows(it, ts, TS, j0, j1);
+        float m, l, acc[8];
+        wave_tokens<DT, D, U, NT, false>(a, it, hg, j0, j1, m, l, acc);
+        if (TS > 1) {
             comb[wave][0][lane] = m;
             comb[wave][1][lane] = l;
 #pragma unroll
             for (int i = 0; i < 8; i++) comb[wave][2 + i][lane] = acc[i];
             __syncthreads();
-            if (ts == 0) {
-                float mm = m;
-                for (int t = 1; t < TS; t++) mm = fmaxf(mm, comb[wave + t][0][lane]);
-                const float w0 = fast_exp2(m - mm);  // split 0 is never empty, so mm is finite
-                l *= w0;
+            if (ts == 0) combine_splits<TS>(comb, wave, lane, m, l, acc);
+        }
+        const int h = hg * GH + lane / LPH;
+        if (ts == 0 && h < a.H) emit_chunk<D, false>(a, it, h, lane % LPH, m, l, acc);
+        if (TS > 1) __syncthreads();  // comb is reused by the next item
+    }
+}
+
+// The whole layer-step in one launch (s3_decode_step): TS*HS compute waves plus ONE epilogue wave.
+// Compute waves stream their token shares (taking the new row from k_new / v_new and appending it),
+// drop (max, sum, weighted sum) into one of two LDS buffers and move on to the next item after a
+// single barrier.  The epilogue wave merges the splits, writes the output or the chunk partial,
+// announces the chunk on the context's arrival counter and, if it delivered the last chunk, merges
+// the chunks; all its memory latencies overlap with the compute waves' next item.  Workgroup 0
+// also publishes len_out and the zero rows of empty contexts.
+template <int DT, int D, int TS, int HS, int U, bool NT>
+__global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const AttnArgs a) {
+    constexpr int LPH = D / 8;
+    constexpr int GH = 64 / LPH;
+    constexpr int NWC = TS * HS;  // compute waves
+    extern __shared__ int cum[];  // [2][n + 1]
+    __shared__ int wave_sums[2 * (NWC + 1)];
+    __shared__ float comb[2][NWC][10][64];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const bool epilogue = wave == NWC;
+    const int ts = wave % TS, hs = wave / TS;
+    const int n_hg = (a.H + GH - 1) / GH;
+    const int n_hgb = (n_hg + HS - 1) / HS;
+    const int chunk = scan_chunks(a, cum, wave_sums, n_hgb);
+    const int64_t total = (int64_t)(cum[a.n] + cum[2 * a.n + 1]) * n_hgb;
+
+    if (blockIdx.x == 0) {
+        for (int b = threadIdx.x; b < a.n; b += (NWC + 1) * 64) {
+            if (a.len_out) a.len_out[b] = a.cur_len[b] + 1;
+            if (chunks_of(a, b, chunk) == 0) {  // empty or refused context: zero output row
+                const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                for (int e = 0; e < a.H * D; e += 8) store_out8(a.out, a.out_dtype, (int64_t)b * a.H * D + e, z);
+            }
+        }
+    }
+
+    int parity = 0;
+    for (int64_t item = blockIdx.x; item < total; item += gridDim.x, parity ^= 1) {
+        const Item it = decode_item(a, cum, item, n_hgb, chunk);
+        if (!epilogue) {
+            int j0, j1;
+            split_rows(it, ts, TS, j0, j1);
+            float m, l, acc[8];
+            wave_tokens<DT, D, U, NT, true>(a, it, it.hgb * HS + hs, j0, j1, m, l, acc);
+            comb[parity][wave][0][lane] = m;
+            comb[parity][wave][1][lane] = l;
 #pragma unroll
-                for (int i = 0; i < 8; i++) acc[i] *= w0;
-                for (int t = 1; t < TS; t++) {
-                    const float wt = fast_exp2(comb[wave + t][0][lane] - mm);
-                    l += wt * comb[wave + t][1][lane];
-#pragma unroll
-                    for (int i = 0; i < 8; i++) acc[i] += wt * comb[wave + t][2 + i][lane];
+            for (int i = 0; i < 8; i++) comb[parity][wave][2 + i][lane] = acc[i];
+        }
+        // The only barrier of an item.  Buffer `parity` is next written two items later, after the
+        // barrier of item+1, which the epilogue wave reaches only when it is done reading it.
+        __syncthreads();
+        if (epilogue) {
+            for (int s = 0; s < HS; s++) {
+                const int h = (it.hgb * HS + s) * GH + lane / LPH;
+                if (h < a.H) {
+                    float m, l, acc[8];
+                    combine_splits<TS>(comb[parity], s * TS, lane, m, l, acc);
+                    emit_chunk<D, true>(a, it, h, lane % LPH, m, l, acc);
                 }
-                m = mm;
+            }
+            if (it.nchunks > 1) {
+                __builtin_amdgcn_s_waitcnt(0);  // this wave's partial stores have completed
+                unsigned int *cnt = a.arrivals + (int64_t)it.b * n_hgb + it.hgb;
+                unsigned int old = 0;
+                if (lane == 0) old = atomicAdd(cnt, 1u);
+                old = __builtin_amdgcn_readfirstlane(old);
+                if (old == (unsigned int)(it.nchunks - 1)) {  // every chunk of this context has arrived
+                    if (lane == 0) atomicExch(cnt, 0u);        // leave the counter clean for the next launch
+                    for (int s = 0; s < HS; s++) {
+                        const int h = (it.hgb * HS + s) * GH + lane / LPH;
+                        if (h < a.H) merge_chunks<D, true>(a, it.b, h, lane % LPH, it.nchunks);
+                    }
+                }
             }
         }
-        if (ts == 0 && h_ok) {
-            if (nchunks == 1) {
-                const float inv = 1.f / l;
-                float o[8];
-#pragma unroll
-                for (int i = 0; i < 8; i++) o[i] = acc[i] * inv;
-                store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, o);
-            } else {
-                const int64_t pi = ((int64_t)b * a.max_chunks + c) * a.H + h;
-                if (dl == 0) a.part_ml[pi] = make_float2(m, l);
-                f32x4 *pa = (f32x4 *)(a.part_acc + pi * D + dl * 8);
-                pa[0] = (f32x4){acc[0], acc[1], acc[2], acc[3]};
-                pa[1] = (f32x4){acc[4], acc[5], acc[6], acc[7]};
-            }
-        }
-        if (FUSED && nchunks > 1) {  // uniform over the workgroup: b is
-            __threadfence();         // this wave's partials are visible device-wide ...
-            __syncthreads();         // ... before thread 0 announces the chunk
-            if (threadIdx.x == 0) {
-                unsigned int *cnt = a.arrivals + (int64_t)b * n_hgb + hgb;
-                const unsigned int old = atomicAdd(cnt, 1u);
-                const int last = old == (unsigned int)(nchunks - 1);
-                if (last) atomicExch(cnt, 0u);  // every chunk has arrived: leave the counter clean
-                last_flag = last;
-            }
-            __syncthreads();
-            if (last_flag) {
-                __threadfence();  // see the other workgroups' partials
-                if (ts == 0 && h_ok) merge_chunks<D>(a, b, h, dl, nchunks);
-            }
-        }
-        if (TS > 1 || FUSED) __syncthreads();  // comb / last_flag are reused by the next item
     }
 }
 
@@ -454,10 +690,10 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     const int b = (int)(wid / n_hg), hg = (int)(wid % n_hg);
     const int h = hg * GH + lane / LPH, dl = lane % LPH;
     if (h >= a.H) return;
-    const int nchunks = (checked_len(a, b) + a.chunk - 1) / a.chunk;
+    const int nchunks = chunks_of(a, b, a.chunk);
     if (nchunks == 1) return;
     if (nchunks > 1) {
-        merge_chunks<D>(a, b, h, dl, nchunks);
+        merge_chunks<D, false>(a, b, h, dl, nchunks);
         return;
     }
     const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -470,19 +706,25 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
 struct Variant {
     int ts, hs, u, nt;
 };
+#define S3_VARIANTS(X) \
+    X(0, 4, 1, 4, true)   \
+    X(1, 8, 1, 4, true)   \
+    X(2, 4, 2, 4, true)   \
+    X(3, 1, 4, 4, true)   \
+    X(4, 8, 1, 8, true)   \
+    X(5, 2, 4, 4, true)   \
+    X(6, 1, 8, 4, true)   \
+    X(7, 4, 1, 2, true)   \
+    X(8, 4, 1, 4, false)  \
+    X(9, 8, 1, 4, false)  \
+    X(10, 4, 1, 8, true)  \
+    X(11, 2, 2, 4, true)  \
+    X(12, 2, 1, 8, true)  \
+    X(13, 4, 2, 8, true)
 static const Variant kVariants[] = {
-    {4, 1, 4, 1},   // 0
-    {8, 1, 4, 1},   // 1
-    {4, 2, 4, 1},   // 2
-    {1, 4, 4, 1},   // 3
-    {8, 1, 8, 1},   // 4
-    {16, 1, 4, 1},  // 5
-    {2, 8, 4, 1},   // 6
-    {4, 1, 2, 1},   // 7
-    {4, 1, 4, 0},   // 8
-    {8, 1, 4, 0},   // 9
-    {4, 1, 8, 1},   // 10
-    {2, 2, 4, 1},   // 11
+#define X(i, ts, hs, u, nt) {ts, hs, u, nt},
+    S3_VARIANTS(X)
+#undef X
 };
 int s3i_num_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0])); }
 
@@ -491,18 +733,10 @@ typedef void (*attn_fn)(const AttnArgs);
 template <int DT, int D, bool FUSED>
 static attn_fn pick_variant(int v) {
     switch (v) {
-        case 0: return attn_partial_kernel<DT, D, 4, 1, 4, true, FUSED>;
-        case 1: return attn_partial_kernel<DT, D, 8, 1, 4, true, FUSED>;
-        case 2: return attn_partial_kernel<DT, D, 4, 2, 4, true, FUSED>;
-        case 3: return attn_partial_kernel<DT, D, 1, 4, 4, true, FUSED>;
-        case 4: return attn_partial_kernel<DT, D, 8, 1, 8, true, FUSED>;
-        case 5: return attn_partial_kernel<DT, D, 16, 1, 4, true, FUSED>;
-        case 6: return attn_partial_kernel<DT, D, 2, 8, 4, true, FUSED>;
-        case 7: return attn_partial_kernel<DT, D, 4, 1, 2, true, FUSED>;
-        case 8: return attn_partial_kernel<DT, D, 4, 1, 4, false, FUSED>;
-        case 9: return attn_partial_kernel<DT, D, 8, 1, 4, false, FUSED>;
-        case 10: return attn_partial_kernel<DT, D, 4, 1, 8, true, FUSED>;
-        case 11: return attn_partial_kernel<DT, D, 2, 2, 4, true, FUSED>;
+#define X(i, ts, hs, u, nt) \
+    case i: return FUSED ? (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt> : (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt>;
+        S3_VARIANTS(X)
+#undef X
         default: return nullptr;
     }
 }
@@ -616,10 +850,11 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
                             const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
                             bool fused, const void *k_new, const void *v_new, int32_t *len_out) {
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
+    // Defaults from sweeps on MI355X: large chunks keep most contexts in one piece (no cross-workgroup
+    // merge), eight waves share an item's rows evenly.
     const int variant = a->variant >= 0 ? a->variant : 1;
     const Variant &vr = kVariants[variant];
-    const int chunk = a->chunk > 0 ? a->chunk : 128;
-    if (chunk % vr.ts) return S3_ERR_INVALID;
+    const int chunk = a->chunk > 0 ? a->chunk : 1024;
     attn_fn fn = fused ? pick_kernel<true>(a->cfg.kv_dtype, D, variant) : pick_kernel<false>(a->cfg.kv_dtype, D, variant);
     if (!fn) return S3_ERR_INVALID;
     const int GH = 512 / D;
@@ -636,7 +871,12 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
     args.n = n;
     args.H = H;
     args.chunk = chunk;
-    args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
+    // fused launches pick their chunk on the device between chunk_min and chunk, from the batch's
+    // total rows, aiming at target_items items; the partial buffer is sized for chunk_min
+    const bool adaptive = fused && a->target_items > 0;
+    args.chunk_min = adaptive ? (a->chunk_min > 0 ? a->chunk_min : 128) : chunk;
+    if (args.chunk_min > chunk) args.chunk_min = chunk;
+    args.max_chunks = (a->cfg.max_len + args.chunk_min - 1) / args.chunk_min;
     args.out_dtype = out_dtype;
     args.max_len = a->cfg.max_len;
     args.len_add = fused ? 1 : 0;
@@ -657,10 +897,11 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
     args.part_acc = (float *)((char *)a->scratch + cnt_bytes);
     args.part_ml = (float2 *)((char *)a->scratch + cnt_bytes + acc_bytes);
 
-    const int nw = vr.ts * vr.hs;
+    const int nw = vr.ts * vr.hs + (fused ? 1 : 0);  // the fused kernel adds an epilogue wave
     const int cus = a->num_cus > 0 ? a->num_cus : 256;
-    const int blocks = a->grid_blocks > 0 ? a->grid_blocks : cus * (32 / nw);
-    const size_t dyn_lds = (size_t)(n + 1) * sizeof(int);
+    const int blocks = a->grid_blocks > 0 ? a->grid_blocks : cus * (32 / (vr.ts * vr.hs));
+    args.target_items = adaptive ? a->target_items : 0;
+    const size_t dyn_lds = (size_t)2 * (n + 1) * sizeof(int);
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     if (a->profile) {
         for (int i = 0; i < 3; i++) {
@@ -717,11 +958,15 @@ extern "C" int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t f
     if (!k_rows || !v_rows) return S3_ERR_INVALID;
     const size_t nbytes = (size_t)n_rows * a->row_bytes;
     const int64_t row0 = s->off + first_row;
-    int rc = s3i_launch_copy_planes((const char *)k_rows, a->plane(layer, 0) + row0 * a->row_bytes, nbytes, 0, 0, 1,
-                                    stream);
-    if (rc != S3_OK) return rc;
-    return s3i_launch_copy_planes((const char *)v_rows, a->plane(layer, 1) + row0 * a->row_bytes, nbytes, 0, 0, 1,
-                                  stream);
+    if (((uintptr_t)k_rows & 15) || ((uintptr_t)v_rows & 15)) return S3_ERR_INVALID;
+    const size_t n16 = nbytes / 16;
+    size_t blocks = (n16 + 1023) / 1024;
+    if (blocks > 4096) blocks = 4096;
+    hipLaunchKernelGGL(copy_pair_kernel, dim3((unsigned)blocks, 2), dim3(256), 0, (hipStream_t)stream,
+                       (const char *)k_rows, a->plane(layer, 0) + row0 * a->row_bytes, (const char *)v_rows,
+                       a->plane(layer, 1) + row0 * a->row_bytes, n16);
+    HIP_TRY(hipGetLastError());
+    return S3_OK;
 }
 
 extern "C" int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,

@@ -56,7 +56,8 @@ class DecodeEngine:
         self.slot_off_dev = None
         self.len_dev = None
         self.len_next = None
-        self._dirty = True
+        self._dirty = True   # the device arrays must be rebuilt (batch membership or order changed)
+        self._patch = set()  # entries whose offset / length changed in place
         self.out = None
 
     # -- helpers ----------------------------------------------------------
@@ -94,6 +95,11 @@ class DecodeEngine:
         return host.to(self.dev, non_blocking=True)
 
     def _sync_arrays(self):
+        if not self._dirty and self._patch:
+            idx = np.fromiter(self._patch, np.int32)
+            s3.check(s3.s3_kv_batch_patch(self.n_active, self.slot_off_dev, self.len_dev, idx, self.off[idx],
+                                          self.len[idx], self._stream_ptr()), "s3_kv_batch_patch")
+        self._patch.clear()
         if self._dirty:
             self.slot_off_dev = self._upload(self.off)
             self.len_dev = self._upload(self.len)
@@ -161,6 +167,7 @@ class DecodeEngine:
             if st == s3.S3_OK:
                 self.off[i], self.cap[i] = off, cap
                 self.n_grown += 1
+                self._patch.add(i)
             elif st in (s3.S3_ERR_NOMEM, s3.S3_ERR_MAXLEN):
                 drop.append(i)  # cannot continue on the device (the paper evicts such a sequence to the host)
             else:
@@ -173,7 +180,6 @@ class DecodeEngine:
             keep = np.ones(self.n_active, bool)
             keep[drop] = False
             self._keep(keep)
-        self._dirty = True
 
     def _keep(self, mask):
         for name in ("serial", "slot", "off", "cap", "len", "total"):
@@ -226,7 +232,9 @@ class DecodeEngine:
                 if got:
                     (self.serial[i], self.slot[i], self.off[i], self.cap[i], self.len[i], self.total[i]) = got[0]
                     keep[i] = True
-        self._keep(keep)
+                    self._patch.add(i)
+        if not keep.all():
+            self._keep(keep)
 
     def step(self, tensors, prefill, check_host=False):
         self.grow_full_slots()

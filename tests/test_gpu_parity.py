@@ -326,8 +326,10 @@ def test_grow_moves_rows_bit_exactly_and_leaves_other_slots_alone():
 
 
 def test_fused_step_equals_append_then_attention_bit_for_bit():
-    """s3_decode_step is defined as s3_kv_append + s3_decode_attention over pos+1 rows: same output
-    bits, same arena rows, len_out = pos + 1; for every variant and a few chunk sizes."""
+    """s3_decode_step is defined as s3_kv_append + s3_decode_attention over pos+1 rows: same arena
+    rows, len_out = pos + 1 and, when both cut the contexts into the same chunks (target_items 0),
+    the same output bits; with the fused kernel choosing its own chunk size the outputs agree to
+    rounding.  For every variant and a few chunk sizes."""
     pos = [0, 1, 30, 31, 63, 64, 127, 128, 255, 256, 700, 1023, 5, 64]
     caps = [p + 1 for p in pos]
     H, D, dt = 16, 256, s3.S3_F16
@@ -343,6 +345,7 @@ def test_fused_step_equals_append_then_attention_bit_for_bit():
             for r, fused in zip(rigs, (False, True)):
                 s3.s3_kv_set_param(r.a, "variant", variant)
                 s3.s3_kv_set_param(r.a, "chunk", chunk)
+                assert s3.s3_kv_set_param(r.a, "target_items", 0) == 0
                 off_d = torch.tensor(r.offs.tolist(), dtype=torch.int64, device=DEV)
                 pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
                 out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
@@ -361,6 +364,15 @@ def test_fused_step_equals_append_then_attention_bit_for_bit():
                 rows.append([rig_read(r, sid, 0, w_, c) for sid, c in zip(r.ids.tolist(), caps) for w_ in (0, 1)])
             assert np.array_equal(outs[0], outs[1]), (variant, chunk)
             assert all(np.array_equal(x, y) for x, y in zip(rows[0], rows[1])), (variant, chunk)
+            for target in (-1, 3, 40, 100000):  # device-chosen chunk sizes: same result up to summation order
+                r = rigs[1]
+                assert s3.s3_kv_set_param(r.a, "target_items", target) == 0
+                out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+                off_d = torch.tensor(r.offs.tolist(), dtype=torch.int64, device=DEV)
+                pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+                assert s3.s3_decode_step(r.a, 0, n, off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, None, r.stream) == 0
+                torch.cuda.synchronize()
+                assert np.abs(out.cpu().numpy() - outs[0]).max() < 2e-5, (variant, chunk, target)
     for r in rigs:
         r.close()
 
@@ -387,6 +399,26 @@ def test_fused_step_refuses_full_slots_and_skips_bad_entries():
     got = out.cpu().numpy()
     assert not got[0].any() and np.isfinite(got[1]).all()
     rig.close()
+
+
+def test_batch_patch_rewrites_only_the_named_entries():
+    n = 100
+    off = torch.arange(n, dtype=torch.int64, device=DEV) * 64
+    ln = torch.arange(n, dtype=torch.int32, device=DEV)
+    idx = list(range(0, 100, 3))  # 34 updates: more than one launch's worth
+    new_off = [7000 + i for i in idx]
+    new_len = [900 + i for i in idx]
+    st = torch.cuda.current_stream().cuda_stream
+    assert s3.s3_kv_batch_patch(n, off, ln, idx, new_off, new_len, st) == 0
+    want_off = (np.arange(n) * 64).astype(np.int64)
+    want_len = np.arange(n).astype(np.int32)
+    want_off[idx] = new_off
+    want_len[idx] = new_len
+    assert off.cpu().numpy().tolist() == want_off.tolist() and ln.cpu().numpy().tolist() == want_len.tolist()
+    assert s3.s3_kv_batch_patch(n, off, None, [5], [1], None, st) == 0  # offsets only
+    assert int(off[5]) == 1 and int(ln[5]) == want_len[5]
+    assert s3.s3_kv_batch_patch(n, off, ln, [100], [1], [1], st) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_batch_patch(n, None, None, [1], [1], [1], st) == s3.S3_ERR_INVALID
 
 
 # ---------------------------------------------------------------- traces
