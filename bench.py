@@ -25,17 +25,22 @@ PEAK_HBM_GBPS = 8000.0
 def parse():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=128)
-    ap.add_argument("--warmup", type=int, default=8)
+    ap.add_argument("--steps", type=int, default=None, help="timed decode steps (default: per workload)")
+    ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4"])
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--grid-blocks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time the attention kernel with events")
+    ap.add_argument("--event-every", type=int, default=8,
+                    help="bracket every k-th attention launch with HIP events (each bracket costs a few us)")
     ap.add_argument("--c3-bytes", type=float, default=200e9)
     ap.add_argument("--unfused", action="store_true", help="append + attention + merge kernels instead of one")
     return ap.parse_args()
+
+
+DEFAULT_STEPS = {"c1": (128, 8), "c2": (256, 8), "c3": (3, 1), "c4": (56, 8)}  # (timed, warm-up)
 
 
 def make_device_sources(w, eng, torch, ring=8):
@@ -44,26 +49,41 @@ def make_device_sources(w, eng, torch, ring=8):
     gen = torch.Generator(device=eng.dev)
     gen.manual_seed(w.seed)
     tdt = eng.kv_dtype_torch()
-    bmax = max(len(w.seqs), 1)
-    qkv = torch.randn((ring, 3, bmax, w.n_heads, w.head_dim), generator=gen, device=eng.dev, dtype=torch.float32).to(tdt)
     rows = torch.randn((2, w.max_len, w.n_heads, w.head_dim), generator=gen, device=eng.dev,
                        dtype=torch.float32).to(tdt)
-    state = {"i": 0}
+    state = {"i": 0, "qkv": None}
 
     def prefill(serial, layer, n_rows):
         return rows[0, :n_rows], rows[1, :n_rows]
 
     def tensors(layer, n):
-        t = qkv[state["i"] % ring]
+        if state["qkv"] is None or state["qkv"].shape[2] < n:  # sized once, for the largest batch seen
+            bmax = max(n, eng.n_active, 1 if w.arena_bytes else len(w.seqs))
+            state["qkv"] = torch.randn((ring, 3, bmax, w.n_heads, w.head_dim), generator=gen, device=eng.dev,
+                                       dtype=torch.float32).to(tdt)
+        t = state["qkv"][state["i"] % ring]
         state["i"] += 1
         return t[0, :n], t[1, :n], t[2, :n]
 
-    return prefill, tensors, (qkv, rows)
+    return prefill, tensors, (state, rows)
 
 
-def cpu_baseline(w, eng, torch, budget_s=12.0):
+def read_traffic(kernel, workload):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary of this
+    same command, if there is one (bench.py cannot collect counters itself)."""
+    path = os.path.join(ROOT, "profiles", f"{kernel}_{workload}_pmc.txt")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_launch:"):
+                return int(float(line.split(":")[1]))
+    except OSError:
+        pass
+    return None
+
+
+def cpu_baseline(w, lens, budget_s=12.0):
     """Time the oracle as it stands (fp32 attention, OpenMP over (sequence, head) on all host
-    cores) on the final batch state of the run: whole-batch passes over one layer are repeated
+    cores) on the batch state at the start of the timed region: whole-batch passes over one layer are repeated
     until the time budget is used (at least one pass; a pass that would not fit the budget is cut
     to a prefix of the batch).  K/V values are N(0,1) like the GPU's; the oracle's run time does
     not depend on them."""
@@ -78,7 +98,6 @@ def cpu_baseline(w, eng, torch, budget_s=12.0):
         cores = min(cores, omp)
     H, D = w.n_heads, w.head_dim
     rng = np.random.default_rng(w.seed)
-    lens = eng.len.copy()
     kv = wl.normal_bits(rng, (2, int(w.max_len), H, D), w.dtype)
     done_bytes, done_seqs, t_used, used = 0, 0, 0.0, cores
     n_take = min(lens.size, 16)  # first a small probe to size the passes
@@ -100,7 +119,7 @@ def cpu_baseline(w, eng, torch, budget_s=12.0):
             break
     return {"value": round(done_bytes / t_used / 1e9, 4), "unit": "GB/s", "cores": int(used), "kind": "oracle",
             "seq_steps_per_s": round(done_seqs / t_used, 2),
-            "sample": f"one layer of oracle attention over prefixes of the final batch state ({lens.size} sequences), "
+            "sample": f"one layer of oracle attention over prefixes of the batch state at the start of the timed region ({lens.size} sequences), "
                       f"{passes} passes, {done_seqs} sequence-steps, {t_used:.1f} s of CPU work, OpenMP over "
                       "(sequence, head)"}
 
@@ -121,6 +140,8 @@ def main():
     s3.lib()
     w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4}[args.workload]() if args.workload != "c3" else wl.c3(
         target_bytes=int(args.c3_bytes))
+    steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload][0]
+    warmup = args.warmup if args.warmup is not None else DEFAULT_STEPS[args.workload][1]
     eng = DecodeEngine(w, log_events=False, fused=not args.unfused)
     if args.variant >= 0:
         s3.check(s3.s3_kv_set_param(eng.arena, "variant", args.variant))
@@ -132,22 +153,26 @@ def main():
     eng.start(prefill, stop_when_full=(args.workload == "c3"))
     torch.cuda.synchronize()
 
-    for _ in range(args.warmup):
+    for _ in range(warmup):
         eng.step(tensors, prefill)
     torch.cuda.synchronize()
+    lens_at_start = eng.len.copy()
+    every = max(1, args.event_every)
     if not args.no_kernel_events:
-        s3.check(s3.s3_kv_set_param(eng.arena, "profile", 1))
+        s3.check(s3.s3_kv_set_param(eng.arena, "profile", every))
     grown0, retired0 = eng.n_grown, eng.n_retired
-    total_bytes, seq_steps, attn_bytes = 0, 0, 0
+    total_bytes, seq_steps, launch_bytes = 0, 0, []
     torch.cuda.synchronize()
     t0 = time.perf_counter()
-    for _ in range(args.steps):
+    for _ in range(steps):
         eng.step(tensors, prefill)
         total_bytes += eng.last_step_bytes
         seq_steps += eng.last_step_seqs
+        launch_bytes += [eng.last_step_bytes // w.n_layers] * w.n_layers
     t_enqueue = time.perf_counter() - t0  # host time to enqueue every step (no device wait in it)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    args.steps, args.warmup = steps, warmup
 
     res = {
         "metric": "decode-attention achieved HBM GB/s", "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
@@ -157,11 +182,13 @@ def main():
         "pct_of_peak_hbm": round(100 * total_bytes / dt / 1e9 / PEAK_HBM_GBPS, 2),
         "seq_steps_per_s": round(seq_steps / dt, 1),
         "host_enqueue_ms_per_step": round(t_enqueue / args.steps * 1e3, 5),
-        "config": {"workload": w.name, "batch": eng.n_active, "n_layers": w.n_layers, "n_heads": w.n_heads,
-                   "head_dim": w.head_dim, "mean_context": round(float(eng.len.mean()), 1),
+        "config": {"workload": w.name, "batch": int(lens_at_start.size), "n_layers": w.n_layers,
+                   "n_heads": w.n_heads, "head_dim": w.head_dim,
+                   "mean_context_at_start": round(float(lens_at_start.mean()), 1),
                    "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
                    "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
+                   "path": "append+attention+merge kernels" if args.unfused else "one s3_decode_step kernel per layer",
                    "variant": s3.s3_kv_get_param(eng.arena, "variant")[1],
                    "chunk": s3.s3_kv_get_param(eng.arena, "chunk")[1]},
     }
@@ -169,16 +196,21 @@ def main():
         launches = s3.s3_kv_get_param(eng.arena, "profile_launches")[1]
         part_ns = s3.s3_kv_get_param(eng.arena, "profile_partial_ns")[1]
         merge_ns = s3.s3_kv_get_param(eng.arena, "profile_merge_ns")[1]
-        per_launch_bytes = total_bytes / max(launches, 1)
+        sampled = launch_bytes[::every]  # the launches that were bracketed: every k-th, from the first
+        assert len(sampled) == launches, (len(sampled), launches)
+        per_launch_bytes = sum(sampled) / max(launches, 1)
         avg_us = part_ns / max(launches, 1) / 1e3
         achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if avg_us > 0 else 0.0
-        res["roofline"] = {"bound": "hbm", "kernel": "attn_partial_kernel", "achieved": round(achieved, 1),
+        kernel = "attn_partial_kernel" if args.unfused else "attn_step_kernel"
+        res["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
-                           "traffic": None, "avg_kernel_us": round(avg_us, 2),
-                           "avg_merge_kernel_us": round(merge_ns / max(launches, 1) / 1e3, 2), "launches": launches,
+                           "traffic": read_traffic(kernel, args.workload), "avg_kernel_us": round(avg_us, 2),
+                           "timed_launches": launches, "of_launches": len(launch_bytes),
                            "algorithmic_bytes_per_launch": int(per_launch_bytes)}
+        if args.unfused:
+            res["roofline"]["avg_merge_kernel_us"] = round(merge_ns / max(launches, 1) / 1e3, 2)
     if not args.no_cpu_baseline:
-        res["cpu_baseline"] = cpu_baseline(w, eng, torch)
+        res["cpu_baseline"] = cpu_baseline(w, lens_at_start)
     eng.close()
     print(json.dumps(res))
 

@@ -181,7 +181,8 @@ int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, 
  *                  about this many work items; 0 or -1 (default): use "chunk" as is
  *   "grid_blocks"  workgroups launched (0 = library default)
  *   "variant"      kernel variant index, -1 = default (see get "n_variants")
- *   "profile"      1: bracket every attention launch with HIP events on its stream; 0: off + reset
+ *   "profile"      k > 0: bracket every k-th attention launch (counted from this call) with HIP events
+ *                  on its stream; 0: off; both reset the sums
  * get names: the above plus "n_variants", "n_grows", "live_slots", "scratch_bytes", "num_cus" and,
  * after "profile" 1, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
  * launches since the last reset; reading them waits for the recorded events).

@@ -240,11 +240,12 @@ extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
         a->variant = (int32_t)value;
         return S3_OK;
     }
-    if (!strcmp(name, "profile")) {  // 1: time every attention launch with events; 0: off (and reset)
-        if (value != 0 && value != 1) return S3_ERR_INVALID;
+    if (!strcmp(name, "profile")) {  // k > 0: time every k-th attention launch with events; 0: off; both reset
+        if (value < 0 || value > 1000000) return S3_ERR_INVALID;
         if (!a->base) return S3_ERR_INVALID;
         s3i_profile_reset(a);
-        a->profile = value != 0;
+        a->profile = (int32_t)value;
+        a->prof_tick = 0;
         return S3_OK;
     }
     return S3_ERR_INVALID;

@@ -34,7 +34,8 @@ struct s3_arena {
     size_t scratch_bytes = 0;
 
     // optional timing of the attention kernels with events on the launch stream
-    bool profile = false;
+    int32_t profile = 0;       // k > 0: bracket every k-th attention launch with events
+    int64_t prof_tick = 0;     // attention launches since profiling was switched on
     std::vector<void *> prof_events;  // triples: before partial, after partial, after merge
     size_t prof_used = 0;             // events handed out since the last collect
     double prof_partial_ms = 0.0, prof_merge_ms = 0.0;

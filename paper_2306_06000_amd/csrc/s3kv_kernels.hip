@@ -903,7 +903,8 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
     args.target_items = adaptive ? a->target_items : 0;
     const size_t dyn_lds = (size_t)2 * (n + 1) * sizeof(int);
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
-    if (a->profile) {
+    const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
+    if (timed) {
         for (int i = 0; i < 3; i++) {
             const int prc = prof_next_event(a, &ev[i]);
             if (prc != S3_OK) return prc;
@@ -912,7 +913,7 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
     }
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)(nw * 64)), dyn_lds, (hipStream_t)stream, args);
     HIP_TRY(hipGetLastError());
-    if (a->profile) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
+    if (timed) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
     if (!fused) {
         const unsigned mblocks = (unsigned)(((int64_t)n * n_hg + 3) / 4);
         void (*mfn)(const AttnArgs) =
@@ -920,7 +921,7 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
         hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, args);
         HIP_TRY(hipGetLastError());
     }
-    if (a->profile) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
+    if (timed) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
     return S3_OK;
 }
 
