@@ -173,6 +173,13 @@ int s3_kv_batch_patch(int32_t n, int64_t *slot_off, int32_t *len, int32_t n_upda
 int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,
                     int32_t n_rows, void *dst, void *stream);
 
+/* Measurement aid: the rate a plain streaming kernel reaches over the first `bytes` of the arena
+ * (mode 0: 128-bit reads only; mode 1: copy of the first `bytes` onto the next `bytes`, counted as
+ * 2*bytes moved), averaged over `reps` back-to-back launches on the default stream, in GB/s.
+ * DESTROYS arena contents in mode 1.  Synchronises the device.  Says what fraction of the nominal
+ * HBM peak is attainable at all, next to the attention kernel's own figure. */
+int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps, double *gbps /*HOST*/);
+
 /* Launch-shape knobs of the attention kernels and measurement switches.  set names:
  *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default); for
  *                  s3_decode_step the upper bound of the chunk the kernel picks itself

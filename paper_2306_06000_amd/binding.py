@@ -42,6 +42,7 @@ SIGNATURES = {
     "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "s3_kv_batch_patch": (ctypes.c_int, [_i32, _vp, _vp, _i32, _pi32, _pi64, _pi32, _vp]),
     "s3_kv_read_rows": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp]),
+    "s3_kv_probe_bandwidth": (ctypes.c_int, [_vp, ctypes.c_size_t, _i32, _i32, ctypes.POINTER(ctypes.c_double)]),
     "s3_kv_set_param": (ctypes.c_int, [_vp, ctypes.c_char_p, _i64]),
     "s3_kv_get_param": (ctypes.c_int, [_vp, ctypes.c_char_p, _pi64]),
     "s3_last_hip_error": (ctypes.c_char_p, []),
@@ -182,6 +183,13 @@ def s3_kv_batch_patch(n, slot_off, length, idx, new_off, new_len, stream=0):
 def s3_kv_read_rows(arena, slot_id, layer, which, first_row, n_rows, dst, stream=0):
     return lib().s3_kv_read_rows(arena, int(slot_id), int(layer), int(which), int(first_row), int(n_rows), _ptr(dst),
                                  stream or None)
+
+
+def s3_kv_probe_bandwidth(arena, nbytes, mode=0, reps=10):
+    """-> (status, GB/s) of a plain streaming read (mode 0) or copy (mode 1) over the arena's first bytes."""
+    g = ctypes.c_double(0.0)
+    st = lib().s3_kv_probe_bandwidth(arena, int(nbytes), int(mode), int(reps), ctypes.byref(g))
+    return st, g.value
 
 
 def s3_kv_set_param(arena, name, value):

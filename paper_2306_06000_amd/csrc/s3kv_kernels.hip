@@ -121,6 +121,59 @@ int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src
 }
 
 // ------------------------------------------------------------------------------------------
+// bandwidth probe: what a plain streaming kernel reaches on this device, to put the attention
+// kernel's number next to (the attainable HBM rate is below the nominal peak)
+// ------------------------------------------------------------------------------------------
+static int ensure_scratch(s3_arena *a, size_t need);
+
+__global__ void __launch_bounds__(256) read_probe_kernel(const char *src, size_t n16, unsigned int *sink) {
+    const u32x4 *s = (const u32x4 *)src;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 a = __builtin_nontemporal_load(s + i), b = __builtin_nontemporal_load(s + i + stride),
+                    c = __builtin_nontemporal_load(s + i + 2 * stride), d = __builtin_nontemporal_load(s + i + 3 * stride);
+        acc ^= a ^ b ^ c ^ d;
+    }
+    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(s + i);
+    const unsigned int x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+    if (x == 0x9E3779B9u) *sink = x;  // practically never: keeps the loads alive
+}
+
+extern "C" int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps, double *gbps) {
+    if (!a || !a->base || !gbps || reps <= 0 || (mode != 0 && mode != 1)) return S3_ERR_INVALID;
+    bytes &= ~(size_t)15;
+    if (bytes == 0 || (mode == 0 ? bytes : 2 * bytes) > a->dev_bytes) return S3_ERR_INVALID;
+    const int rc = ensure_scratch(a, 256);
+    if (rc != S3_OK) return rc;
+    hipEvent_t e0, e1;
+    HIP_TRY(hipEventCreate(&e0));
+    HIP_TRY(hipEventCreate(&e1));
+    const size_t n16 = bytes / 16;
+    const int cus = a->num_cus > 0 ? a->num_cus : 256;
+    for (int r = -2; r < reps; r++) {  // two untimed warm-up passes
+        if (r == 0) HIP_TRY(hipEventRecord(e0, nullptr));
+        if (mode == 0) {
+            hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)(cus * 8)), dim3(256), 0, nullptr, a->base, n16,
+                               (unsigned int *)((char *)a->scratch + 128));
+        } else {
+            hipLaunchKernelGGL(copy_planes_kernel, dim3((unsigned)(cus * 8), 1), dim3(256), 0, nullptr, a->base,
+                               a->base + bytes, n16, (size_t)0, (size_t)0);
+        }
+        HIP_TRY(hipGetLastError());
+    }
+    HIP_TRY(hipEventRecord(e1, nullptr));
+    HIP_TRY(hipEventSynchronize(e1));
+    float ms = 0.f;
+    HIP_TRY(hipEventElapsedTime(&ms, e0, e1));
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    *gbps = (double)(mode == 0 ? bytes : 2 * bytes) * reps / (ms * 1e-3) / 1e9;
+    return S3_OK;
+}
+
+// ------------------------------------------------------------------------------------------
 // append
 // ------------------------------------------------------------------------------------------
 // grid (n, 2): block (b, which) copies one row of H*D elements into row off+pos of the plane.
