@@ -499,44 +499,37 @@ __device__ __forceinline__ Item decode_item(const AttnArgs &a, const int *cum, i
 // DT: element type of q/K/V.  D: head_dim.  U: tokens per load batch.  NT: non-temporal loads.
 // FUSED: row len-1 is still only in k_new / v_new: it is taken from there and, by the wave whose
 // range holds it, written into the arena (the append).
+// PF: software pipelining - the loads of the next batch of U tokens are issued before the current
+// batch is reduced, so the wave always has loads in flight (two register sets, used alternately).
 template <int DT, int D, int U, bool NT, bool FUSED>
-__device__ __forceinline__ void wave_tokens(const AttnArgs &a, const Item &it, int hg, int j0, int j1, float &m,
-                                            float &l, float (&acc)[8]) {
-    constexpr int LPH = D / 8;    // lanes per head
-    constexpr int GH = 64 / LPH;  // heads per wave
-    const int lane = threadIdx.x & 63;
-    const int g = lane / LPH, dl = lane % LPH;
-    const int h = hg * GH + g;
-    const bool h_ok = h < a.H;
-    const int hc = h_ok ? h : a.H - 1;
-    const int64_t rstride = (int64_t)a.H * D * 2;
-    const int64_t lane_byte = ((int64_t)hc * D + dl * 8) * 2;
-    const char *kp = a.kplane + it.off * rstride + lane_byte;
-    const char *vp = a.vplane + it.off * rstride + lane_byte;
-    const int64_t in_byte = ((int64_t)it.b * a.H * D) * 2 + lane_byte;  // this lane's slice of row b of q/k_new/v_new
-    const u32x4 qv = *(const u32x4 *)(a.q + in_byte);
-    const int jnew = FUSED ? it.len - 1 : -1;
+struct TokenStream {
+    static constexpr int LPH = D / 8;    // lanes per head
+    static constexpr int GH = 64 / LPH;  // heads per wave
+    const char *kp, *vp, *knew, *vnew;
+    int64_t rstride;
+    int jnew, j1;
+    float scale_log2e;
+    u32x4 qv;
 
-    m = -INFINITY;
-    l = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; i++) acc[i] = 0.f;
-    for (int j = j0; j < j1; j += U) {
-        u32x4 kk[U], vv[U];
+    __device__ __forceinline__ void load(int j, u32x4 (&kk)[U], u32x4 (&vv)[U]) const {
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const int jj = min(j + u, j1 - 1);
             const char *src = kp + (int64_t)jj * rstride;
-            if (FUSED) src = (jj == jnew) ? a.k_new + in_byte : src;
+            if (FUSED) src = (jj == jnew) ? knew : src;
             kk[u] = load16<NT>(src);
         }
 #pragma unroll
         for (int u = 0; u < U; u++) {
             const int jj = min(j + u, j1 - 1);
             const char *src = vp + (int64_t)jj * rstride;
-            if (FUSED) src = (jj == jnew) ? a.v_new + in_byte : src;
+            if (FUSED) src = (jj == jnew) ? vnew : src;
             vv[u] = load16<NT>(src);
         }
+    }
+
+    __device__ __forceinline__ void reduce(int j, const u32x4 (&kk)[U], const u32x4 (&vv)[U], float &m, float &l,
+                                           float (&acc)[8]) const {
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; u++) s[u] = dot8<DT>(qv, kk[u]);
@@ -545,7 +538,7 @@ __device__ __forceinline__ void wave_tokens(const AttnArgs &a, const Item &it, i
         float mb = -INFINITY;
 #pragma unroll
         for (int u = 0; u < U; u++) {
-            s[u] = (j + u < j1) ? s[u] * a.scale_log2e : -INFINITY;
+            s[u] = (j + u < j1) ? s[u] * scale_log2e : -INFINITY;
             mb = fmaxf(mb, s[u]);
         }
         const float mn = fmaxf(m, mb);  // finite: the batch holds at least one real token
@@ -561,9 +554,57 @@ __device__ __forceinline__ void wave_tokens(const AttnArgs &a, const Item &it, i
         }
         m = mn;
     }
-    if (FUSED && h_ok && j0 <= jnew && jnew < j1) {  // the append: this wave owns the new row's slice
-        *(u32x4 *)(a.kplane + (it.off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.k_new + in_byte);
-        *(u32x4 *)(a.vplane + (it.off + jnew) * rstride + lane_byte) = *(const u32x4 *)(a.v_new + in_byte);
+};
+
+template <int DT, int D, int U, bool NT, bool FUSED, bool PF>
+__device__ __forceinline__ void wave_tokens(const AttnArgs &a, const Item &it, int hg, int j0, int j1, float &m,
+                                            float &l, float (&acc)[8]) {
+    typedef TokenStream<DT, D, U, NT, FUSED> TS_t;
+    const int lane = threadIdx.x & 63;
+    const int g = lane / TS_t::LPH, dl = lane % TS_t::LPH;
+    const int h = hg * TS_t::GH + g;
+    const bool h_ok = h < a.H;
+    const int hc = h_ok ? h : a.H - 1;
+    const int64_t rstride = (int64_t)a.H * D * 2;
+    const int64_t lane_byte = ((int64_t)hc * D + dl * 8) * 2;
+    const int64_t in_byte = ((int64_t)it.b * a.H * D) * 2 + lane_byte;  // this lane's slice of row b of q/k_new/v_new
+    TS_t st;
+    st.kp = a.kplane + it.off * rstride + lane_byte;
+    st.vp = a.vplane + it.off * rstride + lane_byte;
+    st.knew = FUSED ? a.k_new + in_byte : nullptr;
+    st.vnew = FUSED ? a.v_new + in_byte : nullptr;
+    st.rstride = rstride;
+    st.jnew = FUSED ? it.len - 1 : -1;
+    st.j1 = j1;
+    st.scale_log2e = a.scale_log2e;
+    st.qv = *(const u32x4 *)(a.q + in_byte);
+
+    m = -INFINITY;
+    l = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] = 0.f;
+    if (!PF) {
+        for (int j = j0; j < j1; j += U) {
+            u32x4 kk[U], vv[U];
+            st.load(j, kk, vv);
+            st.reduce(j, kk, vv, m, l, acc);
+        }
+    } else if (j0 < j1) {
+        u32x4 ka[U], va[U], kb[U], vb[U];
+        st.load(j0, ka, va);
+        for (int j = j0; j < j1; j += 2 * U) {
+            const bool more = j + U < j1;
+            if (more) st.load(j + U, kb, vb);
+            st.reduce(j, ka, va, m, l, acc);
+            if (more) {
+                if (j + 2 * U < j1) st.load(j + 2 * U, ka, va);
+                st.reduce(j + U, kb, vb, m, l, acc);
+            }
+        }
+    }
+    if (FUSED && h_ok && j0 <= st.jnew && st.jnew < j1) {  // the append: this wave owns the new row's slice
+        *(u32x4 *)(a.kplane + (it.off + st.jnew) * rstride + lane_byte) = *(const u32x4 *)(a.k_new + in_byte);
+        *(u32x4 *)(a.vplane + (it.off + st.jnew) * rstride + lane_byte) = *(const u32x4 *)(a.v_new + in_byte);
     }
 }
 
@@ -616,7 +657,7 @@ __device__ __forceinline__ void emit_chunk(const AttnArgs &a, const Item &it, in
 
 // Attention only (s3_decode_attention): TS*HS waves; the TS waves of a head group split the chunk's
 // tokens and merge through LDS; multi-chunk contexts are finished by attn_merge_kernel.
-template <int DT, int D, int TS, int HS, int U, bool NT>
+template <int DT, int D, int TS, int HS, int U, bool NT, bool PF>
 __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArgs a) {
     constexpr int LPH = D / 8;
     constexpr int GH = 64 / LPH;
@@ -638,7 +679,7 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
         int j0, j1;
         split_rows(it, ts, TS, j0, j1);
         float m, l, acc[8];
-        wave_tokens<DT, D, U, NT, false>(a, it, hg, j0, j1, m, l, acc);
+        wave_tokens<DT, D, U, NT, false, PF>(a, it, hg, j0, j1, m, l, acc);
         if (TS > 1) {
             comb[wave][0][lane] = m;
             comb[wave][1][lane] = l;
@@ -660,7 +701,7 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
 // announces the chunk on the context's arrival counter and, if it delivered the last chunk, merges
 // the chunks; all its memory latencies overlap with the compute waves' next item.  Workgroup 0
 // also publishes len_out and the zero rows of empty contexts.
-template <int DT, int D, int TS, int HS, int U, bool NT>
+template <int DT, int D, int TS, int HS, int U, bool NT, bool PF>
 __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const AttnArgs a) {
     constexpr int LPH = D / 8;
     constexpr int GH = 64 / LPH;
@@ -694,7 +735,7 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
             int j0, j1;
             split_rows(it, ts, TS, j0, j1);
             float m, l, acc[8];
-            wave_tokens<DT, D, U, NT, true>(a, it, it.hgb * HS + hs, j0, j1, m, l, acc);
+            wave_tokens<DT, D, U, NT, true, PF>(a, it, it.hgb * HS + hs, j0, j1, m, l, acc);
             comb[parity][wave][0][lane] = m;
             comb[parity][wave][1][lane] = l;
 #pragma unroll
@@ -757,25 +798,36 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
 // variant table and launchers
 // ------------------------------------------------------------------------------------------
 struct Variant {
-    int ts, hs, u, nt;
+    int ts, hs, u, nt, pf;
 };
-#define S3_VARIANTS(X) \
-    X(0, 4, 1, 4, true)   \
-    X(1, 8, 1, 4, true)   \
-    X(2, 4, 2, 4, true)   \
-    X(3, 1, 4, 4, true)   \
-    X(4, 8, 1, 8, true)   \
-    X(5, 2, 4, 4, true)   \
-    X(6, 1, 8, 4, true)   \
-    X(7, 4, 1, 2, true)   \
-    X(8, 4, 1, 4, false)  \
-    X(9, 8, 1, 4, false)  \
-    X(10, 4, 1, 8, true)  \
-    X(11, 2, 2, 4, true)  \
-    X(12, 2, 1, 8, true)  \
-    X(13, 4, 2, 8, true)
+// (index, TS, HS, U, NT, PF)
+#define S3_VARIANTS(X)            \
+    X(0, 4, 1, 4, true, false)    \
+    X(1, 8, 1, 4, true, false)    \
+    X(2, 4, 2, 4, true, false)    \
+    X(3, 1, 4, 4, true, false)    \
+    X(4, 8, 1, 8, true, false)    \
+    X(5, 2, 4, 4, true, false)    \
+    X(6, 1, 8, 4, true, false)    \
+    X(7, 4, 1, 2, true, false)    \
+    X(8, 4, 1, 4, false, false)   \
+    X(9, 8, 1, 4, false, false)   \
+    X(10, 4, 1, 8, true, false)   \
+    X(11, 2, 2, 4, true, false)   \
+    X(12, 2, 1, 8, true, false)   \
+    X(13, 4, 2, 8, true, false)   \
+    X(14, 7, 1, 4, true, true)    \
+    X(15, 3, 1, 4, true, true)    \
+    X(16, 8, 1, 2, true, true)    \
+    X(17, 8, 1, 4, true, true)    \
+    X(18, 7, 1, 2, true, true)    \
+    X(19, 15, 1, 2, true, true)   \
+    X(20, 15, 1, 4, true, true)   \
+    X(21, 7, 1, 4, true, false)   \
+    X(22, 7, 2, 2, true, true)    \
+    X(23, 4, 1, 4, true, true)
 static const Variant kVariants[] = {
-#define X(i, ts, hs, u, nt) {ts, hs, u, nt},
+#define X(i, ts, hs, u, nt, pf) {ts, hs, u, nt, pf},
     S3_VARIANTS(X)
 #undef X
 };
@@ -786,8 +838,8 @@ typedef void (*attn_fn)(const AttnArgs);
 template <int DT, int D, bool FUSED>
 static attn_fn pick_variant(int v) {
     switch (v) {
-#define X(i, ts, hs, u, nt) \
-    case i: return FUSED ? (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt> : (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt>;
+#define X(i, ts, hs, u, nt, pf) \
+    case i: return FUSED ? (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt, pf> : (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt, pf>;
         S3_VARIANTS(X)
 #undef X
         default: return nullptr;
