@@ -33,7 +33,7 @@ def parse():
     ap.add_argument("--grid-blocks", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time the attention kernel with events")
-    ap.add_argument("--event-every", type=int, default=8,
+    ap.add_argument("--event-every", type=int, default=16,
                     help="bracket every k-th attention launch with HIP events (each bracket costs a few us)")
     ap.add_argument("--c3-bytes", type=float, default=200e9)
     ap.add_argument("--unfused", action="store_true", help="append + attention + merge kernels instead of one")

@@ -181,11 +181,8 @@ int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, 
 int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps, double *gbps /*HOST*/);
 
 /* Launch-shape knobs of the attention kernels and measurement switches.  set names:
- *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default); for
- *                  s3_decode_step the upper bound of the chunk the kernel picks itself
- *   "chunk_min"    lower bound of that pick (multiple of 32; 0 = library default)
- *   "target_items" > 0: s3_decode_step picks its chunk on the device so that the batch's total rows make
- *                  about this many work items; 0 or -1 (default): use "chunk" as is
+ *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default)
+ *   "classes"      length classes of the longest-first work order (1..8; 0 = library default)
  *   "grid_blocks"  workgroups launched (0 = library default)
  *   "variant"      kernel variant index, -1 = default (see get "n_variants")
  *   "profile"      k > 0: bracket every k-th attention launch (counted from this call) with HIP events

@@ -220,14 +220,9 @@ extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
         a->chunk = (int32_t)value;
         return S3_OK;
     }
-    if (!strcmp(name, "chunk_min")) {
-        if (value != 0 && (value < 32 || value > 2048 || value % 32)) return S3_ERR_INVALID;
-        a->chunk_min = (int32_t)value;
-        return S3_OK;
-    }
-    if (!strcmp(name, "target_items")) {
-        if (value < -1 || value > (1 << 20)) return S3_ERR_INVALID;
-        a->target_items = (int32_t)value;
+    if (!strcmp(name, "classes")) {
+        if (value < 0 || value > 8) return S3_ERR_INVALID;
+        a->ncls = (int32_t)value;
         return S3_OK;
     }
     if (!strcmp(name, "grid_blocks")) {
@@ -255,8 +250,7 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
     if (!a || !name || !value) return S3_ERR_INVALID;
     if (!strcmp(name, "chunk")) *value = a->chunk;
     else if (!strcmp(name, "grid_blocks")) *value = a->grid_blocks;
-    else if (!strcmp(name, "chunk_min")) *value = a->chunk_min;
-    else if (!strcmp(name, "target_items")) *value = a->target_items;
+    else if (!strcmp(name, "classes")) *value = a->ncls;
     else if (!strcmp(name, "variant")) *value = a->variant;
     else if (!strcmp(name, "n_variants")) *value = s3i_num_variants();
     else if (!strcmp(name, "n_grows")) *value = a->n_grows;

@@ -43,8 +43,7 @@ struct s3_arena {
 
     // launch-shape knobs (0 = default)
     int32_t chunk = 0;
-    int32_t chunk_min = 0;
-    int32_t target_items = -1;  // -1: library default, 0: fixed chunks, > 0: items a fused launch aims at
+    int32_t ncls = 0;  // length classes of the work order (0: library default)
     int32_t grid_blocks = 0;
     int32_t variant = -1;
     int32_t num_cus = 0;

@@ -204,8 +204,7 @@ struct AttnArgs {
     float2 *part_ml;   // [n][max_chunks][H]  (running max in log2 units, sum)
     int64_t n_tokens;  // arena capacity N
     int32_t n, H, chunk, max_chunks, out_dtype, max_len;
-    int32_t chunk_min;     // smallest chunk the launch may choose (sizes max_chunks)
-    int32_t target_items;  // > 0: pick the chunk so that about this many (chunk, head block) items exist
+    int32_t ncls;          // length classes of the work order (1..8)
     int32_t len_add;    // 0: cur_len is the context length; 1 (fused step): cur_len is the append position
     float scale_log2e;  // scale * log2(e): scores are kept in log2 units so that exp is v_exp_f32
     // fused step only
@@ -317,77 +316,131 @@ __device__ __forceinline__ u32x4 load16(const char *p) {
     return NT ? __builtin_nontemporal_load((const u32x4 *)p) : *(const u32x4 *)p;
 }
 
-// Work order of a launch.  Contexts of two or more chunks come first (their chunks in batch order),
-// single-chunk contexts after them: the cross-workgroup merges of the long contexts then overlap with
-// the streaming of the short ones instead of forming the tail of the kernel.  The whole workgroup
-// builds two exclusive prefix sums in LDS: multi[0..n] counts chunks of multi-chunk contexts,
-// single[0..n] counts single-chunk contexts (layout: multi at cum[0], single at cum[n+1]).
+// Work order of a launch: longest contexts first.  Contexts are put into `ncls` length classes
+// relative to the longest context of the batch; the work list holds the chunks of class 0 (the longest)
+// in batch order, then class 1, and so on.  Long items therefore start first and the short ones fill
+// the end of the kernel (a ragged batch in random order ran 10 % slower), and the cross-workgroup
+// merges of multi-chunk contexts overlap with the streaming of the rest.  The whole workgroup builds
+// one exclusive prefix sum of chunk counts per class in LDS: pre[c][0..n] at cum[c * (n + 1)].
+#define S3_MAX_CLASSES 8
+#define S3_MAX_WAVES 16
+
 __device__ __forceinline__ int chunks_of(const AttnArgs &a, int b, int chunk) {
     return (checked_len(a, b) + chunk - 1) / chunk;
 }
 
-// Returns the chunk size of this launch: a.chunk, or (target_items > 0) the size that cuts the
-// batch's total rows into about target_items (chunk, head block) items, within [chunk_min, a.chunk],
-// so that every resident workgroup gets one item of similar size whatever the length mix is.
-__device__ __forceinline__ int scan_chunks(const AttnArgs &a, int *cum, int *wave_sums, int n_hgb) {
+__device__ __forceinline__ int class_of(int len, int max_len_seen, int ncls) {
+    return ncls - 1 - min(ncls - 1, len * ncls / (max_len_seen + 1));  // len * ncls < 2^31: len <= max_len <= 2^20
+}
+
+// Inclusive prefix sum over the 64 lanes of a wave with DPP row operations (no LDS round trips):
+// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the row totals are carried into the
+// following rows (row_bcast:15 into rows 1 and 3, row_bcast:31 into rows 2 and 3).
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_scan_step(int v) {
+    return v + __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false);
+}
+__device__ __forceinline__ int wave_inclusive_scan(int v) {
+    v = dpp_scan_step<0x111, 0xF>(v);  // row_shr:1
+    v = dpp_scan_step<0x112, 0xF>(v);  // row_shr:2
+    v = dpp_scan_step<0x114, 0xF>(v);  // row_shr:4
+    v = dpp_scan_step<0x118, 0xF>(v);  // row_shr:8
+    v = dpp_scan_step<0x142, 0xA>(v);  // row_bcast:15 -> rows 1, 3
+    v = dpp_scan_step<0x143, 0xC>(v);  // row_bcast:31 -> rows 2, 3
+    return v;
+}
+
+// LDS picture of the batch built by every workgroup at kernel start (dynamic shared memory):
+//   off[n] (int64), len[n] (int32, 0 for refused entries), pre[ncls][n + 1] (int32)
+struct BatchView {
+    const int64_t *off;
+    const int *len;
+    const int *pre;
+    int n, ncls, total;
+};
+
+__device__ __forceinline__ size_t batch_view_bytes(int n, int ncls) {
+    return (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)ncls * (n + 1) * 4;
+}
+
+// One pass over the device arrays (each entry is read from global memory once and checked once),
+// then class-wise exclusive prefix sums of the chunk counts.
+__device__ __forceinline__ BatchView build_batch_view(const AttnArgs &a, char *dyn, int *wave_sums) {
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int nthreads = blockDim.x, nwaves = nthreads >> 6;
-    int *multi = cum, *single = cum + a.n + 1;
-    const int per = (a.n + nthreads - 1) / nthreads;
-    const int b0 = min(a.n, tid * per), b1 = min(a.n, b0 + per);
-    int chunk = a.chunk;
-    if (a.target_items > 0) {
-        int rows = 0;
-        for (int b = b0; b < b1; b++) rows += checked_len(a, b);
-#pragma unroll
-        for (int d = 32; d >= 1; d >>= 1) rows += __shfl_xor(rows, d);
-        if (lane == 0) wave_sums[wave] = rows;
-        __syncthreads();
-        int64_t total_rows = 0;
-        for (int i = 0; i < nwaves; i++) total_rows += wave_sums[i];
-        __syncthreads();  // wave_sums is reused below
-        const int64_t want = (total_rows * n_hgb + a.target_items - 1) / a.target_items;
-        chunk = (int)min((int64_t)a.chunk, max((int64_t)a.chunk_min, (want + 31) / 32 * 32));
-    }
-    int sum_m = 0, sum_s = 0;
+    const int ncls = a.ncls, chunk = a.chunk, n = a.n;
+    int64_t *off_s = (int64_t *)dyn;
+    int *len_s = (int *)(dyn + (size_t)n * 8);
+    int *pre = len_s + ((n + 1) & ~1);
+    const int per = (n + nthreads - 1) / nthreads;
+    const int b0 = min(n, tid * per), b1 = min(n, b0 + per);
+    int mx = 0;
     for (int b = b0; b < b1; b++) {
-        const int k = chunks_of(a, b, chunk);
-        sum_m += k >= 2 ? k : 0;
-        sum_s += k == 1;
+        const int len = checked_len(a, b);
+        len_s[b] = len;
+        off_s[b] = a.slot_off[b];
+        mx = max(mx, len);
     }
-    int incl_m = sum_m, incl_s = sum_s;
 #pragma unroll
-    for (int d = 1; d < 64; d <<= 1) {
-        const int tm = __shfl_up(incl_m, d), tsn = __shfl_up(incl_s, d);
-        if (lane >= d) {
-            incl_m += tm;
-            incl_s += tsn;
+    for (int d = 32; d >= 1; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
+    if (lane == 0) wave_sums[wave] = mx;
+    __syncthreads();
+    for (int i = 0; i < nwaves; i++) mx = max(mx, wave_sums[i]);
+    __syncthreads();  // wave_sums is reused below
+    int cnt[S3_MAX_CLASSES], incl[S3_MAX_CLASSES];
+#pragma unroll
+    for (int c = 0; c < S3_MAX_CLASSES; c++) cnt[c] = 0;
+    for (int b = b0; b < b1; b++) {
+        const int len = len_s[b];
+        const int k = (len + chunk - 1) / chunk;
+        const int cl = class_of(len, mx, ncls);
+#pragma unroll
+        for (int c = 0; c < S3_MAX_CLASSES; c++) cnt[c] += (c == cl) ? k : 0;
+    }
+#pragma unroll
+    for (int c = 0; c < S3_MAX_CLASSES; c++) {
+        if (c < ncls) {  // uniform
+            const int v = wave_inclusive_scan(cnt[c]);
+            incl[c] = v;
+            if (lane == 63) wave_sums[c * S3_MAX_WAVES + wave] = v;
         }
     }
-    if (lane == 63) {
-        wave_sums[wave] = incl_m;
-        wave_sums[nwaves + wave] = incl_s;
-    }
     __syncthreads();
-    int base_m = 0, base_s = 0;
-    for (int i = 0; i < wave; i++) {
-        base_m += wave_sums[i];
-        base_s += wave_sums[nwaves + i];
+    int run[S3_MAX_CLASSES];
+#pragma unroll
+    for (int c = 0; c < S3_MAX_CLASSES; c++) {
+        run[c] = 0;
+        if (c < ncls) {
+            int base = 0;
+            for (int i = 0; i < wave; i++) base += wave_sums[c * S3_MAX_WAVES + i];
+            run[c] = base + incl[c] - cnt[c];
+        }
     }
-    int run_m = base_m + incl_m - sum_m, run_s = base_s + incl_s - sum_s;
     for (int b = b0; b < b1; b++) {
-        const int k = chunks_of(a, b, chunk);
-        multi[b] = run_m;
-        single[b] = run_s;
-        run_m += k >= 2 ? k : 0;
-        run_s += k == 1;
+        const int len = len_s[b];
+        const int k = (len + chunk - 1) / chunk;
+        const int cl = class_of(len, mx, ncls);
+#pragma unroll
+        for (int c = 0; c < S3_MAX_CLASSES; c++) {
+            if (c < ncls) pre[c * (n + 1) + b] = run[c];
+            run[c] += (c == cl) ? k : 0;
+        }
     }
     if (tid == nthreads - 1) {
-        multi[a.n] = run_m;
-        single[a.n] = run_s;
+#pragma unroll
+        for (int c = 0; c < S3_MAX_CLASSES; c++)
+            if (c < ncls) pre[c * (n + 1) + n] = run[c];
     }
     __syncthreads();
-    return chunk;
+    BatchView v;
+    v.off = off_s;
+    v.len = len_s;
+    v.pre = pre;
+    v.n = n;
+    v.ncls = ncls;
+    v.total = 0;
+    for (int c = 0; c < ncls; c++) v.total += pre[c * (n + 1) + n];
+    return v;
 }
 
 // Partials that cross workgroups inside ONE launch (fused step) must not sit in a cache that
@@ -471,27 +524,33 @@ __device__ __forceinline__ void split_rows(const Item &it, int ts, int TS, int &
     j1 = min(end, j0 + per);
 }
 
-__device__ __forceinline__ Item decode_item(const AttnArgs &a, const int *cum, int64_t item, int n_hgb, int chunk) {
+__device__ __forceinline__ Item decode_item(const AttnArgs &a, const BatchView &v, int64_t item, int n_hgb) {
     Item it;
     int w = (int)(item / n_hgb);
     it.hgb = (int)(item - (int64_t)w * n_hgb);
-    const int *pre = cum;  // multi-chunk contexts first
-    const bool is_single = w >= cum[a.n];
-    if (is_single) {
-        w -= cum[a.n];
-        pre = cum + a.n + 1;
+    const int *pre = v.pre;
+    for (int c = 0; c < v.ncls - 1; c++) {  // which class the item falls into
+        const int t = pre[v.n];
+        if (w < t) break;
+        w -= t;
+        pre += v.n + 1;
     }
-    int lo = 0, hi = a.n - 1;
+    int lo = 0, hi = v.n - 1;
     while (lo < hi) {  // first b with pre[b+1] > w
         const int mid = (lo + hi) >> 1;
         if (pre[mid + 1] > w) hi = mid; else lo = mid + 1;
     }
     it.b = lo;
-    it.c = is_single ? 0 : w - pre[lo];
-    it.nchunks = is_single ? 1 : pre[lo + 1] - pre[lo];
-    it.len = checked_len(a, lo);
-    it.off = a.slot_off[lo];
-    it.clen = balanced_chunk_len(it.len, it.nchunks, chunk);
+    it.c = w - pre[lo];
+    it.nchunks = pre[lo + 1] - pre[lo];
+    it.len = v.len[lo];
+    it.off = v.off[lo];
+    if (it.c < 0 || it.c >= it.nchunks) {  // cannot happen with a consistent view; never index rows from it
+        it.c = 0;
+        it.nchunks = 1;
+        it.len = 0;
+    }
+    it.clen = balanced_chunk_len(it.len, it.nchunks, a.chunk);
     return it;
 }
 
@@ -662,19 +721,19 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
     constexpr int LPH = D / 8;
     constexpr int GH = 64 / LPH;
     constexpr int NW = TS * HS;
-    extern __shared__ int cum[];  // [2][n + 1]
-    __shared__ int wave_sums[2 * NW];
+    extern __shared__ __align__(16) char dyn_lds[];  // the batch view
+    __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
     __shared__ float comb[TS > 1 ? NW : 1][10][64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int ts = wave % TS, hs = wave / TS;
     const int n_hg = (a.H + GH - 1) / GH;
     const int n_hgb = (n_hg + HS - 1) / HS;
-    const int chunk = scan_chunks(a, cum, wave_sums, n_hgb);
-    const int64_t total = (int64_t)(cum[a.n] + cum[2 * a.n + 1]) * n_hgb;
+    const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
+    const int64_t total = (int64_t)bv.total * n_hgb;
 
     for (int64_t item = blockIdx.x; item < total; item += gridDim.x) {
-        const Item it = decode_item(a, cum, item, n_hgb, chunk);
+        const Item it = decode_item(a, bv, item, n_hgb);
         const int hg = it.hgb * HS + hs;
         int j0, j1;
         split_rows(it, ts, TS, j0, j1);
@@ -706,8 +765,8 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
     constexpr int LPH = D / 8;
     constexpr int GH = 64 / LPH;
     constexpr int NWC = TS * HS;  // compute waves
-    extern __shared__ int cum[];  // [2][n + 1]
-    __shared__ int wave_sums[2 * (NWC + 1)];
+    extern __shared__ __align__(16) char dyn_lds[];  // the batch view
+    __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
     __shared__ float comb[2][NWC][10][64];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -715,22 +774,26 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
     const int ts = wave % TS, hs = wave / TS;
     const int n_hg = (a.H + GH - 1) / GH;
     const int n_hgb = (n_hg + HS - 1) / HS;
-    const int chunk = scan_chunks(a, cum, wave_sums, n_hgb);
-    const int64_t total = (int64_t)(cum[a.n] + cum[2 * a.n + 1]) * n_hgb;
+    const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
+    const int64_t total = (int64_t)bv.total * n_hgb;
 
     if (blockIdx.x == 0) {
-        for (int b = threadIdx.x; b < a.n; b += (NWC + 1) * 64) {
-            if (a.len_out) a.len_out[b] = a.cur_len[b] + 1;
-            if (chunks_of(a, b, chunk) == 0) {  // empty or refused context: zero output row
+        const int nthreads = (NWC + 1) * 64;
+        if (a.len_out)
+            for (int b = threadIdx.x; b < a.n; b += nthreads) a.len_out[b] = a.cur_len[b] + 1;
+        const int per_row = a.H * D / 8;  // empty or refused contexts get a zero output row
+        for (int64_t e = threadIdx.x; e < (int64_t)a.n * per_row; e += nthreads) {
+            const int b = (int)(e / per_row);
+            if (bv.len[b] == 0) {
                 const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                for (int e = 0; e < a.H * D; e += 8) store_out8(a.out, a.out_dtype, (int64_t)b * a.H * D + e, z);
+                store_out8(a.out, a.out_dtype, e * 8, z);
             }
         }
     }
 
     int parity = 0;
     for (int64_t item = blockIdx.x; item < total; item += gridDim.x, parity ^= 1) {
-        const Item it = decode_item(a, cum, item, n_hgb, chunk);
+        const Item it = decode_item(a, bv, item, n_hgb);
         if (!epilogue) {
             int j0, j1;
             split_rows(it, ts, TS, j0, j1);
@@ -811,21 +874,13 @@ struct Variant {
     X(6, 1, 8, 4, true, false)    \
     X(7, 4, 1, 2, true, false)    \
     X(8, 4, 1, 4, false, false)   \
-    X(9, 8, 1, 4, false, false)   \
-    X(10, 4, 1, 8, true, false)   \
-    X(11, 2, 2, 4, true, false)   \
-    X(12, 2, 1, 8, true, false)   \
-    X(13, 4, 2, 8, true, false)   \
-    X(14, 7, 1, 4, true, true)    \
-    X(15, 3, 1, 4, true, true)    \
-    X(16, 8, 1, 2, true, true)    \
-    X(17, 8, 1, 4, true, true)    \
-    X(18, 7, 1, 2, true, true)    \
-    X(19, 15, 1, 2, true, true)   \
-    X(20, 15, 1, 4, true, true)   \
-    X(21, 7, 1, 4, true, false)   \
-    X(22, 7, 2, 2, true, true)    \
-    X(23, 4, 1, 4, true, true)
+    X(9, 4, 1, 8, true, false)    \
+    X(10, 4, 2, 8, true, false)   \
+    X(11, 7, 1, 4, true, true)    \
+    X(12, 8, 1, 2, true, true)    \
+    X(13, 15, 1, 2, true, true)   \
+    X(14, 3, 1, 4, true, true)    \
+    X(15, 2, 1, 8, true, false)
 static const Variant kVariants[] = {
 #define X(i, ts, hs, u, nt, pf) {ts, hs, u, nt, pf},
     S3_VARIANTS(X)
@@ -976,12 +1031,11 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
     args.n = n;
     args.H = H;
     args.chunk = chunk;
-    // fused launches pick their chunk on the device between chunk_min and chunk, from the batch's
-    // total rows, aiming at target_items items; the partial buffer is sized for chunk_min
-    const bool adaptive = fused && a->target_items > 0;
-    args.chunk_min = adaptive ? (a->chunk_min > 0 ? a->chunk_min : 128) : chunk;
-    if (args.chunk_min > chunk) args.chunk_min = chunk;
-    args.max_chunks = (a->cfg.max_len + args.chunk_min - 1) / args.chunk_min;
+    args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
+    // length classes of the longest-first work order: small batches gain from it (their kernels are
+    // short, the tail matters); for large batches the extra prologue work per class costs more than
+    // the order gains.  Measured on MI355X.
+    args.ncls = a->ncls > 0 ? a->ncls : n <= 128 ? 4 : n <= 256 ? 2 : 1;
     args.out_dtype = out_dtype;
     args.max_len = a->cfg.max_len;
     args.len_add = fused ? 1 : 0;
@@ -1004,9 +1058,26 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
 
     const int nw = vr.ts * vr.hs + (fused ? 1 : 0);  // the fused kernel adds an epilogue wave
     const int cus = a->num_cus > 0 ? a->num_cus : 256;
-    const int blocks = a->grid_blocks > 0 ? a->grid_blocks : cus * (32 / (vr.ts * vr.hs));
-    args.target_items = adaptive ? a->target_items : 0;
-    const size_t dyn_lds = (size_t)2 * (n + 1) * sizeof(int);
+    const size_t dyn_lds = (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)args.ncls * (n + 1) * 4;
+    // Grid: exactly the workgroups that are resident at once (every workgroup pays the batch-view
+    // prologue once and then walks the work list with a stride).  Asked from the runtime once per
+    // kernel and LDS size class.
+    int blocks = a->grid_blocks;
+    if (blocks <= 0) {
+        static std::map<std::pair<const void *, size_t>, int> resident;  // (kernel, LDS KiB) -> workgroups per CU
+        const std::pair<const void *, size_t> key((const void *)fn, (dyn_lds + 4095) / 4096);
+        auto it = resident.find(key);
+        if (it == resident.end()) {
+            if (dyn_lds > 16384)
+                HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                            (int)(key.second * 4096)));
+            int per_cu = 0;
+            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)fn, nw * 64, key.second * 4096));
+            if (per_cu < 1) return S3_ERR_INVALID;  // does not fit the device at all
+            it = resident.emplace(key, per_cu).first;
+        }
+        blocks = cus * it->second * (n > 128 ? 2 : 1);  // large batches: two rounds balance better than one
+    }
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
     if (timed) {
