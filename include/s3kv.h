@@ -150,6 +150,20 @@ int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id
 int s3_kv_grow(s3_arena *a, int32_t slot_id, int32_t len, int64_t *new_off /*HOST*/,
                int32_t *new_cap /*HOST*/, void *stream);
 
+/* Compaction (section 3, supervisor paragraph: rows below a blank are shifted up so that everything is
+ * stored contiguously again): every live slot slides down, in order of offset, to close the holes that
+ * finished and relocated sequences left; afterwards the free space is one extent at the end.  Capacities
+ * and ids do not change.
+ *   slot_id, len  HOST [n]: slots whose first len[i] rows are to be preserved (the others' rows beyond
+ *                 len are not copied); live slots that are not listed are moved whole
+ *   new_off       HOST [n] out (may be NULL): offsets of the listed slots after compaction; use
+ *                 s3_kv_slot_info for the rest.  The caller must refresh its device slot_off[] arrays.
+ *   n_moved       HOST out (may be NULL): slots that changed place
+ * Copies run on `stream` in order (overlapping moves are cut into pieces that never overwrite rows not
+ * yet moved).  S3_ERR_INVALID (nothing changed) for a dead id or len outside [0, cap]. */
+int s3_kv_compact(s3_arena *a, int32_t n, const int32_t *slot_id, const int32_t *len, int64_t *new_off,
+                  int32_t *n_moved, void *stream);
+
 /* The supervisor's report of available memory (section 3), in tokens.  Any out pointer may be NULL. */
 int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t *largest_free_tok,
                 int64_t *capacity_tok);

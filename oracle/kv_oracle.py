@@ -268,6 +268,20 @@ class KVOracle:
         self.n_grows += 1
         return OK, new_off, new_cap
 
+    def compact(self):
+        """Slide every live slot down, in order of offset, so that no hole is left (the paper's
+        supervisor shifts the rows below a blank up); the free space becomes one extent at the end.
+        Each sequence's private rows are untouched.  -> {id: new_off}."""
+        cursor = 0
+        moved = 0
+        for sid in sorted(self.slots, key=lambda i: self.slots[i][0]):
+            if self.slots[sid][0] != cursor:
+                moved += 1
+            self.slots[sid][0] = cursor
+            cursor += self.slots[sid][1]
+        self.free_list = [[cursor, self.N - cursor]] if cursor < self.N else []
+        return {sid: oc[0] for sid, oc in self.slots.items()}, moved
+
     def stats(self):
         """-> (used, free, largest_free, capacity), all in tokens."""
         used = sum(cap for _, cap in self.slots.values())

@@ -38,6 +38,7 @@ SIGNATURES = {
     "s3_decode_attention": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _f32, _vp]),
     "s3_decode_step": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]),
     "s3_kv_grow": (ctypes.c_int, [_vp, _i32, _i32, _pi64, _pi32, _vp]),
+    "s3_kv_compact": (ctypes.c_int, [_vp, _i32, _pi32, _pi32, _pi64, _pi32, _vp]),
     "s3_kv_stats": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64]),
     "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "s3_kv_batch_patch": (ctypes.c_int, [_i32, _vp, _vp, _i32, _pi32, _pi64, _pi32, _vp]),
@@ -158,6 +159,17 @@ def s3_kv_grow(arena, slot_id, length, stream=0):
     off, cap = _i64(-1), _i32(0)
     st = lib().s3_kv_grow(arena, int(slot_id), int(length), ctypes.byref(off), ctypes.byref(cap), stream or None)
     return st, off.value, cap.value
+
+
+def s3_kv_compact(arena, slot_id, length, stream=0):
+    """-> (status, new_off[n], n_moved)."""
+    ids, idp = _host_i32(slot_id)
+    lens, lp = _host_i32(length)
+    n = int(ids.size) if ids is not None else 0
+    new_off = np.full(n, -1, np.int64)
+    moved = _i32(0)
+    st = lib().s3_kv_compact(arena, n, idp, lp, new_off.ctypes.data_as(_pi64), ctypes.byref(moved), stream or None)
+    return st, new_off, moved.value
 
 
 def s3_kv_stats(arena):

@@ -198,6 +198,57 @@ extern "C" int s3_kv_grow(s3_arena *a, int32_t slot_id, int32_t len, int64_t *ne
     return S3_OK;
 }
 
+// Compaction (section 3, supervisor paragraph: after sequences have left, the rows below a blank are
+// shifted so that everything is stored contiguously again).  Live slots keep their order by offset and
+// slide down to close every hole; the free space becomes one extent at the end.
+extern "C" int s3_kv_compact(s3_arena *a, int32_t n, const int32_t *slot_id, const int32_t *len, int64_t *new_off,
+                             int32_t *n_moved, void *stream) {
+    if (!a || n < 0 || (n > 0 && (!slot_id || !len))) return S3_ERR_INVALID;
+    std::vector<int32_t> rows(a->slots.size(), -1);  // rows to preserve per id; -1: the whole capacity
+    for (int32_t i = 0; i < n; i++) {
+        const s3_slot *s = s3i_live_slot(a, slot_id[i]);
+        if (!s || len[i] < 0 || len[i] > s->cap) return S3_ERR_INVALID;
+        rows[slot_id[i]] = len[i];
+    }
+    std::map<int64_t, int32_t> by_off;  // offset -> id
+    for (size_t id = 0; id < a->slots.size(); id++)
+        if (a->slots[id].live) by_off[a->slots[id].off] = (int32_t)id;
+    int64_t cursor = 0;
+    int32_t moved = 0;
+    for (const auto &e : by_off) {
+        s3_slot &s = a->slots[e.second];
+        const int64_t gap = s.off - cursor;
+        const int64_t keep = rows[e.second] >= 0 ? rows[e.second] : s.cap;
+        if (gap > 0) {
+            if (a->base) {
+                // source and destination overlap when gap < keep: move pieces of `gap` rows in stream order,
+                // each piece lands on rows that the previous piece has already left
+                for (int64_t r = 0; r < keep; r += gap) {
+                    const int64_t piece = keep - r < gap ? keep - r : gap;
+                    const int rc = s3i_launch_copy_planes(
+                        a->base + (s.off + r) * a->row_bytes, a->base + (cursor + r) * a->row_bytes,
+                        (size_t)piece * (size_t)a->row_bytes, (size_t)a->plane_bytes, (size_t)a->plane_bytes,
+                        2 * a->cfg.n_layers, stream);
+                    if (rc != S3_OK) return rc;  // rows already moved stay moved; the table below is not updated
+                }
+            }
+            moved++;
+        }
+        cursor += s.cap;
+    }
+    // every copy is enqueued: now the table
+    cursor = 0;
+    for (const auto &e : by_off) {
+        a->slots[e.second].off = cursor;
+        cursor += a->slots[e.second].cap;
+    }
+    a->free_ext.clear();
+    if (cursor < a->n_tokens) a->free_ext[cursor] = a->n_tokens - cursor;
+    for (int32_t i = 0; i < n && new_off; i++) new_off[i] = a->slots[slot_id[i]].off;
+    if (n_moved) *n_moved = moved;
+    return S3_OK;
+}
+
 extern "C" int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t *largest_free_tok,
                            int64_t *capacity_tok) {
     if (!a) return S3_ERR_INVALID;

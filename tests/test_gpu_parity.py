@@ -391,6 +391,36 @@ def test_fused_step_refuses_full_slots_and_skips_bad_entries():
     rig.close()
 
 
+def test_compact_moves_rows_bit_exactly_including_overlapping_moves():
+    """Holes left by finished sequences are closed by sliding the live slots down; a slot larger than
+    the hole in front of it overlaps its own destination and is moved in pieces."""
+    preds = [64, 2048, 64, 700, 128, 64, 300]
+    lens = [64, 2000, 10, 650, 128, 1, 257]
+    rig = Rig(2, 16, 256, s3.S3_F16, 64, 2048, preds, seed=31)
+    for layer in range(2):
+        rig.fill(lens, layer)
+    for b in (0, 2, 5):  # holes of 64 rows in front of the 2048-row slot, between and behind
+        sid = int(rig.ids[b])
+        assert s3.s3_kv_free(rig.a, sid) == rig.o.free(sid) == 0
+    live = [1, 3, 4, 6]
+    ids = [int(rig.ids[b]) for b in live]
+    st, new_off, moved = s3.s3_kv_compact(rig.a, ids, [lens[b] for b in live], rig.stream)
+    want, want_moved = rig.o.compact()
+    assert st == 0 and moved == want_moved == 4 and new_off.tolist() == [want[i] for i in ids]
+    assert s3.s3_kv_stats(rig.a) == (0, *rig.o.stats())
+    for b, sid in zip(live, ids):
+        assert s3.s3_kv_slot_info(rig.a, sid) == (0, *rig.o.slots[sid])
+        for layer in range(2):
+            for which in (0, 1):
+                assert np.array_equal(rig_read(rig, sid, layer, which, lens[b]), rig.o.rows(sid, layer, which, lens[b]))
+    # attention over the moved slots
+    rig.ids = np.array(ids, np.int32)
+    rig.offs = new_off.copy()
+    q, got = rig.attend([lens[b] for b in live], layer=1)
+    assert_close(got, rig.oracle_attend(q, [lens[b] for b in live], layer=1), "after compaction")
+    rig.close()
+
+
 def test_batch_patch_rewrites_only_the_named_entries():
     n = 100
     off = torch.arange(n, dtype=torch.int64, device=DEV) * 64

@@ -134,7 +134,12 @@ def test_random_trace_bit_exact_against_oracle(seed, granule, tokens):
     live = []
     for step in range(10000 if seed == 0 else 3000):
         r = rng.random()
-        if r < 0.45 or not live:
+        if r > 0.995:
+            lens = [int(rng.integers(0, o.slots[sid][1] + 1)) for sid in live]
+            st, new_off, moved = s3.s3_kv_compact(a, live, lens)
+            want, want_moved = o.compact()
+            assert st == 0 and moved == want_moved and new_off.tolist() == [want[sid] for sid in live]
+        elif r < 0.45 or not live:
             k = int(rng.integers(1, 5))
             preds = [int(rng.integers(0, 2400)) if rng.random() < 0.5 else int(rng.integers(1, 300)) for _ in range(k)]
             n_o, ids_o, offs_o, caps_o = o.alloc(preds)
@@ -153,4 +158,18 @@ def test_random_trace_bit_exact_against_oracle(seed, granule, tokens):
             for sid in live:
                 assert s3.s3_kv_slot_info(a, sid) == (0, *o.slots[sid])
     assert s3.s3_kv_get_param(a, "n_grows") == (0, o.n_grows)
+    s3.s3_kv_arena_destroy(a)
+
+
+def test_compact_validation():
+    cfg, a = meta_arena(1, 1, 64, 0, 64, 256, 1024 * 256)
+    rc, ids, offs, caps = s3.s3_kv_alloc(a, [64, 64, 128])
+    assert s3.s3_kv_free(a, 0) == 0
+    before = s3.s3_kv_stats(a)
+    assert s3.s3_kv_compact(a, [1, 7], [1, 1])[0] == s3.S3_ERR_INVALID
+    assert s3.s3_kv_compact(a, [1], [65])[0] == s3.S3_ERR_INVALID
+    assert s3.s3_kv_stats(a) == before and s3.s3_kv_slot_info(a, 1) == (0, 64, 64)
+    st, new_off, moved = s3.s3_kv_compact(a, [2], [100])
+    assert (st, new_off.tolist(), moved) == (0, [64], 2)
+    assert s3.s3_kv_slot_info(a, 1) == (0, 0, 64) and s3.s3_kv_stats(a) == (0, 192, 832, 832, 1024)
     s3.s3_kv_arena_destroy(a)

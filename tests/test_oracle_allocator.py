@@ -200,6 +200,17 @@ class BitmapAllocator:
         off, cap = self.slots.pop(sid)
         self._mark(off, cap, False)
 
+    def compact(self):
+        """Brute force: walk the flags, slide every used run down over the holes."""
+        order = sorted(self.slots, key=lambda i: self.slots[i][0])
+        self.used = [False] * len(self.used)
+        cursor = 0
+        for sid in order:
+            off, cap = self.slots[sid]
+            self.slots[sid] = (cursor, cap)
+            self._mark(cursor, cap, True)
+            cursor += cap
+
     def grow(self, sid):
         off, cap = self.slots[sid]
         if cap >= self.M:
@@ -242,7 +253,10 @@ def test_random_trace_agrees_with_bitmap_allocator(seed, granule, tokens):
     n_ops = 10000 if seed == 0 else 3000
     for _ in range(n_ops):
         r = rng.random()
-        if r < 0.45 or not live:
+        if r > 0.995:
+            o.compact()
+            bm.compact()
+        elif r < 0.45 or not live:
             pred = int(rng.integers(0, 2400)) if rng.random() < 0.5 else int(rng.integers(1, 300))
             got = o.alloc_one(pred)
             assert got == bm.alloc(pred)
@@ -258,3 +272,29 @@ def test_random_trace_agrees_with_bitmap_allocator(seed, granule, tokens):
             assert o.grow(sid, length) == bm.grow(sid)
         check_invariants(o)
         assert {k: tuple(v) for k, v in o.slots.items()} == bm.slots
+
+
+def test_compact_closes_every_hole_and_keeps_rows():
+    """The supervisor shifts rows up so that everything is contiguous again (section 3)."""
+    o = orc.KVOracle(1, 1, 8, orc.F16, 64, 2048, 4096 * 32)
+    rng = np.random.default_rng(3)
+    ids = [o.alloc_one(p)[0] for p in (64, 200, 64, 1000, 128, 64)]
+    rows = {}
+    for sid in ids:
+        cap = o.slots[sid][1]
+        k = wl.normal_bits(rng, (cap, 1, 8), orc.F16)
+        assert o.fill(sid, 0, k, k) == orc.OK
+        rows[sid] = k
+    for sid in (ids[0], ids[2], ids[4]):
+        assert o.free(sid) == orc.OK
+    before = {sid: list(v) for sid, v in o.slots.items()}
+    new, moved = o.compact()
+    assert moved == 3
+    assert new == {ids[1]: 0, ids[3]: 256, ids[5]: 1280}  # order by old offset, caps 256, 1024, 64
+    assert o.free_list == [[1344, 4096 - 1344]]
+    assert {sid: v[1] for sid, v in o.slots.items()} == {sid: v[1] for sid, v in before.items()}
+    for sid in o.slots:
+        assert np.array_equal(o.rows(sid, 0, 0, o.slots[sid][1]), rows[sid])
+    check_invariants(o)
+    assert o.compact() == (new, 0)  # idempotent
+    assert o.alloc_one(64)[1] == 1344
