@@ -164,6 +164,22 @@ int s3_kv_grow(s3_arena *a, int32_t slot_id, int32_t len, int64_t *new_off /*HOS
 int s3_kv_compact(s3_arena *a, int32_t n, const int32_t *slot_id, const int32_t *len, int64_t *new_off,
                   int32_t *n_moved, void *stream);
 
+/* Eviction to the host and reload (the paper's own handling of a sequence that used up its reservation,
+ * section 3, supervisor paragraph; its cost is the "penalty" of section 4.3).  Use when s3_kv_grow
+ * answers S3_ERR_NOMEM, or to make room for others.
+ *   s3_kv_evict_bytes  bytes of host memory needed for len rows of every plane (< 0: bad argument)
+ *   s3_kv_evict        copies rows [0, len) of K and V of every layer to host_buf (HOST, pinned memory
+ *                      makes the copies asynchronous; layout [2*n_layers][len][H][D]) on `stream`, then
+ *                      frees the slot.  host_buf is complete once the stream has passed the copies.
+ *   s3_kv_restore      reserves a slot for predicted_len (>= len; the paper doubles the old reservation),
+ *                      copies the rows back on `stream`; returns the new id / offset / capacity.
+ *                      S3_ERR_NOMEM if nothing fits (state unchanged). */
+int64_t s3_kv_evict_bytes(const s3_arena *a, int32_t len);
+int s3_kv_evict(s3_arena *a, int32_t slot_id, int32_t len, void *host_buf /*HOST*/, void *stream);
+int s3_kv_restore(s3_arena *a, int32_t predicted_len, int32_t len, const void *host_buf /*HOST*/,
+                  int32_t *slot_id /*HOST out*/, int64_t *slot_off /*HOST out*/, int32_t *slot_cap /*HOST out*/,
+                  void *stream);
+
 /* The supervisor's report of available memory (section 3), in tokens.  Any out pointer may be NULL. */
 int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t *largest_free_tok,
                 int64_t *capacity_tok);

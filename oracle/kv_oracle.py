@@ -268,6 +268,28 @@ class KVOracle:
         self.n_grows += 1
         return OK, new_off, new_cap
 
+    def evict(self, sid, length):
+        """Move a sequence's rows [0, length) out of the cache (to the request pool in host memory, as
+        the paper's supervisor does with a sequence that ran out of room) and free its slot.
+        -> (status, rows [n_layers][2][length][H][D])."""
+        if sid not in self.slots or length < 0 or length > self.slots[sid][1]:
+            return ERR_INVALID, None
+        blob = self.data[sid][:, :, :length].copy()
+        self.free(sid)
+        return OK, blob
+
+    def restore(self, predicted_len, blob):
+        """Re-admit an evicted sequence with a new (the paper: doubled) reservation.
+        -> (status, id, off, cap)."""
+        length = blob.shape[2]
+        if predicted_len < length:
+            return ERR_INVALID, -1, -1, 0
+        sid, off, cap = self.alloc_one(predicted_len)
+        if sid < 0:
+            return ERR_NOMEM, -1, -1, 0
+        self.data[sid][:, :, :length] = blob
+        return OK, sid, off, cap
+
     def compact(self):
         """Slide every live slot down, in order of offset, so that no hole is left (the paper's
         supervisor shifts the rows below a blank up); the free space becomes one extent at the end.

@@ -39,6 +39,9 @@ SIGNATURES = {
     "s3_decode_step": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]),
     "s3_kv_grow": (ctypes.c_int, [_vp, _i32, _i32, _pi64, _pi32, _vp]),
     "s3_kv_compact": (ctypes.c_int, [_vp, _i32, _pi32, _pi32, _pi64, _pi32, _vp]),
+    "s3_kv_evict_bytes": (_i64, [_vp, _i32]),
+    "s3_kv_evict": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
+    "s3_kv_restore": (ctypes.c_int, [_vp, _i32, _i32, _vp, _pi32, _pi64, _pi32, _vp]),
     "s3_kv_stats": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64]),
     "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "s3_kv_batch_patch": (ctypes.c_int, [_i32, _vp, _vp, _i32, _pi32, _pi64, _pi32, _vp]),
@@ -170,6 +173,23 @@ def s3_kv_compact(arena, slot_id, length, stream=0):
     moved = _i32(0)
     st = lib().s3_kv_compact(arena, n, idp, lp, new_off.ctypes.data_as(_pi64), ctypes.byref(moved), stream or None)
     return st, new_off, moved.value
+
+
+def s3_kv_evict_bytes(arena, length):
+    return int(lib().s3_kv_evict_bytes(arena, int(length)))
+
+
+def s3_kv_evict(arena, slot_id, length, host_buf, stream=0):
+    """host_buf: CPU tensor / numpy array (pinned for asynchronous copies) of s3_kv_evict_bytes bytes."""
+    return lib().s3_kv_evict(arena, int(slot_id), int(length), _ptr(host_buf), stream or None)
+
+
+def s3_kv_restore(arena, predicted_len, length, host_buf, stream=0):
+    """-> (status, slot_id, off, cap)."""
+    sid, off, cap = _i32(-1), _i64(-1), _i32(0)
+    st = lib().s3_kv_restore(arena, int(predicted_len), int(length), _ptr(host_buf), ctypes.byref(sid),
+                             ctypes.byref(off), ctypes.byref(cap), stream or None)
+    return st, sid.value, off.value, cap.value
 
 
 def s3_kv_stats(arena):

@@ -1146,6 +1146,50 @@ extern "C" int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t f
     return S3_OK;
 }
 
+// ---- evict to / restore from host memory (the paper's own misprediction path, section 3 and 4.3) ----
+extern "C" int64_t s3_kv_evict_bytes(const s3_arena *a, int32_t len) {
+    if (!a || len < 0 || len > a->cfg.max_len) return S3_ERR_INVALID;
+    return (int64_t)2 * a->cfg.n_layers * len * a->row_bytes;
+}
+
+extern "C" int s3_kv_evict(s3_arena *a, int32_t slot_id, int32_t len, void *host_buf, void *stream) {
+    const s3_slot *s = s3i_live_slot(a, slot_id);
+    if (!s || !a->base || len < 0 || len > s->cap || (len > 0 && !host_buf)) return S3_ERR_INVALID;
+    const size_t piece = (size_t)len * (size_t)a->row_bytes;
+    const int planes = 2 * a->cfg.n_layers;
+    for (int p = 0; p < planes && piece; p++)
+        HIP_TRY(hipMemcpyAsync((char *)host_buf + (size_t)p * piece,
+                               a->base + (int64_t)p * a->plane_bytes + s->off * a->row_bytes, piece,
+                               hipMemcpyDeviceToHost, (hipStream_t)stream));
+    return s3_kv_free(a, slot_id);
+}
+
+extern "C" int s3_kv_restore(s3_arena *a, int32_t predicted_len, int32_t len, const void *host_buf, int32_t *slot_id,
+                             int64_t *slot_off, int32_t *slot_cap, void *stream) {
+    if (!a || !a->base || !slot_id || len < 0 || predicted_len < len || (len > 0 && !host_buf)) return S3_ERR_INVALID;
+    if (len > a->cfg.max_len) return S3_ERR_INVALID;
+    int32_t id = -1, cap = 0;
+    int64_t off = -1;
+    const int admitted = s3_kv_alloc(a, 1, &predicted_len, &id, &off, &cap);
+    if (admitted < 0) return admitted;
+    if (admitted == 0) return S3_ERR_NOMEM;
+    const size_t piece = (size_t)len * (size_t)a->row_bytes;
+    const int planes = 2 * a->cfg.n_layers;
+    for (int p = 0; p < planes && piece; p++) {
+        const hipError_t e = hipMemcpyAsync(a->base + (int64_t)p * a->plane_bytes + off * a->row_bytes,
+                                            (const char *)host_buf + (size_t)p * piece, piece, hipMemcpyHostToDevice,
+                                            (hipStream_t)stream);
+        if (e != hipSuccess) {
+            (void)s3_kv_free(a, id);
+            return hip_fail("hipMemcpyAsync(restore)", e);
+        }
+    }
+    *slot_id = id;
+    if (slot_off) *slot_off = off;
+    if (slot_cap) *slot_cap = cap;
+    return S3_OK;
+}
+
 extern "C" int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,
                                int32_t n_rows, void *dst, void *stream) {
     const s3_slot *s = s3i_live_slot(a, slot_id);

@@ -421,6 +421,39 @@ def test_compact_moves_rows_bit_exactly_including_overlapping_moves():
     rig.close()
 
 
+def test_evict_to_host_and_restore_with_doubled_reservation():
+    preds = [300, 128, 64]
+    lens = [257, 128, 40]
+    rig = Rig(2, 12, 128, s3.S3_BF16, 64, 512, preds, seed=33, arena_tokens=640)  # 320 + 128 + 64 used
+    for layer in range(2):
+        rig.fill(lens, layer)
+    sid = int(rig.ids[1])
+    assert s3.s3_kv_grow(rig.a, sid, 128, rig.stream)[0] == s3.S3_ERR_NOMEM  # 256 needed, 128 free
+    nbytes = s3.s3_kv_evict_bytes(rig.a, 128)
+    assert nbytes == 2 * 2 * 128 * 12 * 128 * 2
+    host = torch.empty(nbytes, dtype=torch.uint8).pin_memory()
+    assert s3.s3_kv_evict(rig.a, sid, 128, host, rig.stream) == 0
+    st_o, blob = rig.o.evict(sid, 128)
+    assert st_o == 0 and s3.s3_kv_stats(rig.a) == (0, *rig.o.stats())
+    torch.cuda.synchronize()
+    assert np.array_equal(host.numpy().view(np.uint16).reshape(2, 2, 128, 12, 128), blob)
+    assert s3.s3_kv_evict(rig.a, sid, 1, host, rig.stream) == s3.S3_ERR_INVALID  # already gone
+    # the second sequence finishes; now the doubled reservation fits
+    assert s3.s3_kv_restore(rig.a, 256, 128, host, rig.stream)[0] == s3.S3_ERR_NOMEM
+    assert rig.o.restore(256, blob)[0] == orc.ERR_NOMEM
+    assert s3.s3_kv_free(rig.a, int(rig.ids[2])) == rig.o.free(int(rig.ids[2])) == 0
+    got = s3.s3_kv_restore(rig.a, 256, 128, host, rig.stream)
+    assert got == rig.o.restore(256, blob) and got[3] == 256
+    new_id = got[1]
+    for layer in range(2):
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, new_id, layer, which, 128), rig.o.rows(new_id, layer, which, 128))
+            assert np.array_equal(rig_read(rig, int(rig.ids[0]), layer, which, 257),
+                                  rig.o.rows(int(rig.ids[0]), layer, which, 257))
+    assert s3.s3_kv_restore(rig.a, 100, 128, host, rig.stream)[0] == s3.S3_ERR_INVALID
+    rig.close()
+
+
 def test_batch_patch_rewrites_only_the_named_entries():
     n = 100
     off = torch.arange(n, dtype=torch.int64, device=DEV) * 64
