@@ -203,6 +203,24 @@ int s3_kv_batch_patch(int32_t n, int64_t *slot_off, int32_t *len, int32_t n_upda
 int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,
                     int32_t n_rows, void *dst, void *stream);
 
+/* Length-aware scheduler (section 3, scheduler paragraph; host integers only).  A request pool plus the
+ * decreasing-first-fit pass: the pool is ordered by the capacity each request would reserve, largest
+ * first (equal sizes in arrival order), and walked once; a request joins the batch iff s3_kv_alloc
+ * finds room for it; the walk ends when no token of the arena is free, when max_out requests have been
+ * admitted, or at the end of the pool.  Call s3_sched_admit again at every iteration, after the finished
+ * sequences were freed (iteration-level scheduling, same section).
+ *   s3_sched_submit    put a request (caller's id, predicted TOTAL length) into the pool
+ *   s3_sched_admit     request_id / slot_id / slot_off / slot_cap: HOST [max_out] out; returns the number
+ *                      admitted (they leave the pool), or an error (< 0)
+ *   s3_sched_pool_size requests still waiting */
+typedef struct s3_sched s3_sched;
+int s3_sched_create(s3_sched **out /*HOST*/, s3_arena *a);
+void s3_sched_destroy(s3_sched *s);
+int s3_sched_submit(s3_sched *s, int64_t request_id, int32_t predicted_len);
+int s3_sched_admit(s3_sched *s, int32_t max_out, int64_t *request_id, int32_t *slot_id, int64_t *slot_off,
+                   int32_t *slot_cap);
+int s3_sched_pool_size(const s3_sched *s);
+
 /* Measurement aid: the rate a plain streaming kernel reaches over the first `bytes` of the arena
  * (mode 0: 128-bit reads only; mode 1: copy of the first `bytes` onto the next `bytes`, counted as
  * 2*bytes moved), averaged over `reps` back-to-back launches on the default stream, in GB/s.

@@ -340,3 +340,33 @@ class KVOracle:
         Ks = [self.data[s][layer, 0] for s in ids]
         Vs = [self.data[s][layer, 1] for s in ids]
         return attention_ragged(q, Ks, Vs, lens, self.dtype, scale, precision, threads)[0]
+
+
+class SchedulerOracle:
+    """Decreasing first fit with a single bin, step by step as the paper's scheduler paragraph (section 3)
+    states it: sort the pool by KV-cache size, largest first (equal sizes keep arrival order - the paper
+    does not say); walk it once; a request whose cache fits the memory that is left joins the batch and
+    the memory shrinks by its size; stop when no memory is left or the pool has been walked.  "Fits"
+    is asked from the slot allocator (first fit), so fragmentation can refuse what the total would hold."""
+
+    def __init__(self, kv: "KVOracle"):
+        self.kv = kv
+        self.pool = []  # (request id, predicted total length), arrival order
+
+    def submit(self, request_id, predicted_len):
+        self.pool.append((request_id, predicted_len))
+
+    def admit(self, max_out):
+        order = sorted(range(len(self.pool)), key=lambda i: -self.kv.capacity_for(self.pool[i][1]))  # stable
+        admitted, taken = [], set()
+        for i in order:
+            if len(admitted) >= max_out or self.kv.stats()[1] <= 0:
+                break
+            rid, pred = self.pool[i]
+            sid, off, cap = self.kv.alloc_one(pred)
+            if sid < 0:
+                continue
+            admitted.append((rid, sid, off, cap))
+            taken.add(i)
+        self.pool = [r for i, r in enumerate(self.pool) if i not in taken]
+        return admitted

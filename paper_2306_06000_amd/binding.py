@@ -42,6 +42,11 @@ SIGNATURES = {
     "s3_kv_evict_bytes": (_i64, [_vp, _i32]),
     "s3_kv_evict": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
     "s3_kv_restore": (ctypes.c_int, [_vp, _i32, _i32, _vp, _pi32, _pi64, _pi32, _vp]),
+    "s3_sched_create": (ctypes.c_int, [ctypes.POINTER(_vp), _vp]),
+    "s3_sched_destroy": (None, [_vp]),
+    "s3_sched_submit": (ctypes.c_int, [_vp, _i64, _i32]),
+    "s3_sched_admit": (ctypes.c_int, [_vp, _i32, _pi64, _pi32, _pi64, _pi32]),
+    "s3_sched_pool_size": (ctypes.c_int, [_vp]),
     "s3_kv_stats": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64]),
     "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "s3_kv_batch_patch": (ctypes.c_int, [_i32, _vp, _vp, _i32, _pi32, _pi64, _pi32, _vp]),
@@ -190,6 +195,36 @@ def s3_kv_restore(arena, predicted_len, length, host_buf, stream=0):
     st = lib().s3_kv_restore(arena, int(predicted_len), int(length), _ptr(host_buf), ctypes.byref(sid),
                              ctypes.byref(off), ctypes.byref(cap), stream or None)
     return st, sid.value, off.value, cap.value
+
+
+def s3_sched_create(arena):
+    h = _vp()
+    st = lib().s3_sched_create(ctypes.byref(h), arena)
+    return st, (h if st == S3_OK else None)
+
+
+def s3_sched_destroy(sched):
+    lib().s3_sched_destroy(sched)
+
+
+def s3_sched_submit(sched, request_id, predicted_len):
+    return lib().s3_sched_submit(sched, int(request_id), int(predicted_len))
+
+
+def s3_sched_admit(sched, max_out):
+    """-> (admitted or status, request_id[], slot_id[], slot_off[], slot_cap[]) trimmed to the admitted ones."""
+    rid = np.zeros(max_out, np.int64)
+    sid = np.zeros(max_out, np.int32)
+    off = np.zeros(max_out, np.int64)
+    cap = np.zeros(max_out, np.int32)
+    rc = lib().s3_sched_admit(sched, int(max_out), rid.ctypes.data_as(_pi64), sid.ctypes.data_as(_pi32),
+                              off.ctypes.data_as(_pi64), cap.ctypes.data_as(_pi32))
+    k = max(rc, 0)
+    return rc, rid[:k], sid[:k], off[:k], cap[:k]
+
+
+def s3_sched_pool_size(sched):
+    return lib().s3_sched_pool_size(sched)
 
 
 def s3_kv_stats(arena):
