@@ -27,17 +27,20 @@ def device_bits(bits, torch_dtype, device):
     return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch_dtype)
 
 
-def make_sources(w, engine):
-    """prefill(serial, layer, rows) and tensors_for(step) closures that upload the seeded inputs."""
+def make_sources(w, engine, source=None):
+    """prefill(serial, layer, rows) and tensors_for(step) closures that upload the seeded inputs.
+    source: a workloads.PooledSource for full-size runs (default: fresh draws per call)."""
     tdt = engine.kv_dtype_torch()
+    get_rows = source.prefill_rows if source else (lambda serial, layer, rows: wl.prefill_rows(w, serial, layer, rows))
+    get_step = source.step_tensors if source else (lambda step, layer, n: wl.step_tensors(w, step, layer, n))
 
     def prefill(serial, layer, rows):
-        k, v = wl.prefill_rows(w, serial, layer, rows)
+        k, v = get_rows(serial, layer, rows)
         return device_bits(k, tdt, engine.dev), device_bits(v, tdt, engine.dev)
 
     def tensors_for(step):
         def tensors(layer, n):
-            q, k, v = wl.step_tensors(w, step, layer, n)
+            q, k, v = get_step(step, layer, n)
             return tuple(device_bits(x, tdt, engine.dev) for x in (q, k, v))
 
         return tensors
@@ -49,8 +52,10 @@ class OracleReplay:
     """Replays an engine event log on the CPU oracle; every integer the library returned must
     equal the oracle's.  Keeps serial -> oracle id so that rows can be compared afterwards."""
 
-    def __init__(self, w, arena_tokens):
+    def __init__(self, w, arena_tokens, source=None):
         self.w = w
+        self.get_rows = source.prefill_rows if source else (lambda serial, layer, rows: wl.prefill_rows(w, serial, layer, rows))
+        self.get_step = source.step_tensors if source else (lambda step, layer, n: wl.step_tensors(w, step, layer, n))
         self.o = orc.KVOracle(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len,
                               arena_tokens * w.bytes_per_token)
         self.sid = {}   # serial -> slot id
@@ -72,7 +77,7 @@ class OracleReplay:
             elif kind == "fill":
                 _, serial, sid, rows = ev
                 for layer in range(w.n_layers):
-                    k, v = wl.prefill_rows(w, serial, layer, rows)
+                    k, v = self.get_rows(serial, layer, rows)
                     assert o.fill(sid, layer, k, v) == orc.OK
                 self.len[serial] = rows
             elif kind == "grow":
@@ -91,7 +96,7 @@ class OracleReplay:
                 t = self.step_idx
                 last = None
                 for layer in range(w.n_layers):
-                    q, k, v = wl.step_tensors(w, t, layer, n)
+                    q, k, v = self.get_step(t, layer, n)
                     for b, serial in enumerate(serials):
                         assert o.append(self.sid[serial], layer, self.len[serial], k[b], v[b]) == orc.OK
                     if t in attend_steps and layer == w.n_layers - 1:
