@@ -15,7 +15,7 @@ S3_F16, S3_BF16, S3_F32 = 0, 1, 2
 S3_OK, S3_ERR_INVALID, S3_ERR_NOMEM, S3_ERR_SLOT_FULL, S3_ERR_MAXLEN, S3_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libs3kv.so")
+LIB_PATH = os.environ.get("S3KV_LIB") or os.path.join(_HERE, "libs3kv.so")  # S3KV_LIB: a diagnostic build
 _lib = None
 
 
