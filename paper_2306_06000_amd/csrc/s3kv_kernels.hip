@@ -969,6 +969,12 @@ void s3i_profile_reset(s3_arena *a) {
     (void)s3i_profile_collect(a);
     a->prof_partial_ms = a->prof_merge_ms = 0.0;
     a->prof_launches = 0;
+    // events are created here, not at the first timed launch: creating one costs tens of microseconds
+    while (a->prof_events.size() < 3 * 64) {
+        hipEvent_t e;
+        if (hipEventCreate(&e) != hipSuccess) break;
+        a->prof_events.push_back((void *)e);
+    }
 }
 
 extern "C" void s3_kv_arena_destroy(s3_arena *a) {
