@@ -27,7 +27,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed decode steps (default: per workload)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4"])
+    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c5"])
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--grid-blocks", type=int, default=0)
@@ -40,7 +40,7 @@ def parse():
     return ap.parse_args()
 
 
-DEFAULT_STEPS = {"c1": (128, 8), "c2": (256, 8), "c3": (3, 1), "c4": (56, 8)}  # (timed, warm-up)
+DEFAULT_STEPS = {"c1": (128, 8), "c2": (256, 8), "c3": (3, 1), "c4": (56, 8), "c5": (128, 8)}  # (timed, warm-up)
 
 
 def make_device_sources(w, eng, torch, ring=8):
@@ -49,7 +49,7 @@ def make_device_sources(w, eng, torch, ring=8):
     gen = torch.Generator(device=eng.dev)
     gen.manual_seed(w.seed)
     tdt = eng.kv_dtype_torch()
-    rows = torch.randn((2, w.max_len, w.n_heads, w.head_dim), generator=gen, device=eng.dev,
+    rows = torch.randn((2, w.max_len, w.kv_heads, w.head_dim), generator=gen, device=eng.dev,
                        dtype=torch.float32).to(tdt)
     state = {"i": 0, "qkv": None}
 
@@ -61,9 +61,13 @@ def make_device_sources(w, eng, torch, ring=8):
             bmax = max(n, eng.n_active, 1 if w.arena_bytes else len(w.seqs))
             state["qkv"] = torch.randn((ring, 3, bmax, w.n_heads, w.head_dim), generator=gen, device=eng.dev,
                                        dtype=torch.float32).to(tdt)
+            if w.kv_heads < w.n_heads:  # shared key/value heads: contiguous [n][kv_heads][D] rows of their own
+                state["kv"] = torch.randn((ring, 2, bmax, w.kv_heads, w.head_dim), generator=gen, device=eng.dev,
+                                          dtype=torch.float32).to(tdt)
         t = state["qkv"][state["i"] % ring]
+        kv = state["kv"][state["i"] % ring] if w.kv_heads < w.n_heads else t[1:]
         state["i"] += 1
-        return t[0, :n], t[1, :n], t[2, :n]
+        return t[0, :n], kv[0, :n], kv[1, :n]
 
     return prefill, tensors, (state, rows)
 
@@ -98,7 +102,7 @@ def cpu_baseline(w, lens, budget_s=12.0):
         cores = min(cores, omp)
     H, D = w.n_heads, w.head_dim
     rng = np.random.default_rng(w.seed)
-    kv = wl.normal_bits(rng, (2, int(w.max_len), H, D), w.dtype)
+    kv = wl.normal_bits(rng, (2, int(w.max_len), w.kv_heads, D), w.dtype)
     done_bytes, done_seqs, t_used, used = 0, 0, 0.0, cores
     n_take = min(lens.size, 16)  # first a small probe to size the passes
     passes = 0
@@ -110,7 +114,7 @@ def cpu_baseline(w, lens, budget_s=12.0):
                                        threads=cores)
         dt = time.perf_counter() - t0
         t_used += dt
-        done_bytes += int(2 * H * D * 2 * lens[idx].sum() + idx.size * H * D * (2 + 4))
+        done_bytes += int(2 * w.kv_heads * D * 2 * lens[idx].sum() + idx.size * H * D * (2 + 4))
         done_seqs += int(idx.size)
         passes += 1
         rate = idx.size / dt
@@ -138,8 +142,9 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     s3.lib()
-    w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4}[args.workload]() if args.workload != "c3" else wl.c3(
+    w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4, "c5": wl.c5}[args.workload]() if args.workload != "c3" else wl.c3(
         target_bytes=int(args.c3_bytes))
+    shared_kv = w.kv_heads < w.n_heads  # not one of the paper's models: measured as a widening, not the headline
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload][0]
     warmup = args.warmup if args.warmup is not None else DEFAULT_STEPS[args.workload][1]
     eng = DecodeEngine(w, log_events=False, fused=not args.unfused)
@@ -183,12 +188,13 @@ def main():
         "seq_steps_per_s": round(seq_steps / dt, 1),
         "host_enqueue_ms_per_step": round(t_enqueue / args.steps * 1e3, 5),
         "config": {"workload": w.name, "batch": int(lens_at_start.size), "n_layers": w.n_layers,
-                   "n_heads": w.n_heads, "head_dim": w.head_dim,
+                   "n_heads": w.n_heads, "n_kv_heads": w.kv_heads, "head_dim": w.head_dim,
                    "mean_context_at_start": round(float(lens_at_start.mean()), 1),
                    "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
                    "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
-                   "path": "append+attention+merge kernels" if args.unfused else "one s3_decode_step kernel per layer",
+                   "path": "append kernel + shared-kv attention kernel per layer" if shared_kv else
+                           "append+attention+merge kernels" if args.unfused else "one s3_decode_step kernel per layer",
                    "variant": s3.s3_kv_get_param(eng.arena, "variant")[1],
                    "chunk": s3.s3_kv_get_param(eng.arena, "chunk")[1]},
     }
@@ -201,7 +207,7 @@ def main():
         per_launch_bytes = sum(sampled) / max(launches, 1)
         avg_us = part_ns / max(launches, 1) / 1e3
         achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if avg_us > 0 else 0.0
-        kernel = "attn_partial_kernel" if args.unfused else "attn_step_kernel"
+        kernel = "attn_gqa_kernel" if shared_kv else "attn_partial_kernel" if args.unfused else "attn_step_kernel"
         res["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
                            "traffic": read_traffic(kernel, args.workload), "avg_kernel_us": round(avg_us, 2),

@@ -15,7 +15,9 @@
  * Units.  Slot offsets, capacities, lengths and positions are in TOKEN ROWS.  One
  * token row holds, for every layer, one key and one value vector of
  * n_heads*head_dim elements: bytes_per_token = 2*n_layers*n_heads*head_dim*elem
- * (= the paper's 4*l*d_h bytes for two-byte elements, section 2.1).  How rows are
+ * (= the paper's 4*l*d_h bytes for two-byte elements, section 2.1); with fewer K/V heads than query
+ * heads (multi-query attention, which the paper's related-work section names as a complementary way to
+ * shrink the cache) n_kv_heads takes the place of n_heads in that count.  How rows are
  * placed inside the arena is private to the library.
  *
  * Conventions.  Every call returns an s3_status (or a non-negative count where
@@ -61,6 +63,9 @@ typedef struct {
     int32_t kv_dtype;  /* s3_dtype of q, K, V: S3_F16 or S3_BF16                         */
     int32_t granule;   /* G: capacities are multiples of G tokens (> 0)                  */
     int32_t max_len;   /* M: largest capacity, tokens; a multiple of G                   */
+    int32_t n_kv_heads; /* heads of K and V: 0 or n_heads = one per query head; a divisor of n_heads =
+                           grouped-query, 1 = multi-query attention (each K/V head serves
+                           n_heads / n_kv_heads query heads; q and out keep n_heads)       */
 } s3_kv_config;
 
 /* KV-cache bytes one token occupies: 2 * n_layers * n_heads * head_dim * sizeof(element)
@@ -137,6 +142,8 @@ int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, co
  * workgroup that delivers the last chunk of a context merges the chunks, so no second kernel runs.
  *   len_out   DEVICE [n] int32 or NULL: receives pos[b] + 1, the positions of the next step; must not
  *             be the same array as pos (S3_ERR_INVALID) - alternate between two arrays. */
+/* (With n_kv_heads < n_heads the same call runs as two launches, the append and a grouped-query
+ * attention kernel that handles each context whole; results and checks are the same.) */
 int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
                    const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
                    const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out, void *stream);

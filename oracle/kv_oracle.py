@@ -109,8 +109,11 @@ def weighted_sum(p, V, dtype, precision="f32"):
 def attention_ragged(q, K_list, V_list, lens, dtype, scale=None, precision="f32", threads=1):
     """softmax(q K^T * scale) V per (sequence, head) over each sequence's own length.
 
-    q: [n][H][D] 16-bit patterns.  K_list[b], V_list[b]: [rows_b][H][D] 16-bit
+    q: [n][H][D] 16-bit patterns.  K_list[b], V_list[b]: [rows_b][Hkv][D] 16-bit
     patterns with rows_b >= lens[b]; only the first lens[b] rows are read.
+    Hkv == H is multi-head attention (section 2.1); Hkv < H is the grouped form
+    of the multi-query attention the related-work section names: query head h
+    reads key/value head h // (H // Hkv).
     scale None means 1/sqrt(D).  Returns (out [n][H][D] real, threads used).
     """
     npt, ct = _REAL[precision]
@@ -121,15 +124,17 @@ def attention_ragged(q, K_list, V_list, lens, dtype, scale=None, precision="f32"
     lens = np.ascontiguousarray(lens, np.int32)
     Ks = [np.ascontiguousarray(k, np.uint16) for k in K_list]
     Vs = [np.ascontiguousarray(v, np.uint16) for v in V_list]
+    Hkv = Ks[0].shape[1] if n else H
+    assert 1 <= Hkv <= H and H % Hkv == 0
     for b in range(n):
-        assert Ks[b].shape[1:] == (H, D) and Vs[b].shape[1:] == (H, D)
+        assert Ks[b].shape[1:] == (Hkv, D) and Vs[b].shape[1:] == (Hkv, D)
         assert 0 <= lens[b] <= Ks[b].shape[0] and lens[b] <= Vs[b].shape[0]
     PT = ctypes.POINTER(ctypes.c_uint16)
     kp = (PT * max(n, 1))(*[_c(k, ctypes.c_uint16) for k in Ks])
     vp = (PT * max(n, 1))(*[_c(v, ctypes.c_uint16) for v in Vs])
     out = np.zeros((n, H, D), npt)
     used = getattr(_lib(), f"s3o_attention_batch_{precision}")(
-        n, H, D, dtype, kp, vp, _c(lens, ctypes.c_int32), _c(q, ctypes.c_uint16), ct(scale), _c(out, ct),
+        n, H, Hkv, D, dtype, kp, vp, _c(lens, ctypes.c_int32), _c(q, ctypes.c_uint16), ct(scale), _c(out, ct),
         int(threads))
     if used < 0:
         raise MemoryError("oracle scratch allocation failed")
@@ -157,13 +162,19 @@ def merge_partials(parts):
 class KVOracle:
     """Slot allocator + per-sequence KV storage, step by step as the header describes."""
 
-    def __init__(self, n_layers, n_heads, head_dim, dtype, granule, max_len, arena_bytes, store=True):
+    def __init__(self, n_layers, n_heads, head_dim, dtype, granule, max_len, arena_bytes, store=True,
+                 n_kv_heads=None):
         assert granule > 0 and max_len > 0 and max_len % granule == 0
         self.n_layers, self.H, self.D, self.dtype = n_layers, n_heads, head_dim, dtype
+        # key/value heads per cached row: all heads (section 2.1) unless the model shares them
+        # between query heads (multi-query attention, related work)
+        self.Hkv = n_heads if not n_kv_heads else n_kv_heads
+        assert n_heads % self.Hkv == 0
         self.G, self.M = granule, max_len
         self.elem_bytes = 2
-        # K and V, every layer, H*D numbers of elem_bytes each: the paper's 4*l*d_h for 2-byte numbers
-        self.bytes_per_token = 2 * n_layers * n_heads * head_dim * self.elem_bytes
+        # K and V, every layer, Hkv*D numbers of elem_bytes each: the paper's 4*l*d_h for 2-byte numbers
+        # when Hkv*D = d_h
+        self.bytes_per_token = 2 * n_layers * self.Hkv * head_dim * self.elem_bytes
         self.N = arena_bytes // self.bytes_per_token  # token rows the memory can hold
         self.free_list = [[0, self.N]] if self.N > 0 else []  # sorted by offset, coalesced
         self.slots = {}  # id -> [off, cap]
@@ -223,7 +234,7 @@ class KVOracle:
         sid = self._new_id()
         self.slots[sid] = [off, cap]
         if self.store:
-            self.data[sid] = np.zeros((self.n_layers, 2, cap, self.H, self.D), np.uint16)
+            self.data[sid] = np.zeros((self.n_layers, 2, cap, self.Hkv, self.D), np.uint16)
         return sid, off, cap
 
     def alloc(self, predicted_lens):
@@ -260,7 +271,7 @@ class KVOracle:
         if new_off < 0:
             return ERR_NOMEM, -1, 0
         if self.store:
-            fresh = np.zeros((self.n_layers, 2, new_cap, self.H, self.D), np.uint16)
+            fresh = np.zeros((self.n_layers, 2, new_cap, self.Hkv, self.D), np.uint16)
             fresh[:, :, :length] = self.data[sid][:, :, :length]
             self.data[sid] = fresh
         self._release(off, cap)

@@ -127,17 +127,25 @@ int FN(s3o_attend_one)(const uint16_t *q, const uint16_t *K, const uint16_t *V, 
 }
 
 /* A ragged batch.  Sequence b has its own K and V storage, K_ptr[b] / V_ptr[b],
- * laid out [rows][H][D]; it attends over its first len[b] rows only (no padding).
- * q and out are [n][H][D].  The (sequence, head) pairs are independent, so they
- * may be spread over `threads` OpenMP threads (1 = plain serial loops); the
- * arithmetic of each pair is the same either way.  Returns the number of
- * threads used, or -1 on allocation failure. */
-int FN(s3o_attention_batch)(int n, int H, int D, int dtype, const uint16_t *const *K_ptr,
+ * laid out [rows][Hkv][D]; it attends over its first len[b] rows only (no padding).
+ * q and out are [n][H][D].  Hkv == H is the paper's multi-head attention (section
+ * 2.1).  Hkv < H (Hkv divides H) is multi-query attention, which the paper's
+ * related-work section names as a way to shrink the cache, in its grouped form:
+ * the H query heads are split into Hkv runs of H / Hkv consecutive heads, and run k
+ * shares key/value head k; Hkv == 1 is multi-query attention proper (every head
+ * reads the one key/value head).  Each query head still computes the same three
+ * steps.  The (sequence, head) pairs are independent, so they may be spread over
+ * `threads` OpenMP threads (1 = plain serial loops); the arithmetic of each pair
+ * is the same either way.  Returns the number of threads used, or -1 on
+ * allocation failure or if Hkv does not divide H. */
+int FN(s3o_attention_batch)(int n, int H, int Hkv, int D, int dtype, const uint16_t *const *K_ptr,
                             const uint16_t *const *V_ptr, const int32_t *len, const uint16_t *q,
                             REAL scale, REAL *out, int threads)
 {
     int used = 1, fail = 0;
     int64_t pairs = (int64_t)n * H;
+    if (Hkv < 1 || H % Hkv) return -1;
+    int heads_per_kv = H / Hkv;
 #ifdef _OPENMP
     if (threads < 1) threads = 1;
     used = threads;
@@ -145,8 +153,9 @@ int FN(s3o_attention_batch)(int n, int H, int D, int dtype, const uint16_t *cons
 #endif
     for (int64_t i = 0; i < pairs; i++) {
         int b = (int)(i / H), h = (int)(i % H);
-        int rc = FN(s3o_attend_one)(q + ((int64_t)b * H + h) * D, K_ptr[b] + (int64_t)h * D,
-                                    V_ptr[b] + (int64_t)h * D, (int64_t)H * D, len[b], D, dtype, scale,
+        int hk = h / heads_per_kv; /* the key/value head this query head reads */
+        int rc = FN(s3o_attend_one)(q + ((int64_t)b * H + h) * D, K_ptr[b] + (int64_t)hk * D,
+                                    V_ptr[b] + (int64_t)hk * D, (int64_t)Hkv * D, len[b], D, dtype, scale,
                                     out + ((int64_t)b * H + h) * D);
         if (rc) fail |= 1;
     }

@@ -21,7 +21,8 @@ _lib = None
 
 class s3_kv_config(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
-                ("kv_dtype", ctypes.c_int32), ("granule", ctypes.c_int32), ("max_len", ctypes.c_int32)]
+                ("kv_dtype", ctypes.c_int32), ("granule", ctypes.c_int32), ("max_len", ctypes.c_int32),
+                ("n_kv_heads", ctypes.c_int32)]
 
 
 _vp, _i32, _i64, _f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
@@ -101,8 +102,8 @@ class S3Error(RuntimeError):
         super().__init__(f"{where}: {lib().s3_status_str(status).decode()} {detail}".strip())
 
 
-def make_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len):
-    return s3_kv_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len)
+def make_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_heads=0):
+    return s3_kv_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_heads)
 
 
 def s3_kv_bytes_per_token(cfg):

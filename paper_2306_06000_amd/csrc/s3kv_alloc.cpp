@@ -41,13 +41,15 @@ static bool config_ok(const s3_kv_config *c) {
     if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
     if (c->kv_dtype != S3_F16 && c->kv_dtype != S3_BF16) return false;
     if (c->granule <= 0 || c->max_len <= 0 || c->max_len % c->granule != 0) return false;
+    if (c->n_kv_heads < 0 || (c->n_kv_heads > 0 && (c->n_kv_heads > c->n_heads || c->n_heads % c->n_kv_heads))) return false;
     return true;
 }
 
 extern "C" int64_t s3_kv_bytes_per_token(const s3_kv_config *cfg) {
     if (!config_ok(cfg)) return S3_ERR_INVALID;
     // K and V, every layer, H*D two-byte numbers: 4*l*d_h bytes (section 2.1)
-    return (int64_t)2 * cfg->n_layers * cfg->n_heads * cfg->head_dim * 2;
+    const int kv_heads = cfg->n_kv_heads > 0 ? cfg->n_kv_heads : cfg->n_heads;
+    return (int64_t)2 * cfg->n_layers * kv_heads * cfg->head_dim * 2;
 }
 
 extern "C" int s3_kv_arena_init(s3_arena **out, const s3_kv_config *cfg, void *dev_base, size_t dev_bytes) {
@@ -59,7 +61,8 @@ extern "C" int s3_kv_arena_init(s3_arena **out, const s3_kv_config *cfg, void *d
     a->base = (char *)dev_base;
     a->dev_bytes = dev_bytes;
     a->elem_bytes = 2;
-    a->row_bytes = (int64_t)cfg->n_heads * cfg->head_dim * a->elem_bytes;
+    if (a->cfg.n_kv_heads == 0) a->cfg.n_kv_heads = cfg->n_heads;
+    a->row_bytes = (int64_t)a->cfg.n_kv_heads * cfg->head_dim * a->elem_bytes;
     a->n_tokens = (int64_t)(dev_bytes / (size_t)s3_kv_bytes_per_token(cfg));
     a->plane_bytes = a->n_tokens * a->row_bytes;
     if (a->n_tokens > 0) a->free_ext[0] = a->n_tokens;

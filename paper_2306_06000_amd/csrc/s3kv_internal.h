@@ -20,7 +20,7 @@ struct s3_arena {
     size_t dev_bytes = 0;
     int64_t n_tokens = 0;      // N: token rows the arena holds
     int64_t elem_bytes = 2;
-    int64_t row_bytes = 0;     // H * D * elem
+    int64_t row_bytes = 0;     // kv heads * D * elem
     int64_t plane_bytes = 0;   // N * row_bytes; plane p = 2*layer + (0: K, 1: V)
 
     std::map<int64_t, int64_t> free_ext;  // offset -> size, disjoint, coalesced

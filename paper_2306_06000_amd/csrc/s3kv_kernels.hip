@@ -19,6 +19,7 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#include <string.h>
 
 #include "s3kv_internal.h"
 
@@ -203,7 +204,8 @@ struct AttnArgs {
     float *part_acc;   // [n][max_chunks][H][D]
     float2 *part_ml;   // [n][max_chunks][H]  (running max in log2 units, sum)
     int64_t n_tokens;  // arena capacity N
-    int32_t n, H, chunk, max_chunks, out_dtype, max_len;
+    int32_t n, H, chunk, max_chunks, out_dtype, max_len;  // H: heads of a K/V row
+    int32_t Hq;            // query heads (= H unless grouped-query / multi-query attention)
     int32_t ncls;          // length classes of the work order (1..8)
     int32_t len_add;    // 0: cur_len is the context length; 1 (fused step): cur_len is the append position
     float scale_log2e;  // scale * log2(e): scores are kept in log2 units so that exp is v_exp_f32
@@ -843,6 +845,123 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
     }
 }
 
+// Grouped-query / multi-query attention (n_kv_heads < n_heads; the paper's related-work section names
+// multi-query attention as a complementary way to shrink the cache): K/V rows hold H heads, q and out
+// Hq = H * group heads; K/V head k serves query heads k*group .. k*group+group-1.  A wave's 128-bit
+// load covers 1 KiB of consecutive arena bytes as in the multi-head kernels: GH K/V heads of one row
+// or, when a row has fewer than GH heads (H dividing GH), GH/H whole consecutive rows, each lane group
+// then keeping its own online-softmax state for its share of the rows.  Every lane carries GQ query
+// heads per K/V head; group/GQ items per K/V head group re-read the same rows.  One workgroup handles
+// a whole context: its TS waves split the rows and merge through LDS, one query head at a time, so
+// there are no cross-workgroup partials.  With len_add = 1 it is the attention half of a decode step
+// whose append ran as its own launch before it.
+template <int DT, int D, int GQ, int TS, int U>
+__global__ void __launch_bounds__(TS * 64) attn_gqa_kernel(const AttnArgs a) {
+    constexpr int LPH = D / 8;
+    constexpr int GH = 64 / LPH;
+    __shared__ float comb[TS][10][64];
+    const int lane = threadIdx.x & 63, ts = threadIdx.x >> 6;
+    const int group = a.Hq / a.H;
+    const int tpw = (a.H < GH && GH % a.H == 0) ? GH / a.H : 1;  // rows per wave load
+    const int n_kvhg = (a.H + GH - 1) / GH, n_qsub = group / GQ;
+    const int64_t per_seq = (int64_t)n_kvhg * n_qsub;
+    const int64_t total = (int64_t)a.n * per_seq;
+    if (blockIdx.x == 0 && a.len_out)
+        for (int b = threadIdx.x; b < a.n; b += TS * 64) a.len_out[b] = a.cur_len[b] + 1;
+
+    const int slot = lane / LPH, dl = lane % LPH;
+    const int tsub = tpw > 1 ? slot / a.H : 0;
+    for (int64_t item = blockIdx.x; item < total; item += gridDim.x) {
+        const int b = (int)(item / per_seq);
+        const int r = (int)(item - (int64_t)b * per_seq);
+        const int kvhg = r / n_qsub, qsub = r - kvhg * n_qsub;
+        const int len = checked_len(a, b);
+        const int64_t off = a.slot_off[b];
+        const int hk = tpw > 1 ? slot % a.H : kvhg * GH + slot;
+        const bool hk_ok = hk < a.H;
+        const int hkc = hk_ok ? hk : a.H - 1;
+        const int per = (len + TS - 1) / TS;
+        const int j0 = min(len, ts * per), j1 = min(len, j0 + per);
+        const int64_t rstride = (int64_t)a.H * D * 2;
+        const int64_t lane_byte = ((int64_t)hkc * D + dl * 8) * 2;
+        const char *kp = a.kplane + off * rstride + lane_byte;
+        const char *vp = a.vplane + off * rstride + lane_byte;
+        const int hq0 = hkc * group + qsub * GQ;  // first of this lane's GQ query heads
+        u32x4 qv[GQ];
+#pragma unroll
+        for (int i = 0; i < GQ; i++)
+            qv[i] = *(const u32x4 *)(a.q + (((int64_t)b * a.Hq + hq0 + i) * D + dl * 8) * 2);
+        float m[GQ], l[GQ], acc[GQ][8];
+#pragma unroll
+        for (int i = 0; i < GQ; i++) {
+            m[i] = -INFINITY;
+            l[i] = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
+        }
+        for (int j = j0; j < j1; j += U * tpw) {
+            u32x4 kk[U], vv[U];
+#pragma unroll
+            for (int u = 0; u < U; u++) kk[u] = load16<true>(kp + (int64_t)min(j + u * tpw + tsub, j1 - 1) * rstride);
+#pragma unroll
+            for (int u = 0; u < U; u++) vv[u] = load16<true>(vp + (int64_t)min(j + u * tpw + tsub, j1 - 1) * rstride);
+#pragma unroll
+            for (int i = 0; i < GQ; i++) {
+                float s[U], mb = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const float d = group_sum<LPH>(dot8<DT>(qv[i], kk[u]));
+                    s[u] = (j + u * tpw + tsub < j1) ? d * a.scale_log2e : -INFINITY;
+                    mb = fmaxf(mb, s[u]);
+                }
+                // a lane group whose rows of this batch are all past the end keeps its state
+                const float mn = fmaxf(m[i], mb);
+                const float alpha = (mn == -INFINITY) ? 1.f : fast_exp2(m[i] - mn);
+                l[i] *= alpha;
+#pragma unroll
+                for (int e = 0; e < 8; e++) acc[i][e] *= alpha;
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const float p = (mn == -INFINITY) ? 0.f : fast_exp2(s[u] - mn);
+                    l[i] += p;
+                    axpy8<DT>(acc[i], p, vv[u]);
+                }
+                m[i] = mn;
+            }
+        }
+        const bool writer = ts == 0 && hk_ok && tsub == 0;
+#pragma unroll
+        for (int i = 0; i < GQ; i++) {
+            comb[ts][0][lane] = m[i];
+            comb[ts][1][lane] = l[i];
+#pragma unroll
+            for (int e = 0; e < 8; e++) comb[ts][2 + e][lane] = acc[i][e];
+            __syncthreads();
+            if (writer) {
+                float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                if (len > 0) {  // rows start at wave 0, lane group 0, so the maximum is finite
+                    float mm = -INFINITY, ll = 0.f;
+                    for (int t = 0; t < TS; t++)
+                        for (int g = 0; g < tpw; g++) mm = fmaxf(mm, comb[t][0][lane + g * a.H * LPH]);
+                    for (int t = 0; t < TS; t++)
+                        for (int g = 0; g < tpw; g++) {
+                            const int src = lane + g * a.H * LPH;
+                            const float wt = fast_exp2(comb[t][0][src] - mm);
+                            ll += wt * comb[t][1][src];
+#pragma unroll
+                            for (int e = 0; e < 8; e++) o[e] += wt * comb[t][2 + e][src];
+                        }
+                    const float inv = 1.f / ll;
+#pragma unroll
+                    for (int e = 0; e < 8; e++) o[e] *= inv;
+                }
+                store_out8(a.out, a.out_dtype, ((int64_t)b * a.Hq + hq0 + i) * D + dl * 8, o);
+            }
+            __syncthreads();  // comb is reused by the next query head and the next item
+        }
+    }
+}
+
 // One wave per (sequence, head group): merge the chunk partials of contexts longer than one
 // chunk; write zeros for empty contexts; leave single-chunk contexts (already final) alone.
 template <int D>
@@ -920,6 +1039,30 @@ static attn_fn pick_kernel(int dt, int d, int v) {
         if (d == 64) return pick_variant<S3_BF16, 64, FUSED>(v);
         if (d == 128) return pick_variant<S3_BF16, 128, FUSED>(v);
         if (d == 256) return pick_variant<S3_BF16, 256, FUSED>(v);
+    }
+    return nullptr;
+}
+
+template <int DT, int D>
+static attn_fn pick_gqa_width(int gq) {
+    switch (gq) {
+        case 1: return attn_gqa_kernel<DT, D, 1, 8, 4>;
+        case 2: return attn_gqa_kernel<DT, D, 2, 8, 4>;
+        case 4: return attn_gqa_kernel<DT, D, 4, 8, 4>;
+        case 8: return attn_gqa_kernel<DT, D, 8, 8, 2>;
+        default: return nullptr;
+    }
+}
+
+static attn_fn pick_gqa(int dt, int d, int gq) {
+    if (dt == S3_F16) {
+        if (d == 64) return pick_gqa_width<S3_F16, 64>(gq);
+        if (d == 128) return pick_gqa_width<S3_F16, 128>(gq);
+        if (d == 256) return pick_gqa_width<S3_F16, 256>(gq);
+    } else {
+        if (d == 64) return pick_gqa_width<S3_BF16, 64>(gq);
+        if (d == 128) return pick_gqa_width<S3_BF16, 128>(gq);
+        if (d == 256) return pick_gqa_width<S3_BF16, 256>(gq);
     }
     return nullptr;
 }
@@ -1019,11 +1162,71 @@ static int check_slots_host(const s3_arena *a, int32_t n, const int32_t *slot_id
     return full ? S3_ERR_SLOT_FULL : S3_OK;
 }
 
+// Grouped-query / multi-query configurations: with_append = true runs the append as its own launch
+// first (same stream), then the attention over pos + 1 rows, which also publishes the new lengths.
+static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
+                      const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
+                      bool with_append, const void *k_new, const void *v_new, int32_t *len_out) {
+    const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
+    const int group = Hq / Hkv;
+    const int gq = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+    attn_fn fn = pick_gqa(a->cfg.kv_dtype, D, gq);
+    if (!fn) return S3_ERR_INVALID;
+    if (with_append) {
+        hipLaunchKernelGGL(append_kernel, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
+                           a->plane(layer, 1), slot_off, len_or_pos, (const char *)k_new, (const char *)v_new,
+                           a->row_bytes, a->n_tokens, a->cfg.max_len);
+        HIP_TRY(hipGetLastError());
+    }
+    AttnArgs args;
+    memset(&args, 0, sizeof(args));
+    args.kplane = a->plane(layer, 0);
+    args.vplane = a->plane(layer, 1);
+    args.q = (const char *)q;
+    args.slot_off = slot_off;
+    args.cur_len = len_or_pos;
+    args.out = out;
+    args.n_tokens = a->n_tokens;
+    args.n = n;
+    args.H = Hkv;
+    args.Hq = Hq;
+    args.out_dtype = out_dtype;
+    args.max_len = a->cfg.max_len;
+    args.len_add = with_append ? 1 : 0;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+    args.scale_log2e = scale * 1.4426950408889634f;
+    args.len_out = with_append ? len_out : nullptr;
+    const int GH = 512 / D;
+    const int64_t items = (int64_t)n * ((Hkv + GH - 1) / GH) * (group / gq);
+    const int cus = a->num_cus > 0 ? a->num_cus : 256;
+    const int64_t cap = a->grid_blocks > 0 ? a->grid_blocks : (int64_t)cus * 4;
+    const unsigned blocks = (unsigned)(items < cap ? items : cap);
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
+    if (timed) {
+        for (int i = 0; i < 3; i++) {
+            const int prc = prof_next_event(a, &ev[i]);
+            if (prc != S3_OK) return prc;
+        }
+        HIP_TRY(hipEventRecord(ev[0], (hipStream_t)stream));
+    }
+    hipLaunchKernelGGL(fn, dim3(blocks), dim3(512), 0, (hipStream_t)stream, args);
+    HIP_TRY(hipGetLastError());
+    if (timed) {  // no merge kernel here: the second interval is empty
+        HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
+        HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
+    }
+    return S3_OK;
+}
+
 // Shared by s3_decode_attention (fused = false: partial kernel + merge kernel) and s3_decode_step
 // (fused = true: one kernel that also appends, merges and publishes the new lengths).
 static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
                             const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
                             bool fused, const void *k_new, const void *v_new, int32_t *len_out) {
+    if (a->cfg.n_kv_heads < a->cfg.n_heads)
+        return launch_gqa(a, layer, n, q, slot_off, len_or_pos, out, out_dtype, scale, stream, fused, k_new, v_new,
+                          len_out);
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     // Defaults from sweeps on MI355X: large chunks keep most contexts in one piece (no cross-workgroup
     // merge), eight waves share an item's rows evenly.
@@ -1045,6 +1248,7 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
     args.n_tokens = a->n_tokens;
     args.n = n;
     args.H = H;
+    args.Hq = H;
     args.chunk = chunk;
     args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
     // length classes of the longest-first work order: small batches gain from it (their kernels are

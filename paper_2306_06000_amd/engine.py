@@ -27,7 +27,7 @@ class DecodeEngine:
         self.w = w
         self.fused = fused  # True: one s3_decode_step launch per layer; False: append + attention calls
         self.dev = torch.device(device)
-        self.cfg = s3.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len)
+        self.cfg = s3.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len, w.n_kv_heads)
         self.bpt = s3.s3_kv_bytes_per_token(self.cfg)
         if arena_tokens is None:
             if w.arena_bytes:
@@ -254,12 +254,13 @@ class DecodeEngine:
         e = 2
         e_out = {s3.S3_F32: 4, s3.S3_F16: 2, s3.S3_BF16: 2}[self.out_dtype]
         hd = self.w.n_heads * self.w.head_dim
+        kvd = self.w.kv_heads * self.w.head_dim  # elements of one cached row
         B = self.n_active
-        return 2 * hd * e * int(self.len.sum()) + B * hd * e + B * hd * e_out + 4 * B * hd * e
+        return 2 * kvd * e * int(self.len.sum()) + B * hd * e + B * hd * e_out + 4 * B * kvd * e
 
     def read_slot(self, a, layer, which, n_rows=None):
         n_rows = a.len if n_rows is None else n_rows
-        dst = torch.empty((n_rows, self.w.n_heads, self.w.head_dim), dtype=torch.int16, device=self.dev)
+        dst = torch.empty((n_rows, self.w.kv_heads, self.w.head_dim), dtype=torch.int16, device=self.dev)
         s3.check(s3.s3_kv_read_rows(self.arena, a.slot, layer, which, 0, n_rows, dst, self._stream_ptr()),
                  "s3_kv_read_rows")
         return dst.cpu().numpy().view(np.uint16)

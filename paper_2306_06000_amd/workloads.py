@@ -73,6 +73,7 @@ class Workload:
     refill: bool = False
     arena_bytes: int = 0                            # 0: sized by the harness from the slots
     note: str = ""
+    n_kv_heads: int = 0                             # 0: every head has its own K/V (multi-head attention)
 
     @property
     def seed(self) -> int:
@@ -83,8 +84,12 @@ class Workload:
         return 2
 
     @property
+    def kv_heads(self) -> int:
+        return self.n_kv_heads or self.n_heads
+
+    @property
     def row_bytes(self) -> int:
-        return self.n_heads * self.head_dim * self.elem_bytes
+        return self.kv_heads * self.head_dim * self.elem_bytes
 
     @property
     def bytes_per_token(self) -> int:
@@ -172,8 +177,18 @@ def c4(batch: int = 128, steps: int = 64) -> Workload:
     return Workload("C4-gpt3-share", 4, 1, 12, 128, BF16, 128, 2048, batch, steps, seqs)
 
 
+def c5(batch: int = 64, steps: int = 128, n_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
+       dtype: int = BF16) -> Workload:
+    """Shared key/value heads (grouped-query; n_kv_heads = 1 is multi-query attention, which the
+    paper's related-work section names as complementary): C1's lengths, mispredictions and refill
+    on a 32-query-head / 8-KV-head, d = 128 shape.  Not one of the paper's measured models."""
+    base = c1(batch, steps)
+    return Workload(f"C5-shared-kv-{n_heads}q{n_kv_heads}kv", 5, 1, n_heads, head_dim, dtype, base.granule,
+                    base.max_len, batch, steps, base.seqs, base.pool, base.refill, n_kv_heads=n_kv_heads)
+
+
 def by_name(name: str) -> Workload:
-    return {"c0": c0, "c1": c1, "c2": c2, "c3": c3, "c4": c4}[name.lower()]()
+    return {"c0": c0, "c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5}[name.lower()]()
 
 
 def step_tensors(w: Workload, step: int, layer: int, n: int):
@@ -181,14 +196,16 @@ def step_tensors(w: Workload, step: int, layer: int, n: int):
     rng = np.random.default_rng([w.seed, 1, step, layer])
     shape = (3, n, w.n_heads, w.head_dim)
     t = normal_bits(rng, shape, w.dtype)
-    return t[0], t[1], t[2]
+    hk = w.kv_heads  # shared K/V heads: the first kv_heads of the same draw
+    return t[0], np.ascontiguousarray(t[1][:, :hk]), np.ascontiguousarray(t[2][:, :hk])
 
 
 def prefill_rows(w: Workload, seq_serial: int, layer: int, rows: int):
     """K and V rows [rows][H][D] a sequence holds when it joins (stand-in for the prompt phase)."""
     rng = np.random.default_rng([w.seed, 2, seq_serial, layer])
     t = normal_bits(rng, (2, rows, w.n_heads, w.head_dim), w.dtype)
-    return t[0], t[1]
+    hk = w.kv_heads
+    return np.ascontiguousarray(t[0][:, :hk]), np.ascontiguousarray(t[1][:, :hk])
 
 
 class PooledSource:
@@ -206,10 +223,12 @@ class PooledSource:
 
     def prefill_rows(self, serial: int, layer: int, rows: int):
         start = (serial * 37 + layer * 11) % 128
-        return self.rows[0, start:start + rows], self.rows[1, start:start + rows]
+        hk = self.w.kv_heads
+        return self.rows[0, start:start + rows, :hk], self.rows[1, start:start + rows, :hk]
 
     def step_tensors(self, step: int, layer: int, n: int):
         t = self.qkv[(step * self.w.n_layers + layer) % self.ring]
         shift = (step * 131 + layer * 17) % self.w.head_dim
         t = np.roll(t[:, :n], shift, axis=-1)
-        return t[0], t[1], t[2]
+        hk = self.w.kv_heads
+        return t[0], t[1][:, :hk], t[2][:, :hk]

@@ -57,7 +57,7 @@ class OracleReplay:
         self.get_rows = source.prefill_rows if source else (lambda serial, layer, rows: wl.prefill_rows(w, serial, layer, rows))
         self.get_step = source.step_tensors if source else (lambda step, layer, n: wl.step_tensors(w, step, layer, n))
         self.o = orc.KVOracle(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len,
-                              arena_tokens * w.bytes_per_token)
+                              arena_tokens * w.bytes_per_token, n_kv_heads=w.n_kv_heads)
         self.sid = {}   # serial -> slot id
         self.len = {}   # serial -> rows cached
         self.step_idx = 0

@@ -28,16 +28,18 @@ def need_gpu_and_lib():
 class Rig:
     """A small arena with hand-placed sequences, mirrored in the oracle."""
 
-    def __init__(self, n_layers, H, D, dtype, G, M, preds, seed, arena_tokens=None):
+    def __init__(self, n_layers, H, D, dtype, G, M, preds, seed, arena_tokens=None, Hkv=None):
         self.n_layers, self.H, self.D, self.dtype = n_layers, H, D, dtype
-        self.cfg = s3.make_config(n_layers, H, D, dtype, G, M)
+        self.Hkv = Hkv or H  # heads of a cached row
+        self.cfg = s3.make_config(n_layers, H, D, dtype, G, M, 0 if Hkv is None else Hkv)
         bpt = s3.s3_kv_bytes_per_token(self.cfg)
         caps = [min(M, max(G, -(-p // G) * G)) for p in preds]
         self.N = arena_tokens or (sum(caps) + 3 * M)
         self.mem = torch.zeros(self.N * bpt, dtype=torch.uint8, device=DEV)
         st, self.a = s3.s3_kv_arena_init(self.cfg, self.mem, self.mem.numel())
         assert st == 0
-        self.o = orc.KVOracle(n_layers, H, D, dtype, G, M, self.N * bpt)
+        self.o = orc.KVOracle(n_layers, H, D, dtype, G, M, self.N * bpt, n_kv_heads=Hkv)
+        assert bpt == self.o.bytes_per_token
         rc, self.ids, self.offs, self.caps = s3.s3_kv_alloc(self.a, preds)
         n_o, ids_o, offs_o, caps_o = self.o.alloc(preds)
         assert rc == n_o == len(preds)
@@ -49,8 +51,8 @@ class Rig:
         for sid, L in zip(self.ids.tolist(), lens):
             if L == 0:
                 continue
-            k = wl.normal_bits(self.rng, (L, self.H, self.D), self.dtype)
-            v = wl.normal_bits(self.rng, (L, self.H, self.D), self.dtype)
+            k = wl.normal_bits(self.rng, (L, self.Hkv, self.D), self.dtype)
+            v = wl.normal_bits(self.rng, (L, self.Hkv, self.D), self.dtype)
             assert self.o.fill(sid, layer, k, v) == 0
             st = s3.s3_kv_fill(self.a, sid, layer, 0, L, device_bits(k, TDT[self.dtype], DEV),
                                device_bits(v, TDT[self.dtype], DEV), self.stream)
@@ -142,7 +144,7 @@ def test_c0_read_as_pre_append_lengths_needs_two_grows():
 
 
 def rig_read(rig, sid, layer, which, rows):
-    dst = torch.empty((int(rows), rig.H, rig.D), dtype=torch.int16, device=DEV)
+    dst = torch.empty((int(rows), rig.Hkv, rig.D), dtype=torch.int16, device=DEV)
     assert s3.s3_kv_read_rows(rig.a, sid, layer, which, 0, int(rows), dst, rig.stream) == 0
     return dst.cpu().numpy().view(np.uint16)
 
@@ -509,6 +511,79 @@ def run_trace(w, steps, attend_steps, arena_tokens=None, variant=None, chunk=Non
     assert stats["grows"] == rep.o.n_grows
     eng.close()
     return stats
+
+
+# ---------------------------------------------------------------- shared key/value heads
+GQA_SHAPES = [  # (query heads, kv heads, head dim)
+    (32, 8, 128), (16, 1, 256), (8, 1, 64), (8, 2, 64), (12, 4, 128), (6, 3, 256), (24, 8, 64), (64, 8, 128),
+    (16, 16, 128), (12, 2, 128), (9, 3, 64), (40, 5, 128),
+]
+
+
+@pytest.mark.parametrize("dtype", [s3.S3_F16, s3.S3_BF16])
+@pytest.mark.parametrize("H,Hkv,D", GQA_SHAPES)
+def test_shared_kv_heads_attention(H, Hkv, D, dtype):
+    """n_kv_heads < n_heads (grouped-query; 1 = multi-query, related work): rows hold Hkv heads,
+    query head h reads head h // (H // Hkv).  Ragged lengths incl. empty, one row and a tail that
+    is no multiple of the rows a wave load covers.  (16, 16, 128) with the field set explicitly is
+    plain multi-head attention and takes the multi-head kernels."""
+    lens = [0, 1, 2, 3, 7, 8, 9, 31, 33, 64, 100, 255, 257, 600, 1, 5]
+    rig = Rig(2, H, D, dtype, 64, 1024, [max(1, L) for L in lens], seed=70 + H + Hkv, Hkv=Hkv)
+    rig.fill(lens, layer=1)
+    for out_dtype in (s3.S3_F32, s3.S3_F16 if dtype == s3.S3_F16 else s3.S3_BF16):
+        q, got = rig.attend(lens, layer=1, out_dtype=out_dtype)
+        want = rig.oracle_attend(q, lens, layer=1)
+        if out_dtype == s3.S3_F32:
+            assert_close(got, want, f"shared kv {H}/{Hkv} d{D}")
+            assert not got[0].any()  # empty context: zeros
+        else:
+            assert np.abs(got - want).max() <= 2e-2
+    rig.close()
+
+
+@pytest.mark.parametrize("H,Hkv,D,dtype", [(32, 8, 128, s3.S3_BF16), (16, 1, 256, s3.S3_F16), (8, 2, 64, s3.S3_F16)])
+def test_shared_kv_heads_decode_step_appends_then_attends(H, Hkv, D, dtype):
+    """s3_decode_step with shared heads: the new [Hkv][D] rows land at row pos of both planes
+    (bit-exact against the oracle's rows), len_out = pos + 1, attention over pos + 1 rows within
+    tolerance; a full slot is refused on the host with nothing written."""
+    pos = [0, 1, 31, 63, 64, 100, 255, 513, 5]
+    caps = [p + 1 for p in pos]
+    rig = Rig(1, H, D, dtype, 64, 1024, caps, seed=90 + H, Hkv=Hkv)
+    rig.fill(pos)
+    n = len(pos)
+    q = wl.normal_bits(rig.rng, (n, H, D), dtype)
+    k = wl.normal_bits(rig.rng, (n, Hkv, D), dtype)
+    v = wl.normal_bits(rig.rng, (n, Hkv, D), dtype)
+    qd, kd, vd = (device_bits(x, TDT[dtype], DEV) for x in (q, k, v))
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    full = list(rig.caps.tolist())
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=rig.ids, pos_host=full) == s3.S3_ERR_SLOT_FULL
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=rig.ids, pos_host=pos) == 0
+    torch.cuda.synchronize()
+    assert len_out.cpu().tolist() == caps
+    for b, sid in enumerate(rig.ids.tolist()):
+        assert rig.o.append(sid, 0, pos[b], k[b], v[b]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, sid, 0, which, rig.caps[b]), rig.o.data[sid][0, which])
+    assert_close(out.cpu().numpy(), rig.oracle_attend(q, caps), f"shared kv step {H}/{Hkv}")
+    rig.close()
+
+
+@pytest.mark.parametrize("fused", [True, False])
+def test_c5_shared_kv_trace_with_grow_free_and_refill(fused):
+    w = wl.c5(batch=48, steps=48)
+    stats = run_trace(w, w.steps, attend_steps=[0, 20, 47], fused=fused)
+    assert stats["frees"] >= 1
+
+
+def test_c5_multi_query_trace():
+    w = wl.c5(batch=32, steps=24, n_heads=16, n_kv_heads=1, head_dim=256, dtype=wl.F16)
+    run_trace(w, w.steps, attend_steps=[0, 23])
 
 
 @pytest.mark.parametrize("fused", [True, False])

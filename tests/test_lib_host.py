@@ -53,11 +53,16 @@ def test_bytes_per_token_matches_the_paper_example():
     assert s3.s3_kv_bytes_per_token(bad) == s3.S3_ERR_INVALID
     gptj = s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048)
     assert s3.s3_kv_bytes_per_token(gptj) == 458752
+    # shared key/value heads (multi-query attention, related work): only the cached heads count
+    assert s3.s3_kv_bytes_per_token(s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048, 16)) == 458752
+    assert s3.s3_kv_bytes_per_token(s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048, 4)) == 458752 // 4
+    assert s3.s3_kv_bytes_per_token(s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048, 1)) == 458752 // 16
 
 
 def test_config_validation():
     for bad in [(0, 16, 256, 0, 64, 2048), (1, 0, 256, 0, 64, 2048), (1, 16, 100, 0, 64, 2048),
-                (1, 16, 256, 2, 64, 2048), (1, 16, 256, 0, 0, 2048), (1, 16, 256, 0, 64, 2000)]:
+                (1, 16, 256, 2, 64, 2048), (1, 16, 256, 0, 0, 2048), (1, 16, 256, 0, 64, 2000),
+                (1, 16, 256, 0, 64, 2048, 3), (1, 16, 256, 0, 64, 2048, 32), (1, 16, 256, 0, 64, 2048, -1)]:
         st, a = s3.s3_kv_arena_init(s3.make_config(*bad), None, 1 << 20)
         assert st == s3.S3_ERR_INVALID and a is None
 

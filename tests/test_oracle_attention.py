@@ -284,6 +284,60 @@ def test_explicit_scale_is_used():
     assert np.allclose(a[0, 0], want, atol=1e-6)
 
 
+# ---------------------------------------------------------------- shared key/value heads
+@pytest.mark.parametrize("H,Hkv", [(8, 2), (8, 1), (12, 4), (6, 6)])
+def test_shared_kv_heads_match_torch_sdpa_with_repeated_heads(H, Hkv):
+    """Grouped / multi-query attention (related work): query head h reads key/value head
+    h // (H // Hkv).  Textbook routine: repeat every key/value head H // Hkv times in place and
+    run ordinary multi-head attention.  A wrong head mapping (h % Hkv, a transposed group) or a
+    wrong row stride fails here because all heads hold different numbers."""
+    import torch
+
+    dtype = orc.F16
+    rng = np.random.default_rng(21)
+    D = 64
+    lens = [1, 37, 130]
+    q = wl.normal_bits(rng, (3, H, D), dtype)
+    K = [wl.normal_bits(rng, (L + 2, Hkv, D), dtype) for L in lens]
+    V = [wl.normal_bits(rng, (L + 2, Hkv, D), dtype) for L in lens]
+    out, _ = orc.attention_ragged(q, K, V, lens, dtype, None, "f64", threads=2)
+    g = H // Hkv
+    for b, L in enumerate(lens):
+        tq = torch.from_numpy(np_widen(q[b], dtype)).reshape(1, H, 1, D)
+        tk = torch.from_numpy(np_widen(K[b][:L], dtype)).permute(1, 0, 2).repeat_interleave(g, dim=0).reshape(1, H, L, D)
+        tv = torch.from_numpy(np_widen(V[b][:L], dtype)).permute(1, 0, 2).repeat_interleave(g, dim=0).reshape(1, H, L, D)
+        want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).reshape(H, D).numpy()
+        assert np.allclose(out[b], want, atol=1e-12)
+
+
+def test_shared_kv_heads_equal_multi_head_on_copied_heads():
+    """The same thing without a library: materialise the shared heads as H separate (equal) heads
+    and run the multi-head oracle; bit-equal because each head's arithmetic is the same."""
+    dtype = orc.BF16
+    rng = np.random.default_rng(22)
+    H, Hkv, D = 8, 2, 32
+    lens = [5, 64]
+    q = wl.normal_bits(rng, (2, H, D), dtype)
+    K = [wl.normal_bits(rng, (L, Hkv, D), dtype) for L in lens]
+    V = [wl.normal_bits(rng, (L, Hkv, D), dtype) for L in lens]
+    shared, _ = orc.attention_ragged(q, K, V, lens, dtype)
+    full, _ = orc.attention_ragged(q, [np.repeat(k, H // Hkv, axis=1) for k in K],
+                                   [np.repeat(v, H // Hkv, axis=1) for v in V], lens, dtype)
+    assert np.array_equal(shared, full)
+
+
+def test_kv_oracle_bytes_per_token_counts_kv_heads_only():
+    """Cache bytes per token are 2 (K and V) * layers * kv heads * d * 2 bytes: with all heads this
+    is the 4*l*d_h of section 2.1; sharing key/value heads divides it by the group size."""
+    full = orc.KVOracle(28, 16, 256, orc.F16, 64, 2048, 1 << 30, store=False)
+    mqa = orc.KVOracle(28, 16, 256, orc.F16, 64, 2048, 1 << 30, store=False, n_kv_heads=1)
+    gqa = orc.KVOracle(28, 16, 256, orc.F16, 64, 2048, 1 << 30, store=False, n_kv_heads=4)
+    assert full.bytes_per_token == 4 * 28 * 4096
+    assert mqa.bytes_per_token * 16 == full.bytes_per_token
+    assert gqa.bytes_per_token * 4 == full.bytes_per_token
+    assert mqa.N == (1 << 30) // mqa.bytes_per_token
+
+
 # ---------------------------------------------------------------- oracle accuracy, split-K identity
 def test_fp32_oracle_close_to_float64_twin_on_c0():
     w = wl.c0()
