@@ -36,6 +36,9 @@ def parse():
     ap.add_argument("--event-every", type=int, default=16,
                     help="bracket every k-th attention launch with HIP events (each bracket costs a few us)")
     ap.add_argument("--c3-bytes", type=float, default=200e9)
+    ap.add_argument("--heads", type=str, default="", help="c5 only: query heads, kv heads, head dim as Q,KV,D")
+    ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (not c3); the "
+                    "default is the configuration the metric is quoted on")
     ap.add_argument("--unfused", action="store_true", help="append + attention + merge kernels instead of one")
     return ap.parse_args()
 
@@ -142,7 +145,11 @@ def main():
 
     assert torch.cuda.is_available(), "bench.py needs the GPU"
     s3.lib()
-    w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4, "c5": wl.c5}[args.workload]() if args.workload != "c3" else wl.c3(
+    kw = {"batch": args.batch} if args.batch > 0 else {}
+    if args.heads and args.workload == "c5":
+        hq, hkv, hd = (int(x) for x in args.heads.split(","))
+        kw.update(n_heads=hq, n_kv_heads=hkv, head_dim=hd)
+    w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4, "c5": wl.c5}[args.workload](**kw) if args.workload != "c3" else wl.c3(
         target_bytes=int(args.c3_bytes))
     shared_kv = w.kv_heads < w.n_heads  # not one of the paper's models: measured as a widening, not the headline
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload][0]

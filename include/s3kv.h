@@ -239,7 +239,8 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default)
  *   "classes"      length classes of the longest-first work order (1..8; 0 = library default)
  *   "grid_blocks"  workgroups launched (0 = library default)
- *   "variant"      kernel variant index, -1 = default (see get "n_variants")
+ *   "variant"      kernel variant index, -1 = default (see get "n_variants"; arenas with shared
+ *                  key/value heads have their own, shorter, list)
  *   "profile"      k > 0: bracket every k-th attention launch (counted from this call) with HIP events
  *                  on its stream; 0: off; both reset the sums
  * get names: the above plus "n_variants", "n_grows", "live_slots", "scratch_bytes", "num_cus" and,

@@ -6,7 +6,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs3kv.so")
-SOURCES = ["s3kv_kernels.hip", "s3kv_alloc.cpp", "s3kv_sched.cpp"]
+SOURCES = ["s3kv_kernels.hip", "s3kv_gqa.hip", "s3kv_alloc.cpp", "s3kv_sched.cpp"]
+HEADERS = ["s3kv_internal.h", "s3kv_device.h"]
 
 
 def _hipcc() -> str:
@@ -17,30 +18,39 @@ def _hipcc() -> str:
 
 
 def build_lib(force: bool = True, verbose: bool = False) -> str:
+    """Compile every source to an object (in parallel, one hipcc each), then link the shared library."""
+    from concurrent.futures import ThreadPoolExecutor
+
     srcs = [os.path.join(CSRC, s) for s in SOURCES]
-    deps = srcs + [os.path.join(CSRC, "s3kv_internal.h"), os.path.join(ROOT, "include", "s3kv.h")]
+    deps = srcs + [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(ROOT, "include", "s3kv.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
+    objdir = os.path.join(HERE, "_build")
+    os.makedirs(objdir, exist_ok=True)
+    flags = ["-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC",
+             # keep the compiler from forming packed-fp32 instructions
+             "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+             # fuse a*b+c only inside one expression: the max-subtracted exponent s - max(s) must stay
+             # an exact zero for the largest score (cross-statement fusing would turn it into a residual)
+             "-ffp-contract=on",
+             "-Wall", "-Wno-unused-function",
+             "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+
+    def run(cmd):
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+        out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
+        if res.returncode != 0:
+            raise RuntimeError("hipcc failed:\n" + out)
+        if verbose and out.strip():
+            print(out, flush=True)
+
+    objs = [os.path.join(objdir, os.path.basename(s) + ".o") for s in srcs]
+    with ThreadPoolExecutor(max_workers=min(len(srcs), int(os.environ.get("MAX_JOBS", "8")))) as pool:
+        list(pool.map(lambda so: run([_hipcc()] + flags + ["-c", "-x", "hip", so[0], "-o", so[1]]), zip(srcs, objs)))
     tmp = LIB + ".tmp"
-    cmd = [_hipcc(), "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
-           # keep the compiler from forming packed-fp32 instructions
-           "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-           # fuse a*b+c only inside one expression: the max-subtracted exponent s - max(s) must stay
-           # an exact zero for the largest score (cross-statement fusing would turn it into a residual)
-           "-ffp-contract=on",
-           "-Wall", "-Wno-unused-function",
-           "-I", os.path.join(ROOT, "include"), "-I", CSRC]
-    for s in srcs:
-        cmd += ["-x", "hip", s]
-    cmd += ["-o", tmp]
-    if verbose:
-        print(" ".join(cmd))
-    res = subprocess.run(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
-    out = "\n".join(l for l in res.stdout.splitlines() if "packed-fp32-ops" not in l)
-    if res.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + out)
-    if verbose and out.strip():
-        print(out)
+    run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp])
     os.replace(tmp, LIB)
     return LIB
 

@@ -267,6 +267,11 @@ extern "C" int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_t
     return S3_OK;
 }
 
+// The attention kernel family an arena uses depends on whether its key/value heads are shared.
+static int s3i_variants_of(const s3_arena *a) {
+    return a->cfg.n_kv_heads < a->cfg.n_heads ? s3i_num_gqa_shapes() : s3i_num_variants();
+}
+
 extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
     if (!a || !name) return S3_ERR_INVALID;
     if (!strcmp(name, "chunk")) {
@@ -285,7 +290,7 @@ extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
         return S3_OK;
     }
     if (!strcmp(name, "variant")) {
-        if (value < -1 || value >= s3i_num_variants()) return S3_ERR_INVALID;
+        if (value < -1 || value >= s3i_variants_of(a)) return S3_ERR_INVALID;
         a->variant = (int32_t)value;
         return S3_OK;
     }
@@ -306,7 +311,7 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
     else if (!strcmp(name, "grid_blocks")) *value = a->grid_blocks;
     else if (!strcmp(name, "classes")) *value = a->ncls;
     else if (!strcmp(name, "variant")) *value = a->variant;
-    else if (!strcmp(name, "n_variants")) *value = s3i_num_variants();
+    else if (!strcmp(name, "n_variants")) *value = s3i_variants_of(a);
     else if (!strcmp(name, "n_grows")) *value = a->n_grows;
     else if (!strcmp(name, "live_slots")) *value = (int64_t)a->slots.size() - (int64_t)a->dead_ids.size();
     else if (!strcmp(name, "scratch_bytes")) *value = (int64_t)a->scratch_bytes;

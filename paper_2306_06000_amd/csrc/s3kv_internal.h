@@ -63,7 +63,8 @@ void s3i_set_hip_error(const char *what, int code, const char *text);
 // device work (s3kv_kernels.hip); each returns an s3_status
 int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src_plane_stride,
                            size_t dst_plane_stride, int planes, void *stream);
-int s3i_num_variants();
+int s3i_num_variants();    // kernel variants of the multi-head attention kernels
+int s3i_num_gqa_shapes();  // shapes of the shared-K/V (grouped-query) attention kernel
 int s3i_profile_collect(s3_arena *a);  // synchronises on the recorded events and accumulates the sums
 void s3i_profile_reset(s3_arena *a);
 int s3i_device_cus(int32_t *cus);

@@ -23,12 +23,7 @@
 
 #include "s3kv_internal.h"
 
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-
-#define S3_MAX_BATCH 4095
+#include "s3kv_device.h"
 
 static int hip_fail(const char *what, hipError_t e) {
     s3i_set_hip_error(what, (int)e, hipGetErrorString(e));
@@ -194,368 +189,6 @@ __global__ void __launch_bounds__(256) append_kernel(char *kplane, char *vplane,
 // ------------------------------------------------------------------------------------------
 // attention
 // ------------------------------------------------------------------------------------------
-struct AttnArgs {
-    char *kplane;
-    char *vplane;
-    const char *q;
-    const int64_t *slot_off;
-    const int32_t *cur_len;  // rows to attend minus len_add
-    void *out;
-    float *part_acc;   // [n][max_chunks][H][D]
-    float2 *part_ml;   // [n][max_chunks][H]  (running max in log2 units, sum)
-    int64_t n_tokens;  // arena capacity N
-    int32_t n, H, chunk, max_chunks, out_dtype, max_len;  // H: heads of a K/V row
-    int32_t Hq;            // query heads (= H unless grouped-query / multi-query attention)
-    int32_t ncls;          // length classes of the work order (1..8)
-    int32_t len_add;    // 0: cur_len is the context length; 1 (fused step): cur_len is the append position
-    float scale_log2e;  // scale * log2(e): scores are kept in log2 units so that exp is v_exp_f32
-    // fused step only
-    const char *k_new;
-    const char *v_new;
-    int32_t *len_out;        // may be null
-    unsigned int *arrivals;  // [n][n_hgb] chunk-arrival counters, zero between launches
-};
-
-__device__ __forceinline__ int checked_len(const AttnArgs &a, int b) {
-    const int64_t off = a.slot_off[b];
-    const int32_t raw = a.cur_len[b];
-    const int64_t len = (int64_t)raw + a.len_add;
-    const bool ok = off >= 0 && raw >= 0 && len <= a.max_len && off + len <= a.n_tokens;
-    return ok ? (int)len : 0;
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_sum_step(float v) {
-    const int bits = __builtin_bit_cast(int, v);
-    const int moved = __builtin_amdgcn_update_dpp(0, bits, CTRL, 0xF, 0xF, true);
-    return v + __builtin_bit_cast(float, moved);
-}
-
-// Sum over groups of LANES adjacent lanes (8, 16 or 32); every lane of a group gets the sum.
-template <int LANES>
-__device__ __forceinline__ float group_sum(float v) {
-    v = dpp_sum_step<0xB1>(v);   // quad_perm [1,0,3,2]: lane ^ 1
-    v = dpp_sum_step<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2
-    v = dpp_sum_step<0x141>(v);  // row_half_mirror: the other quad of each 8
-    if (LANES >= 16) v = dpp_sum_step<0x140>(v);  // row_mirror: the other 8 of each 16
-    if (LANES >= 32)
-    {
-        const int bits = __builtin_bit_cast(int, v);
-        const int other = __builtin_amdgcn_ds_swizzle(bits, 0x401F);  // lane ^ 16
-        v += __builtin_bit_cast(float, other);
-    }
-    return v;
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-// Note: __builtin_bit_cast applied directly to a vector-element expression (v[i]) reads element 0
-// with this compiler, so elements are always copied into a scalar first.
-template <int DT>
-__device__ __forceinline__ float dot8(const u32x4 a, const u32x4 b) {
-    float s = 0.f;
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        const unsigned ai = a[i], bi = b[i];
-        if (DT == S3_F16)
-            s = __builtin_amdgcn_fdot2(__builtin_bit_cast(f16x2, ai), __builtin_bit_cast(f16x2, bi), s, false);
-        else
-            s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, ai), __builtin_bit_cast(bf16x2, bi), s, false);
-    }
-    return s;
-}
-
-template <int DT>
-__device__ __forceinline__ void axpy8(float (&acc)[8], const float p, const u32x4 v) {
-#pragma unroll
-    for (int i = 0; i < 4; i++) {
-        float lo, hi;
-        const unsigned vi = v[i];
-        if (DT == S3_F16) {
-            const f16x2 h = __builtin_bit_cast(f16x2, vi);
-            lo = (float)h[0];
-            hi = (float)h[1];
-        } else {
-            const unsigned lo_bits = vi << 16, hi_bits = vi & 0xFFFF0000u;
-            lo = __builtin_bit_cast(float, lo_bits);
-            hi = __builtin_bit_cast(float, hi_bits);
-        }
-        acc[2 * i] = fmaf(p, lo, acc[2 * i]);
-        acc[2 * i + 1] = fmaf(p, hi, acc[2 * i + 1]);
-    }
-}
-
-__device__ __forceinline__ unsigned f32_to_bf16_rne(float f) {
-    unsigned u = __builtin_bit_cast(unsigned, f);
-    if ((u & 0x7FFFFFFFu) > 0x7F800000u) return (u >> 16) | 0x40u;  // NaN stays NaN
-    return (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;
-}
-
-// Store 8 consecutive output elements starting at element index e of `out`.
-__device__ __forceinline__ void store_out8(void *out, int out_dtype, int64_t e, const float (&v)[8]) {
-    if (out_dtype == S3_F32) {
-        f32x4 *p = (f32x4 *)((float *)out + e);
-        p[0] = (f32x4){v[0], v[1], v[2], v[3]};
-        p[1] = (f32x4){v[4], v[5], v[6], v[7]};
-    } else {
-        u32x4 w;
-#pragma unroll
-        for (int i = 0; i < 4; i++) {
-            if (out_dtype == S3_F16) {
-                const f16x2 h = {(_Float16)v[2 * i], (_Float16)v[2 * i + 1]};
-                const unsigned packed = __builtin_bit_cast(unsigned, h);
-                w[i] = packed;
-            } else {
-                w[i] = f32_to_bf16_rne(v[2 * i]) | (f32_to_bf16_rne(v[2 * i + 1]) << 16);
-            }
-        }
-        *(u32x4 *)((uint16_t *)out + e) = w;
-    }
-}
-
-template <bool NT>
-__device__ __forceinline__ u32x4 load16(const char *p) {
-    return NT ? __builtin_nontemporal_load((const u32x4 *)p) : *(const u32x4 *)p;
-}
-
-// Work order of a launch: longest contexts first.  Contexts are put into `ncls` length classes
-// relative to the longest context of the batch; the work list holds the chunks of class 0 (the longest)
-// in batch order, then class 1, and so on.  Long items therefore start first and the short ones fill
-// the end of the kernel (a ragged batch in random order ran 10 % slower), and the cross-workgroup
-// merges of multi-chunk contexts overlap with the streaming of the rest.  The whole workgroup builds
-// one exclusive prefix sum of chunk counts per class in LDS: pre[c][0..n] at cum[c * (n + 1)].
-#define S3_MAX_CLASSES 8
-#define S3_MAX_WAVES 16
-
-__device__ __forceinline__ int chunks_of(const AttnArgs &a, int b, int chunk) {
-    return (checked_len(a, b) + chunk - 1) / chunk;
-}
-
-__device__ __forceinline__ int class_of(int len, int max_len_seen, int ncls) {
-    return ncls - 1 - min(ncls - 1, len * ncls / (max_len_seen + 1));  // len * ncls < 2^31: len <= max_len <= 2^20
-}
-
-// Inclusive prefix sum over the 64 lanes of a wave with DPP row operations (no LDS round trips):
-// shifts by 1, 2, 4, 8 inside each row of 16 lanes, then the row totals are carried into the
-// following rows (row_bcast:15 into rows 1 and 3, row_bcast:31 into rows 2 and 3).
-template <int CTRL, int ROW_MASK>
-__device__ __forceinline__ int dpp_scan_step(int v) {
-    return v + __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false);
-}
-__device__ __forceinline__ int wave_inclusive_scan(int v) {
-    v = dpp_scan_step<0x111, 0xF>(v);  // row_shr:1
-    v = dpp_scan_step<0x112, 0xF>(v);  // row_shr:2
-    v = dpp_scan_step<0x114, 0xF>(v);  // row_shr:4
-    v = dpp_scan_step<0x118, 0xF>(v);  // row_shr:8
-    v = dpp_scan_step<0x142, 0xA>(v);  // row_bcast:15 -> rows 1, 3
-    v = dpp_scan_step<0x143, 0xC>(v);  // row_bcast:31 -> rows 2, 3
-    return v;
-}
-
-// LDS picture of the batch built by every workgroup at kernel start (dynamic shared memory):
-//   off[n] (int64), len[n] (int32, 0 for refused entries), pre[ncls][n + 1] (int32)
-struct BatchView {
-    const int64_t *off;
-    const int *len;
-    const int *pre;
-    int n, ncls, total;
-};
-
-__device__ __forceinline__ size_t batch_view_bytes(int n, int ncls) {
-    return (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)ncls * (n + 1) * 4;
-}
-
-// One pass over the device arrays (each entry is read from global memory once and checked once),
-// then class-wise exclusive prefix sums of the chunk counts.
-__device__ __forceinline__ BatchView build_batch_view(const AttnArgs &a, char *dyn, int *wave_sums) {
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int nthreads = blockDim.x, nwaves = nthreads >> 6;
-    const int ncls = a.ncls, chunk = a.chunk, n = a.n;
-    int64_t *off_s = (int64_t *)dyn;
-    int *len_s = (int *)(dyn + (size_t)n * 8);
-    int *pre = len_s + ((n + 1) & ~1);
-    const int per = (n + nthreads - 1) / nthreads;
-    const int b0 = min(n, tid * per), b1 = min(n, b0 + per);
-    int mx = 0;
-    for (int b = b0; b < b1; b++) {
-        const int len = checked_len(a, b);
-        len_s[b] = len;
-        off_s[b] = a.slot_off[b];
-        mx = max(mx, len);
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
-    if (lane == 0) wave_sums[wave] = mx;
-    __syncthreads();
-    for (int i = 0; i < nwaves; i++) mx = max(mx, wave_sums[i]);
-    __syncthreads();  // wave_sums is reused below
-    int cnt[S3_MAX_CLASSES], incl[S3_MAX_CLASSES];
-#pragma unroll
-    for (int c = 0; c < S3_MAX_CLASSES; c++) cnt[c] = 0;
-    for (int b = b0; b < b1; b++) {
-        const int len = len_s[b];
-        const int k = (len + chunk - 1) / chunk;
-        const int cl = class_of(len, mx, ncls);
-#pragma unroll
-        for (int c = 0; c < S3_MAX_CLASSES; c++) cnt[c] += (c == cl) ? k : 0;
-    }
-#pragma unroll
-    for (int c = 0; c < S3_MAX_CLASSES; c++) {
-        if (c < ncls) {  // uniform
-            const int v = wave_inclusive_scan(cnt[c]);
-            incl[c] = v;
-            if (lane == 63) wave_sums[c * S3_MAX_WAVES + wave] = v;
-        }
-    }
-    __syncthreads();
-    int run[S3_MAX_CLASSES];
-#pragma unroll
-    for (int c = 0; c < S3_MAX_CLASSES; c++) {
-        run[c] = 0;
-        if (c < ncls) {
-            int base = 0;
-            for (int i = 0; i < wave; i++) base += wave_sums[c * S3_MAX_WAVES + i];
-            run[c] = base + incl[c] - cnt[c];
-        }
-    }
-    for (int b = b0; b < b1; b++) {
-        const int len = len_s[b];
-        const int k = (len + chunk - 1) / chunk;
-        const int cl = class_of(len, mx, ncls);
-#pragma unroll
-        for (int c = 0; c < S3_MAX_CLASSES; c++) {
-            if (c < ncls) pre[c * (n + 1) + b] = run[c];
-            run[c] += (c == cl) ? k : 0;
-        }
-    }
-    if (tid == nthreads - 1) {
-#pragma unroll
-        for (int c = 0; c < S3_MAX_CLASSES; c++)
-            if (c < ncls) pre[c * (n + 1) + n] = run[c];
-    }
-    __syncthreads();
-    BatchView v;
-    v.off = off_s;
-    v.len = len_s;
-    v.pre = pre;
-    v.n = n;
-    v.ncls = ncls;
-    v.total = 0;
-    for (int c = 0; c < ncls; c++) v.total += pre[c * (n + 1) + n];
-    return v;
-}
-
-// Partials that cross workgroups inside ONE launch (fused step) must not sit in a cache that
-// another XCD cannot see: they are written and read with device-scope relaxed atomics, which on
-// gfx950 are plain 32-bit stores / loads that go through to memory-side coherence.  No cache
-// write-back or invalidate is needed then (those cost far more than the partials themselves).
-template <bool COHERENT>
-__device__ __forceinline__ void put_partial(float *p, float v) {
-    if (COHERENT) __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    else *p = v;
-}
-template <bool COHERENT>
-__device__ __forceinline__ float get_partial(const float *p) {
-    return COHERENT ? __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : *p;
-}
-
-// Merge the chunk partials of (sequence b, head h) for this lane's 8-element slice and store the
-// final output row slice.  nchunks >= 2.  Four chunks are loaded per round so that the (cache
-// bypassing) loads of a round are in flight together.
-template <int D, bool COHERENT>
-__device__ __forceinline__ void merge_chunks(const AttnArgs &a, int b, int h, int dl, int nchunks) {
-    const int64_t p0 = ((int64_t)b * a.max_chunks) * a.H + h;
-    const float *ml = (const float *)a.part_ml;
-    float mm = -INFINITY, l = 0.f;
-    float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    for (int c0 = 0; c0 < nchunks; c0 += 4) {
-        float mv[4], lv[4], av[4][8];
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const int64_t pi = p0 + (int64_t)min(c0 + u, nchunks - 1) * a.H;
-            mv[u] = get_partial<COHERENT>(ml + 2 * pi);
-            lv[u] = get_partial<COHERENT>(ml + 2 * pi + 1);
-            const float *pa = a.part_acc + pi * D + dl * 8;
-#pragma unroll
-            for (int i = 0; i < 8; i++) av[u][i] = get_partial<COHERENT>(pa + i);
-        }
-        float mn = mm;
-#pragma unroll
-        for (int u = 0; u < 4; u++) mn = fmaxf(mn, mv[u]);  // repeats of the last chunk do not change the max
-        const float alpha = fast_exp2(mm - mn);
-        l *= alpha;
-#pragma unroll
-        for (int i = 0; i < 8; i++) o[i] *= alpha;
-#pragma unroll
-        for (int u = 0; u < 4; u++) {
-            const float wgt = (c0 + u < nchunks) ? fast_exp2(mv[u] - mn) : 0.f;
-            l += wgt * lv[u];
-#pragma unroll
-            for (int i = 0; i < 8; i++) o[i] += wgt * av[u][i];
-        }
-        mm = mn;
-    }
-    const float inv = 1.f / l;
-#pragma unroll
-    for (int i = 0; i < 8; i++) o[i] *= inv;
-    store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, o);
-}
-
-// What a workgroup item is: chunk c of sequence b for head block hgb.
-struct Item {
-    int b, c, nchunks, len, hgb;
-    int clen;  // rows per chunk of this context: the context is cut into nchunks near-equal pieces
-    int64_t off;
-};
-
-// Rows per chunk when a context of len rows is cut into nchunks pieces: near-equal pieces; falls
-// back to `chunk` if rounding would leave the last piece empty.
-__device__ __forceinline__ int balanced_chunk_len(int len, int nchunks, int chunk) {
-    if (nchunks <= 1) return chunk;
-    const int clen = (len + nchunks - 1) / nchunks;
-    return (nchunks - 1) * clen < len ? clen : chunk;
-}
-
-// Rows [j0, j1) of item `it` that token split ts of TS takes: the item's rows are divided evenly
-// (split 0 is never empty; trailing splits may be).
-__device__ __forceinline__ void split_rows(const Item &it, int ts, int TS, int &j0, int &j1) {
-    const int start = it.c * it.clen;
-    const int end = min(it.len, start + it.clen);
-    const int per = (end - start + TS - 1) / TS;
-    j0 = min(end, start + ts * per);
-    j1 = min(end, j0 + per);
-}
-
-__device__ __forceinline__ Item decode_item(const AttnArgs &a, const BatchView &v, int64_t item, int n_hgb) {
-    Item it;
-    int w = (int)(item / n_hgb);
-    it.hgb = (int)(item - (int64_t)w * n_hgb);
-    const int *pre = v.pre;
-    for (int c = 0; c < v.ncls - 1; c++) {  // which class the item falls into
-        const int t = pre[v.n];
-        if (w < t) break;
-        w -= t;
-        pre += v.n + 1;
-    }
-    int lo = 0, hi = v.n - 1;
-    while (lo < hi) {  // first b with pre[b+1] > w
-        const int mid = (lo + hi) >> 1;
-        if (pre[mid + 1] > w) hi = mid; else lo = mid + 1;
-    }
-    it.b = lo;
-    it.c = w - pre[lo];
-    it.nchunks = pre[lo + 1] - pre[lo];
-    it.len = v.len[lo];
-    it.off = v.off[lo];
-    if (it.c < 0 || it.c >= it.nchunks) {  // cannot happen with a consistent view; never index rows from it
-        it.c = 0;
-        it.nchunks = 1;
-        it.len = 0;
-    }
-    it.clen = balanced_chunk_len(it.len, it.nchunks, a.chunk);
-    return it;
-}
-
 // One wave's share of an item: tokens [j0, j1) of head group hg, online softmax in fp32.
 // DT: element type of q/K/V.  D: head_dim.  U: tokens per load batch.  NT: non-temporal loads.
 // FUSED: row len-1 is still only in k_new / v_new: it is taken from there and, by the wave whose
@@ -711,18 +344,9 @@ __device__ __forceinline__ void emit_chunk(const AttnArgs &a, const Item &it, in
     const int64_t pi = ((int64_t)it.b * a.max_chunks + it.c) * a.H + h;
     float *pml = (float *)a.part_ml + 2 * pi;
     float *pa = a.part_acc + pi * D + dl * 8;
-    if (COHERENT) {
-        if (dl == 0) {
-            put_partial<true>(pml, m);
-            put_partial<true>(pml + 1, l);
-        }
-#pragma unroll
-        for (int i = 0; i < 8; i++) put_partial<true>(pa + i, acc[i]);
-    } else {
-        if (dl == 0) a.part_ml[pi] = make_float2(m, l);
-        ((f32x4 *)pa)[0] = (f32x4){acc[0], acc[1], acc[2], acc[3]};
-        ((f32x4 *)pa)[1] = (f32x4){acc[4], acc[5], acc[6], acc[7]};
-    }
+    if (dl == 0) put_partial2<COHERENT>(pml, (f32x2){m, l});
+    put_partial4<COHERENT>(pa, (f32x4){acc[0], acc[1], acc[2], acc[3]});
+    put_partial4<COHERENT>(pa + 4, (f32x4){acc[4], acc[5], acc[6], acc[7]});
 }
 
 // Attention only (s3_decode_attention): TS*HS waves; the TS waves of a head group split the chunk's
@@ -837,127 +461,10 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
                     if (lane == 0) atomicExch(cnt, 0u);        // leave the counter clean for the next launch
                     for (int s = 0; s < HS; s++) {
                         const int h = (it.hgb * HS + s) * GH + lane / LPH;
-                        if (h < a.H) merge_chunks<D, true>(a, it.b, h, lane % LPH, it.nchunks);
+                        if (h < a.H) merge_chunks<D, true>(a, a.H, it.b, h, lane % LPH, it.nchunks);
                     }
                 }
             }
-        }
-    }
-}
-
-// Grouped-query / multi-query attention (n_kv_heads < n_heads; the paper's related-work section names
-// multi-query attention as a complementary way to shrink the cache): K/V rows hold H heads, q and out
-// Hq = H * group heads; K/V head k serves query heads k*group .. k*group+group-1.  A wave's 128-bit
-// load covers 1 KiB of consecutive arena bytes as in the multi-head kernels: GH K/V heads of one row
-// or, when a row has fewer than GH heads (H dividing GH), GH/H whole consecutive rows, each lane group
-// then keeping its own online-softmax state for its share of the rows.  Every lane carries GQ query
-// heads per K/V head; group/GQ items per K/V head group re-read the same rows.  One workgroup handles
-// a whole context: its TS waves split the rows and merge through LDS, one query head at a time, so
-// there are no cross-workgroup partials.  With len_add = 1 it is the attention half of a decode step
-// whose append ran as its own launch before it.
-template <int DT, int D, int GQ, int TS, int U>
-__global__ void __launch_bounds__(TS * 64) attn_gqa_kernel(const AttnArgs a) {
-    constexpr int LPH = D / 8;
-    constexpr int GH = 64 / LPH;
-    __shared__ float comb[TS][10][64];
-    const int lane = threadIdx.x & 63, ts = threadIdx.x >> 6;
-    const int group = a.Hq / a.H;
-    const int tpw = (a.H < GH && GH % a.H == 0) ? GH / a.H : 1;  // rows per wave load
-    const int n_kvhg = (a.H + GH - 1) / GH, n_qsub = group / GQ;
-    const int64_t per_seq = (int64_t)n_kvhg * n_qsub;
-    const int64_t total = (int64_t)a.n * per_seq;
-    if (blockIdx.x == 0 && a.len_out)
-        for (int b = threadIdx.x; b < a.n; b += TS * 64) a.len_out[b] = a.cur_len[b] + 1;
-
-    const int slot = lane / LPH, dl = lane % LPH;
-    const int tsub = tpw > 1 ? slot / a.H : 0;
-    for (int64_t item = blockIdx.x; item < total; item += gridDim.x) {
-        const int b = (int)(item / per_seq);
-        const int r = (int)(item - (int64_t)b * per_seq);
-        const int kvhg = r / n_qsub, qsub = r - kvhg * n_qsub;
-        const int len = checked_len(a, b);
-        const int64_t off = a.slot_off[b];
-        const int hk = tpw > 1 ? slot % a.H : kvhg * GH + slot;
-        const bool hk_ok = hk < a.H;
-        const int hkc = hk_ok ? hk : a.H - 1;
-        const int per = (len + TS - 1) / TS;
-        const int j0 = min(len, ts * per), j1 = min(len, j0 + per);
-        const int64_t rstride = (int64_t)a.H * D * 2;
-        const int64_t lane_byte = ((int64_t)hkc * D + dl * 8) * 2;
-        const char *kp = a.kplane + off * rstride + lane_byte;
-        const char *vp = a.vplane + off * rstride + lane_byte;
-        const int hq0 = hkc * group + qsub * GQ;  // first of this lane's GQ query heads
-        u32x4 qv[GQ];
-#pragma unroll
-        for (int i = 0; i < GQ; i++)
-            qv[i] = *(const u32x4 *)(a.q + (((int64_t)b * a.Hq + hq0 + i) * D + dl * 8) * 2);
-        float m[GQ], l[GQ], acc[GQ][8];
-#pragma unroll
-        for (int i = 0; i < GQ; i++) {
-            m[i] = -INFINITY;
-            l[i] = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; e++) acc[i][e] = 0.f;
-        }
-        for (int j = j0; j < j1; j += U * tpw) {
-            u32x4 kk[U], vv[U];
-#pragma unroll
-            for (int u = 0; u < U; u++) kk[u] = load16<true>(kp + (int64_t)min(j + u * tpw + tsub, j1 - 1) * rstride);
-#pragma unroll
-            for (int u = 0; u < U; u++) vv[u] = load16<true>(vp + (int64_t)min(j + u * tpw + tsub, j1 - 1) * rstride);
-#pragma unroll
-            for (int i = 0; i < GQ; i++) {
-                float s[U], mb = -INFINITY;
-#pragma unroll
-                for (int u = 0; u < U; u++) {
-                    const float d = group_sum<LPH>(dot8<DT>(qv[i], kk[u]));
-                    s[u] = (j + u * tpw + tsub < j1) ? d * a.scale_log2e : -INFINITY;
-                    mb = fmaxf(mb, s[u]);
-                }
-                // a lane group whose rows of this batch are all past the end keeps its state
-                const float mn = fmaxf(m[i], mb);
-                const float alpha = (mn == -INFINITY) ? 1.f : fast_exp2(m[i] - mn);
-                l[i] *= alpha;
-#pragma unroll
-                for (int e = 0; e < 8; e++) acc[i][e] *= alpha;
-#pragma unroll
-                for (int u = 0; u < U; u++) {
-                    const float p = (mn == -INFINITY) ? 0.f : fast_exp2(s[u] - mn);
-                    l[i] += p;
-                    axpy8<DT>(acc[i], p, vv[u]);
-                }
-                m[i] = mn;
-            }
-        }
-        const bool writer = ts == 0 && hk_ok && tsub == 0;
-#pragma unroll
-        for (int i = 0; i < GQ; i++) {
-            comb[ts][0][lane] = m[i];
-            comb[ts][1][lane] = l[i];
-#pragma unroll
-            for (int e = 0; e < 8; e++) comb[ts][2 + e][lane] = acc[i][e];
-            __syncthreads();
-            if (writer) {
-                float o[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                if (len > 0) {  // rows start at wave 0, lane group 0, so the maximum is finite
-                    float mm = -INFINITY, ll = 0.f;
-                    for (int t = 0; t < TS; t++)
-                        for (int g = 0; g < tpw; g++) mm = fmaxf(mm, comb[t][0][lane + g * a.H * LPH]);
-                    for (int t = 0; t < TS; t++)
-                        for (int g = 0; g < tpw; g++) {
-                            const int src = lane + g * a.H * LPH;
-                            const float wt = fast_exp2(comb[t][0][src] - mm);
-                            ll += wt * comb[t][1][src];
-#pragma unroll
-                            for (int e = 0; e < 8; e++) o[e] += wt * comb[t][2 + e][src];
-                        }
-                    const float inv = 1.f / ll;
-#pragma unroll
-                    for (int e = 0; e < 8; e++) o[e] *= inv;
-                }
-                store_out8(a.out, a.out_dtype, ((int64_t)b * a.Hq + hq0 + i) * D + dl * 8, o);
-            }
-            __syncthreads();  // comb is reused by the next query head and the next item
         }
     }
 }
@@ -978,7 +485,7 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     const int nchunks = chunks_of(a, b, a.chunk);
     if (nchunks == 1) return;
     if (nchunks > 1) {
-        merge_chunks<D, false>(a, b, h, dl, nchunks);
+        merge_chunks<D, false>(a, a.H, b, h, dl, nchunks);
         return;
     }
     const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -1016,7 +523,6 @@ static const Variant kVariants[] = {
 };
 int s3i_num_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0])); }
 
-typedef void (*attn_fn)(const AttnArgs);
 
 template <int DT, int D, bool FUSED>
 static attn_fn pick_variant(int v) {
@@ -1039,30 +545,6 @@ static attn_fn pick_kernel(int dt, int d, int v) {
         if (d == 64) return pick_variant<S3_BF16, 64, FUSED>(v);
         if (d == 128) return pick_variant<S3_BF16, 128, FUSED>(v);
         if (d == 256) return pick_variant<S3_BF16, 256, FUSED>(v);
-    }
-    return nullptr;
-}
-
-template <int DT, int D>
-static attn_fn pick_gqa_width(int gq) {
-    switch (gq) {
-        case 1: return attn_gqa_kernel<DT, D, 1, 8, 4>;
-        case 2: return attn_gqa_kernel<DT, D, 2, 8, 4>;
-        case 4: return attn_gqa_kernel<DT, D, 4, 8, 4>;
-        case 8: return attn_gqa_kernel<DT, D, 8, 8, 2>;
-        default: return nullptr;
-    }
-}
-
-static attn_fn pick_gqa(int dt, int d, int gq) {
-    if (dt == S3_F16) {
-        if (d == 64) return pick_gqa_width<S3_F16, 64>(gq);
-        if (d == 128) return pick_gqa_width<S3_F16, 128>(gq);
-        if (d == 256) return pick_gqa_width<S3_F16, 256>(gq);
-    } else {
-        if (d == 64) return pick_gqa_width<S3_BF16, 64>(gq);
-        if (d == 128) return pick_gqa_width<S3_BF16, 128>(gq);
-        if (d == 256) return pick_gqa_width<S3_BF16, 256>(gq);
     }
     return nullptr;
 }
@@ -1162,6 +644,24 @@ static int check_slots_host(const s3_arena *a, int32_t n, const int32_t *slot_id
     return full ? S3_ERR_SLOT_FULL : S3_OK;
 }
 
+// Workgroups of `fn` (threads per workgroup, dynamic LDS bytes) that one CU holds at once.  Asked
+// from the runtime once per kernel and LDS size class (4 KiB steps).
+static int resident_per_cu(const void *fn, int threads, size_t dyn_lds, int *per_cu) {
+    static std::map<std::pair<const void *, size_t>, int> resident;  // (kernel, LDS in 4 KiB) -> workgroups per CU
+    const std::pair<const void *, size_t> key(fn, (dyn_lds + 4095) / 4096);
+    auto it = resident.find(key);
+    if (it == resident.end()) {
+        if (dyn_lds > 16384)
+            HIP_TRY(hipFuncSetAttribute(fn, hipFuncAttributeMaxDynamicSharedMemorySize, (int)(key.second * 4096)));
+        int got = 0;
+        HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&got, fn, threads, key.second * 4096));
+        if (got < 1) return S3_ERR_INVALID;  // does not fit the device at all
+        it = resident.emplace(key, got).first;
+    }
+    *per_cu = it->second;
+    return S3_OK;
+}
+
 // Grouped-query / multi-query configurations: with_append = true runs the append as its own launch
 // first (same stream), then the attention over pos + 1 rows, which also publishes the new lengths.
 static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
@@ -1170,7 +670,8 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
     const int group = Hq / Hkv;
     const int gq = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
-    attn_fn fn = pick_gqa(a->cfg.kv_dtype, D, gq);
+    int threads = 0;
+    attn_fn fn = s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;
     if (with_append) {
         hipLaunchKernelGGL(append_kernel, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
@@ -1197,10 +698,28 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     args.scale_log2e = scale * 1.4426950408889634f;
     args.len_out = with_append ? len_out : nullptr;
     const int GH = 512 / D;
-    const int64_t items = (int64_t)n * ((Hkv + GH - 1) / GH) * (group / gq);
+    const int per_seq = ((Hkv + GH - 1) / GH) * (group / gq);
+    // Few (sequence, head group) pairs: cut contexts finer so that the chip still has work everywhere.
+    const int chunk = a->chunk > 0 ? a->chunk : (int64_t)n * per_seq >= 2048 ? 1024 : (int64_t)n * per_seq >= 512 ? 512 : 256;
+    args.chunk = chunk;
+    args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
+    // scratch: [partial sums][partial (max, sum)], one partial per (sequence, chunk, query head)
+    const size_t n_part = (size_t)n * args.max_chunks * Hq;
+    const size_t acc_bytes = n_part * D * sizeof(float);
+    const int src = ensure_scratch(a, acc_bytes + n_part * sizeof(float2));
+    if (src != S3_OK) return src;
+    args.part_acc = (float *)a->scratch;
+    args.part_ml = (float2 *)((char *)a->scratch + acc_bytes);
+    args.ncls = a->ncls > 0 ? a->ncls : n <= 128 ? 4 : n <= 256 ? 2 : 1;
+    const size_t dyn_lds = (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)args.ncls * (n + 1) * 4;
     const int cus = a->num_cus > 0 ? a->num_cus : 256;
-    const int64_t cap = a->grid_blocks > 0 ? a->grid_blocks : (int64_t)cus * 4;
-    const unsigned blocks = (unsigned)(items < cap ? items : cap);
+    int blocks = a->grid_blocks;
+    if (blocks <= 0) {  // the workgroups that are resident at once walk the work list with a stride
+        int per_cu = 0;
+        const int orc = resident_per_cu((const void *)fn, threads, dyn_lds, &per_cu);
+        if (orc != S3_OK) return orc;
+        blocks = cus * per_cu;
+    }
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
     if (timed) {
@@ -1210,12 +729,19 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
         }
         HIP_TRY(hipEventRecord(ev[0], (hipStream_t)stream));
     }
-    hipLaunchKernelGGL(fn, dim3(blocks), dim3(512), 0, (hipStream_t)stream, args);
+    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)threads), dyn_lds, (hipStream_t)stream, args);
     HIP_TRY(hipGetLastError());
-    if (timed) {  // no merge kernel here: the second interval is empty
-        HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
-        HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
+    if (timed) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
+    {  // the merge (and the zero rows of empty contexts) index partials and output by query head
+        AttnArgs margs = args;
+        margs.H = Hq;
+        const unsigned mblocks = (unsigned)(((int64_t)n * ((Hq + GH - 1) / GH) + 3) / 4);
+        void (*mfn)(const AttnArgs) =
+            D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
+        hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, margs);
+        HIP_TRY(hipGetLastError());
     }
+    if (timed) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
     return S3_OK;
 }
 
@@ -1283,19 +809,10 @@ static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q
     // kernel and LDS size class.
     int blocks = a->grid_blocks;
     if (blocks <= 0) {
-        static std::map<std::pair<const void *, size_t>, int> resident;  // (kernel, LDS KiB) -> workgroups per CU
-        const std::pair<const void *, size_t> key((const void *)fn, (dyn_lds + 4095) / 4096);
-        auto it = resident.find(key);
-        if (it == resident.end()) {
-            if (dyn_lds > 16384)
-                HIP_TRY(hipFuncSetAttribute((const void *)fn, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                            (int)(key.second * 4096)));
-            int per_cu = 0;
-            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)fn, nw * 64, key.second * 4096));
-            if (per_cu < 1) return S3_ERR_INVALID;  // does not fit the device at all
-            it = resident.emplace(key, per_cu).first;
-        }
-        blocks = cus * it->second * (n > 128 ? 2 : 1);  // large batches: two rounds balance better than one
+        int per_cu = 0;
+        const int orc = resident_per_cu((const void *)fn, nw * 64, dyn_lds, &per_cu);
+        if (orc != S3_OK) return orc;
+        blocks = cus * per_cu * (n > 128 ? 2 : 1);  // large batches: two rounds balance better than one
     }
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;

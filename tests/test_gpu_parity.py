@@ -538,6 +538,18 @@ def test_shared_kv_heads_attention(H, Hkv, D, dtype):
             assert not got[0].any()  # empty context: zeros
         else:
             assert np.abs(got - want).max() <= 2e-2
+    # every kernel shape; chunk sizes from contexts in up to 19 pieces (merged by the second kernel)
+    # to all in one piece
+    shapes = n_variants(rig.a) if Hkv < H else 1
+    for shape in range(shapes):
+        if Hkv < H:
+            assert s3.s3_kv_set_param(rig.a, "variant", shape) == 0
+        for chunk in (32, 160, 1024):
+            assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+            q, got = rig.attend(lens, layer=1)
+            assert_close(got, rig.oracle_attend(q, lens, layer=1), f"shared kv {H}/{Hkv} d{D} shape {shape} chunk {chunk}")
+    if Hkv < H:
+        assert s3.s3_kv_set_param(rig.a, "variant", shapes) == s3.S3_ERR_INVALID
     rig.close()
 
 
