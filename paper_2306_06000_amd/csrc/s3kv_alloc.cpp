@@ -269,7 +269,7 @@ extern "C" int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_t
 
 // The attention kernel family an arena uses depends on whether its key/value heads are shared.
 static int s3i_variants_of(const s3_arena *a) {
-    return a->cfg.n_kv_heads < a->cfg.n_heads ? s3i_num_gqa_shapes() : s3i_num_variants();
+    return a->cfg.n_kv_heads < a->cfg.n_heads ? s3i_num_gqa_shapes() + 1 : s3i_num_variants();  // + the matrix-core kernel
 }
 
 extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {

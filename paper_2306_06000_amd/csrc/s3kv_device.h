@@ -400,3 +400,6 @@ typedef void (*attn_fn)(const AttnArgs);
 // lane (1, 2, 4 or 8), shape = index into its (waves, rows per load batch) table, < 0 for the
 // default of that gq.  Returns the kernel and its workgroup size, or null.
 attn_fn s3i_pick_gqa(int dt, int d, int gq, int shape, int *threads);
+// Matrix-core kernel for shared key/value heads (defined in s3kv_gqa_mfma.hip); 256 threads per
+// workgroup, one work item per wave.
+attn_fn s3i_pick_gqa_mfma(int dt, int d);

@@ -1,0 +1,246 @@
+// Matrix-core attention kernel for shared key/value heads (multi-query / grouped-query attention,
+// which the paper's related-work section names as a complementary way to shrink the cache), gfx950.
+// Launched by the host code in s3kv_kernels.hip through the pointer s3i_pick_gqa_mfma returns.
+//
+// With one cached head serving `group` query heads, a decode step is no longer one dot product per
+// cached row but a small dense contraction: scores S^T[rows x heads] = K[rows x D] . Q^T[D x heads]
+// and output O^T[D x heads] = V^T[D x rows] . P^T[rows x heads].  The vector-ALU kernel repeats the
+// dot / exp / accumulate work per query head and becomes instruction bound from about eight heads
+// per cached head; here both products run on MFMA and every (row, head) score is handled by
+// exactly one lane.
+//
+// One wave = one work item = (sequence, chunk of its context, K/V head, block of 16 query heads);
+// the four waves of a workgroup are independent (no barrier after the batch-view prologue).  Per
+// tile of 16 cached rows:
+//   * K: lane (r = lane % 16, g = lane / 16) loads 16 bytes (8 elements) of row r at element offset
+//     32*ks + 8*g, ks = 0 .. D/32-1: that is the A operand of v_mfma_f32_16x16x32 directly (row r,
+//     contraction slots of lane group g); Q^T is the B operand, loaded once per item with the same
+//     slot assignment (head = lane % 16), so whichever way the instruction numbers its contraction
+//     slots, both operands agree.  The accumulator holds S^T[row 4*g + i][head lane % 16], i < 4.
+//   * softmax: scale into log2 units, mask rows past the end, running maximum per head (over the
+//     four registers, then across the four lane groups), p = exp2(s - m), running sum.
+//   * V: the accumulator layout of S^T is already the B-operand layout of v_mfma_f32_16x16x16
+//     (4 contraction slots = rows 4*g .. 4*g+3, column = head), so P^T needs no shuffle.  The A
+//     operand V^T (row of the product = output element d, contraction = cached rows) needs four
+//     cached rows at ONE d per lane, while memory holds eight d of one row per 16-byte load: the V
+//     tile goes through a per-wave LDS buffer (row-major, row stride padded by 8 bytes so that the
+//     four lane groups hit different banks) and is read back as 16-bit gathers.
+//   * p is rounded to the storage type for the second product; for bfloat16 (8-bit mantissa) it
+//     is split into a high and a low bfloat16 part and the product is issued for both, which
+//     keeps the weights' error near 2^-16 instead of 2^-9.
+// Accumulators: O^T block db holds O^T[d = 16*db + 4*g + i][head], fp32.  Results leave as the
+// final row (single-chunk contexts) or as a chunk partial (max, sum, unnormalised row) that
+// attn_merge_kernel finishes, as in the vector-ALU kernel.
+#include "s3kv_device.h"
+
+typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef short i16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma_scores(const u32x4 a, const u32x4 b, const f32x4 c) {
+    if (DT == S3_F16)
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
+}
+
+template <int DT>
+__device__ __forceinline__ f32x4 mfma_values(const u32x2 a, const u32x2 b, const f32x4 c) {
+    if (DT == S3_F16)
+        return __builtin_amdgcn_mfma_f32_16x16x16f16(__builtin_bit_cast(f16x4, a), __builtin_bit_cast(f16x4, b), c, 0, 0, 0);
+    return __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(i16x4, a), __builtin_bit_cast(i16x4, b), c, 0, 0, 0);
+}
+
+__device__ __forceinline__ unsigned pack_f16(float lo, float hi) {
+    const f16x2 h = {(_Float16)lo, (_Float16)hi};
+    return __builtin_bit_cast(unsigned, h);
+}
+__device__ __forceinline__ float bf16_bits_to_f32(unsigned b) {
+    const unsigned w = b << 16;
+    return __builtin_bit_cast(float, w);
+}
+
+// Four consecutive output elements starting at element index e.
+__device__ __forceinline__ void store_out4(void *out, int out_dtype, int64_t e, const f32x4 v) {
+    if (out_dtype == S3_F32) {
+        *(f32x4 *)((float *)out + e) = v;
+    } else {
+        u32x2 w;
+        if (out_dtype == S3_F16) {
+            w[0] = pack_f16(v[0], v[1]);
+            w[1] = pack_f16(v[2], v[3]);
+        } else {
+            w[0] = f32_to_bf16_rne(v[0]) | (f32_to_bf16_rne(v[1]) << 16);
+            w[1] = f32_to_bf16_rne(v[2]) | (f32_to_bf16_rne(v[3]) << 16);
+        }
+        *(u32x2 *)((uint16_t *)out + e) = w;
+    }
+}
+
+template <int DT, int D>
+__global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
+    constexpr int KS = D / 32;            // contraction steps of the score product
+    constexpr int DB = D / 16;            // 16-element blocks of an output row
+    constexpr int PPR = D / 8;            // 16-byte pieces per cached row of one head
+    constexpr int VL = 16 * PPR / 64;     // 16-byte loads per lane for a 16-row V tile
+    constexpr int VSTRIDE = D * 2 + 8;    // LDS row stride of the V tile, bytes
+    extern __shared__ __align__(16) char dyn_lds[];  // the batch view
+    __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
+    __shared__ __align__(16) char vtile[4][16 * VSTRIDE];
+
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int n = lane & 15, g = lane >> 4;
+    const int group = a.Hq / a.H;
+    const int nqb = (group + 15) / 16;  // blocks of 16 query heads per K/V head
+    const int per_seq = a.H * nqb;
+    const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
+    const int64_t total = (int64_t)bv.total * per_seq;
+    if (blockIdx.x == 0 && a.len_out)
+        for (int b = threadIdx.x; b < a.n; b += 256) a.len_out[b] = a.cur_len[b] + 1;
+
+    char *vt = vtile[wave];
+    const int64_t rstride = (int64_t)a.H * D * 2;
+    for (int64_t item = (int64_t)blockIdx.x * 4 + wave; item < total; item += (int64_t)gridDim.x * 4) {
+        const Item it = decode_item(a, bv, item, per_seq);
+        const int hk = it.hgb / nqb, qb = it.hgb - hk * nqb;
+        const int start = it.c * it.clen, end = min(it.len, start + it.clen);
+        const int head = qb * 16 + n;  // query head of this lane's column, within the group
+        const bool head_ok = head < group;
+        const int hq = hk * group + (head_ok ? head : group - 1);
+
+        u32x4 qop[KS];
+#pragma unroll
+        for (int ks = 0; ks < KS; ks++) {
+            qop[ks] = *(const u32x4 *)(a.q + (((int64_t)it.b * a.Hq + hq) * D + ks * 32 + g * 8) * 2);
+            if (!head_ok) qop[ks] = (u32x4){0u, 0u, 0u, 0u};  // padding columns: zero scores, never stored
+        }
+        const char *kbase = a.kplane + it.off * rstride + (int64_t)hk * D * 2;
+        const char *vbase = a.vplane + it.off * rstride + (int64_t)hk * D * 2;
+
+        f32x4 o[DB];
+#pragma unroll
+        for (int db = 0; db < DB; db++) o[db] = (f32x4){0.f, 0.f, 0.f, 0.f};
+        float m = -INFINITY, lsum = 0.f;
+
+        // Loads of one 16-row tile (rows past the chunk's end are clamped to its last row and masked later).
+        auto load_tile = [&](int r0, u32x4 (&kop)[KS], u32x4 (&vv)[VL]) {
+            const int krow = min(r0 + n, end - 1);
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) kop[ks] = load16<false>(kbase + krow * rstride + (ks * 32 + g * 8) * 2);
+#pragma unroll
+            for (int i = 0; i < VL; i++) {
+                const int idx = i * 64 + lane;
+                vv[i] = load16<true>(vbase + (int64_t)min(r0 + idx / PPR, end - 1) * rstride + (idx % PPR) * 16);
+            }
+        };
+        auto reduce_tile = [&](int r0, const u32x4 (&kop)[KS], const u32x4 (&vv)[VL]) {
+            f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ks++) s = mfma_scores<DT>(kop[ks], qop[ks], s);
+
+            float sv[4], mt = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                sv[i] = (r0 + 4 * g + i < end) ? s[i] * a.scale_log2e : -INFINITY;
+                mt = fmaxf(mt, sv[i]);
+            }
+            mt = fmaxf(mt, __shfl_xor(mt, 16));
+            mt = fmaxf(mt, __shfl_xor(mt, 32));
+            const float mn = fmaxf(m, mt);  // finite: row r0 is inside the chunk
+            const float alpha = fast_exp2(m - mn);
+            float p[4], ps = 0.f;
+#pragma unroll
+            for (int i = 0; i < 4; i++) {
+                p[i] = fast_exp2(sv[i] - mn);
+                ps += p[i];
+            }
+            lsum = lsum * alpha + ps;
+            m = mn;
+#pragma unroll
+            for (int db = 0; db < DB; db++) o[db] *= alpha;
+
+            u32x2 pop, pop_lo;
+            if (DT == S3_F16) {
+                pop[0] = pack_f16(p[0], p[1]);
+                pop[1] = pack_f16(p[2], p[3]);
+            } else {
+                unsigned hi[4], lo[4];
+#pragma unroll
+                for (int i = 0; i < 4; i++) {
+                    hi[i] = f32_to_bf16_rne(p[i]);
+                    lo[i] = f32_to_bf16_rne(p[i] - bf16_bits_to_f32(hi[i]));
+                }
+                pop[0] = hi[0] | (hi[1] << 16);
+                pop[1] = hi[2] | (hi[3] << 16);
+                pop_lo[0] = lo[0] | (lo[1] << 16);
+                pop_lo[1] = lo[2] | (lo[3] << 16);
+            }
+
+            // V tile through this wave's LDS buffer.  The LDS unit serves one wave's operations in
+            // issue order; the wave barriers only keep the compiler from moving them across.
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int i = 0; i < VL; i++) {
+                const int idx = i * 64 + lane;
+                char *dst = vt + (idx / PPR) * VSTRIDE + (idx % PPR) * 16;
+                const u32x4 w = vv[i];
+                *(u32x2 *)dst = (u32x2){w[0], w[1]};
+                *(u32x2 *)(dst + 8) = (u32x2){w[2], w[3]};
+            }
+            __builtin_amdgcn_wave_barrier();
+#pragma unroll
+            for (int db = 0; db < DB; db++) {
+                const unsigned short *src = (const unsigned short *)(vt + (4 * g) * VSTRIDE) + db * 16 + n;
+                const unsigned v0 = src[0], v1 = src[VSTRIDE / 2], v2 = src[2 * (VSTRIDE / 2)], v3 = src[3 * (VSTRIDE / 2)];
+                const u32x2 vop = (u32x2){v0 | (v1 << 16), v2 | (v3 << 16)};
+                o[db] = mfma_values<DT>(vop, pop, o[db]);
+                if (DT != S3_F16) o[db] = mfma_values<DT>(vop, pop_lo, o[db]);
+            }
+            __builtin_amdgcn_wave_barrier();
+        };
+        // Two register sets used alternately: the next tile's loads are in flight while this one is reduced.
+        u32x4 k0[KS], v0[VL], k1[KS], v1[VL];
+        load_tile(start, k0, v0);
+        for (int r0 = start;;) {
+            load_tile(r0 + 16, k1, v1);
+            reduce_tile(r0, k0, v0);
+            r0 += 16;
+            if (r0 >= end) break;
+            load_tile(r0 + 16, k0, v0);
+            reduce_tile(r0, k1, v1);
+            r0 += 16;
+            if (r0 >= end) break;
+        }
+
+        lsum += __shfl_xor(lsum, 16);
+        lsum += __shfl_xor(lsum, 32);
+        if (head_ok) {
+            if (it.nchunks == 1) {
+                const float inv = 1.f / lsum;
+#pragma unroll
+                for (int db = 0; db < DB; db++)
+                    store_out4(a.out, a.out_dtype, ((int64_t)it.b * a.Hq + hq) * D + db * 16 + 4 * g, o[db] * inv);
+            } else {
+                const int64_t pi = ((int64_t)it.b * a.max_chunks + it.c) * a.Hq + hq;
+                if (g == 0) a.part_ml[pi] = make_float2(m, lsum);
+#pragma unroll
+                for (int db = 0; db < DB; db++) *(f32x4 *)(a.part_acc + pi * D + db * 16 + 4 * g) = o[db];
+            }
+        }
+    }
+}
+
+attn_fn s3i_pick_gqa_mfma(int dt, int d) {
+    if (dt == S3_F16) {
+        if (d == 64) return attn_gqa_mfma_kernel<S3_F16, 64>;
+        if (d == 128) return attn_gqa_mfma_kernel<S3_F16, 128>;
+        if (d == 256) return attn_gqa_mfma_kernel<S3_F16, 256>;
+    } else {
+        if (d == 64) return attn_gqa_mfma_kernel<S3_BF16, 64>;
+        if (d == 128) return attn_gqa_mfma_kernel<S3_BF16, 128>;
+        if (d == 256) return attn_gqa_mfma_kernel<S3_BF16, 256>;
+    }
+    return nullptr;
+}

@@ -670,8 +670,11 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
     const int group = Hq / Hkv;
     const int gq = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
-    int threads = 0;
-    attn_fn fn = s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
+    // Variant indices of a shared-K/V arena: the shapes of the vector-ALU kernel, then the matrix-core
+    // kernel, which is the default from four query heads per cached head (measured on MI355X).
+    const bool mfma = a->variant == s3i_num_gqa_shapes() || (a->variant < 0 && group >= 4);
+    int threads = 256;
+    attn_fn fn = mfma ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D) : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;
     if (with_append) {
         hipLaunchKernelGGL(append_kernel, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
@@ -698,9 +701,13 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     args.scale_log2e = scale * 1.4426950408889634f;
     args.len_out = with_append ? len_out : nullptr;
     const int GH = 512 / D;
-    const int per_seq = ((Hkv + GH - 1) / GH) * (group / gq);
+    // work items per chunk: (K/V head groups x query sub-blocks), or for the matrix-core kernel
+    // (K/V heads x blocks of 16 query heads), there one item per wave
+    const int per_seq = mfma ? Hkv * ((group + 15) / 16) : ((Hkv + GH - 1) / GH) * (group / gq);
     // Few (sequence, head group) pairs: cut contexts finer so that the chip still has work everywhere.
-    const int chunk = a->chunk > 0 ? a->chunk : (int64_t)n * per_seq >= 2048 ? 1024 : (int64_t)n * per_seq >= 512 ? 512 : 256;
+    const int chunk = a->chunk > 0 ? a->chunk
+                      : mfma     ? 128  // one wave per item: short items keep every SIMD busy
+                      : (int64_t)n * per_seq >= 2048 ? 1024 : (int64_t)n * per_seq >= 512 ? 512 : 256;
     args.chunk = chunk;
     args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
     // scratch: [partial sums][partial (max, sum)], one partial per (sequence, chunk, query head)
