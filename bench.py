@@ -214,7 +214,9 @@ def main():
         per_launch_bytes = sum(sampled) / max(launches, 1)
         avg_us = part_ns / max(launches, 1) / 1e3
         achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if avg_us > 0 else 0.0
-        kernel = "attn_gqa_kernel" if shared_kv else "attn_partial_kernel" if args.unfused else "attn_step_kernel"
+        kind = s3.s3_kv_get_param(eng.arena, "kernel_kind")[1]
+        kernel = {1: "attn_gqa_kernel", 2: "attn_gqa_mfma_kernel"}.get(
+            kind, "attn_partial_kernel" if args.unfused else "attn_step_kernel")
         res["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
                            "traffic": read_traffic(kernel, args.workload), "avg_kernel_us": round(avg_us, 2),

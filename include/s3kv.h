@@ -243,7 +243,9 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *                  key/value heads have their own, shorter, list)
  *   "profile"      k > 0: bracket every k-th attention launch (counted from this call) with HIP events
  *                  on its stream; 0: off; both reset the sums
- * get names: the above plus "n_variants", "n_grows", "live_slots", "scratch_bytes", "num_cus" and,
+ * get names: the above plus "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,
+ * 2 shared-K/V matrix-core kernel: what the next attention launch uses), "n_variants", "n_grows",
+ * "live_slots", "scratch_bytes", "num_cus" and,
  * after "profile" 1, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
  * launches since the last reset; reading them waits for the recorded events).
  * Returns S3_ERR_INVALID for an unknown name or a value out of range. */

@@ -272,6 +272,12 @@ static int s3i_variants_of(const s3_arena *a) {
     return a->cfg.n_kv_heads < a->cfg.n_heads ? s3i_num_gqa_shapes() + 1 : s3i_num_variants();  // + the matrix-core kernel
 }
 
+int s3i_kernel_kind(const s3_arena *a) {
+    if (a->cfg.n_kv_heads >= a->cfg.n_heads) return 0;
+    const int group = a->cfg.n_heads / a->cfg.n_kv_heads;
+    return (a->variant == s3i_num_gqa_shapes() || (a->variant < 0 && group >= 4)) ? 2 : 1;
+}
+
 extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
     if (!a || !name) return S3_ERR_INVALID;
     if (!strcmp(name, "chunk")) {
@@ -312,6 +318,7 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
     else if (!strcmp(name, "classes")) *value = a->ncls;
     else if (!strcmp(name, "variant")) *value = a->variant;
     else if (!strcmp(name, "n_variants")) *value = s3i_variants_of(a);
+    else if (!strcmp(name, "kernel_kind")) *value = s3i_kernel_kind(a);
     else if (!strcmp(name, "n_grows")) *value = a->n_grows;
     else if (!strcmp(name, "live_slots")) *value = (int64_t)a->slots.size() - (int64_t)a->dead_ids.size();
     else if (!strcmp(name, "scratch_bytes")) *value = (int64_t)a->scratch_bytes;

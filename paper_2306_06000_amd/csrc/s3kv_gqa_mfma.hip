@@ -17,8 +17,9 @@
 //     contraction slots of lane group g); Q^T is the B operand, loaded once per item with the same
 //     slot assignment (head = lane % 16), so whichever way the instruction numbers its contraction
 //     slots, both operands agree.  The accumulator holds S^T[row 4*g + i][head lane % 16], i < 4.
-//   * softmax: scale into log2 units, mask rows past the end, running maximum per head (over the
-//     four registers, then across the four lane groups), p = exp2(s - m), running sum.
+//   * softmax: scale into log2 units, mask rows past the end, tile maximum per head (over the four
+//     registers, then across the four lane groups); the exponent reference m follows the maximum
+//     lazily (see the loop), p = exp2(s - m), running sum.
 //   * V: the accumulator layout of S^T is already the B-operand layout of v_mfma_f32_16x16x16
 //     (4 contraction slots = rows 4*g .. 4*g+3, column = head), so P^T needs no shuffle.  The A
 //     operand V^T (row of the product = output element d, contraction = cached rows) needs four
@@ -57,9 +58,9 @@ __device__ __forceinline__ unsigned pack_f16(float lo, float hi) {
     const f16x2 h = {(_Float16)lo, (_Float16)hi};
     return __builtin_bit_cast(unsigned, h);
 }
-__device__ __forceinline__ float bf16_bits_to_f32(unsigned b) {
-    const unsigned w = b << 16;
-    return __builtin_bit_cast(float, w);
+__device__ __forceinline__ unsigned pack_bf16(float lo, float hi) {  // round to nearest even (v_cvt_pk_bf16_f32)
+    const bf16x2 h = {(__bf16)lo, (__bf16)hi};
+    return __builtin_bit_cast(unsigned, h);
 }
 
 // Four consecutive output elements starting at element index e.
@@ -86,6 +87,7 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
     constexpr int PPR = D / 8;            // 16-byte pieces per cached row of one head
     constexpr int VL = 16 * PPR / 64;     // 16-byte loads per lane for a 16-row V tile
     constexpr int VSTRIDE = D * 2 + 8;    // LDS row stride of the V tile, bytes
+    constexpr float RESCALE_LOG2 = 8.f;   // see the softmax step
     extern __shared__ __align__(16) char dyn_lds[];  // the batch view
     __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
     __shared__ __align__(16) char vtile[4][16 * VSTRIDE];
@@ -102,6 +104,7 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
 
     char *vt = vtile[wave];
     const int64_t rstride = (int64_t)a.H * D * 2;
+    const unsigned rs32 = (unsigned)rstride;  // a cached row of all K/V heads: below 2^32 bytes
     for (int64_t item = (int64_t)blockIdx.x * 4 + wave; item < total; item += (int64_t)gridDim.x * 4) {
         const Item it = decode_item(a, bv, item, per_seq);
         const int hk = it.hgb / nqb, qb = it.hgb - hk * nqb;
@@ -126,13 +129,13 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
 
         // Loads of one 16-row tile (rows past the chunk's end are clamped to its last row and masked later).
         auto load_tile = [&](int r0, u32x4 (&kop)[KS], u32x4 (&vv)[VL]) {
-            const int krow = min(r0 + n, end - 1);
+            const char *krow = kbase + (uint64_t)(unsigned)min(r0 + n, end - 1) * rs32 + g * 16;
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) kop[ks] = load16<false>(kbase + krow * rstride + (ks * 32 + g * 8) * 2);
+            for (int ks = 0; ks < KS; ks++) kop[ks] = load16<false>(krow + ks * 64);
 #pragma unroll
             for (int i = 0; i < VL; i++) {
                 const int idx = i * 64 + lane;
-                vv[i] = load16<true>(vbase + (int64_t)min(r0 + idx / PPR, end - 1) * rstride + (idx % PPR) * 16);
+                vv[i] = load16<true>(vbase + (uint64_t)(unsigned)min(r0 + idx / PPR, end - 1) * rs32 + (idx % PPR) * 16);
             }
         };
         auto reduce_tile = [&](int r0, const u32x4 (&kop)[KS], const u32x4 (&vv)[VL]) {
@@ -148,34 +151,40 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
             }
             mt = fmaxf(mt, __shfl_xor(mt, 16));
             mt = fmaxf(mt, __shfl_xor(mt, 32));
-            const float mn = fmaxf(m, mt);  // finite: row r0 is inside the chunk
-            const float alpha = fast_exp2(m - mn);
-            float p[4], ps = 0.f;
+            // Lazy reference: m is the exponent reference of the running sums, not necessarily the
+            // running maximum.  It moves (and the accumulators are rescaled) only when a tile's
+            // maximum exceeds it by more than RESCALE_LOG2, so p stays below 2^RESCALE_LOG2 and the
+            // rescale, which would otherwise run for almost every tile, runs for the first tile and
+            // then hardly ever.  (max, sum, row) leave the kernel consistent with whatever m is, which
+            // is all the merge of chunks needs.
+            const bool move = mt > m + RESCALE_LOG2;  // first tile: m = -inf
+            if (__builtin_amdgcn_ballot_w64(move) != 0) {
+                const float mn = move ? mt : m;
+                const float alpha = fast_exp2(m - mn);  // 1 where the reference stays, 0 on the first tile
+                lsum *= alpha;
+#pragma unroll
+                for (int db = 0; db < DB; db++) o[db] *= alpha;
+                m = mn;
+            }
+            float p[4];
 #pragma unroll
             for (int i = 0; i < 4; i++) {
-                p[i] = fast_exp2(sv[i] - mn);
-                ps += p[i];
+                p[i] = fast_exp2(sv[i] - m);
+                lsum += p[i];
             }
-            lsum = lsum * alpha + ps;
-            m = mn;
-#pragma unroll
-            for (int db = 0; db < DB; db++) o[db] *= alpha;
 
             u32x2 pop, pop_lo;
             if (DT == S3_F16) {
                 pop[0] = pack_f16(p[0], p[1]);
                 pop[1] = pack_f16(p[2], p[3]);
             } else {
-                unsigned hi[4], lo[4];
+                float r[4];
 #pragma unroll
-                for (int i = 0; i < 4; i++) {
-                    hi[i] = f32_to_bf16_rne(p[i]);
-                    lo[i] = f32_to_bf16_rne(p[i] - bf16_bits_to_f32(hi[i]));
-                }
-                pop[0] = hi[0] | (hi[1] << 16);
-                pop[1] = hi[2] | (hi[3] << 16);
-                pop_lo[0] = lo[0] | (lo[1] << 16);
-                pop_lo[1] = lo[2] | (lo[3] << 16);
+                for (int i = 0; i < 4; i++) r[i] = p[i] - (float)(__bf16)p[i];  // what the high part misses
+                pop[0] = pack_bf16(p[0], p[1]);
+                pop[1] = pack_bf16(p[2], p[3]);
+                pop_lo[0] = pack_bf16(r[0], r[1]);
+                pop_lo[1] = pack_bf16(r[2], r[3]);
             }
 
             // V tile through this wave's LDS buffer.  The LDS unit serves one wave's operations in

@@ -670,9 +670,8 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
     const int group = Hq / Hkv;
     const int gq = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
-    // Variant indices of a shared-K/V arena: the shapes of the vector-ALU kernel, then the matrix-core
-    // kernel, which is the default from four query heads per cached head (measured on MI355X).
-    const bool mfma = a->variant == s3i_num_gqa_shapes() || (a->variant < 0 && group >= 4);
+    // Variant indices of a shared-K/V arena: the shapes of the vector-ALU kernel, then the matrix-core kernel.
+    const bool mfma = s3i_kernel_kind(a) == 2;
     int threads = 256;
     attn_fn fn = mfma ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D) : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;

@@ -177,11 +177,12 @@ def c4(batch: int = 128, steps: int = 64) -> Workload:
     return Workload("C4-gpt3-share", 4, 1, 12, 128, BF16, 128, 2048, batch, steps, seqs)
 
 
-def c5(batch: int = 64, steps: int = 128, n_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
+def c5(batch: int = 256, steps: int = 128, n_heads: int = 32, n_kv_heads: int = 8, head_dim: int = 128,
        dtype: int = BF16) -> Workload:
     """Shared key/value heads (grouped-query; n_kv_heads = 1 is multi-query attention, which the
     paper's related-work section names as complementary): C1's lengths, mispredictions and refill
-    on a 32-query-head / 8-KV-head, d = 128 shape.  Not one of the paper's measured models."""
+    on a 32-query-head / 8-KV-head, d = 128 shape, at four times C1's batch (a cache row is a
+    quarter of the multi-head one).  Not one of the paper's measured models."""
     base = c1(batch, steps)
     return Workload(f"C5-shared-kv-{n_heads}q{n_kv_heads}kv", 5, 1, n_heads, head_dim, dtype, base.granule,
                     base.max_len, batch, steps, base.seqs, base.pool, base.refill, n_kv_heads=n_kv_heads)
