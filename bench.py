@@ -40,6 +40,10 @@ def parse():
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (not c3); the "
                     "default is the configuration the metric is quoted on")
     ap.add_argument("--unfused", action="store_true", help="append + attention + merge kernels instead of one")
+    ap.add_argument("--drain", action="store_true", help="finished sequences are not replaced: the batch shrinks")
+    ap.add_argument("--flush-mb", type=int, default=0, help="diagnostic: overwrite a buffer of this many MB between "
+                    "steps so that the memory-side cache holds none of the previous step's rows; every launch is "
+                    "then bracketed and only roofline.* is meaningful (value includes the flushes)")
     return ap.parse_args()
 
 
@@ -124,7 +128,15 @@ def cpu_baseline(w, lens, budget_s=12.0):
         n_take = int(max(1, min(lens.size, rate * min(budget_s - t_used, 4.0))))
         if budget_s - t_used < 0.05:
             break
+    # the same code on one thread (plain serial loops), on a short prefix
+    n1 = min(lens.size, 4)
+    q1 = wl.normal_bits(rng, (n1, H, D), w.dtype)
+    t0 = time.perf_counter()
+    orc.attention_ragged(q1, [kv[0]] * n1, [kv[1]] * n1, lens[:n1], w.dtype, None, "f32", threads=1)
+    dt1 = time.perf_counter() - t0
+    one_thread = (2 * w.kv_heads * D * 2 * int(lens[:n1].sum()) + n1 * H * D * (2 + 4)) / dt1 / 1e9
     return {"value": round(done_bytes / t_used / 1e9, 4), "unit": "GB/s", "cores": int(used), "kind": "oracle",
+            "one_thread_value": round(one_thread, 4),
             "seq_steps_per_s": round(done_seqs / t_used, 2),
             "sample": f"one layer of oracle attention over prefixes of the batch state at the start of the timed region ({lens.size} sequences), "
                       f"{passes} passes, {done_seqs} sequence-steps, {t_used:.1f} s of CPU work, OpenMP over "
@@ -151,6 +163,8 @@ def main():
         kw.update(n_heads=hq, n_kv_heads=hkv, head_dim=hd)
     w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4, "c5": wl.c5}[args.workload](**kw) if args.workload != "c3" else wl.c3(
         target_bytes=int(args.c3_bytes))
+    if args.drain:
+        w.refill = False
     shared_kv = w.kv_heads < w.n_heads  # not one of the paper's models: measured as a widening, not the headline
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload][0]
     warmup = args.warmup if args.warmup is not None else DEFAULT_STEPS[args.workload][1]
@@ -169,22 +183,28 @@ def main():
         eng.step(tensors, prefill)
     torch.cuda.synchronize()
     lens_at_start = eng.len.copy()
-    every = max(1, args.event_every)
+    every = 1 if args.flush_mb else max(1, args.event_every)
+    flush = torch.empty(args.flush_mb << 20, dtype=torch.uint8, device=eng.dev) if args.flush_mb else None
     if not args.no_kernel_events:
         s3.check(s3.s3_kv_set_param(eng.arena, "profile", every))
     grown0, retired0 = eng.n_grown, eng.n_retired
-    total_bytes, seq_steps, launch_bytes = 0, 0, []
+    total_bytes, seq_steps, launch_bytes, steps_done = 0, 0, [], 0
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
+        if eng.n_active == 0:  # drain runs: every sequence has finished
+            break
+        if flush is not None:
+            flush.fill_(1)
         eng.step(tensors, prefill)
+        steps_done += 1
         total_bytes += eng.last_step_bytes
         seq_steps += eng.last_step_seqs
         launch_bytes += [eng.last_step_bytes // w.n_layers] * w.n_layers
     t_enqueue = time.perf_counter() - t0  # host time to enqueue every step (no device wait in it)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
-    args.steps, args.warmup = steps, warmup
+    args.steps, args.warmup = steps_done, warmup
 
     res = {
         "metric": "decode-attention achieved HBM GB/s", "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
@@ -197,6 +217,7 @@ def main():
         "config": {"workload": w.name, "batch": int(lens_at_start.size), "n_layers": w.n_layers,
                    "n_heads": w.n_heads, "n_kv_heads": w.kv_heads, "head_dim": w.head_dim,
                    "mean_context_at_start": round(float(lens_at_start.mean()), 1),
+                   "batch_at_end": int(eng.n_active), "refill": bool(w.refill),
                    "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
                    "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
@@ -220,10 +241,14 @@ def main():
         res["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),
                            "traffic": read_traffic(kernel, args.workload), "avg_kernel_us": round(avg_us, 2),
+                           "kernel_us_p10_p50_p90": [round(s3.s3_kv_get_param(eng.arena, f"profile_p{q}_ns")[1] / 1e3, 2)
+                                                     for q in (10, 50, 90)],
                            "timed_launches": launches, "of_launches": len(launch_bytes),
                            "algorithmic_bytes_per_launch": int(per_launch_bytes)}
         if args.unfused:
             res["roofline"]["avg_merge_kernel_us"] = round(merge_ns / max(launches, 1) / 1e3, 2)
+    if args.flush_mb:
+        res["config"]["cache_flush_MB_between_steps"] = args.flush_mb
     if not args.no_cpu_baseline:
         res["cpu_baseline"] = cpu_baseline(w, lens_at_start)
     eng.close()

@@ -246,8 +246,10 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  * get names: the above plus "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,
  * 2 shared-K/V matrix-core kernel: what the next attention launch uses), "n_variants", "n_grows",
  * "live_slots", "scratch_bytes", "num_cus" and,
- * after "profile" 1, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
- * launches since the last reset; reading them waits for the recorded events).
+ * after "profile" k, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
+ * timed launches since the last reset) and "profile_p10_ns", "profile_p50_ns", "profile_p90_ns"
+ * (nearest-rank percentiles of the attention kernel's bracketed duration); reading them waits for
+ * the recorded events.
  * Returns S3_ERR_INVALID for an unknown name or a value out of range. */
 int s3_kv_set_param(s3_arena *a, const char *name /*HOST*/, int64_t value);
 int s3_kv_get_param(const s3_arena *a, const char *name /*HOST*/, int64_t *value /*HOST*/);

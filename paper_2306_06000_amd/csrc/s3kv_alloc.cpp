@@ -13,6 +13,8 @@
 #include <new>
 #include <string>
 
+#include <algorithm>
+
 #include "s3kv_internal.h"
 
 static thread_local std::string g_hip_error;
@@ -329,6 +331,16 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
         if (!strcmp(name, "profile_launches")) *value = a->prof_launches;
         else if (!strcmp(name, "profile_partial_ns")) *value = (int64_t)(a->prof_partial_ms * 1e6);
         else if (!strcmp(name, "profile_merge_ns")) *value = (int64_t)(a->prof_merge_ms * 1e6);
+        else if (!strcmp(name, "profile_p10_ns") || !strcmp(name, "profile_p50_ns") || !strcmp(name, "profile_p90_ns")) {
+            // nearest-rank percentile of the timed launches' first interval (the attention kernel)
+            std::vector<float> d = a->prof_durations_ms;
+            if (d.empty()) { *value = 0; return S3_OK; }
+            std::sort(d.begin(), d.end());
+            const int pct = name[9] == '1' ? 10 : name[9] == '5' ? 50 : 90;
+            size_t k = (d.size() * pct + 99) / 100;
+            if (k > 0) k--;
+            *value = (int64_t)(d[k] * 1e6);
+        }
         else return S3_ERR_INVALID;
     }
     else return S3_ERR_INVALID;

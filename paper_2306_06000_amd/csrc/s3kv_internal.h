@@ -40,6 +40,7 @@ struct s3_arena {
     size_t prof_used = 0;             // events handed out since the last collect
     double prof_partial_ms = 0.0, prof_merge_ms = 0.0;
     int64_t prof_launches = 0;
+    std::vector<float> prof_durations_ms;  // first interval of every timed launch since the last reset
 
     // launch-shape knobs (0 = default)
     int32_t chunk = 0;

@@ -585,6 +585,7 @@ int s3i_profile_collect(s3_arena *a) {
         a->prof_partial_ms += p;
         a->prof_merge_ms += m;
         a->prof_launches++;
+        a->prof_durations_ms.push_back(p);
     }
     a->prof_used = 0;
     return S3_OK;
@@ -594,6 +595,7 @@ void s3i_profile_reset(s3_arena *a) {
     (void)s3i_profile_collect(a);
     a->prof_partial_ms = a->prof_merge_ms = 0.0;
     a->prof_launches = 0;
+    a->prof_durations_ms.clear();
     // events are created here, not at the first timed launch: creating one costs tens of microseconds
     while (a->prof_events.size() < 3 * 64) {
         hipEvent_t e;

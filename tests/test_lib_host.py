@@ -166,6 +166,23 @@ def test_random_trace_bit_exact_against_oracle(seed, granule, tokens):
     s3.s3_kv_arena_destroy(a)
 
 
+def test_profile_percentiles_are_zero_without_timed_launches():
+    cfg, a = meta_arena(1, 16, 256, s3.S3_F16, 64, 2048, 1 << 24)
+    for q in (10, 50, 90):
+        assert s3.s3_kv_get_param(a, f"profile_p{q}_ns") == (0, 0)
+    assert s3.s3_kv_get_param(a, "profile_p75_ns")[0] == s3.S3_ERR_INVALID
+    assert s3.s3_kv_get_param(a, "kernel_kind") == (0, 0)
+    s3.s3_kv_arena_destroy(a)
+    st, b = s3.s3_kv_arena_init(s3.make_config(1, 16, 256, s3.S3_F16, 64, 2048, 8), None, 1 << 24)
+    assert st == 0 and s3.s3_kv_get_param(b, "kernel_kind") == (0, 1)   # two query heads per cached head
+    assert s3.s3_kv_set_param(b, "variant", s3.s3_kv_get_param(b, "n_variants")[1] - 1) == 0
+    assert s3.s3_kv_get_param(b, "kernel_kind") == (0, 2)               # the last index is the matrix-core kernel
+    s3.s3_kv_arena_destroy(b)
+    st, c = s3.s3_kv_arena_init(s3.make_config(1, 16, 256, s3.S3_F16, 64, 2048, 1), None, 1 << 24)
+    assert st == 0 and s3.s3_kv_get_param(c, "kernel_kind") == (0, 2)
+    s3.s3_kv_arena_destroy(c)
+
+
 def test_compact_validation():
     cfg, a = meta_arena(1, 1, 64, 0, 64, 256, 1024 * 256)
     rc, ids, offs, caps = s3.s3_kv_alloc(a, [64, 64, 128])
