@@ -39,6 +39,7 @@ import numpy as np
 
 OK, ERR_INVALID, ERR_NOMEM, ERR_SLOT_FULL, ERR_MAXLEN = 0, -1, -2, -3, -4
 F16, BF16 = 0, 1
+E4M3 = 2  # 8-bit cache rows: one e4m3 code in the low byte of each uint16 the oracle stores
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None
@@ -73,15 +74,25 @@ def widen(bits, dtype, precision="f32"):
     return out
 
 
-def scores(q, K, dtype, scale, precision="f32"):
-    """Step 1 for one head: q [D], K [L][D] (16-bit patterns) -> s [L]."""
+def quantize_e4m3(x):
+    """float32 values -> e4m3 codes (uint16 array, code in the low byte): nearest, ties to even,
+    saturating at +-448, NaN -> 0x7f.  What an 8-bit cache stores for a new row."""
+    x = np.ascontiguousarray(x, np.float32)
+    out = np.empty(x.shape, np.uint8)
+    _lib().s3o_quantize_e4m3_f32(_c(x, ctypes.c_float), ctypes.c_int64(x.size), _c(out, ctypes.c_uint8))
+    return out.astype(np.uint16)
+
+
+def scores(q, K, dtype, scale, precision="f32", q_dtype=None):
+    """Step 1 for one head: q [D], K [L][D] (stored patterns) -> s [L]."""
     npt, ct = _REAL[precision]
     q = np.ascontiguousarray(q, np.uint16)
     K = np.ascontiguousarray(K, np.uint16)
     L, D = K.shape
     s = np.empty(L, npt)
-    getattr(_lib(), f"s3o_scores_{precision}")(_c(q, ctypes.c_uint16), _c(K, ctypes.c_uint16),
-                                               ctypes.c_int64(D), L, D, dtype, ct(scale), _c(s, ct))
+    getattr(_lib(), f"s3o_scores_{precision}")(_c(q, ctypes.c_uint16), dtype if q_dtype is None else q_dtype,
+                                               _c(K, ctypes.c_uint16), ctypes.c_int64(D), L, D, dtype, ct(scale),
+                                               _c(s, ct))
     return s
 
 
@@ -106,7 +117,7 @@ def weighted_sum(p, V, dtype, precision="f32"):
     return o
 
 
-def attention_ragged(q, K_list, V_list, lens, dtype, scale=None, precision="f32", threads=1):
+def attention_ragged(q, K_list, V_list, lens, dtype, scale=None, precision="f32", threads=1, q_dtype=None):
     """softmax(q K^T * scale) V per (sequence, head) over each sequence's own length.
 
     q: [n][H][D] 16-bit patterns.  K_list[b], V_list[b]: [rows_b][Hkv][D] 16-bit
@@ -114,7 +125,8 @@ def attention_ragged(q, K_list, V_list, lens, dtype, scale=None, precision="f32"
     Hkv == H is multi-head attention (section 2.1); Hkv < H is the grouped form
     of the multi-query attention the related-work section names: query head h
     reads key/value head h // (H // Hkv).
-    scale None means 1/sqrt(D).  Returns (out [n][H][D] real, threads used).
+    dtype is the storage type of K and V; q has the same type unless q_dtype says otherwise (8-bit
+    caches keep 16-bit queries).  scale None means 1/sqrt(D).  Returns (out [n][H][D] real, threads used).
     """
     npt, ct = _REAL[precision]
     q = np.ascontiguousarray(q, np.uint16)
@@ -134,7 +146,7 @@ def attention_ragged(q, K_list, V_list, lens, dtype, scale=None, precision="f32"
     vp = (PT * max(n, 1))(*[_c(v, ctypes.c_uint16) for v in Vs])
     out = np.zeros((n, H, D), npt)
     used = getattr(_lib(), f"s3o_attention_batch_{precision}")(
-        n, H, Hkv, D, dtype, kp, vp, _c(lens, ctypes.c_int32), _c(q, ctypes.c_uint16), ct(scale), _c(out, ct),
+        n, H, Hkv, D, dtype, dtype if q_dtype is None else q_dtype, kp, vp, _c(lens, ctypes.c_int32), _c(q, ctypes.c_uint16), ct(scale), _c(out, ct),
         int(threads))
     if used < 0:
         raise MemoryError("oracle scratch allocation failed")
@@ -163,7 +175,7 @@ class KVOracle:
     """Slot allocator + per-sequence KV storage, step by step as the header describes."""
 
     def __init__(self, n_layers, n_heads, head_dim, dtype, granule, max_len, arena_bytes, store=True,
-                 n_kv_heads=None):
+                 n_kv_heads=None, act_dtype=None):
         assert granule > 0 and max_len > 0 and max_len % granule == 0
         self.n_layers, self.H, self.D, self.dtype = n_layers, n_heads, head_dim, dtype
         # key/value heads per cached row: all heads (section 2.1) unless the model shares them
@@ -171,7 +183,11 @@ class KVOracle:
         self.Hkv = n_heads if not n_kv_heads else n_kv_heads
         assert n_heads % self.Hkv == 0
         self.G, self.M = granule, max_len
-        self.elem_bytes = 2
+        # 8-bit cache rows (quantised cache, related work): queries and new rows stay 16-bit (act_dtype)
+        # and a new row is quantised once, when it is appended
+        self.act_dtype = dtype if act_dtype is None else act_dtype
+        assert dtype != E4M3 or self.act_dtype in (F16, BF16)
+        self.elem_bytes = 1 if dtype == E4M3 else 2
         # K and V, every layer, Hkv*D numbers of elem_bytes each: the paper's 4*l*d_h for 2-byte numbers
         # when Hkv*D = d_h
         self.bytes_per_token = 2 * n_layers * self.Hkv * head_dim * self.elem_bytes
@@ -324,12 +340,16 @@ class KVOracle:
 
     # -- rows -------------------------------------------------------------
     def append(self, sid, layer, pos, k_row, v_row):
-        """Write the new token's key and value ([H][D] patterns) into row pos."""
+        """Write the new token's key and value ([H][D] patterns) into row pos.  An 8-bit cache gets
+        the 16-bit values rounded to the nearest e4m3 code (ties to even, saturating)."""
         if sid not in self.slots or not (0 <= layer < self.n_layers) or pos < 0:
             return ERR_INVALID
         off, cap = self.slots[sid]
         if pos >= cap:
             return ERR_SLOT_FULL
+        if self.dtype == E4M3:
+            k_row = quantize_e4m3(widen(k_row, self.act_dtype))
+            v_row = quantize_e4m3(widen(v_row, self.act_dtype))
         self.data[sid][layer, 0, pos] = k_row
         self.data[sid][layer, 1, pos] = v_row
         return OK
@@ -350,7 +370,7 @@ class KVOracle:
     def attention(self, layer, ids, lens, q, scale=None, precision="f32", threads=1):
         Ks = [self.data[s][layer, 0] for s in ids]
         Vs = [self.data[s][layer, 1] for s in ids]
-        return attention_ragged(q, Ks, Vs, lens, self.dtype, scale, precision, threads)[0]
+        return attention_ragged(q, Ks, Vs, lens, self.dtype, scale, precision, threads, q_dtype=self.act_dtype)[0]
 
 
 class SchedulerOracle:

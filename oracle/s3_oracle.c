@@ -13,8 +13,9 @@
  * rows.  No tiling, no running ("online") softmax, no reordering.
  *
  * Inputs are the values as stored in the KV cache: 16-bit patterns of IEEE
- * binary16 (dtype 0) or bfloat16 (dtype 1).  They are widened to REAL before
- * any arithmetic.  The file is compiled twice: REAL = float (the fp32 oracle)
+ * binary16 (dtype 0) or bfloat16 (dtype 1), or 8-bit e4m3 codes (dtype 2, one code
+ * in the low byte of each uint16_t; the query then has a 16-bit type of its own,
+ * qdtype).  They are widened to REAL before any arithmetic.  The file is compiled twice: REAL = float (the fp32 oracle)
  * and REAL = double (its twin, used to bound the fp32 oracle's own error).
  *
  * Row addressing: element d of row j of a matrix is base[j * row_stride + d];
@@ -64,7 +65,45 @@ static REAL widen_bf16(uint16_t h)
     return (REAL)f;
 }
 
-static REAL widen(uint16_t h, int dtype) { return dtype == 0 ? widen_f16(h) : widen_bf16(h); }
+/* 8-bit float e4m3 ("fn": finite + NaN, no infinities; the open 8-bit format most 8-bit caches use):
+ * 1 sign, 4 exponent (bias 7), 3 fraction bits.  exponent 0: zero / subnormal f * 2^-9;
+ * exponent 15 with fraction 7: NaN; everything else (1 + f/8) * 2^(e-7), largest 448. */
+static REAL widen_e4m3(uint8_t b)
+{
+    int sign = b >> 7, e = (b >> 3) & 15, f = b & 7;
+    double v;
+    if (e == 15 && f == 7) return (REAL)NAN;
+    if (e == 0) v = ldexp((double)f, -9);
+    else v = ldexp(1.0 + f / 8.0, e - 7);
+    return (REAL)(sign ? -v : v);
+}
+
+/* REAL-independent: nearest e4m3 code of a float, ties to the even code, magnitudes beyond the
+ * largest finite value (448) saturate to it, NaN -> 0x7f.  Written as a search over the 127
+ * non-negative finite codes so that it shares nothing with a bit-twiddling implementation. */
+static uint8_t quantize_e4m3(float x)
+{
+    if (x != x) return 0x7f;
+    uint8_t sign = (uint8_t)(signbit(x) ? 0x80 : 0);
+    double a = fabs((double)x);
+    if (a >= 448.0) return (uint8_t)(sign | 0x7e);
+    int lo = 0, hi = 0x7e; /* codes are monotone in value: find the last code with value <= a */
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if ((double)widen_e4m3((uint8_t)mid) <= a) lo = mid; else hi = mid - 1;
+    }
+    if (lo == 0x7e) return (uint8_t)(sign | lo);
+    double below = (double)widen_e4m3((uint8_t)lo), above = (double)widen_e4m3((uint8_t)(lo + 1));
+    double dl = a - below, du = above - a;
+    int code = dl < du ? lo : du < dl ? lo + 1 : ((lo & 1) ? lo + 1 : lo);
+    return (uint8_t)(sign | code);
+}
+
+/* 16-bit storage types carry their pattern in a uint16_t; the 8-bit type (dtype 2) in its low byte. */
+static REAL widen(uint16_t h, int dtype)
+{
+    return dtype == 0 ? widen_f16(h) : dtype == 1 ? widen_bf16(h) : widen_e4m3((uint8_t)h);
+}
 
 /* Exposed so that tests can pin the widening against an independent library. */
 void FN(s3o_widen)(const uint16_t *src, int64_t n, int dtype, REAL *dst)
@@ -72,13 +111,19 @@ void FN(s3o_widen)(const uint16_t *src, int64_t n, int dtype, REAL *dst)
     for (int64_t i = 0; i < n; i++) dst[i] = widen(src[i], dtype);
 }
 
+/* Quantise n floats to e4m3 codes (what an 8-bit cache stores for a new row). */
+void FN(s3o_quantize_e4m3)(const float *src, int64_t n, uint8_t *dst)
+{
+    for (int64_t i = 0; i < n; i++) dst[i] = quantize_e4m3(src[i]);
+}
+
 /* Step 1: s_j = scale * sum_d q[d] * K[j][d],  j = 0..L-1. */
-void FN(s3o_scores)(const uint16_t *q, const uint16_t *K, int64_t row_stride, int L, int D,
+void FN(s3o_scores)(const uint16_t *q, int qdtype, const uint16_t *K, int64_t row_stride, int L, int D,
                     int dtype, REAL scale, REAL *s)
 {
     for (int j = 0; j < L; j++) {
         REAL dot = 0;
-        for (int d = 0; d < D; d++) dot += widen(q[d], dtype) * widen(K[(int64_t)j * row_stride + d], dtype);
+        for (int d = 0; d < D; d++) dot += widen(q[d], qdtype) * widen(K[(int64_t)j * row_stride + d], dtype);
         s[j] = dot * scale;
     }
 }
@@ -109,8 +154,8 @@ void FN(s3o_weighted_sum)(const REAL *p, const uint16_t *V, int64_t row_stride, 
 
 /* One (sequence, head): the three steps in order.  L == 0 (nothing cached) is
  * defined as an all-zero output row.  Returns 0, or -1 if scratch allocation fails. */
-int FN(s3o_attend_one)(const uint16_t *q, const uint16_t *K, const uint16_t *V, int64_t row_stride, int L,
-                       int D, int dtype, REAL scale, REAL *o)
+int FN(s3o_attend_one)(const uint16_t *q, int qdtype, const uint16_t *K, const uint16_t *V, int64_t row_stride,
+                       int L, int D, int dtype, REAL scale, REAL *o)
 {
     if (L <= 0) {
         for (int d = 0; d < D; d++) o[d] = 0;
@@ -119,7 +164,7 @@ int FN(s3o_attend_one)(const uint16_t *q, const uint16_t *K, const uint16_t *V, 
     REAL *s = (REAL *)malloc(sizeof(REAL) * (size_t)L * 2);
     if (!s) return -1;
     REAL *p = s + L;
-    FN(s3o_scores)(q, K, row_stride, L, D, dtype, scale, s);
+    FN(s3o_scores)(q, qdtype, K, row_stride, L, D, dtype, scale, s);
     FN(s3o_softmax)(s, L, p);
     FN(s3o_weighted_sum)(p, V, row_stride, L, D, dtype, o);
     free(s);
@@ -138,7 +183,7 @@ int FN(s3o_attend_one)(const uint16_t *q, const uint16_t *K, const uint16_t *V, 
  * `threads` OpenMP threads (1 = plain serial loops); the arithmetic of each pair
  * is the same either way.  Returns the number of threads used, or -1 on
  * allocation failure or if Hkv does not divide H. */
-int FN(s3o_attention_batch)(int n, int H, int Hkv, int D, int dtype, const uint16_t *const *K_ptr,
+int FN(s3o_attention_batch)(int n, int H, int Hkv, int D, int dtype, int qdtype, const uint16_t *const *K_ptr,
                             const uint16_t *const *V_ptr, const int32_t *len, const uint16_t *q,
                             REAL scale, REAL *out, int threads)
 {
@@ -154,7 +199,7 @@ int FN(s3o_attention_batch)(int n, int H, int Hkv, int D, int dtype, const uint1
     for (int64_t i = 0; i < pairs; i++) {
         int b = (int)(i / H), h = (int)(i % H);
         int hk = h / heads_per_kv; /* the key/value head this query head reads */
-        int rc = FN(s3o_attend_one)(q + ((int64_t)b * H + h) * D, K_ptr[b] + (int64_t)hk * D,
+        int rc = FN(s3o_attend_one)(q + ((int64_t)b * H + h) * D, qdtype, K_ptr[b] + (int64_t)hk * D,
                                     V_ptr[b] + (int64_t)hk * D, (int64_t)Hkv * D, len[b], D, dtype, scale,
                                     out + ((int64_t)b * H + h) * D);
         if (rc) fail |= 1;

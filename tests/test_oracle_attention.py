@@ -338,6 +338,80 @@ def test_kv_oracle_bytes_per_token_counts_kv_heads_only():
     assert mqa.N == (1 << 30) // mqa.bytes_per_token
 
 
+# ---------------------------------------------------------------- 8-bit (e4m3) cache rows
+def test_e4m3_widening_matches_torch_for_all_codes():
+    import torch
+
+    codes = np.arange(256, dtype=np.uint16)
+    got = orc.widen(codes, orc.E4M3, "f32")
+    want = torch.arange(256, dtype=torch.uint8).view(torch.float8_e4m3fn).float().numpy()
+    nan = np.isnan(want)
+    assert nan.sum() == 2 and np.array_equal(np.isnan(got), nan)      # 0x7f and 0xff
+    assert np.array_equal(got[~nan], want[~nan])
+    assert got[0x7e] == 448.0 and got[0x01] == 2.0 ** -9 and got[0x38] == 1.0  # the format's corner values
+
+
+def test_e4m3_quantiser_matches_torch_below_overflow_and_saturates_above():
+    """Nearest code, ties to even: torch's float8_e4m3fn conversion is the library routine for that
+    wherever the value does not overflow (it yields NaN on overflow; the cache saturates instead)."""
+    import torch
+
+    rng = np.random.default_rng(31)
+    x = np.concatenate([rng.standard_normal(200000).astype(np.float32) * 3,
+                        rng.uniform(-464, 464, 50000).astype(np.float32),
+                        (rng.standard_normal(20000) * 2.0 ** -8).astype(np.float32),   # subnormal range
+                        np.array([0.0, -0.0, 2.0 ** -10, 3 * 2.0 ** -11, 2.0 ** -9, 17.0, 19.0, 448.0, 463.9], np.float32)])
+    # every midpoint between neighbouring codes (ties) and both its float neighbours
+    vals = orc.widen(np.arange(0x7f, dtype=np.uint16), orc.E4M3, "f64")
+    mids = ((vals[:-1] + vals[1:]) / 2).astype(np.float32)
+    x = np.concatenate([x, mids, -mids, np.nextafter(mids, np.float32(0)), np.nextafter(mids, np.float32(1e9))])
+    got = orc.quantize_e4m3(x).astype(np.uint8)
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(got, want)
+    # overflow: saturate to the largest finite code with the sign kept; NaN stays NaN
+    big = np.array([464.0, 465.0, 1e6, np.inf, -464.0, -1e30, -np.inf], np.float32)
+    assert orc.quantize_e4m3(big).tolist() == [0x7e, 0x7e, 0x7e, 0x7e, 0xfe, 0xfe, 0xfe]
+    assert orc.quantize_e4m3(np.array([np.nan], np.float32)).tolist() == [0x7f]
+    # every finite code is a fixed point
+    codes = np.array([c for c in range(256) if c not in (0x7f, 0xff)], np.uint16)
+    back = orc.quantize_e4m3(orc.widen(codes, orc.E4M3, "f32"))
+    assert np.array_equal(back[codes != 0x80], codes[codes != 0x80]) and back[codes == 0x80].tolist() == [0x80]
+
+
+def test_e4m3_cache_attention_matches_torch_sdpa_on_widened_rows():
+    import torch
+
+    rng = np.random.default_rng(32)
+    H, D, lens = 4, 64, [1, 50, 129]
+    q = wl.normal_bits(rng, (3, H, D), orc.BF16)
+    K = [orc.quantize_e4m3(rng.standard_normal((L, H, D)).astype(np.float32)) for L in lens]
+    V = [orc.quantize_e4m3(rng.standard_normal((L, H, D)).astype(np.float32)) for L in lens]
+    out, _ = orc.attention_ragged(q, K, V, lens, orc.E4M3, None, "f64", threads=2, q_dtype=orc.BF16)
+    f8 = lambda c: torch.from_numpy(c.astype(np.uint8)).view(torch.float8_e4m3fn).double()
+    for b, L in enumerate(lens):
+        tq = torch.from_numpy(np_widen(q[b], orc.BF16)).reshape(1, H, 1, D)
+        tk = f8(K[b]).permute(1, 0, 2).reshape(1, H, L, D)
+        tv = f8(V[b]).permute(1, 0, 2).reshape(1, H, L, D)
+        want = torch.nn.functional.scaled_dot_product_attention(tq, tk, tv).reshape(H, D).numpy()
+        assert np.allclose(out[b], want, atol=1e-12)
+    # length 1 reads the stored codes back exactly
+    assert np.array_equal(out[0], orc.widen(V[0][0], orc.E4M3, "f64"))
+
+
+def test_e4m3_kv_oracle_quantises_on_append_and_halves_the_bytes():
+    o16 = orc.KVOracle(2, 4, 64, orc.F16, 64, 256, 1 << 24)
+    o8 = orc.KVOracle(2, 4, 64, orc.E4M3, 64, 256, 1 << 24, act_dtype=orc.F16)
+    assert o8.bytes_per_token * 2 == o16.bytes_per_token and o8.N == 2 * o16.N
+    assert o8.alloc([10])[0] == 1
+    rng = np.random.default_rng(33)
+    k = wl.normal_bits(rng, (4, 64), orc.F16)
+    v = wl.normal_bits(rng, (4, 64), orc.F16)
+    assert o8.append(0, 1, 0, k, v) == 0
+    import torch
+    want = torch.from_numpy(k.view(np.float16).astype(np.float32)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(o8.rows(0, 1, 0, 1)[0].astype(np.uint8), want)
+
+
 # ---------------------------------------------------------------- oracle accuracy, split-K identity
 def test_fp32_oracle_close_to_float64_twin_on_c0():
     w = wl.c0()
