@@ -10,6 +10,7 @@ the same timed region.  `cpu_baseline` is the CPU oracle timed on this machine's hos
 bounded sample of the same workload.
 """
 import argparse
+import gc
 import json
 import os
 import sys
@@ -27,7 +28,7 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None, help="timed decode steps (default: per workload)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c5"])
+    ap.add_argument("--workload", default="c1", choices=["c1", "c2", "c3", "c4", "c5", "c6"])
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--grid-blocks", type=int, default=0)
@@ -47,7 +48,7 @@ def parse():
     return ap.parse_args()
 
 
-DEFAULT_STEPS = {"c1": (128, 8), "c2": (256, 8), "c3": (3, 1), "c4": (56, 8), "c5": (128, 8)}  # (timed, warm-up)
+DEFAULT_STEPS = {"c1": (128, 8), "c2": (256, 8), "c3": (3, 1), "c4": (56, 8), "c5": (128, 8), "c6": (128, 8)}  # (timed, warm-up)
 
 
 def make_device_sources(w, eng, torch, ring=8):
@@ -55,9 +56,12 @@ def make_device_sources(w, eng, torch, ring=8):
     of prompt rows that newcomers are filled from.  Seeded torch generator on the device."""
     gen = torch.Generator(device=eng.dev)
     gen.manual_seed(w.seed)
-    tdt = eng.kv_dtype_torch()
-    rows = torch.randn((2, w.max_len, w.kv_heads, w.head_dim), generator=gen, device=eng.dev,
-                       dtype=torch.float32).to(tdt)
+    tdt = eng.act_dtype_torch()
+    rows = torch.randn((2, w.max_len, w.kv_heads, w.head_dim), generator=gen, device=eng.dev, dtype=torch.float32)
+    if eng.kv_dtype_torch() == torch.uint8:  # 8-bit cache rows: N(0,1) as e4m3 codes, converted by torch on the host
+        rows = rows.cpu().to(torch.float8_e4m3fn).view(torch.uint8).to(eng.dev)
+    else:
+        rows = rows.to(tdt)
     state = {"i": 0, "qkv": None}
 
     def prefill(serial, layer, n_rows):
@@ -115,13 +119,13 @@ def cpu_baseline(w, lens, budget_s=12.0):
     passes = 0
     while t_used < budget_s:
         idx = np.arange(n_take)
-        q = wl.normal_bits(rng, (idx.size, H, D), w.dtype)
+        q = wl.normal_bits(rng, (idx.size, H, D), w.q_dtype)
         t0 = time.perf_counter()
         _, used = orc.attention_ragged(q, [kv[0]] * idx.size, [kv[1]] * idx.size, lens[idx], w.dtype, None, "f32",
-                                       threads=cores)
+                                       threads=cores, q_dtype=w.q_dtype)
         dt = time.perf_counter() - t0
         t_used += dt
-        done_bytes += int(2 * w.kv_heads * D * 2 * lens[idx].sum() + idx.size * H * D * (2 + 4))
+        done_bytes += int(2 * w.kv_heads * D * w.elem_bytes * lens[idx].sum() + idx.size * H * D * (2 + 4))
         done_seqs += int(idx.size)
         passes += 1
         rate = idx.size / dt
@@ -130,11 +134,11 @@ def cpu_baseline(w, lens, budget_s=12.0):
             break
     # the same code on one thread (plain serial loops), on a short prefix
     n1 = min(lens.size, 4)
-    q1 = wl.normal_bits(rng, (n1, H, D), w.dtype)
+    q1 = wl.normal_bits(rng, (n1, H, D), w.q_dtype)
     t0 = time.perf_counter()
-    orc.attention_ragged(q1, [kv[0]] * n1, [kv[1]] * n1, lens[:n1], w.dtype, None, "f32", threads=1)
+    orc.attention_ragged(q1, [kv[0]] * n1, [kv[1]] * n1, lens[:n1], w.dtype, None, "f32", threads=1, q_dtype=w.q_dtype)
     dt1 = time.perf_counter() - t0
-    one_thread = (2 * w.kv_heads * D * 2 * int(lens[:n1].sum()) + n1 * H * D * (2 + 4)) / dt1 / 1e9
+    one_thread = (2 * w.kv_heads * D * w.elem_bytes * int(lens[:n1].sum()) + n1 * H * D * (2 + 4)) / dt1 / 1e9
     return {"value": round(done_bytes / t_used / 1e9, 4), "unit": "GB/s", "cores": int(used), "kind": "oracle",
             "one_thread_value": round(one_thread, 4),
             "seq_steps_per_s": round(done_seqs / t_used, 2),
@@ -161,7 +165,7 @@ def main():
     if args.heads and args.workload == "c5":
         hq, hkv, hd = (int(x) for x in args.heads.split(","))
         kw.update(n_heads=hq, n_kv_heads=hkv, head_dim=hd)
-    w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4, "c5": wl.c5}[args.workload](**kw) if args.workload != "c3" else wl.c3(
+    w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4, "c5": wl.c5, "c6": wl.c6}[args.workload](**kw) if args.workload != "c3" else wl.c3(
         target_bytes=int(args.c3_bytes))
     if args.drain:
         w.refill = False
@@ -189,6 +193,10 @@ def main():
         s3.check(s3.s3_kv_set_param(eng.arena, "profile", every))
     grown0, retired0 = eng.n_grown, eng.n_retired
     total_bytes, seq_steps, launch_bytes, steps_done = 0, 0, [], 0
+    # The interpreter's cyclic garbage collector is kept out of the timed region (a full collection takes
+    # tens of milliseconds here and would land on whichever step triggers it): collect now, resume after.
+    gc.collect()
+    gc.disable()
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for _ in range(steps):
@@ -204,13 +212,14 @@ def main():
     t_enqueue = time.perf_counter() - t0  # host time to enqueue every step (no device wait in it)
     torch.cuda.synchronize()
     dt = time.perf_counter() - t0
+    gc.enable()
     args.steps, args.warmup = steps_done, warmup
 
     res = {
         "metric": "decode-attention achieved HBM GB/s", "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f16" if w.dtype == 0 else "bf16", "data": "synthetic",
+        "dtype": {0: "f16", 1: "bf16", 3: "e4m3 rows, f16 queries, f32 arithmetic"}[w.dtype], "data": "synthetic",
         "pct_of_peak_hbm": round(100 * total_bytes / dt / 1e9 / PEAK_HBM_GBPS, 2),
         "seq_steps_per_s": round(seq_steps / dt, 1),
         "host_enqueue_ms_per_step": round(t_enqueue / args.steps * 1e3, 5),
@@ -222,6 +231,7 @@ def main():
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
                    "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
                    "path": "append kernel + shared-kv attention kernel per layer" if shared_kv else
+                           "quantising append kernel + attention kernel over 8-bit rows + merge per layer" if w.dtype == 3 else
                            "append+attention+merge kernels" if args.unfused else "one s3_decode_step kernel per layer",
                    "variant": s3.s3_kv_get_param(eng.arena, "variant")[1],
                    "chunk": s3.s3_kv_get_param(eng.arena, "chunk")[1]},
@@ -236,7 +246,7 @@ def main():
         avg_us = part_ns / max(launches, 1) / 1e3
         achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if avg_us > 0 else 0.0
         kind = s3.s3_kv_get_param(eng.arena, "kernel_kind")[1]
-        kernel = {1: "attn_gqa_kernel", 2: "attn_gqa_mfma_kernel"}.get(
+        kernel = {1: "attn_gqa_kernel", 2: "attn_gqa_mfma_kernel", 3: "attn_fp8_kernel"}.get(
             kind, "attn_partial_kernel" if args.unfused else "attn_step_kernel")
         res["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),

@@ -45,7 +45,9 @@ extern "C" {
 
 typedef struct s3_arena s3_arena; /* opaque; host-side metadata owned by the library */
 
-typedef enum { S3_F16 = 0, S3_BF16 = 1, S3_F32 = 2 } s3_dtype;
+/* S3_E4M3: 8-bit float, 1 sign / 4 exponent (bias 7) / 3 fraction bits, no infinities, largest 448
+ * (cache rows only; related work: quantisation as a complementary way to shrink the cache). */
+typedef enum { S3_F16 = 0, S3_BF16 = 1, S3_F32 = 2, S3_E4M3 = 3 } s3_dtype;
 
 typedef enum {
     S3_OK = 0,
@@ -60,15 +62,21 @@ typedef struct {
     int32_t n_layers;  /* l: transformer layers whose K and V the arena holds            */
     int32_t n_heads;   /* H                                                              */
     int32_t head_dim;  /* D: 64, 128 or 256                                              */
-    int32_t kv_dtype;  /* s3_dtype of q, K, V: S3_F16 or S3_BF16                         */
+    int32_t kv_dtype;  /* s3_dtype of the cache rows (and, if 16-bit, of q, k_new, v_new):
+                          S3_F16, S3_BF16 or S3_E4M3                                     */
     int32_t granule;   /* G: capacities are multiples of G tokens (> 0)                  */
     int32_t max_len;   /* M: largest capacity, tokens; a multiple of G                   */
     int32_t n_kv_heads; /* heads of K and V: 0 or n_heads = one per query head; a divisor of n_heads =
                            grouped-query, 1 = multi-query attention (each K/V head serves
                            n_heads / n_kv_heads query heads; q and out keep n_heads)       */
+    int32_t act_dtype; /* kv_dtype == S3_E4M3 only: type of q, k_new, v_new, S3_F16 or S3_BF16 (append
+                          rounds a new row to the nearest e4m3 code, ties to even, saturating at
+                          +-448, NaN -> 0x7f; attention widens the codes exactly).  Ignored for 16-bit
+                          caches.  8-bit caches need n_kv_heads == n_heads; s3_kv_fill and
+                          s3_kv_read_rows move codes (one byte per element).              */
 } s3_kv_config;
 
-/* KV-cache bytes one token occupies: 2 * n_layers * n_heads * head_dim * sizeof(element)
+/* KV-cache bytes one token occupies: 2 * n_layers * n_kv_heads * head_dim * sizeof(element)
  * (section 2.1: 4*l*d_h bytes in half precision).  Returns the byte count, or
  * S3_ERR_INVALID (< 0) for a bad config. */
 int64_t s3_kv_bytes_per_token(const s3_kv_config *cfg /*HOST*/);
@@ -116,7 +124,8 @@ int s3_kv_slot_info(const s3_arena *a, int32_t slot_id, int64_t *off /*HOST*/, i
  *             its reservation: call s3_kv_grow), anything else bad gives S3_ERR_INVALID; in
  *             both cases nothing is written.  When NULL the caller vouches for the positions.
  *   slot_off  DEVICE [n] int64, pos DEVICE [n] int32
- *   k_new, v_new  DEVICE [n][H][D] elements of kv_dtype, 16-byte aligned */
+ *   k_new, v_new  DEVICE [n][H][D] elements of kv_dtype (8-bit caches: of act_dtype, quantised here;
+ *                 shared K/V heads: [n][n_kv_heads][D]), 16-byte aligned */
 int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
                  const int64_t *slot_off, const int32_t *pos, const void *k_new, const void *v_new,
                  void *stream);
@@ -126,7 +135,7 @@ int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, 
  * over the sequence's own rows only (no padding).  cur_len[b] == 0 gives a zero row.
  * Arithmetic is fp32 (dot products, max-subtracted softmax, weighted sum); contexts are
  * cut into chunks whose partial (max, sum, weighted sum) are merged by a second kernel.
- *   q         DEVICE [n][H][D] kv_dtype, 16-byte aligned
+ *   q         DEVICE [n][H][D] kv_dtype (8-bit caches: act_dtype), 16-byte aligned
  *   slot_off  DEVICE [n] int64, cur_len DEVICE [n] int32
  *   out       DEVICE [n][H][D] of out_dtype (S3_F32, S3_F16 or S3_BF16), 16-byte aligned
  *   scale     <= 0 means 1/sqrt(D)
@@ -244,7 +253,7 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *   "profile"      k > 0: bracket every k-th attention launch (counted from this call) with HIP events
  *                  on its stream; 0: off; both reset the sums
  * get names: the above plus "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,
- * 2 shared-K/V matrix-core kernel: what the next attention launch uses), "n_variants", "n_grows",
+ * 2 shared-K/V matrix-core kernel, 3 kernel for 8-bit rows: what the next attention launch uses), "n_variants", "n_grows",
  * "live_slots", "scratch_bytes", "num_cus" and,
  * after "profile" k, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
  * timed launches since the last reset) and "profile_p10_ns", "profile_p50_ns", "profile_p90_ns"

@@ -39,7 +39,7 @@ import numpy as np
 
 OK, ERR_INVALID, ERR_NOMEM, ERR_SLOT_FULL, ERR_MAXLEN = 0, -1, -2, -3, -4
 F16, BF16 = 0, 1
-E4M3 = 2  # 8-bit cache rows: one e4m3 code in the low byte of each uint16 the oracle stores
+E4M3 = 3  # 8-bit cache rows: one e4m3 code in the low byte of each uint16 the oracle stores
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _LIB = None

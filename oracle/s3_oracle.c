@@ -13,7 +13,7 @@
  * rows.  No tiling, no running ("online") softmax, no reordering.
  *
  * Inputs are the values as stored in the KV cache: 16-bit patterns of IEEE
- * binary16 (dtype 0) or bfloat16 (dtype 1), or 8-bit e4m3 codes (dtype 2, one code
+ * binary16 (dtype 0) or bfloat16 (dtype 1), or 8-bit e4m3 codes (dtype 3, one code
  * in the low byte of each uint16_t; the query then has a 16-bit type of its own,
  * qdtype).  They are widened to REAL before any arithmetic.  The file is compiled twice: REAL = float (the fp32 oracle)
  * and REAL = double (its twin, used to bound the fp32 oracle's own error).
@@ -99,7 +99,8 @@ static uint8_t quantize_e4m3(float x)
     return (uint8_t)(sign | code);
 }
 
-/* 16-bit storage types carry their pattern in a uint16_t; the 8-bit type (dtype 2) in its low byte. */
+/* 16-bit storage types carry their pattern in a uint16_t; the 8-bit type (dtype 3, the number the
+ * library's interface gives it) in its low byte. */
 static REAL widen(uint16_t h, int dtype)
 {
     return dtype == 0 ? widen_f16(h) : dtype == 1 ? widen_bf16(h) : widen_e4m3((uint8_t)h);

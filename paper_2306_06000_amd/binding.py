@@ -11,7 +11,7 @@ import os
 
 import numpy as np
 
-S3_F16, S3_BF16, S3_F32 = 0, 1, 2
+S3_F16, S3_BF16, S3_F32, S3_E4M3 = 0, 1, 2, 3
 S3_OK, S3_ERR_INVALID, S3_ERR_NOMEM, S3_ERR_SLOT_FULL, S3_ERR_MAXLEN, S3_ERR_HIP = 0, -1, -2, -3, -4, -5
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
@@ -22,7 +22,7 @@ _lib = None
 class s3_kv_config(ctypes.Structure):
     _fields_ = [("n_layers", ctypes.c_int32), ("n_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
                 ("kv_dtype", ctypes.c_int32), ("granule", ctypes.c_int32), ("max_len", ctypes.c_int32),
-                ("n_kv_heads", ctypes.c_int32)]
+                ("n_kv_heads", ctypes.c_int32), ("act_dtype", ctypes.c_int32)]
 
 
 _vp, _i32, _i64, _f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_float
@@ -102,8 +102,8 @@ class S3Error(RuntimeError):
         super().__init__(f"{where}: {lib().s3_status_str(status).decode()} {detail}".strip())
 
 
-def make_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_heads=0):
-    return s3_kv_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_heads)
+def make_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_heads=0, act_dtype=0):
+    return s3_kv_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_heads, act_dtype)
 
 
 def s3_kv_bytes_per_token(cfg):

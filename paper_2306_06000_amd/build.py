@@ -6,7 +6,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs3kv.so")
-SOURCES = ["s3kv_kernels.hip", "s3kv_gqa.hip", "s3kv_gqa_mfma.hip", "s3kv_alloc.cpp", "s3kv_sched.cpp"]
+SOURCES = ["s3kv_kernels.hip", "s3kv_gqa.hip", "s3kv_gqa_mfma.hip", "s3kv_fp8.hip", "s3kv_alloc.cpp", "s3kv_sched.cpp"]
 HEADERS = ["s3kv_internal.h", "s3kv_device.h"]
 
 

@@ -41,7 +41,11 @@ static bool config_ok(const s3_kv_config *c) {
     if (!c) return false;
     if (c->n_layers <= 0 || c->n_heads <= 0) return false;
     if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
-    if (c->kv_dtype != S3_F16 && c->kv_dtype != S3_BF16) return false;
+    if (c->kv_dtype != S3_F16 && c->kv_dtype != S3_BF16 && c->kv_dtype != S3_E4M3) return false;
+    if (c->kv_dtype == S3_E4M3) {  // 8-bit rows: 16-bit activations, one cached head per query head
+        if (c->act_dtype != S3_F16 && c->act_dtype != S3_BF16) return false;
+        if (c->n_kv_heads != 0 && c->n_kv_heads != c->n_heads) return false;
+    }
     if (c->granule <= 0 || c->max_len <= 0 || c->max_len % c->granule != 0) return false;
     if (c->n_kv_heads < 0 || (c->n_kv_heads > 0 && (c->n_kv_heads > c->n_heads || c->n_heads % c->n_kv_heads))) return false;
     return true;
@@ -51,7 +55,7 @@ extern "C" int64_t s3_kv_bytes_per_token(const s3_kv_config *cfg) {
     if (!config_ok(cfg)) return S3_ERR_INVALID;
     // K and V, every layer, H*D two-byte numbers: 4*l*d_h bytes (section 2.1)
     const int kv_heads = cfg->n_kv_heads > 0 ? cfg->n_kv_heads : cfg->n_heads;
-    return (int64_t)2 * cfg->n_layers * kv_heads * cfg->head_dim * 2;
+    return (int64_t)2 * cfg->n_layers * kv_heads * cfg->head_dim * (cfg->kv_dtype == S3_E4M3 ? 1 : 2);
 }
 
 extern "C" int s3_kv_arena_init(s3_arena **out, const s3_kv_config *cfg, void *dev_base, size_t dev_bytes) {
@@ -62,8 +66,9 @@ extern "C" int s3_kv_arena_init(s3_arena **out, const s3_kv_config *cfg, void *d
     a->cfg = *cfg;
     a->base = (char *)dev_base;
     a->dev_bytes = dev_bytes;
-    a->elem_bytes = 2;
+    a->elem_bytes = cfg->kv_dtype == S3_E4M3 ? 1 : 2;
     if (a->cfg.n_kv_heads == 0) a->cfg.n_kv_heads = cfg->n_heads;
+    if (cfg->kv_dtype != S3_E4M3) a->cfg.act_dtype = cfg->kv_dtype;
     a->row_bytes = (int64_t)a->cfg.n_kv_heads * cfg->head_dim * a->elem_bytes;
     a->n_tokens = (int64_t)(dev_bytes / (size_t)s3_kv_bytes_per_token(cfg));
     a->plane_bytes = a->n_tokens * a->row_bytes;
@@ -271,10 +276,12 @@ extern "C" int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_t
 
 // The attention kernel family an arena uses depends on whether its key/value heads are shared.
 static int s3i_variants_of(const s3_arena *a) {
+    if (a->cfg.kv_dtype == S3_E4M3) return s3i_num_fp8_shapes();
     return a->cfg.n_kv_heads < a->cfg.n_heads ? s3i_num_gqa_shapes() + 1 : s3i_num_variants();  // + the matrix-core kernel
 }
 
 int s3i_kernel_kind(const s3_arena *a) {
+    if (a->cfg.kv_dtype == S3_E4M3) return 3;
     if (a->cfg.n_kv_heads >= a->cfg.n_heads) return 0;
     const int group = a->cfg.n_heads / a->cfg.n_kv_heads;
     return (a->variant == s3i_num_gqa_shapes() || (a->variant < 0 && group >= 4)) ? 2 : 1;

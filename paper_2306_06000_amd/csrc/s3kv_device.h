@@ -52,12 +52,12 @@ __device__ __forceinline__ float dpp_sum_step(float v) {
     return v + __builtin_bit_cast(float, moved);
 }
 
-// Sum over groups of LANES adjacent lanes (8, 16 or 32); every lane of a group gets the sum.
+// Sum over groups of LANES adjacent lanes (4, 8, 16 or 32); every lane of a group gets the sum.
 template <int LANES>
 __device__ __forceinline__ float group_sum(float v) {
     v = dpp_sum_step<0xB1>(v);   // quad_perm [1,0,3,2]: lane ^ 1
     v = dpp_sum_step<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2
-    v = dpp_sum_step<0x141>(v);  // row_half_mirror: the other quad of each 8
+    if (LANES >= 8) v = dpp_sum_step<0x141>(v);  // row_half_mirror: the other quad of each 8
     if (LANES >= 16) v = dpp_sum_step<0x140>(v);  // row_mirror: the other 8 of each 16
     if (LANES >= 32)
     {
@@ -400,6 +400,12 @@ typedef void (*attn_fn)(const AttnArgs);
 // lane (1, 2, 4 or 8), shape = index into its (waves, rows per load batch) table, < 0 for the
 // default of that gq.  Returns the kernel and its workgroup size, or null.
 attn_fn s3i_pick_gqa(int dt, int d, int gq, int shape, int *threads);
+// Kernels for 8-bit (e4m3) cache rows (defined in s3kv_fp8.hip): the attention kernel for activation
+// type act (S3_F16 / S3_BF16) and its workgroup size, and the append that quantises a new row.
+attn_fn s3i_pick_fp8(int act, int d, int shape, int *threads);
+typedef void (*append_fp8_fn)(char *, char *, const int64_t *, const int32_t *, const char *, const char *, int32_t,
+                              int64_t, int32_t);
+append_fp8_fn s3i_pick_append_fp8(int act);
 // Matrix-core kernel for shared key/value heads (defined in s3kv_gqa_mfma.hip); 256 threads per
 // workgroup, one work item per wave.
 attn_fn s3i_pick_gqa_mfma(int dt, int d);

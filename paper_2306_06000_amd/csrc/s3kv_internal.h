@@ -66,9 +66,10 @@ int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src
                            size_t dst_plane_stride, int planes, void *stream);
 int s3i_num_variants();    // kernel variants of the multi-head attention kernels
 int s3i_num_gqa_shapes();  // shapes of the shared-K/V (grouped-query) attention kernel
+int s3i_num_fp8_shapes();  // shapes of the attention kernel for 8-bit cache rows
 // Which attention kernel family the arena's next launch uses: 0 multi-head, 1 shared-K/V on the vector
 // ALU, 2 shared-K/V on the matrix cores (variant index = number of shapes, or the default from four
-// query heads per cached head; measured on MI355X).
+// query heads per cached head; measured on MI355X), 3 the kernel for 8-bit cache rows.
 int s3i_kernel_kind(const s3_arena *a);
 int s3i_profile_collect(s3_arena *a);  // synchronises on the recorded events and accumulates the sums
 void s3i_profile_reset(s3_arena *a);

@@ -618,6 +618,24 @@ extern "C" void s3_kv_arena_destroy(s3_arena *a) {
 }
 
 static bool aligned16(const void *p) { return ((uintptr_t)p & 15) == 0; }
+
+// The append of one layer: a bit copy of the new rows, or, for 8-bit caches, their quantisation.
+static int launch_append(s3_arena *a, int32_t layer, int32_t n, const int64_t *slot_off, const int32_t *pos,
+                         const void *k_new, const void *v_new, void *stream) {
+    if (a->cfg.kv_dtype == S3_E4M3) {
+        append_fp8_fn fn = s3i_pick_append_fp8(a->cfg.act_dtype);
+        if (!fn) return S3_ERR_INVALID;
+        hipLaunchKernelGGL(fn, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
+                           a->plane(layer, 1), slot_off, pos, (const char *)k_new, (const char *)v_new,
+                           (int32_t)a->row_bytes, a->n_tokens, a->cfg.max_len);
+    } else {
+        hipLaunchKernelGGL(append_kernel, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
+                           a->plane(layer, 1), slot_off, pos, (const char *)k_new, (const char *)v_new, a->row_bytes,
+                           a->n_tokens, a->cfg.max_len);
+    }
+    HIP_TRY(hipGetLastError());
+    return S3_OK;
+}
 static int check_slots_host(const s3_arena *a, int32_t n, const int32_t *slot_id, const int32_t *pos_host);
 
 extern "C" int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
@@ -628,11 +646,7 @@ extern "C" int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t
     if (!slot_off || !pos || !k_new || !v_new || !aligned16(k_new) || !aligned16(v_new)) return S3_ERR_INVALID;
     const int rc = check_slots_host(a, n, slot_id, pos_host);
     if (rc != S3_OK) return rc;
-    hipLaunchKernelGGL(append_kernel, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
-                       a->plane(layer, 1), slot_off, pos, (const char *)k_new, (const char *)v_new, a->row_bytes,
-                       a->n_tokens, a->cfg.max_len);
-    HIP_TRY(hipGetLastError());
-    return S3_OK;
+    return launch_append(a, layer, n, slot_off, pos, k_new, v_new, stream);
 }
 
 static int check_slots_host(const s3_arena *a, int32_t n, const int32_t *slot_id, const int32_t *pos_host) {
@@ -678,10 +692,8 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     attn_fn fn = mfma ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D) : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;
     if (with_append) {
-        hipLaunchKernelGGL(append_kernel, dim3((unsigned)n, 2), dim3(256), 0, (hipStream_t)stream, a->plane(layer, 0),
-                           a->plane(layer, 1), slot_off, len_or_pos, (const char *)k_new, (const char *)v_new,
-                           a->row_bytes, a->n_tokens, a->cfg.max_len);
-        HIP_TRY(hipGetLastError());
+        const int arc = launch_append(a, layer, n, slot_off, len_or_pos, k_new, v_new, stream);
+        if (arc != S3_OK) return arc;
     }
     AttnArgs args;
     memset(&args, 0, sizeof(args));
@@ -753,11 +765,90 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     return S3_OK;
 }
 
+// 8-bit cache rows: quantising append (own launch), attention over the codes, merge of chunk partials.
+static int launch_fp8(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
+                      const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
+                      bool with_append, const void *k_new, const void *v_new, int32_t *len_out) {
+    const int D = a->cfg.head_dim, H = a->cfg.n_heads;
+    int threads = 0;
+    attn_fn fn = s3i_pick_fp8(a->cfg.act_dtype, D, a->variant, &threads);
+    if (!fn) return S3_ERR_INVALID;
+    if (with_append) {
+        const int arc = launch_append(a, layer, n, slot_off, len_or_pos, k_new, v_new, stream);
+        if (arc != S3_OK) return arc;
+    }
+    AttnArgs args;
+    memset(&args, 0, sizeof(args));
+    args.kplane = a->plane(layer, 0);
+    args.vplane = a->plane(layer, 1);
+    args.q = (const char *)q;
+    args.slot_off = slot_off;
+    args.cur_len = len_or_pos;
+    args.out = out;
+    args.n_tokens = a->n_tokens;
+    args.n = n;
+    args.H = H;
+    args.Hq = H;
+    args.out_dtype = out_dtype;
+    args.max_len = a->cfg.max_len;
+    args.len_add = with_append ? 1 : 0;
+    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
+    args.scale_log2e = scale * 1.4426950408889634f;
+    args.len_out = with_append ? len_out : nullptr;
+    const int GH = 1024 / D;  // heads per 128-bit wave load of one-byte elements
+    const int n_hg = (H + GH - 1) / GH;
+    const int chunk = a->chunk > 0 ? a->chunk : 1024;
+    args.chunk = chunk;
+    args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
+    const size_t n_part = (size_t)n * args.max_chunks * H;
+    const size_t acc_bytes = n_part * D * sizeof(float);
+    const int src = ensure_scratch(a, acc_bytes + n_part * sizeof(float2));
+    if (src != S3_OK) return src;
+    args.part_acc = (float *)a->scratch;
+    args.part_ml = (float2 *)((char *)a->scratch + acc_bytes);
+    args.ncls = a->ncls > 0 ? a->ncls : n <= 128 ? 4 : n <= 256 ? 2 : 1;
+    const size_t dyn_lds = (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)args.ncls * (n + 1) * 4;
+    const int cus = a->num_cus > 0 ? a->num_cus : 256;
+    int blocks = a->grid_blocks;
+    if (blocks <= 0) {
+        int per_cu = 0;
+        const int orc = resident_per_cu((const void *)fn, threads, dyn_lds, &per_cu);
+        if (orc != S3_OK) return orc;
+        blocks = cus * per_cu * (n > 128 ? 2 : 1);
+    }
+    (void)n_hg;
+    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
+    const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
+    if (timed) {
+        for (int i = 0; i < 3; i++) {
+            const int prc = prof_next_event(a, &ev[i]);
+            if (prc != S3_OK) return prc;
+        }
+        HIP_TRY(hipEventRecord(ev[0], (hipStream_t)stream));
+    }
+    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)threads), dyn_lds, (hipStream_t)stream, args);
+    HIP_TRY(hipGetLastError());
+    if (timed) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
+    {
+        const int MGH = 512 / D;  // the merge kernel's own head grouping (8 fp32 elements per lane)
+        const unsigned mblocks = (unsigned)(((int64_t)n * ((H + MGH - 1) / MGH) + 3) / 4);
+        void (*mfn)(const AttnArgs) =
+            D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
+        hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, args);
+        HIP_TRY(hipGetLastError());
+    }
+    if (timed) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
+    return S3_OK;
+}
+
 // Shared by s3_decode_attention (fused = false: partial kernel + merge kernel) and s3_decode_step
 // (fused = true: one kernel that also appends, merges and publishes the new lengths).
 static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
                             const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
                             bool fused, const void *k_new, const void *v_new, int32_t *len_out) {
+    if (a->cfg.kv_dtype == S3_E4M3)
+        return launch_fp8(a, layer, n, q, slot_off, len_or_pos, out, out_dtype, scale, stream, fused, k_new, v_new,
+                          len_out);
     if (a->cfg.n_kv_heads < a->cfg.n_heads)
         return launch_gqa(a, layer, n, q, slot_off, len_or_pos, out, out_dtype, scale, stream, fused, k_new, v_new,
                           len_out);

@@ -27,7 +27,7 @@ class DecodeEngine:
         self.w = w
         self.fused = fused  # True: one s3_decode_step launch per layer; False: append + attention calls
         self.dev = torch.device(device)
-        self.cfg = s3.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len, w.n_kv_heads)
+        self.cfg = s3.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len, w.n_kv_heads, max(w.act_dtype, 0))
         self.bpt = s3.s3_kv_bytes_per_token(self.cfg)
         if arena_tokens is None:
             if w.arena_bytes:
@@ -75,7 +75,12 @@ class DecodeEngine:
         return torch.cuda.current_stream(self.dev).cuda_stream
 
     def kv_dtype_torch(self):
-        return _TORCH_DT[self.w.dtype]
+        """torch type of cache rows handed to fill (8-bit caches: raw codes)."""
+        return torch.uint8 if self.w.dtype == s3.S3_E4M3 else _TORCH_DT[self.w.dtype]
+
+    def act_dtype_torch(self):
+        """torch type of q, k_new, v_new."""
+        return _TORCH_DT[self.w.q_dtype]
 
     @property
     def n_active(self):
@@ -251,16 +256,19 @@ class DecodeEngine:
         """Bytes one layer-step of the CURRENT batch must move, counted after the append (the
         lengths attention sees): K and V rows read once, q read, out written, new k/v read and
         written."""
-        e = 2
+        e = 2                    # q, new k and v: 16-bit
+        ec = self.w.elem_bytes   # cache rows
         e_out = {s3.S3_F32: 4, s3.S3_F16: 2, s3.S3_BF16: 2}[self.out_dtype]
         hd = self.w.n_heads * self.w.head_dim
         kvd = self.w.kv_heads * self.w.head_dim  # elements of one cached row
         B = self.n_active
-        return 2 * kvd * e * int(self.len.sum()) + B * hd * e + B * hd * e_out + 4 * B * kvd * e
+        return 2 * kvd * ec * int(self.len.sum()) + B * hd * e + B * hd * e_out + 2 * B * kvd * (e + ec)
 
     def read_slot(self, a, layer, which, n_rows=None):
         n_rows = a.len if n_rows is None else n_rows
-        dst = torch.empty((n_rows, self.w.kv_heads, self.w.head_dim), dtype=torch.int16, device=self.dev)
+        eight_bit = self.w.dtype == s3.S3_E4M3
+        dst = torch.empty((n_rows, self.w.kv_heads, self.w.head_dim), dtype=torch.uint8 if eight_bit else torch.int16,
+                          device=self.dev)
         s3.check(s3.s3_kv_read_rows(self.arena, a.slot, layer, which, 0, n_rows, dst, self._stream_ptr()),
                  "s3_kv_read_rows")
-        return dst.cpu().numpy().view(np.uint16)
+        return dst.cpu().numpy() if eight_bit else dst.cpu().numpy().view(np.uint16)

@@ -17,6 +17,7 @@ import numpy as np
 
 SEED_BASE = 230606000
 F16, BF16 = 0, 1
+E4M3 = 3  # 8-bit cache rows (the library's S3_E4M3); queries and new rows keep a 16-bit type
 
 
 def f32_to_f16_bits(x: np.ndarray) -> np.ndarray:
@@ -31,7 +32,18 @@ def f32_to_bf16_bits(x: np.ndarray) -> np.ndarray:
     return u.astype(np.uint16)
 
 
+def f32_to_e4m3_codes(x: np.ndarray) -> np.ndarray:
+    """float32 -> e4m3 codes (uint8) through torch's float8_e4m3fn conversion; inputs stay far below
+    the format's largest value, where every convention agrees."""
+    import torch
+
+    t = torch.from_numpy(np.ascontiguousarray(x, np.float32)).to(torch.float8_e4m3fn)
+    return t.view(torch.uint8).numpy()
+
+
 def to_bits(x: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == E4M3:
+        return f32_to_e4m3_codes(x)
     return f32_to_f16_bits(x) if dtype == F16 else f32_to_bf16_bits(x)
 
 
@@ -74,6 +86,7 @@ class Workload:
     arena_bytes: int = 0                            # 0: sized by the harness from the slots
     note: str = ""
     n_kv_heads: int = 0                             # 0: every head has its own K/V (multi-head attention)
+    act_dtype: int = -1                             # type of q / new rows; -1: the cache type (16-bit caches)
 
     @property
     def seed(self) -> int:
@@ -81,7 +94,11 @@ class Workload:
 
     @property
     def elem_bytes(self) -> int:
-        return 2
+        return 1 if self.dtype == E4M3 else 2
+
+    @property
+    def q_dtype(self) -> int:
+        return self.dtype if self.act_dtype < 0 else self.act_dtype
 
     @property
     def kv_heads(self) -> int:
@@ -188,15 +205,24 @@ def c5(batch: int = 256, steps: int = 128, n_heads: int = 32, n_kv_heads: int = 
                     base.max_len, batch, steps, base.seqs, base.pool, base.refill, n_kv_heads=n_kv_heads)
 
 
+def c6(batch: int = 128, steps: int = 128) -> Workload:
+    """8-bit cache rows (quantisation, which the paper's related-work section names as complementary):
+    C1's shape, lengths, mispredictions and refill with e4m3 rows and fp16 queries / new rows, at twice
+    C1's batch (a cache row is half the size).  Not one of the paper's measured configurations."""
+    base = c1(batch, steps)
+    return Workload("C6-e4m3-rows", 6, 1, 16, 256, E4M3, base.granule, base.max_len, batch, steps, base.seqs, base.pool,
+                    base.refill, act_dtype=F16)
+
+
 def by_name(name: str) -> Workload:
-    return {"c0": c0, "c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5}[name.lower()]()
+    return {"c0": c0, "c1": c1, "c2": c2, "c3": c3, "c4": c4, "c5": c5, "c6": c6}[name.lower()]()
 
 
 def step_tensors(w: Workload, step: int, layer: int, n: int):
     """q, k_new, v_new for one (step, layer): [n][H][D] 16-bit patterns, N(0,1)."""
     rng = np.random.default_rng([w.seed, 1, step, layer])
     shape = (3, n, w.n_heads, w.head_dim)
-    t = normal_bits(rng, shape, w.dtype)
+    t = normal_bits(rng, shape, w.q_dtype)  # queries and new rows: the activation type
     hk = w.kv_heads  # shared K/V heads: the first kv_heads of the same draw
     return t[0], np.ascontiguousarray(t[1][:, :hk]), np.ascontiguousarray(t[2][:, :hk])
 
@@ -219,7 +245,7 @@ class PooledSource:
         rng = np.random.default_rng([w.seed, 3])
         self.w = w
         self.rows = normal_bits(rng, (2, w.max_len + 128, w.n_heads, w.head_dim), w.dtype)
-        self.qkv = normal_bits(rng, (ring, 3, n_max, w.n_heads, w.head_dim), w.dtype)
+        self.qkv = normal_bits(rng, (ring, 3, n_max, w.n_heads, w.head_dim), w.q_dtype)
         self.ring = ring
 
     def prefill_rows(self, serial: int, layer: int, rows: int):

@@ -21,16 +21,20 @@ def assert_close(got, want, what=""):
 
 
 def device_bits(bits, torch_dtype, device):
-    """uint16 patterns (numpy) -> device tensor of the 16-bit float type, bit-preserving."""
+    """uint16 patterns (numpy) -> device tensor of the 16-bit float type, bit-preserving; uint8 codes
+    (8-bit cache rows) go up as they are."""
     import torch
 
-    return torch.from_numpy(np.ascontiguousarray(bits).view(np.int16)).to(device).view(torch_dtype)
+    bits = np.ascontiguousarray(bits)
+    if bits.dtype == np.uint8:
+        return torch.from_numpy(bits).to(device)
+    return torch.from_numpy(bits.view(np.int16)).to(device).view(torch_dtype)
 
 
 def make_sources(w, engine, source=None):
     """prefill(serial, layer, rows) and tensors_for(step) closures that upload the seeded inputs.
     source: a workloads.PooledSource for full-size runs (default: fresh draws per call)."""
-    tdt = engine.kv_dtype_torch()
+    tdt, adt = engine.kv_dtype_torch(), engine.act_dtype_torch()
     get_rows = source.prefill_rows if source else (lambda serial, layer, rows: wl.prefill_rows(w, serial, layer, rows))
     get_step = source.step_tensors if source else (lambda step, layer, n: wl.step_tensors(w, step, layer, n))
 
@@ -41,7 +45,7 @@ def make_sources(w, engine, source=None):
     def tensors_for(step):
         def tensors(layer, n):
             q, k, v = get_step(step, layer, n)
-            return tuple(device_bits(x, tdt, engine.dev) for x in (q, k, v))
+            return tuple(device_bits(x, adt, engine.dev) for x in (q, k, v))
 
         return tensors
 
@@ -57,7 +61,8 @@ class OracleReplay:
         self.get_rows = source.prefill_rows if source else (lambda serial, layer, rows: wl.prefill_rows(w, serial, layer, rows))
         self.get_step = source.step_tensors if source else (lambda step, layer, n: wl.step_tensors(w, step, layer, n))
         self.o = orc.KVOracle(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len,
-                              arena_tokens * w.bytes_per_token, n_kv_heads=w.n_kv_heads)
+                              arena_tokens * w.bytes_per_token, n_kv_heads=w.n_kv_heads,
+                              act_dtype=None if w.act_dtype < 0 else w.act_dtype)
         self.sid = {}   # serial -> slot id
         self.len = {}   # serial -> rows cached
         self.step_idx = 0
