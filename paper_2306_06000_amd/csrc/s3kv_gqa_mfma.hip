@@ -31,7 +31,11 @@
 //     keeps the weights' error near 2^-16 instead of 2^-9.
 // Accumulators: O^T block db holds O^T[d = 16*db + 4*g + i][head], fp32.  Results leave as the
 // final row (single-chunk contexts) or as a chunk partial (max, sum, unnormalised row) that
-// attn_merge_kernel finishes, as in the vector-ALU kernel.
+// attn_merge_kernel finishes (merging in this kernel through an arrival counter and device-scope
+// partials, as the fused multi-head step does in its epilogue wave, tripled the kernel's time here:
+// with one wave per item nothing hides the write-through and the counter's round trip).  In a decode
+// step the new row is read from k_new / v_new and appended by the wave that owns it, so the step is
+// this launch plus the merge.
 #include "s3kv_device.h"
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -99,8 +103,10 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
     const int per_seq = a.H * nqb;
     const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
     const int64_t total = (int64_t)bv.total * per_seq;
-    if (blockIdx.x == 0 && a.len_out)
-        for (int b = threadIdx.x; b < a.n; b += 256) a.len_out[b] = a.cur_len[b] + 1;
+    if (blockIdx.x == 0) {
+        if (a.len_out)
+            for (int b = threadIdx.x; b < a.n; b += 256) a.len_out[b] = a.cur_len[b] + 1;
+    }
 
     char *vt = vtile[wave];
     const int64_t rstride = (int64_t)a.H * D * 2;
@@ -119,8 +125,13 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
             qop[ks] = *(const u32x4 *)(a.q + (((int64_t)it.b * a.Hq + hq) * D + ks * 32 + g * 8) * 2);
             if (!head_ok) qop[ks] = (u32x4){0u, 0u, 0u, 0u};  // padding columns: zero scores, never stored
         }
-        const char *kbase = a.kplane + it.off * rstride + (int64_t)hk * D * 2;
-        const char *vbase = a.vplane + it.off * rstride + (int64_t)hk * D * 2;
+        char *kbase = a.kplane + it.off * rstride + (int64_t)hk * D * 2;
+        char *vbase = a.vplane + it.off * rstride + (int64_t)hk * D * 2;
+        // Decode step (len_add = 1): row len-1 is still only in k_new / v_new.  Every reader takes it from
+        // there; the wave of query block 0 whose chunk holds it also writes it into the arena (the append).
+        const int jnew = a.len_add ? it.len - 1 : -1;
+        const char *knew = a.k_new + ((int64_t)it.b * a.H + hk) * D * 2;
+        const char *vnew = a.v_new + ((int64_t)it.b * a.H + hk) * D * 2;
 
         f32x4 o[DB];
 #pragma unroll
@@ -129,16 +140,30 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
 
         // Loads of one 16-row tile (rows past the chunk's end are clamped to its last row and masked later).
         auto load_tile = [&](int r0, u32x4 (&kop)[KS], u32x4 (&vv)[VL]) {
-            const char *krow = kbase + (uint64_t)(unsigned)min(r0 + n, end - 1) * rs32 + g * 16;
+            const int rk = min(r0 + n, end - 1);
+            const char *krow = (rk == jnew ? knew : kbase + (uint64_t)(unsigned)rk * rs32) + g * 16;
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) kop[ks] = load16<false>(krow + ks * 64);
 #pragma unroll
             for (int i = 0; i < VL; i++) {
                 const int idx = i * 64 + lane;
-                vv[i] = load16<true>(vbase + (uint64_t)(unsigned)min(r0 + idx / PPR, end - 1) * rs32 + (idx % PPR) * 16);
+                const int rv = min(r0 + idx / PPR, end - 1);
+                vv[i] = load16<true>((rv == jnew ? vnew : vbase + (uint64_t)(unsigned)rv * rs32) + (idx % PPR) * 16);
             }
         };
         auto reduce_tile = [&](int r0, const u32x4 (&kop)[KS], const u32x4 (&vv)[VL]) {
+            if (qb == 0 && jnew >= r0 && jnew < r0 + 16 && jnew < end) {  // this tile holds the new row: append it
+                if (r0 + n == jnew) {
+#pragma unroll
+                    for (int ks = 0; ks < KS; ks++)
+                        *(u32x4 *)(kbase + (uint64_t)(unsigned)jnew * rs32 + g * 16 + ks * 64) = kop[ks];
+                }
+#pragma unroll
+                for (int i = 0; i < VL; i++) {
+                    const int idx = i * 64 + lane;
+                    if (r0 + idx / PPR == jnew) *(u32x4 *)(vbase + (uint64_t)(unsigned)jnew * rs32 + (idx % PPR) * 16) = vv[i];
+                }
+            }
             f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ks++) s = mfma_scores<DT>(kop[ks], qop[ks], s);

@@ -691,7 +691,7 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     int threads = 256;
     attn_fn fn = mfma ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D) : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;
-    if (with_append) {
+    if (with_append && !mfma) {  // the matrix-core kernel appends by itself
         const int arc = launch_append(a, layer, n, slot_off, len_or_pos, k_new, v_new, stream);
         if (arc != S3_OK) return arc;
     }
@@ -700,6 +700,8 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     args.kplane = a->plane(layer, 0);
     args.vplane = a->plane(layer, 1);
     args.q = (const char *)q;
+    args.k_new = (const char *)k_new;
+    args.v_new = (const char *)v_new;
     args.slot_off = slot_off;
     args.cur_len = len_or_pos;
     args.out = out;
