@@ -678,70 +678,89 @@ static int resident_per_cu(const void *fn, int threads, size_t dyn_lds, int *per
     return S3_OK;
 }
 
-// Grouped-query / multi-query configurations: with_append = true runs the append as its own launch
-// first (same stream), then the attention over pos + 1 rows, which also publishes the new lengths.
-static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
-                      const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
-                      bool with_append, const void *k_new, const void *v_new, int32_t *len_out) {
-    const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
-    const int group = Hq / Hkv;
-    const int gq = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
-    // Variant indices of a shared-K/V arena: the shapes of the vector-ALU kernel, then the matrix-core kernel.
-    const bool mfma = s3i_kernel_kind(a) == 2;
-    int threads = 256;
-    attn_fn fn = mfma ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D) : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
-    if (!fn) return S3_ERR_INVALID;
-    if (with_append && !mfma) {  // the matrix-core kernel appends by itself
-        const int arc = launch_append(a, layer, n, slot_off, len_or_pos, k_new, v_new, stream);
-        if (arc != S3_OK) return arc;
-    }
+// One attention call as the entry points hand it over.  with_append: s3_decode_step (len_or_pos is the
+// append position, the kernels attend over pos + 1 rows and publish len_out).
+struct AttnCall {
+    int32_t layer, n;
+    const void *q;
+    const int64_t *slot_off;
+    const int32_t *len_or_pos;
+    void *out;
+    int32_t out_dtype;
+    float scale;
+    void *stream;
+    bool with_append;
+    const void *k_new, *v_new;
+    int32_t *len_out;
+};
+
+// Kernel arguments every attention kernel shares.  row_heads: heads of a cached row; q_heads: heads of q / out.
+static AttnArgs common_args(const s3_arena *a, const AttnCall &c, int row_heads, int q_heads, int chunk) {
     AttnArgs args;
     memset(&args, 0, sizeof(args));
-    args.kplane = a->plane(layer, 0);
-    args.vplane = a->plane(layer, 1);
-    args.q = (const char *)q;
-    args.k_new = (const char *)k_new;
-    args.v_new = (const char *)v_new;
-    args.slot_off = slot_off;
-    args.cur_len = len_or_pos;
-    args.out = out;
+    args.kplane = a->plane(c.layer, 0);
+    args.vplane = a->plane(c.layer, 1);
+    args.q = (const char *)c.q;
+    args.k_new = (const char *)c.k_new;
+    args.v_new = (const char *)c.v_new;
+    args.slot_off = c.slot_off;
+    args.cur_len = c.len_or_pos;
+    args.out = c.out;
     args.n_tokens = a->n_tokens;
-    args.n = n;
-    args.H = Hkv;
-    args.Hq = Hq;
-    args.out_dtype = out_dtype;
-    args.max_len = a->cfg.max_len;
-    args.len_add = with_append ? 1 : 0;
-    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
-    args.scale_log2e = scale * 1.4426950408889634f;
-    args.len_out = with_append ? len_out : nullptr;
-    const int GH = 512 / D;
-    // work items per chunk: (K/V head groups x query sub-blocks), or for the matrix-core kernel
-    // (K/V heads x blocks of 16 query heads), there one item per wave
-    const int per_seq = mfma ? Hkv * ((group + 15) / 16) : ((Hkv + GH - 1) / GH) * (group / gq);
-    // Few (sequence, head group) pairs: cut contexts finer so that the chip still has work everywhere.
-    const int chunk = a->chunk > 0 ? a->chunk
-                      : mfma     ? 128  // one wave per item: short items keep every SIMD busy
-                      : (int64_t)n * per_seq >= 2048 ? 1024 : (int64_t)n * per_seq >= 512 ? 512 : 256;
+    args.n = c.n;
+    args.H = row_heads;
+    args.Hq = q_heads;
     args.chunk = chunk;
     args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
-    // scratch: [partial sums][partial (max, sum)], one partial per (sequence, chunk, query head)
-    const size_t n_part = (size_t)n * args.max_chunks * Hq;
-    const size_t acc_bytes = n_part * D * sizeof(float);
-    const int src = ensure_scratch(a, acc_bytes + n_part * sizeof(float2));
-    if (src != S3_OK) return src;
-    args.part_acc = (float *)a->scratch;
-    args.part_ml = (float2 *)((char *)a->scratch + acc_bytes);
-    args.ncls = a->ncls > 0 ? a->ncls : n <= 128 ? 4 : n <= 256 ? 2 : 1;
-    const size_t dyn_lds = (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)args.ncls * (n + 1) * 4;
-    const int cus = a->num_cus > 0 ? a->num_cus : 256;
-    int blocks = a->grid_blocks;
-    if (blocks <= 0) {  // the workgroups that are resident at once walk the work list with a stride
-        int per_cu = 0;
-        const int orc = resident_per_cu((const void *)fn, threads, dyn_lds, &per_cu);
-        if (orc != S3_OK) return orc;
-        blocks = cus * per_cu;
+    // length classes of the longest-first work order: small batches gain from it (their kernels are
+    // short, the tail matters); for large batches the extra prologue work per class costs more than
+    // the order gains.  Measured on MI355X.
+    args.ncls = a->ncls > 0 ? a->ncls : c.n <= 128 ? 4 : c.n <= 256 ? 2 : 1;
+    args.out_dtype = c.out_dtype;
+    args.max_len = a->cfg.max_len;
+    args.len_add = c.with_append ? 1 : 0;
+    const float scale = c.scale > 0.f ? c.scale : 1.0f / sqrtf((float)a->cfg.head_dim);
+    args.scale_log2e = scale * 1.4426950408889634f;
+    args.len_out = c.with_append ? c.len_out : nullptr;
+    return args;
+}
+
+// Library scratch: [arrival counters: cnt_bytes, fixed per arena kind, zero between launches]
+// [partial sums][partial (max, sum)], one partial per (sequence, chunk, head of q).
+static int place_scratch(s3_arena *a, AttnArgs &args, size_t cnt_bytes) {
+    const size_t n_part = (size_t)args.n * args.max_chunks * args.Hq;
+    const size_t acc_bytes = n_part * a->cfg.head_dim * sizeof(float);
+    const int rc = ensure_scratch(a, cnt_bytes + acc_bytes + n_part * sizeof(float2));
+    if (rc != S3_OK) return rc;
+    args.arrivals = (unsigned int *)a->scratch;
+    args.part_acc = (float *)((char *)a->scratch + cnt_bytes);
+    args.part_ml = (float2 *)((char *)a->scratch + cnt_bytes + acc_bytes);
+    return S3_OK;
+}
+
+static size_t batch_view_lds(int n, int ncls) {
+    return (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)ncls * (n + 1) * 4;
+}
+
+// Grid of a kernel that walks the work list with a stride: the workgroups that are resident at once
+// (every workgroup pays the batch-view prologue once), times `rounds`; or what the caller set.
+static int stride_grid(const s3_arena *a, const void *fn, int threads, size_t dyn_lds, int rounds, int *blocks) {
+    if (a->grid_blocks > 0) {
+        *blocks = a->grid_blocks;
+        return S3_OK;
     }
+    int per_cu = 0;
+    const int rc = resident_per_cu(fn, threads, dyn_lds, &per_cu);
+    if (rc != S3_OK) return rc;
+    *blocks = (a->num_cus > 0 ? a->num_cus : 256) * per_cu * rounds;
+    return S3_OK;
+}
+
+// Launch the attention kernel and, if merge_heads > 0, attn_merge_kernel over that many heads of q / out
+// (it finishes multi-chunk contexts and writes the zero rows of empty ones).  Every k-th call (the
+// "profile" parameter) is bracketed with events: before, after the attention kernel, after the merge.
+static int launch_attn_kernels(s3_arena *a, attn_fn fn, int blocks, int threads, size_t dyn_lds, void *stream,
+                               const AttnArgs &args, int merge_heads) {
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
     const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
     if (timed) {
@@ -754,10 +773,12 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)threads), dyn_lds, (hipStream_t)stream, args);
     HIP_TRY(hipGetLastError());
     if (timed) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
-    {  // the merge (and the zero rows of empty contexts) index partials and output by query head
+    if (merge_heads > 0) {
+        const int D = a->cfg.head_dim;
         AttnArgs margs = args;
-        margs.H = Hq;
-        const unsigned mblocks = (unsigned)(((int64_t)n * ((Hq + GH - 1) / GH) + 3) / 4);
+        margs.H = merge_heads;  // the merge kernel indexes partials and output by head of q, 512/D heads per wave
+        const int GH = 512 / D;
+        const unsigned mblocks = (unsigned)(((int64_t)args.n * ((merge_heads + GH - 1) / GH) + 3) / 4);
         void (*mfn)(const AttnArgs) =
             D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
         hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, margs);
@@ -767,175 +788,85 @@ static int launch_gqa(s3_arena *a, int32_t layer, int32_t n, const void *q, cons
     return S3_OK;
 }
 
+// Shared key/value heads.  Vector-ALU kernel: append as its own launch, attention, merge.  Matrix-core
+// kernel: attention (which appends the new row itself), merge.
+static int launch_gqa(s3_arena *a, const AttnCall &c) {
+    const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
+    const int group = Hq / Hkv;
+    const int gq = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
+    // Variant indices of a shared-K/V arena: the shapes of the vector-ALU kernel, then the matrix-core kernel.
+    const bool mfma = s3i_kernel_kind(a) == 2;
+    int threads = 256;
+    attn_fn fn = mfma ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D) : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
+    if (!fn) return S3_ERR_INVALID;
+    if (c.with_append && !mfma) {
+        const int arc = launch_append(a, c.layer, c.n, c.slot_off, c.len_or_pos, c.k_new, c.v_new, c.stream);
+        if (arc != S3_OK) return arc;
+    }
+    const int GH = 512 / D;
+    // work items per chunk: (K/V head groups x query sub-blocks), or for the matrix-core kernel
+    // (K/V heads x blocks of 16 query heads), there one item per wave
+    const int per_seq = mfma ? Hkv * ((group + 15) / 16) : ((Hkv + GH - 1) / GH) * (group / gq);
+    // Few (sequence, head group) pairs: cut contexts finer so that the chip still has work everywhere.
+    const int chunk = a->chunk > 0 ? a->chunk
+                      : mfma     ? 128  // one wave per item: short items keep every SIMD busy
+                      : (int64_t)c.n * per_seq >= 2048 ? 1024 : (int64_t)c.n * per_seq >= 512 ? 512 : 256;
+    AttnArgs args = common_args(a, c, Hkv, Hq, chunk);
+    int rc = place_scratch(a, args, 0);
+    if (rc != S3_OK) return rc;
+    const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
+    int blocks = 0;
+    rc = stride_grid(a, (const void *)fn, threads, dyn_lds, 1, &blocks);
+    if (rc != S3_OK) return rc;
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, Hq);
+}
+
 // 8-bit cache rows: quantising append (own launch), attention over the codes, merge of chunk partials.
-static int launch_fp8(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
-                      const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
-                      bool with_append, const void *k_new, const void *v_new, int32_t *len_out) {
+static int launch_fp8(s3_arena *a, const AttnCall &c) {
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     int threads = 0;
     attn_fn fn = s3i_pick_fp8(a->cfg.act_dtype, D, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;
-    if (with_append) {
-        const int arc = launch_append(a, layer, n, slot_off, len_or_pos, k_new, v_new, stream);
+    if (c.with_append) {
+        const int arc = launch_append(a, c.layer, c.n, c.slot_off, c.len_or_pos, c.k_new, c.v_new, c.stream);
         if (arc != S3_OK) return arc;
     }
-    AttnArgs args;
-    memset(&args, 0, sizeof(args));
-    args.kplane = a->plane(layer, 0);
-    args.vplane = a->plane(layer, 1);
-    args.q = (const char *)q;
-    args.slot_off = slot_off;
-    args.cur_len = len_or_pos;
-    args.out = out;
-    args.n_tokens = a->n_tokens;
-    args.n = n;
-    args.H = H;
-    args.Hq = H;
-    args.out_dtype = out_dtype;
-    args.max_len = a->cfg.max_len;
-    args.len_add = with_append ? 1 : 0;
-    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
-    args.scale_log2e = scale * 1.4426950408889634f;
-    args.len_out = with_append ? len_out : nullptr;
-    const int GH = 1024 / D;  // heads per 128-bit wave load of one-byte elements
-    const int n_hg = (H + GH - 1) / GH;
-    const int chunk = a->chunk > 0 ? a->chunk : 1024;
-    args.chunk = chunk;
-    args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
-    const size_t n_part = (size_t)n * args.max_chunks * H;
-    const size_t acc_bytes = n_part * D * sizeof(float);
-    const int src = ensure_scratch(a, acc_bytes + n_part * sizeof(float2));
-    if (src != S3_OK) return src;
-    args.part_acc = (float *)a->scratch;
-    args.part_ml = (float2 *)((char *)a->scratch + acc_bytes);
-    args.ncls = a->ncls > 0 ? a->ncls : n <= 128 ? 4 : n <= 256 ? 2 : 1;
-    const size_t dyn_lds = (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)args.ncls * (n + 1) * 4;
-    const int cus = a->num_cus > 0 ? a->num_cus : 256;
-    int blocks = a->grid_blocks;
-    if (blocks <= 0) {
-        int per_cu = 0;
-        const int orc = resident_per_cu((const void *)fn, threads, dyn_lds, &per_cu);
-        if (orc != S3_OK) return orc;
-        blocks = cus * per_cu * (n > 128 ? 2 : 1);
-    }
-    (void)n_hg;
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
-    const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
-    if (timed) {
-        for (int i = 0; i < 3; i++) {
-            const int prc = prof_next_event(a, &ev[i]);
-            if (prc != S3_OK) return prc;
-        }
-        HIP_TRY(hipEventRecord(ev[0], (hipStream_t)stream));
-    }
-    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)threads), dyn_lds, (hipStream_t)stream, args);
-    HIP_TRY(hipGetLastError());
-    if (timed) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
-    {
-        const int MGH = 512 / D;  // the merge kernel's own head grouping (8 fp32 elements per lane)
-        const unsigned mblocks = (unsigned)(((int64_t)n * ((H + MGH - 1) / MGH) + 3) / 4);
-        void (*mfn)(const AttnArgs) =
-            D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
-        hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, args);
-        HIP_TRY(hipGetLastError());
-    }
-    if (timed) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
-    return S3_OK;
+    AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
+    int rc = place_scratch(a, args, 0);
+    if (rc != S3_OK) return rc;
+    const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
+    int blocks = 0;
+    rc = stride_grid(a, (const void *)fn, threads, dyn_lds, c.n > 128 ? 2 : 1, &blocks);
+    if (rc != S3_OK) return rc;
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, H);
 }
 
-// Shared by s3_decode_attention (fused = false: partial kernel + merge kernel) and s3_decode_step
-// (fused = true: one kernel that also appends, merges and publishes the new lengths).
-static int launch_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
-                            const int32_t *len_or_pos, void *out, int32_t out_dtype, float scale, void *stream,
-                            bool fused, const void *k_new, const void *v_new, int32_t *len_out) {
-    if (a->cfg.kv_dtype == S3_E4M3)
-        return launch_fp8(a, layer, n, q, slot_off, len_or_pos, out, out_dtype, scale, stream, fused, k_new, v_new,
-                          len_out);
-    if (a->cfg.n_kv_heads < a->cfg.n_heads)
-        return launch_gqa(a, layer, n, q, slot_off, len_or_pos, out, out_dtype, scale, stream, fused, k_new, v_new,
-                          len_out);
+// Shared by s3_decode_attention (partial kernel + merge kernel) and s3_decode_step (with_append: one
+// kernel that also appends, merges and publishes the new lengths).
+static int launch_attention(s3_arena *a, const AttnCall &c) {
+    if (a->cfg.kv_dtype == S3_E4M3) return launch_fp8(a, c);
+    if (a->cfg.n_kv_heads < a->cfg.n_heads) return launch_gqa(a, c);
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     // Defaults from sweeps on MI355X: large chunks keep most contexts in one piece (no cross-workgroup
     // merge), eight waves share an item's rows evenly.
     const int variant = a->variant >= 0 ? a->variant : 1;
     const Variant &vr = kVariants[variant];
-    const int chunk = a->chunk > 0 ? a->chunk : 1024;
+    const bool fused = c.with_append;
     attn_fn fn = fused ? pick_kernel<true>(a->cfg.kv_dtype, D, variant) : pick_kernel<false>(a->cfg.kv_dtype, D, variant);
     if (!fn) return S3_ERR_INVALID;
     const int GH = 512 / D;
     const int n_hg = (H + GH - 1) / GH;
-
-    AttnArgs args;
-    args.kplane = a->plane(layer, 0);
-    args.vplane = a->plane(layer, 1);
-    args.q = (const char *)q;
-    args.slot_off = slot_off;
-    args.cur_len = len_or_pos;
-    args.out = out;
-    args.n_tokens = a->n_tokens;
-    args.n = n;
-    args.H = H;
-    args.Hq = H;
-    args.chunk = chunk;
-    args.max_chunks = (a->cfg.max_len + chunk - 1) / chunk;
-    // length classes of the longest-first work order: small batches gain from it (their kernels are
-    // short, the tail matters); for large batches the extra prologue work per class costs more than
-    // the order gains.  Measured on MI355X.
-    args.ncls = a->ncls > 0 ? a->ncls : n <= 128 ? 4 : n <= 256 ? 2 : 1;
-    args.out_dtype = out_dtype;
-    args.max_len = a->cfg.max_len;
-    args.len_add = fused ? 1 : 0;
-    if (!(scale > 0.f)) scale = 1.0f / sqrtf((float)D);
-    args.scale_log2e = scale * 1.4426950408889634f;
-    args.k_new = (const char *)k_new;
-    args.v_new = (const char *)v_new;
-    args.len_out = len_out;
-
-    // scratch: [arrival counters, fixed size][partial sums][partial (max, sum)]
+    AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
+    args.len_out = c.len_out;
     const size_t cnt_bytes = (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;
-    const size_t n_part = (size_t)n * args.max_chunks * H;
-    const size_t acc_bytes = n_part * D * sizeof(float);
-    const size_t need = cnt_bytes + acc_bytes + n_part * sizeof(float2);
-    const int rc = ensure_scratch(a, need);
+    int rc = place_scratch(a, args, cnt_bytes);
     if (rc != S3_OK) return rc;
-    args.arrivals = (unsigned int *)a->scratch;
-    args.part_acc = (float *)((char *)a->scratch + cnt_bytes);
-    args.part_ml = (float2 *)((char *)a->scratch + cnt_bytes + acc_bytes);
-
-    const int nw = vr.ts * vr.hs + (fused ? 1 : 0);  // the fused kernel adds an epilogue wave
-    const int cus = a->num_cus > 0 ? a->num_cus : 256;
-    const size_t dyn_lds = (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)args.ncls * (n + 1) * 4;
-    // Grid: exactly the workgroups that are resident at once (every workgroup pays the batch-view
-    // prologue once and then walks the work list with a stride).  Asked from the runtime once per
-    // kernel and LDS size class.
-    int blocks = a->grid_blocks;
-    if (blocks <= 0) {
-        int per_cu = 0;
-        const int orc = resident_per_cu((const void *)fn, nw * 64, dyn_lds, &per_cu);
-        if (orc != S3_OK) return orc;
-        blocks = cus * per_cu * (n > 128 ? 2 : 1);  // large batches: two rounds balance better than one
-    }
-    hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
-    const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
-    if (timed) {
-        for (int i = 0; i < 3; i++) {
-            const int prc = prof_next_event(a, &ev[i]);
-            if (prc != S3_OK) return prc;
-        }
-        HIP_TRY(hipEventRecord(ev[0], (hipStream_t)stream));
-    }
-    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)(nw * 64)), dyn_lds, (hipStream_t)stream, args);
-    HIP_TRY(hipGetLastError());
-    if (timed) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
-    if (!fused) {
-        const unsigned mblocks = (unsigned)(((int64_t)n * n_hg + 3) / 4);
-        void (*mfn)(const AttnArgs) =
-            D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
-        hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, args);
-        HIP_TRY(hipGetLastError());
-    }
-    if (timed) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
-    return S3_OK;
+    const int threads = (vr.ts * vr.hs + (fused ? 1 : 0)) * 64;  // the fused kernel adds an epilogue wave
+    const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
+    int blocks = 0;
+    rc = stride_grid(a, (const void *)fn, threads, dyn_lds, c.n > 128 ? 2 : 1, &blocks);  // large batches: two rounds balance better
+    if (rc != S3_OK) return rc;
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, fused ? 0 : H);
 }
 
 extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
@@ -944,8 +875,8 @@ extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const 
     if (n == 0) return S3_OK;
     if (!q || !slot_off || !cur_len || !out || !aligned16(q) || !aligned16(out)) return S3_ERR_INVALID;
     if (out_dtype != S3_F32 && out_dtype != S3_F16 && out_dtype != S3_BF16) return S3_ERR_INVALID;
-    return launch_attention(a, layer, n, q, slot_off, cur_len, out, out_dtype, scale, stream, false, nullptr, nullptr,
-                            nullptr);
+    const AttnCall c = {layer, n, q, slot_off, cur_len, out, out_dtype, scale, stream, false, nullptr, nullptr, nullptr};
+    return launch_attention(a, c);
 }
 
 extern "C" int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
@@ -960,7 +891,8 @@ extern "C" int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32
     if (out_dtype != S3_F32 && out_dtype != S3_F16 && out_dtype != S3_BF16) return S3_ERR_INVALID;
     const int rc = check_slots_host(a, n, slot_id, pos_host);
     if (rc != S3_OK) return rc;
-    return launch_attention(a, layer, n, q, slot_off, pos, out, out_dtype, scale, stream, true, k_new, v_new, len_out);
+    const AttnCall c = {layer, n, q, slot_off, pos, out, out_dtype, scale, stream, true, k_new, v_new, len_out};
+    return launch_attention(a, c);
 }
 
 extern "C" int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t first_row, int32_t n_rows,
