@@ -36,10 +36,12 @@ def predicted_total(policy, prompt, output, max_len, seed, accuracy=0.9861, buck
 
 
 def serve(policy, n_requests=4000, arena_bytes=68 * 10**9, n_layers=28, n_heads=16, head_dim=256, granule=64,
-          max_len=2048, seed=0):
+          max_len=2048, seed=0, n_kv_heads=0, kv_dtype=s3.S3_F16):
     """-> dict(avg_batch, iterations, grows, evictions, tokens).  One token per active sequence per
-    iteration; the pool is offered to the scheduler at every iteration."""
-    cfg = s3.make_config(n_layers, n_heads, head_dim, s3.S3_F16, granule, max_len)
+    iteration; the pool is offered to the scheduler at every iteration.  n_kv_heads / kv_dtype select
+    the cache-footprint variants the paper's related-work section calls complementary (shared key/value
+    heads, 8-bit rows): fewer bytes per token, so the same memory holds a larger batch."""
+    cfg = s3.make_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_heads, s3.S3_F16)
     st, arena = s3.s3_kv_arena_init(cfg, None, arena_bytes)
     s3.check(st, "s3_kv_arena_init")
     st, sched = s3.s3_sched_create(arena)
@@ -94,3 +96,5 @@ def serve(policy, n_requests=4000, arena_bytes=68 * 10**9, n_layers=28, n_heads=
 if __name__ == "__main__":
     for pol in ("max", "predicted", "perfect"):
         print(serve(pol))
+    print("8-bit rows:", serve("predicted", kv_dtype=s3.S3_E4M3))
+    print("4 cached heads for 16 query heads:", serve("predicted", n_kv_heads=4))

@@ -108,3 +108,21 @@ def test_serving_simulation_shape():
     assert res["perfect"]["avg_batch"] >= res["predicted"]["avg_batch"]
     assert res["predicted"]["iterations"] * 3 < res["max"]["iterations"]
     assert res["max"]["grows"] == res["perfect"]["grows"] == 0
+
+
+def test_serving_simulation_with_smaller_cache_footprints():
+    """The complementary techniques of the paper's related-work section shrink bytes per token, so the
+    same memory sustains a proportionally larger batch under the same prediction-sized reservation:
+    8-bit rows about twice, four cached heads for sixteen query heads more (until the pool runs dry)."""
+    from paper_2306_06000_amd import binding as s3
+    from paper_2306_06000_amd.simulate import serve
+
+    kw = dict(n_requests=2500, arena_bytes=16 * 10**9, seed=2)
+    base = serve("predicted", **kw)
+    eight = serve("predicted", kv_dtype=s3.S3_E4M3, **kw)
+    shared = serve("predicted", n_kv_heads=4, **kw)
+    for r in (base, eight, shared):
+        assert r["batch_sum"] == r["tokens"]
+    assert 1.8 < eight["avg_batch"] / base["avg_batch"] < 2.1
+    assert shared["avg_batch"] > 2.5 * base["avg_batch"]
+    assert eight["iterations"] < 0.56 * base["iterations"] and shared["iterations"] < eight["iterations"]
