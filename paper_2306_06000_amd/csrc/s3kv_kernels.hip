@@ -393,8 +393,8 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
 // drop (max, sum, weighted sum) into one of two LDS buffers and move on to the next item after a
 // single barrier.  The epilogue wave merges the splits, writes the output or the chunk partial,
 // announces the chunk on the context's arrival counter and, if it delivered the last chunk, merges
-// the chunks; all its memory latencies overlap with the compute waves' next item.  Workgroup 0
-// also publishes len_out and the zero rows of empty contexts.
+// the chunks; all its memory latencies overlap with the compute waves' next item.  len_out and the
+// zero rows of empty contexts are published by the workgroups in turn.
 template <int DT, int D, int TS, int HS, int U, bool NT, bool PF>
 __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const AttnArgs a) {
     constexpr int LPH = D / 8;
@@ -412,17 +412,15 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
     const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
     const int64_t total = (int64_t)bv.total * n_hgb;
 
-    if (blockIdx.x == 0) {
-        const int nthreads = (NWC + 1) * 64;
-        if (a.len_out)
-            for (int b = threadIdx.x; b < a.n; b += nthreads) a.len_out[b] = a.cur_len[b] + 1;
-        const int per_row = a.H * D / 8;  // empty or refused contexts get a zero output row
-        for (int64_t e = threadIdx.x; e < (int64_t)a.n * per_row; e += nthreads) {
-            const int b = (int)(e / per_row);
-            if (bv.len[b] == 0) {
-                const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-                store_out8(a.out, a.out_dtype, e * 8, z);
-            }
+    // Housekeeping that belongs to no item, spread over the workgroups (sequence b goes to workgroup
+    // b mod grid) so that none of them starts its first item late: the new lengths, and a zero output
+    // row for empty or refused contexts.
+    for (int b = blockIdx.x; b < a.n; b += gridDim.x) {
+        if (a.len_out && threadIdx.x == 0) a.len_out[b] = a.cur_len[b] + 1;
+        if (bv.len[b] == 0) {
+            const int per_row = a.H * D / 8;
+            const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int e = threadIdx.x; e < per_row; e += (NWC + 1) * 64) store_out8(a.out, a.out_dtype, ((int64_t)b * per_row + e) * 8, z);
         }
     }
 
