@@ -364,22 +364,34 @@ __device__ __forceinline__ void split_rows(const Item &it, int ts, int TS, int &
     j1 = min(end, j0 + per);
 }
 
+// Work-list position -> item.  Called by whole waves (every lane with the same `item`): the class
+// totals are read by the first lanes at once and the sequence is found by counting, lanes in parallel,
+// the entries whose inclusive prefix does not exceed the position (the prefix sums are non-decreasing,
+// so that count is the first sequence whose range holds it): three dependent LDS round trips
+// instead of a serial class walk plus a binary search.
 __device__ __forceinline__ Item decode_item(const AttnArgs &a, const BatchView &v, int64_t item, int n_hgb) {
     Item it;
+    const int lane = threadIdx.x & 63;
     int w = (int)(item / n_hgb);
     it.hgb = (int)(item - (int64_t)w * n_hgb);
-    const int *pre = v.pre;
+    const int tot = lane < v.ncls ? v.pre[lane * (v.n + 1) + v.n] : 0;
+    int cls = v.ncls - 1;
     for (int c = 0; c < v.ncls - 1; c++) {  // which class the item falls into
-        const int t = pre[v.n];
-        if (w < t) break;
+        const int t = __builtin_amdgcn_readlane(tot, c);
+        if (w < t) {
+            cls = c;
+            break;
+        }
         w -= t;
-        pre += v.n + 1;
     }
-    int lo = 0, hi = v.n - 1;
-    while (lo < hi) {  // first b with pre[b+1] > w
-        const int mid = (lo + hi) >> 1;
-        if (pre[mid + 1] > w) hi = mid; else lo = mid + 1;
+    const int *pre = v.pre + cls * (v.n + 1);
+    int lo = 0;
+    for (int base = 0; base < v.n; base += 64) {
+        const int b = base + lane;
+        const bool below = b < v.n && pre[b + 1] <= w;
+        lo += __builtin_popcountll(__builtin_amdgcn_ballot_w64(below));
     }
+    lo = min(lo, v.n - 1);  // a consistent view never needs this
     it.b = lo;
     it.c = w - pre[lo];
     it.nchunks = pre[lo + 1] - pre[lo];
