@@ -125,3 +125,19 @@ def test_c3_full_200GB_arena_28_layers_sampled():
             for which, ref in ((0, Ks[j]), (1, Vs[j])):
                 assert np.array_equal(eng.read_slot(a, layer, which, a.len + 1), ref)
     eng.close()
+
+
+def test_c5_shared_heads_at_the_benchmarked_batch():
+    """C5 as bench.py times it (batch 256, 32 query / 8 cached heads, matrix-core kernel by default)."""
+    w = wl.c5()
+    assert w.batch == 256
+    grows, frees = full_trace(w, 64, attend_steps=[0, 33, 63], sample_rows=16)
+    assert frees >= 10
+
+
+def test_c6_8_bit_rows_at_the_benchmarked_batch():
+    """C6 as bench.py times it (batch 128, e4m3 rows, fp16 queries)."""
+    w = wl.c6()
+    assert w.batch == 128
+    grows, frees = full_trace(w, 64, attend_steps=[0, 33, 63], sample_rows=16)
+    assert frees >= 5
