@@ -195,6 +195,56 @@ __device__ __forceinline__ BatchView build_batch_view(const AttnArgs &a, char *d
     int64_t *off_s = (int64_t *)dyn;
     int *len_s = (int *)(dyn + (size_t)n * 8);
     int *pre = len_s + ((n + 1) & ~1);
+    constexpr int EMAX = 8;  // entries per lane of the one-wave build
+    if (n <= 64 * EMAX) {
+        // Batches of up to 512 sequences: wave 0 builds the whole view by itself (lane l takes entries
+        // l*E .. l*E+E-1; a serial prefix inside the lane, one DPP scan across lanes per class) and the
+        // workgroup meets at ONE barrier.  The general path below needs four barriers and LDS round trips
+        // between them, which cost every workgroup of a small launch about 1.5 us before its first load.
+        if (wave == 0) {
+            const int E = (n + 63) >> 6;
+            int len[EMAX];
+            int mx = 0;
+#pragma unroll
+            for (int e = 0; e < EMAX; e++) {
+                const int b = lane * E + e;
+                len[e] = 0;
+                if (e < E && b < n) {
+                    len[e] = checked_len(a, b);
+                    len_s[b] = len[e];
+                    off_s[b] = a.slot_off[b];
+                }
+                mx = max(mx, len[e]);
+            }
+#pragma unroll
+            for (int d = 32; d >= 1; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
+            for (int c = 0; c < ncls; c++) {
+                int loc[EMAX], lsum = 0;
+#pragma unroll
+                for (int e = 0; e < EMAX; e++) {
+                    loc[e] = lsum;
+                    if (class_of(len[e], mx, ncls) == c) lsum += (len[e] + chunk - 1) / chunk;
+                }
+                const int incl = wave_inclusive_scan(lsum);
+#pragma unroll
+                for (int e = 0; e < EMAX; e++) {
+                    const int b = lane * E + e;
+                    if (e < E && b < n) pre[c * (n + 1) + b] = incl - lsum + loc[e];
+                }
+                if (lane == 63) pre[c * (n + 1) + n] = incl;
+            }
+        }
+        __syncthreads();
+        BatchView v;
+        v.off = off_s;
+        v.len = len_s;
+        v.pre = pre;
+        v.n = n;
+        v.ncls = ncls;
+        v.total = 0;
+        for (int c = 0; c < ncls; c++) v.total += pre[c * (n + 1) + n];
+        return v;
+    }
     const int per = (n + nthreads - 1) / nthreads;
     const int b0 = min(n, tid * per), b1 = min(n, b0 + per);
     int mx = 0;
