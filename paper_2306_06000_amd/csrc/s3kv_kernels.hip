@@ -21,6 +21,8 @@
 #include <stdint.h>
 #include <string.h>
 
+#include <mutex>
+
 #include "s3kv_internal.h"
 
 #include "s3kv_device.h"
@@ -662,6 +664,8 @@ static int check_slots_host(const s3_arena *a, int32_t n, const int32_t *slot_id
 // from the runtime once per kernel and LDS size class (4 KiB steps).
 static int resident_per_cu(const void *fn, int threads, size_t dyn_lds, int *per_cu) {
     static std::map<std::pair<const void *, size_t>, int> resident;  // (kernel, LDS in 4 KiB) -> workgroups per CU
+    static std::mutex guard;  // shared by all arenas, which may live on different threads
+    std::lock_guard<std::mutex> lock(guard);
     const std::pair<const void *, size_t> key(fn, (dyn_lds + 4095) / 4096);
     auto it = resident.find(key);
     if (it == resident.end()) {
