@@ -38,6 +38,7 @@ def parse():
                     help="bracket every k-th attention launch with HIP events (each bracket costs a few us)")
     ap.add_argument("--c3-bytes", type=float, default=200e9)
     ap.add_argument("--heads", type=str, default="", help="c5 only: query heads, kv heads, head dim as Q,KV,D")
+    ap.add_argument("--kv8", action="store_true", help="c5 only: e4m3 cache rows (bf16 queries) on top of the shared heads")
     ap.add_argument("--batch", type=int, default=0, help="override the workload's batch size (not c3); the "
                     "default is the configuration the metric is quoted on")
     ap.add_argument("--unfused", action="store_true", help="append + attention + merge kernels instead of one")
@@ -165,6 +166,8 @@ def main():
     if args.heads and args.workload == "c5":
         hq, hkv, hd = (int(x) for x in args.heads.split(","))
         kw.update(n_heads=hq, n_kv_heads=hkv, head_dim=hd)
+    if args.kv8 and args.workload == "c5":
+        kw.update(dtype=wl.E4M3)
     w = {"c1": wl.c1, "c2": wl.c2, "c4": wl.c4, "c5": wl.c5, "c6": wl.c6}[args.workload](**kw) if args.workload != "c3" else wl.c3(
         target_bytes=int(args.c3_bytes))
     if args.drain:
@@ -219,7 +222,7 @@ def main():
         "metric": "decode-attention achieved HBM GB/s", "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": {0: "f16", 1: "bf16", 3: "e4m3 rows, f16 queries, f32 arithmetic"}[w.dtype], "data": "synthetic",
+        "dtype": {0: "f16", 1: "bf16", 3: "e4m3 rows, 16-bit queries, f32 arithmetic"}[w.dtype], "data": "synthetic",
         "pct_of_peak_hbm": round(100 * total_bytes / dt / 1e9 / PEAK_HBM_GBPS, 2),
         "seq_steps_per_s": round(seq_steps / dt, 1),
         "host_enqueue_ms_per_step": round(t_enqueue / args.steps * 1e3, 5),
@@ -230,7 +233,8 @@ def main():
                    "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
                    "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
-                   "path": "append kernel + shared-kv attention kernel per layer" if shared_kv else
+                   "path": "quantising append + shared-kv matrix-core attention over 8-bit rows + merge per layer" if shared_kv and w.dtype == 3 else
+                           "shared-kv attention kernel (+ append launch for the vector-ALU kernel) + merge per layer" if shared_kv else
                            "quantising append kernel + attention kernel over 8-bit rows + merge per layer" if w.dtype == 3 else
                            "append+attention+merge kernels" if args.unfused else "one s3_decode_step kernel per layer",
                    "variant": s3.s3_kv_get_param(eng.arena, "variant")[1],
@@ -246,7 +250,7 @@ def main():
         avg_us = part_ns / max(launches, 1) / 1e3
         achieved = per_launch_bytes / (avg_us * 1e-6) / 1e9 if avg_us > 0 else 0.0
         kind = s3.s3_kv_get_param(eng.arena, "kernel_kind")[1]
-        kernel = {1: "attn_gqa_kernel", 2: "attn_gqa_mfma_kernel", 3: "attn_fp8_kernel"}.get(
+        kernel = {1: "attn_gqa_kernel", 2: "attn_gqa_mfma_kernel", 3: "attn_fp8_kernel", 4: "attn_gqa_mfma_kernel"}.get(
             kind, "attn_partial_kernel" if args.unfused else "attn_step_kernel")
         res["roofline"] = {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1),
                            "peak": PEAK_HBM_GBPS, "unit": "GB/s", "frac": round(achieved / PEAK_HBM_GBPS, 4),

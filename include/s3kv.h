@@ -73,8 +73,8 @@ typedef struct {
     int32_t act_dtype; /* kv_dtype == S3_E4M3 only: type of q, k_new, v_new, S3_F16 or S3_BF16 (append
                           rounds a new row to the nearest e4m3 code, ties to even, saturating at
                           +-448, NaN -> 0x7f; attention widens the codes exactly).  Ignored for 16-bit
-                          caches.  8-bit caches need n_kv_heads == n_heads; s3_kv_fill and
-                          s3_kv_read_rows move codes (one byte per element).              */
+                          caches.  s3_kv_fill and s3_kv_read_rows move codes (one byte per
+                          element).                                                       */
 } s3_kv_config;
 
 /* KV-cache bytes one token occupies: 2 * n_layers * n_kv_heads * head_dim * sizeof(element)
@@ -255,7 +255,8 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *   "profile"      k > 0: bracket every k-th attention launch (counted from this call) with HIP events
  *                  on its stream; 0: off; both reset the sums
  * get names: the above plus "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,
- * 2 shared-K/V matrix-core kernel, 3 kernel for 8-bit rows: what the next attention launch uses), "n_variants", "n_grows",
+ * 2 shared-K/V matrix-core kernel, 3 kernel for 8-bit rows, 4 matrix-core kernel over 8-bit rows with
+ * shared heads: what the next attention launch uses), "n_variants", "n_grows",
  * "live_slots", "scratch_bytes", "num_cus" and,
  * after "profile" k, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
  * timed launches since the last reset) and "profile_p10_ns", "profile_p50_ns", "profile_p90_ns"

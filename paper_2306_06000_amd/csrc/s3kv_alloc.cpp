@@ -42,10 +42,7 @@ static bool config_ok(const s3_kv_config *c) {
     if (c->n_layers <= 0 || c->n_heads <= 0) return false;
     if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
     if (c->kv_dtype != S3_F16 && c->kv_dtype != S3_BF16 && c->kv_dtype != S3_E4M3) return false;
-    if (c->kv_dtype == S3_E4M3) {  // 8-bit rows: 16-bit activations, one cached head per query head
-        if (c->act_dtype != S3_F16 && c->act_dtype != S3_BF16) return false;
-        if (c->n_kv_heads != 0 && c->n_kv_heads != c->n_heads) return false;
-    }
+    if (c->kv_dtype == S3_E4M3 && c->act_dtype != S3_F16 && c->act_dtype != S3_BF16) return false;  // 16-bit activations
     if (c->granule <= 0 || c->max_len <= 0 || c->max_len % c->granule != 0) return false;
     if (c->n_kv_heads < 0 || (c->n_kv_heads > 0 && (c->n_kv_heads > c->n_heads || c->n_heads % c->n_kv_heads))) return false;
     return true;
@@ -276,12 +273,12 @@ extern "C" int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_t
 
 // The attention kernel family an arena uses depends on whether its key/value heads are shared.
 static int s3i_variants_of(const s3_arena *a) {
-    if (a->cfg.kv_dtype == S3_E4M3) return s3i_num_fp8_shapes();
+    if (a->cfg.kv_dtype == S3_E4M3) return a->cfg.n_kv_heads < a->cfg.n_heads ? 1 : s3i_num_fp8_shapes();
     return a->cfg.n_kv_heads < a->cfg.n_heads ? s3i_num_gqa_shapes() + 1 : s3i_num_variants();  // + the matrix-core kernel
 }
 
 int s3i_kernel_kind(const s3_arena *a) {
-    if (a->cfg.kv_dtype == S3_E4M3) return 3;
+    if (a->cfg.kv_dtype == S3_E4M3) return a->cfg.n_kv_heads < a->cfg.n_heads ? 4 : 3;
     if (a->cfg.n_kv_heads >= a->cfg.n_heads) return 0;
     const int group = a->cfg.n_heads / a->cfg.n_kv_heads;
     return (a->variant == s3i_num_gqa_shapes() || (a->variant < 0 && group >= 4)) ? 2 : 1;

@@ -471,3 +471,4 @@ append_fp8_fn s3i_pick_append_fp8(int act);
 // Matrix-core kernel for shared key/value heads (defined in s3kv_gqa_mfma.hip); 256 threads per
 // workgroup, one work item per wave.
 attn_fn s3i_pick_gqa_mfma(int dt, int d);
+attn_fn s3i_pick_gqa_mfma8(int act, int d);  // the same over 8-bit (e4m3) rows, q of type act

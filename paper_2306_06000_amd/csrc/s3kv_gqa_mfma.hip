@@ -84,13 +84,26 @@ __device__ __forceinline__ void store_out4(void *out, int out_dtype, int64_t e, 
     }
 }
 
-template <int DT, int D>
+typedef float f32x2w __attribute__((ext_vector_type(2)));
+
+// Two e4m3 codes (bytes 2*half, 2*half+1 of w) -> one 32-bit word of two DT elements, exact.
+template <int DT>
+__device__ __forceinline__ unsigned widen2_e4m3(const unsigned w, const bool upper) {
+    const f32x2w f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true) : __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
+    return DT == S3_F16 ? pack_f16(f[0], f[1]) : pack_bf16(f[0], f[1]);
+}
+
+// KV8: the cache rows are e4m3 codes (one byte per element) and DT is the type of q; a 16-byte load then
+// holds 16 elements, which are widened (exactly) to DT in registers and feed two contraction steps.
+template <int DT, int D, bool KV8>
 __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
+    constexpr int EB = KV8 ? 1 : 2;       // bytes per cached element
     constexpr int KS = D / 32;            // contraction steps of the score product
+    constexpr int KL = KV8 ? D / 64 : KS; // 16-byte K loads per lane and tile
     constexpr int DB = D / 16;            // 16-element blocks of an output row
-    constexpr int PPR = D / 8;            // 16-byte pieces per cached row of one head
+    constexpr int PPR = D * EB / 16;      // 16-byte pieces per cached row of one head
     constexpr int VL = 16 * PPR / 64;     // 16-byte loads per lane for a 16-row V tile
-    constexpr int VSTRIDE = D * 2 + 8;    // LDS row stride of the V tile, bytes
+    constexpr int VSTRIDE = D * EB + 8;   // LDS row stride of the V tile, bytes
     constexpr float RESCALE_LOG2 = 8.f;   // see the softmax step
     extern __shared__ __align__(16) char dyn_lds[];  // the batch view
     __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
@@ -109,7 +122,7 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
     }
 
     char *vt = vtile[wave];
-    const int64_t rstride = (int64_t)a.H * D * 2;
+    const int64_t rstride = (int64_t)a.H * D * EB;
     const unsigned rs32 = (unsigned)rstride;  // a cached row of all K/V heads: below 2^32 bytes
     for (int64_t item = (int64_t)blockIdx.x * 4 + wave; item < total; item += (int64_t)gridDim.x * 4) {
         const Item it = decode_item(a, bv, item, per_seq);
@@ -122,14 +135,18 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
         u32x4 qop[KS];
 #pragma unroll
         for (int ks = 0; ks < KS; ks++) {
-            qop[ks] = *(const u32x4 *)(a.q + (((int64_t)it.b * a.Hq + hq) * D + ks * 32 + g * 8) * 2);
+            // elements of contraction step ks held by lane group g: the same as the K operand's (a 16-byte K
+            // load of 8-bit rows covers 16 elements = steps 2j and 2j+1 of lane group g)
+            const int e0 = KV8 ? (ks >> 1) * 64 + g * 16 + (ks & 1) * 8 : ks * 32 + g * 8;
+            qop[ks] = *(const u32x4 *)(a.q + (((int64_t)it.b * a.Hq + hq) * D + e0) * 2);
             if (!head_ok) qop[ks] = (u32x4){0u, 0u, 0u, 0u};  // padding columns: zero scores, never stored
         }
-        char *kbase = a.kplane + it.off * rstride + (int64_t)hk * D * 2;
-        char *vbase = a.vplane + it.off * rstride + (int64_t)hk * D * 2;
+        char *kbase = a.kplane + it.off * rstride + (int64_t)hk * D * EB;
+        char *vbase = a.vplane + it.off * rstride + (int64_t)hk * D * EB;
         // Decode step (len_add = 1): row len-1 is still only in k_new / v_new.  Every reader takes it from
         // there; the wave of query block 0 whose chunk holds it also writes it into the arena (the append).
-        const int jnew = a.len_add ? it.len - 1 : -1;
+        // (8-bit rows are quantised by the append kernel before this launch: nothing to take from k_new.)
+        const int jnew = (a.len_add && !KV8) ? it.len - 1 : -1;
         const char *knew = a.k_new + ((int64_t)it.b * a.H + hk) * D * 2;
         const char *vnew = a.v_new + ((int64_t)it.b * a.H + hk) * D * 2;
 
@@ -139,11 +156,11 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
         float m = -INFINITY, lsum = 0.f;
 
         // Loads of one 16-row tile (rows past the chunk's end are clamped to its last row and masked later).
-        auto load_tile = [&](int r0, u32x4 (&kop)[KS], u32x4 (&vv)[VL]) {
+        auto load_tile = [&](int r0, u32x4 (&kop)[KL], u32x4 (&vv)[VL]) {
             const int rk = min(r0 + n, end - 1);
             const char *krow = (rk == jnew ? knew : kbase + (uint64_t)(unsigned)rk * rs32) + g * 16;
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) kop[ks] = load16<false>(krow + ks * 64);
+            for (int ks = 0; ks < KL; ks++) kop[ks] = load16<false>(krow + ks * 64);
 #pragma unroll
             for (int i = 0; i < VL; i++) {
                 const int idx = i * 64 + lane;
@@ -151,11 +168,11 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
                 vv[i] = load16<true>((rv == jnew ? vnew : vbase + (uint64_t)(unsigned)rv * rs32) + (idx % PPR) * 16);
             }
         };
-        auto reduce_tile = [&](int r0, const u32x4 (&kop)[KS], const u32x4 (&vv)[VL]) {
+        auto reduce_tile = [&](int r0, const u32x4 (&kop)[KL], const u32x4 (&vv)[VL]) {
             if (qb == 0 && jnew >= r0 && jnew < r0 + 16 && jnew < end) {  // this tile holds the new row: append it
                 if (r0 + n == jnew) {
 #pragma unroll
-                    for (int ks = 0; ks < KS; ks++)
+                    for (int ks = 0; ks < KL; ks++)
                         *(u32x4 *)(kbase + (uint64_t)(unsigned)jnew * rs32 + g * 16 + ks * 64) = kop[ks];
                 }
 #pragma unroll
@@ -166,7 +183,21 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
             }
             f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-            for (int ks = 0; ks < KS; ks++) s = mfma_scores<DT>(kop[ks], qop[ks], s);
+            for (int ks = 0; ks < KS; ks++) {
+                u32x4 kk;
+                if (KV8) {
+                    const u32x4 raw = kop[ks >> 1];
+#pragma unroll
+                    for (int w = 0; w < 2; w++) {
+                        const unsigned word = raw[(ks & 1) * 2 + w];
+                        kk[2 * w] = widen2_e4m3<DT>(word, false);
+                        kk[2 * w + 1] = widen2_e4m3<DT>(word, true);
+                    }
+                } else {
+                    kk = kop[ks];
+                }
+                s = mfma_scores<DT>(kk, qop[ks], s);
+            }
 
             float sv[4], mt = -INFINITY;
 #pragma unroll
@@ -226,16 +257,24 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
             __builtin_amdgcn_wave_barrier();
 #pragma unroll
             for (int db = 0; db < DB; db++) {
-                const unsigned short *src = (const unsigned short *)(vt + (4 * g) * VSTRIDE) + db * 16 + n;
-                const unsigned v0 = src[0], v1 = src[VSTRIDE / 2], v2 = src[2 * (VSTRIDE / 2)], v3 = src[3 * (VSTRIDE / 2)];
-                const u32x2 vop = (u32x2){v0 | (v1 << 16), v2 | (v3 << 16)};
+                u32x2 vop;
+                if (KV8) {
+                    const unsigned char *src = (const unsigned char *)(vt + (4 * g) * VSTRIDE) + db * 16 + n;
+                    const unsigned b0 = src[0], b1 = src[VSTRIDE], b2 = src[2 * VSTRIDE], b3 = src[3 * VSTRIDE];
+                    const unsigned codes = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
+                    vop = (u32x2){widen2_e4m3<DT>(codes, false), widen2_e4m3<DT>(codes, true)};
+                } else {
+                    const unsigned short *src = (const unsigned short *)(vt + (4 * g) * VSTRIDE) + db * 16 + n;
+                    const unsigned v0 = src[0], v1 = src[VSTRIDE / 2], v2 = src[2 * (VSTRIDE / 2)], v3 = src[3 * (VSTRIDE / 2)];
+                    vop = (u32x2){v0 | (v1 << 16), v2 | (v3 << 16)};
+                }
                 o[db] = mfma_values<DT>(vop, pop, o[db]);
                 if (DT != S3_F16) o[db] = mfma_values<DT>(vop, pop_lo, o[db]);
             }
             __builtin_amdgcn_wave_barrier();
         };
         // Two register sets used alternately: the next tile's loads are in flight while this one is reduced.
-        u32x4 k0[KS], v0[VL], k1[KS], v1[VL];
+        u32x4 k0[KL], v0[VL], k1[KL], v1[VL];
         load_tile(start, k0, v0);
         for (int r0 = start;;) {
             load_tile(r0 + 16, k1, v1);
@@ -268,13 +307,27 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
 
 attn_fn s3i_pick_gqa_mfma(int dt, int d) {
     if (dt == S3_F16) {
-        if (d == 64) return attn_gqa_mfma_kernel<S3_F16, 64>;
-        if (d == 128) return attn_gqa_mfma_kernel<S3_F16, 128>;
-        if (d == 256) return attn_gqa_mfma_kernel<S3_F16, 256>;
+        if (d == 64) return attn_gqa_mfma_kernel<S3_F16, 64, false>;
+        if (d == 128) return attn_gqa_mfma_kernel<S3_F16, 128, false>;
+        if (d == 256) return attn_gqa_mfma_kernel<S3_F16, 256, false>;
     } else {
-        if (d == 64) return attn_gqa_mfma_kernel<S3_BF16, 64>;
-        if (d == 128) return attn_gqa_mfma_kernel<S3_BF16, 128>;
-        if (d == 256) return attn_gqa_mfma_kernel<S3_BF16, 256>;
+        if (d == 64) return attn_gqa_mfma_kernel<S3_BF16, 64, false>;
+        if (d == 128) return attn_gqa_mfma_kernel<S3_BF16, 128, false>;
+        if (d == 256) return attn_gqa_mfma_kernel<S3_BF16, 256, false>;
+    }
+    return nullptr;
+}
+
+// The same kernel over 8-bit (e4m3) rows; act is the type of q.
+attn_fn s3i_pick_gqa_mfma8(int act, int d) {
+    if (act == S3_F16) {
+        if (d == 64) return attn_gqa_mfma_kernel<S3_F16, 64, true>;
+        if (d == 128) return attn_gqa_mfma_kernel<S3_F16, 128, true>;
+        if (d == 256) return attn_gqa_mfma_kernel<S3_F16, 256, true>;
+    } else if (act == S3_BF16) {
+        if (d == 64) return attn_gqa_mfma_kernel<S3_BF16, 64, true>;
+        if (d == 128) return attn_gqa_mfma_kernel<S3_BF16, 128, true>;
+        if (d == 256) return attn_gqa_mfma_kernel<S3_BF16, 256, true>;
     }
     return nullptr;
 }

@@ -69,7 +69,8 @@ int s3i_num_gqa_shapes();  // shapes of the shared-K/V (grouped-query) attention
 int s3i_num_fp8_shapes();  // shapes of the attention kernel for 8-bit cache rows
 // Which attention kernel family the arena's next launch uses: 0 multi-head, 1 shared-K/V on the vector
 // ALU, 2 shared-K/V on the matrix cores (variant index = number of shapes, or the default from four
-// query heads per cached head; measured on MI355X), 3 the kernel for 8-bit cache rows.
+// query heads per cached head; measured on MI355X), 3 the kernel for 8-bit cache rows, 4 the matrix-core
+// kernel over 8-bit rows (shared K/V heads with an 8-bit cache).
 int s3i_kernel_kind(const s3_arena *a);
 int s3i_profile_collect(s3_arena *a);  // synchronises on the recorded events and accumulates the sums
 void s3i_profile_reset(s3_arena *a);

@@ -791,17 +791,21 @@ static int launch_attn_kernels(s3_arena *a, attn_fn fn, int blocks, int threads,
 }
 
 // Shared key/value heads.  Vector-ALU kernel: append as its own launch, attention, merge.  Matrix-core
-// kernel: attention (which appends the new row itself), merge.
+// kernel: attention (which appends the new row itself), merge; over 8-bit rows: quantising append,
+// attention, merge.
 static int launch_gqa(s3_arena *a, const AttnCall &c) {
     const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
     const int group = Hq / Hkv;
     const int gq = group % 8 == 0 ? 8 : group % 4 == 0 ? 4 : group % 2 == 0 ? 2 : 1;
     // Variant indices of a shared-K/V arena: the shapes of the vector-ALU kernel, then the matrix-core kernel.
-    const bool mfma = s3i_kernel_kind(a) == 2;
+    const int kind = s3i_kernel_kind(a);
+    const bool mfma = kind == 2 || kind == 4, eight_bit = kind == 4;
     int threads = 256;
-    attn_fn fn = mfma ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D) : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
+    attn_fn fn = eight_bit ? s3i_pick_gqa_mfma8(a->cfg.act_dtype, D)
+                 : mfma    ? s3i_pick_gqa_mfma(a->cfg.kv_dtype, D)
+                           : s3i_pick_gqa(a->cfg.kv_dtype, D, gq, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;
-    if (c.with_append && !mfma) {
+    if (c.with_append && (!mfma || eight_bit)) {  // 16-bit rows: the matrix-core kernel appends by itself
         const int arc = launch_append(a, c.layer, c.n, c.slot_off, c.len_or_pos, c.k_new, c.v_new, c.stream);
         if (arc != S3_OK) return arc;
     }
@@ -846,8 +850,8 @@ static int launch_fp8(s3_arena *a, const AttnCall &c) {
 // Shared by s3_decode_attention (partial kernel + merge kernel) and s3_decode_step (with_append: one
 // kernel that also appends, merges and publishes the new lengths).
 static int launch_attention(s3_arena *a, const AttnCall &c) {
-    if (a->cfg.kv_dtype == S3_E4M3) return launch_fp8(a, c);
     if (a->cfg.n_kv_heads < a->cfg.n_heads) return launch_gqa(a, c);
+    if (a->cfg.kv_dtype == S3_E4M3) return launch_fp8(a, c);
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     // Defaults from sweeps on MI355X: large chunks keep most contexts in one piece (no cross-workgroup
     // merge), eight waves share an item's rows evenly.

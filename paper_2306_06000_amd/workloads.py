@@ -201,8 +201,10 @@ def c5(batch: int = 256, steps: int = 128, n_heads: int = 32, n_kv_heads: int = 
     on a 32-query-head / 8-KV-head, d = 128 shape, at four times C1's batch (a cache row is a
     quarter of the multi-head one).  Not one of the paper's measured models."""
     base = c1(batch, steps)
-    return Workload(f"C5-shared-kv-{n_heads}q{n_kv_heads}kv", 5, 1, n_heads, head_dim, dtype, base.granule,
-                    base.max_len, batch, steps, base.seqs, base.pool, base.refill, n_kv_heads=n_kv_heads)
+    eight = dtype == E4M3  # both footprint variants at once: 8-bit rows of the shared heads, bf16 queries
+    return Workload(f"C5-shared-kv-{n_heads}q{n_kv_heads}kv" + ("-e4m3" if eight else ""), 5, 1, n_heads, head_dim, dtype,
+                    base.granule, base.max_len, batch, steps, base.seqs, base.pool, base.refill, n_kv_heads=n_kv_heads,
+                    act_dtype=BF16 if eight else -1)
 
 
 def c6(batch: int = 128, steps: int = 128) -> Workload:

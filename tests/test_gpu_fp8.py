@@ -28,18 +28,19 @@ def need_gpu_and_lib():
 class Rig8:
     """A small 8-bit arena with hand-placed sequences, mirrored in the oracle."""
 
-    def __init__(self, n_layers, H, D, act, G, M, preds, seed):
-        self.n_layers, self.H, self.D, self.act = n_layers, H, D, act
-        self.cfg = s3.make_config(n_layers, H, D, s3.S3_E4M3, G, M, 0, act)
+    def __init__(self, n_layers, H, D, act, G, M, preds, seed, Hkv=None):
+        self.n_layers, self.Hq, self.D, self.act = n_layers, H, D, act
+        self.H = Hkv or H  # heads of a cached row
+        self.cfg = s3.make_config(n_layers, H, D, s3.S3_E4M3, G, M, 0 if Hkv is None else Hkv, act)
         bpt = s3.s3_kv_bytes_per_token(self.cfg)
-        assert bpt == 2 * n_layers * H * D
+        assert bpt == 2 * n_layers * self.H * D
         caps = [min(M, max(G, -(-p // G) * G)) for p in preds]
         self.N = sum(caps) + 3 * M
         self.mem = torch.zeros(self.N * bpt, dtype=torch.uint8, device=DEV)
         st, self.a = s3.s3_kv_arena_init(self.cfg, self.mem, self.mem.numel())
         assert st == 0
-        assert s3.s3_kv_get_param(self.a, "kernel_kind") == (0, 3)
-        self.o = orc.KVOracle(n_layers, H, D, orc.E4M3, G, M, self.N * bpt, act_dtype=act)
+        assert s3.s3_kv_get_param(self.a, "kernel_kind") == (0, 3 if self.H == H else 4)
+        self.o = orc.KVOracle(n_layers, H, D, orc.E4M3, G, M, self.N * bpt, act_dtype=act, n_kv_heads=Hkv)
         assert bpt == self.o.bytes_per_token
         rc, self.ids, self.offs, self.caps = s3.s3_kv_alloc(self.a, preds)
         n_o, ids_o, offs_o, caps_o = self.o.alloc(preds)
@@ -68,12 +69,12 @@ class Rig8:
 
     def attend(self, lens, layer=0, out_dtype=s3.S3_F32, scale=0.0):
         n = len(lens)
-        q = wl.normal_bits(self.rng, (n, self.H, self.D), self.act)
+        q = wl.normal_bits(self.rng, (n, self.Hq, self.D), self.act)
         qd = device_bits(q, TDT[self.act], DEV)
         off_d = torch.tensor(self.offs.tolist(), dtype=torch.int64, device=DEV)
         len_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
         odt = {s3.S3_F32: torch.float32, s3.S3_F16: torch.float16, s3.S3_BF16: torch.bfloat16}[out_dtype]
-        out = torch.full((n, self.H, self.D), float("nan"), dtype=odt, device=DEV)
+        out = torch.full((n, self.Hq, self.D), float("nan"), dtype=odt, device=DEV)
         st = s3.s3_decode_attention(self.a, layer, n, qd, off_d, len_d, out, out_dtype, scale, self.stream)
         assert st == 0, st
         torch.cuda.synchronize()
@@ -91,7 +92,7 @@ def test_config_rules_for_8_bit_rows():
     ok = s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 0, s3.S3_BF16)
     assert s3.s3_kv_bytes_per_token(ok) == 2 * 16 * 256
     for bad in (s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 0, s3.S3_F32),
-                s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 4, s3.S3_F16),   # shared heads: not built
+                s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 5, s3.S3_F16),   # 5 does not divide 16
                 s3.make_config(1, 16, 256, 4, 64, 2048)):
         assert s3.s3_kv_bytes_per_token(bad) == s3.S3_ERR_INVALID
 
@@ -197,6 +198,52 @@ def test_decode_step_quantises_appends_and_attends(act):
         for which in (0, 1):
             assert np.array_equal(rig.read(sid, 0, which, rig.caps[b]), rig.o.data[sid][0, which].astype(np.uint8))
     assert_close(out.cpu().numpy(), rig.oracle_attend(q, caps), "e4m3 step")
+    rig.close()
+
+
+SHARED8 = [(32, 8, 128), (16, 1, 256), (8, 1, 64), (8, 2, 64), (12, 4, 128), (6, 3, 256), (64, 8, 128), (40, 2, 128), (9, 3, 64)]
+
+
+@pytest.mark.parametrize("act", [s3.S3_F16, s3.S3_BF16])
+@pytest.mark.parametrize("H,Hkv,D", SHARED8)
+def test_shared_heads_over_8_bit_rows(H, Hkv, D, act):
+    """Both footprint variants at once: e4m3 rows of Hkv cached heads, H query heads; the matrix-core
+    kernel widens the codes in registers.  (40, 2, 128) has 20 query heads per cached head: two blocks
+    of 16 columns, the second partly padding."""
+    rig = Rig8(2, H, D, act, 64, 1024, [max(1, L) for L in RAGGED], seed=60 + H + Hkv, Hkv=Hkv)
+    rig.fill(RAGGED, layer=1)
+    for chunk in (0, 32, 160, 1024):
+        assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+        q, got = rig.attend(RAGGED, layer=1)
+        assert_close(got, rig.oracle_attend(q, RAGGED, layer=1), f"e4m3 shared {H}/{Hkv}x{D} chunk {chunk}")
+        assert not got[0].any()
+    rig.close()
+
+
+@pytest.mark.parametrize("H,Hkv,D,act", [(32, 8, 128, s3.S3_BF16), (16, 1, 256, s3.S3_F16)])
+def test_shared_heads_over_8_bit_rows_decode_step(H, Hkv, D, act):
+    pos = [0, 1, 31, 63, 64, 100, 255, 513, 5]
+    caps = [p + 1 for p in pos]
+    rig = Rig8(1, H, D, act, 64, 1024, caps, seed=80 + H, Hkv=Hkv)
+    rig.fill(pos)
+    n = len(pos)
+    q = wl.normal_bits(rig.rng, (n, H, D), act)
+    k = wl.normal_bits(rig.rng, (n, Hkv, D), act)
+    v = wl.normal_bits(rig.rng, (n, Hkv, D), act)
+    qd, kd, vd = (device_bits(x, TDT[act], DEV) for x in (q, k, v))
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=rig.ids, pos_host=pos) == 0
+    torch.cuda.synchronize()
+    assert len_out.cpu().tolist() == caps
+    for b, sid in enumerate(rig.ids.tolist()):
+        assert rig.o.append(sid, 0, pos[b], k[b], v[b]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig.read(sid, 0, which, rig.caps[b]), rig.o.data[sid][0, which].astype(np.uint8))
+    assert_close(out.cpu().numpy(), rig.oracle_attend(q, caps), "e4m3 shared step")
     rig.close()
 
 

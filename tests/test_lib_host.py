@@ -185,18 +185,23 @@ def test_profile_percentiles_are_zero_without_timed_launches():
 
 def test_8_bit_cache_config_on_the_host():
     """e4m3 rows (quantisation, related work): one byte per element, 16-bit activation type required,
-    shared K/V heads not combined with it; the allocator works in tokens as before."""
+    shared K/V heads shrink it further; the allocator works in tokens as before."""
     ok = s3.make_config(28, 16, 256, s3.S3_E4M3, 64, 2048, 0, s3.S3_BF16)
     assert s3.s3_kv_bytes_per_token(ok) == 458752 // 2
     for bad in (s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 0, s3.S3_F32),
                 s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 0, s3.S3_E4M3),
-                s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 4, s3.S3_F16),
+                s3.make_config(1, 16, 256, s3.S3_E4M3, 64, 2048, 5, s3.S3_F16),
                 s3.make_config(1, 16, 256, 4, 64, 2048)):
         assert s3.s3_kv_bytes_per_token(bad) == s3.S3_ERR_INVALID
         assert s3.s3_kv_arena_init(bad, None, 1 << 20)[0] == s3.S3_ERR_INVALID
     st, a = s3.s3_kv_arena_init(ok, None, 100 * 229376)
     assert st == 0 and s3.s3_kv_stats(a)[4] == 100
     assert s3.s3_kv_get_param(a, "kernel_kind") == (0, 3)
+    both = s3.make_config(28, 16, 256, s3.S3_E4M3, 64, 2048, 4, s3.S3_F16)  # 8-bit rows of 4 cached heads
+    assert s3.s3_kv_bytes_per_token(both) == 458752 // 8
+    st, b = s3.s3_kv_arena_init(both, None, 1 << 24)
+    assert st == 0 and s3.s3_kv_get_param(b, "kernel_kind") == (0, 4) and s3.s3_kv_get_param(b, "n_variants") == (0, 1)
+    s3.s3_kv_arena_destroy(b)
     o = orc.KVOracle(28, 16, 256, orc.E4M3, 64, 2048, 100 * 229376, store=False, act_dtype=orc.BF16)
     rc, ids, offs, caps = s3.s3_kv_alloc(a, [10, 65, 3000])
     assert (rc, ids.tolist(), offs.tolist(), caps.tolist()) == o.alloc([10, 65, 3000])
