@@ -11,8 +11,8 @@
 // heads per K/V head; group/GQ items per K/V head group re-read the same rows.
 // Work item = (sequence, chunk of its context, K/V head group, query sub-block), enumerated from the
 // same LDS batch view (near-equal chunks, longest contexts first) as in the multi-head kernels; empty
-// contexts have no item and get their zero rows from the merge kernel.  The TS waves of a workgroup split the chunk's rows and merge through LDS,
-// one query head at a time; wave 0 writes the output (one chunk) or the chunk partial (whole 32-byte
+// contexts have no item and get their zero rows from the merge kernel.  The TS waves of a workgroup
+// split the chunk's rows and merge through LDS, one query head at a time; wave 0 writes the output (one chunk) or the chunk partial (whole 32-byte
 // vector stores per lane: per-element device-scope stores as in the fused multi-head step cost more
 // here than the extra launch), and attn_merge_kernel, launched after it with H = the query head
 // count, finishes multi-chunk contexts.

@@ -1,21 +1,26 @@
-// HIP kernels of libs3kv for gfx950 (MI355X): append, ragged decode-step attention
-// (split over the sequence axis + merge), plane copies (grow / fill / read-back).
+// HIP kernels and launch code of libs3kv for gfx950 (MI355X): append, ragged decode-step attention
+// for multi-head 16-bit caches (split over the sequence axis + merge), plane copies (grow / fill /
+// read-back), and the host side of every attention call.  The kernels for shared key/value heads
+// and for 8-bit rows live in s3kv_gqa.hip, s3kv_gqa_mfma.hip and s3kv_fp8.hip and are launched
+// from here; the device helpers all of them share are in s3kv_device.h.
 //
-// Arena layout.  Plane p = 2*layer + (0: K, 1: V) holds N token rows of H*D elements,
-// token-major: element (token t, head h, d) of a plane sits at ((t*H + h)*D + d).  A slot is the
-// row range [off, off+cap) in EVERY plane, so one sequence's rows of one plane are one
-// contiguous run and the attention kernel streams them with 128-bit loads.
+// Arena layout.  Plane p = 2*layer + (0: K, 1: V) holds N token rows of H*D elements (H = cached
+// heads), token-major: element (token t, head h, d) of a plane sits at ((t*H + h)*D + d).  A slot
+// is the row range [off, off+cap) in EVERY plane, so one sequence's rows of one plane are one
+// contiguous run and the attention kernels stream them with 128-bit loads.
 //
 // Attention work decomposition.  The method is bound by HBM bandwidth (about one flop per byte),
-// so the unit of parallelism is bytes, not sequences: every context is cut into chunks of
-// `chunk` tokens and the (chunk, head-group) pairs of the whole ragged batch form one flat work
-// list that a fixed grid walks with a stride.  A wavefront covers GH = 512/D adjacent heads of
-// one token per 128-bit load (64 lanes x 16 B = 1 KiB of contiguous memory); the D/8 lanes of a
-// head reduce their dot product with DPP row operations, keep a running maximum and sum in
-// fp32, and accumulate their 8-element slice of the output.  The TS waves of a workgroup that
-// share a head group split the chunk's tokens and merge through LDS; chunks of one context
-// merge in a second kernel.  Score s_j = q.K_j * scale as in the section 2.1 equation of the
-// S3 paper; softmax is max-subtracted; everything after the 16-bit loads is fp32.
+// so the unit of parallelism is bytes, not sequences: every context is cut into near-equal chunks
+// of at most `chunk` tokens and the (chunk, head-group) pairs of the whole ragged batch form one
+// flat work list, longest contexts first, that a fixed grid walks with a stride.  A wavefront
+// covers GH = 512/D adjacent heads of one token per 128-bit load (64 lanes x 16 B = 1 KiB of
+// contiguous memory); the D/8 lanes of a head reduce their dot product with DPP row operations,
+// keep a running maximum and sum in fp32, and accumulate their 8-element slice of the output.
+// The TS waves of a workgroup that share a head group split the chunk's tokens and merge through
+// LDS; chunks of one context merge in a second kernel (s3_decode_attention) or, in the fused step,
+// in the epilogue wave of whichever workgroup delivers the last chunk.  Score s_j = q.K_j * scale
+// as in the section 2.1 equation of the S3 paper; softmax is max-subtracted; everything after the
+// 16-bit loads is fp32.
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
