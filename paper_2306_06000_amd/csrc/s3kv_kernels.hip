@@ -231,15 +231,6 @@ struct TokenStream {
 
     __device__ __forceinline__ void reduce(int j, const u32x4 (&kk)[U], const u32x4 (&vv)[U], float &m, float &l,
                                            float (&acc)[8]) const {
-#ifdef S3_DIAG_LOAD_ONLY  // diagnostic build: keep the loads, drop the arithmetic (results are meaningless)
-        unsigned x = 0;
-#pragma unroll
-        for (int u = 0; u < U; u++) x ^= kk[u][0] ^ kk[u][1] ^ kk[u][2] ^ kk[u][3] ^ vv[u][0] ^ vv[u][1] ^ vv[u][2] ^ vv[u][3];
-        acc[0] += (float)(x & 1u);
-        m = 0.f;
-        l = 1.f;
-        return;
-#endif
         float s[U];
 #pragma unroll
         for (int u = 0; u < U; u++) s[u] = dot8<DT>(qv, kk[u]);
