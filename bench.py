@@ -219,7 +219,7 @@ def main():
     args.steps, args.warmup = steps_done, warmup
 
     res = {
-        "metric": "decode-attention achieved HBM GB/s", "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
+        "metric": "decode-attention achieved HBM GB/s (% of peak); sequence-steps/sec at batch B", "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(dt / args.steps * 1e3, 5),
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": {0: "f16", 1: "bf16", 3: "e4m3 rows, 16-bit queries, f32 arithmetic"}[w.dtype], "data": "synthetic",
