@@ -208,6 +208,18 @@ int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t
 int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t first_row, int32_t n_rows,
                const void *k_rows, const void *v_rows, void *stream);
 
+/* Admission of several newcomers in one launch (iteration-level scheduling, section 3: finished
+ * sequences are replaced between two decode steps): exactly n_new s3_kv_fill calls with first_row 0
+ * and, if slot_off / len are given, the s3_kv_batch_patch that puts newcomer i into entry
+ * batch_idx[i] of the running batch (its slot's offset, its n_rows[i] as the length).  All arguments
+ * are checked before anything is enqueued.
+ *   slot_id, n_rows HOST [n_new]; k_rows, v_rows HOST [n_new] arrays of DEVICE pointers to
+ *   [n_rows[i]][H][D] rows of the cache type, 16-byte aligned
+ *   slot_off DEVICE [batch_n] int64 and len DEVICE [batch_n] int32, or both NULL; batch_idx HOST [n_new] */
+int s3_kv_fill_batch(s3_arena *a, int32_t layer, int32_t n_new, const int32_t *slot_id, const int32_t *n_rows,
+                     const void *const *k_rows, const void *const *v_rows, int32_t batch_n, int64_t *slot_off,
+                     int32_t *len, const int32_t *batch_idx, void *stream);
+
 /* For callers that keep slot_off[] / len[] of the running batch in device memory: rewrite n_updates
  * entries (a grown slot's new offset, a newcomer that took a finished sequence's place) without a
  * host-to-device copy; the values travel as kernel arguments.  Stream-ordered like everything else.

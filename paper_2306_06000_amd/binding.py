@@ -51,6 +51,8 @@ SIGNATURES = {
     "s3_kv_stats": (ctypes.c_int, [_vp, _pi64, _pi64, _pi64, _pi64]),
     "s3_kv_fill": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _vp, _vp, _vp]),
     "s3_kv_batch_patch": (ctypes.c_int, [_i32, _vp, _vp, _i32, _pi32, _pi64, _pi32, _vp]),
+    "s3_kv_fill_batch": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, ctypes.POINTER(_vp), ctypes.POINTER(_vp), _i32, _vp,
+                                        _vp, _pi32, _vp]),
     "s3_kv_read_rows": (ctypes.c_int, [_vp, _i32, _i32, _i32, _i32, _i32, _vp, _vp]),
     "s3_kv_probe_bandwidth": (ctypes.c_int, [_vp, ctypes.c_size_t, _i32, _i32, ctypes.POINTER(ctypes.c_double)]),
     "s3_kv_set_param": (ctypes.c_int, [_vp, ctypes.c_char_p, _i64]),
@@ -238,6 +240,22 @@ def s3_kv_stats(arena):
 def s3_kv_fill(arena, slot_id, layer, first_row, n_rows, k_rows, v_rows, stream=0):
     return lib().s3_kv_fill(arena, int(slot_id), int(layer), int(first_row), int(n_rows), _ptr(k_rows), _ptr(v_rows),
                             stream or None)
+
+
+def s3_kv_fill_batch(arena, layer, slot_ids, n_rows, k_rows, v_rows, stream=0, slot_off=None, length=None, batch_n=0,
+                     batch_idx=None):
+    """k_rows / v_rows: sequences of device tensors (or addresses), one per newcomer."""
+    s_arr, sp = _host_i32(slot_ids)
+    r_arr, rp = _host_i32(n_rows)
+    n = int(s_arr.size)
+    kp = (_vp * max(n, 1))(*[_ptr(t) for t in k_rows])
+    vp = (_vp * max(n, 1))(*[_ptr(t) for t in v_rows])
+    if batch_idx is not None:
+        b_arr, bp = _host_i32(batch_idx)
+    else:
+        b_arr, bp = None, None
+    return lib().s3_kv_fill_batch(arena, int(layer), n, sp, rp, kp, vp, int(batch_n), _ptr(slot_off), _ptr(length), bp,
+                                  stream or None)
 
 
 def s3_kv_batch_patch(n, slot_off, length, idx, new_off, new_len, stream=0):

@@ -109,6 +109,75 @@ extern "C" int s3_kv_batch_patch(int32_t n, int64_t *slot_off, int32_t *len, int
     return S3_OK;
 }
 
+// Admission of several newcomers in one launch: their prompt rows (K and V of one layer) and, optionally,
+// their entries of the running batch's device arrays.  Everything travels as kernel arguments.
+#define S3_FILL_MAX 16
+struct FillArgs {
+    const char *ksrc[S3_FILL_MAX];
+    const char *vsrc[S3_FILL_MAX];
+    char *kdst[S3_FILL_MAX];
+    char *vdst[S3_FILL_MAX];
+    int64_t off[S3_FILL_MAX];
+    uint32_t n16[S3_FILL_MAX];
+    int32_t idx[S3_FILL_MAX];
+    int32_t rows[S3_FILL_MAX];
+};
+// grid (x, 2, entries): blockIdx.z picks the newcomer, blockIdx.y K or V, the x blocks stride over its rows.
+__global__ void __launch_bounds__(256) fill_batch_kernel(const FillArgs f, int64_t *slot_off, int32_t *len) {
+    const int z = blockIdx.z;
+    const u32x4 *s = (const u32x4 *)(blockIdx.y ? f.vsrc[z] : f.ksrc[z]);
+    u32x4 *d = (u32x4 *)(blockIdx.y ? f.vdst[z] : f.kdst[z]);
+    const size_t n16 = f.n16[z], stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) d[i] = s[i];
+    if (slot_off && blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
+        slot_off[f.idx[z]] = f.off[z];
+        len[f.idx[z]] = f.rows[z];
+    }
+}
+
+extern "C" int s3_kv_fill_batch(s3_arena *a, int32_t layer, int32_t n_new, const int32_t *slot_id, const int32_t *n_rows,
+                                const void *const *k_rows, const void *const *v_rows, int32_t batch_n,
+                                int64_t *slot_off, int32_t *len, const int32_t *batch_idx, void *stream) {
+    if (!a || !a->base || layer < 0 || layer >= a->cfg.n_layers || n_new < 0) return S3_ERR_INVALID;
+    if (n_new == 0) return S3_OK;
+    if (!slot_id || !n_rows || !k_rows || !v_rows) return S3_ERR_INVALID;
+    const bool patch = slot_off || len;
+    if (patch && (!slot_off || !len || !batch_idx || batch_n <= 0)) return S3_ERR_INVALID;
+    for (int32_t i = 0; i < n_new; i++) {  // everything is checked before anything is enqueued
+        const s3_slot *s = s3i_live_slot(a, slot_id[i]);
+        if (!s || n_rows[i] < 0) return S3_ERR_INVALID;
+        if (n_rows[i] > s->cap) return S3_ERR_SLOT_FULL;
+        if (n_rows[i] > 0 && (!k_rows[i] || !v_rows[i] || ((uintptr_t)k_rows[i] & 15) || ((uintptr_t)v_rows[i] & 15)))
+            return S3_ERR_INVALID;
+        if (patch && (batch_idx[i] < 0 || batch_idx[i] >= batch_n)) return S3_ERR_INVALID;
+    }
+    for (int32_t first = 0; first < n_new; first += S3_FILL_MAX) {
+        FillArgs f;
+        memset(&f, 0, sizeof(f));
+        const int count = n_new - first < S3_FILL_MAX ? n_new - first : S3_FILL_MAX;
+        size_t most = 1;
+        for (int i = 0; i < count; i++) {
+            const s3_slot *s = s3i_live_slot(a, slot_id[first + i]);
+            const size_t n16 = (size_t)n_rows[first + i] * a->row_bytes / 16;
+            f.ksrc[i] = (const char *)k_rows[first + i];
+            f.vsrc[i] = (const char *)v_rows[first + i];
+            f.kdst[i] = a->plane(layer, 0) + s->off * a->row_bytes;
+            f.vdst[i] = a->plane(layer, 1) + s->off * a->row_bytes;
+            f.n16[i] = (uint32_t)n16;
+            f.off[i] = s->off;
+            f.idx[i] = patch ? batch_idx[first + i] : 0;
+            f.rows[i] = n_rows[first + i];
+            if (n16 > most) most = n16;
+        }
+        size_t blocks = (most + 1023) / 1024;
+        if (blocks > 1024) blocks = 1024;
+        hipLaunchKernelGGL(fill_batch_kernel, dim3((unsigned)blocks, 2, (unsigned)count), dim3(256), 0, (hipStream_t)stream,
+                           f, patch ? slot_off : nullptr, patch ? len : nullptr);
+        HIP_TRY(hipGetLastError());
+    }
+    return S3_OK;
+}
+
 int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src_plane_stride,
                            size_t dst_plane_stride, int planes, void *stream) {
     if (nbytes == 0 || planes <= 0) return S3_OK;

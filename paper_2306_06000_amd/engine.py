@@ -125,8 +125,9 @@ class DecodeEngine:
         self._dirty = True
 
     # -- admission --------------------------------------------------------
-    def admit(self, seqs, prefill):
-        """Reserve slots for `seqs` in order (one s3_kv_alloc call) and write their cached rows.
+    def admit(self, seqs, prefill, fill=True):
+        """Reserve slots for `seqs` in order (one s3_kv_alloc call) and write their cached rows
+        (fill=False: the caller writes them, see retire_and_refill).
         prefill(serial, layer, rows) -> (k_rows, v_rows) device tensors [rows][H][D].
         Returns (serial, slot, off, cap, len, total) of the admitted ones."""
         preds = [s.predicted for s in seqs]
@@ -140,7 +141,7 @@ class DecodeEngine:
             if sid < 0:
                 continue
             rows = s.start
-            for layer in range(self.w.n_layers):
+            for layer in range(self.w.n_layers if fill else 0):
                 k_rows, v_rows = prefill(serial, layer, rows)
                 s3.check(s3.s3_kv_fill(self.arena, sid, layer, 0, rows, k_rows, v_rows, self._stream_ptr()),
                          "s3_kv_fill")
@@ -228,16 +229,29 @@ class DecodeEngine:
             self._log("free", int(self.serial[i]), int(self.slot[i]))
             self.n_retired += 1
             keep[i] = False
+        new = []  # batch entries that received a newcomer
         if self.w.refill:
             for i in done.tolist():
                 if self.pool_pos >= len(self.w.pool):
                     break
-                got = self.admit([self.w.pool[self.pool_pos]], prefill)
+                got = self.admit([self.w.pool[self.pool_pos]], prefill, fill=False)
                 self.pool_pos += 1
                 if got:
                     (self.serial[i], self.slot[i], self.off[i], self.cap[i], self.len[i], self.total[i]) = got[0]
                     keep[i] = True
-                    self._patch.add(i)
+                    new.append(i)
+        if new:
+            # the prompt rows of all newcomers of this step in one launch per layer; if the batch keeps its
+            # shape, the first launch also writes their entries of the device arrays
+            in_place = bool(keep.all()) and not self._dirty and self.slot_off_dev is not None
+            for layer in range(self.w.n_layers):
+                rows = [prefill(int(self.serial[i]), layer, int(self.len[i])) for i in new]
+                patch = dict(slot_off=self.slot_off_dev, length=self.len_dev, batch_n=self.n_active,
+                             batch_idx=new) if in_place and layer == 0 else {}
+                s3.check(s3.s3_kv_fill_batch(self.arena, layer, self.slot[new], self.len[new], [r[0] for r in rows],
+                                             [r[1] for r in rows], self._stream_ptr(), **patch), "s3_kv_fill_batch")
+            if not in_place:
+                self._patch.update(new)
         if not keep.all():
             self._keep(keep)
 

@@ -456,6 +456,51 @@ def test_evict_to_host_and_restore_with_doubled_reservation():
     rig.close()
 
 
+def test_fill_batch_equals_fills_plus_patch():
+    """s3_kv_fill_batch = the s3_kv_fill of every newcomer + the s3_kv_batch_patch of their batch entries,
+    in one launch (more than 16 newcomers: several); arguments are checked before anything is enqueued."""
+    H, D, dt = 4, 128, s3.S3_BF16
+    preds = [64, 200, 64, 130, 64, 64, 500, 64, 90, 64, 64, 64, 300, 64, 64, 64, 64, 64, 77, 64]
+    rig = Rig(2, H, D, dt, 64, 512, preds, seed=31)
+    rows = [1, 200, 0, 130, 64, 3, 500, 17, 90, 64, 2, 5, 300, 9, 33, 64, 1, 8, 77, 60]
+    n = len(preds)
+    ks = [wl.normal_bits(rig.rng, (max(r, 1), H, D), dt) for r in rows]
+    vs = [wl.normal_bits(rig.rng, (max(r, 1), H, D), dt) for r in rows]
+    kd = [device_bits(k, TDT[dt], DEV) for k in ks]
+    vd = [device_bits(v, TDT[dt], DEV) for v in vs]
+    batch_n = 32
+    off_d = torch.full((batch_n,), -7, dtype=torch.int64, device=DEV)
+    len_d = torch.full((batch_n,), -7, dtype=torch.int32, device=DEV)
+    idx = [(3 * i + 1) % batch_n for i in range(n)]
+    assert len(set(idx)) == n
+    bad_rows = list(rows)
+    bad_rows[6] = 513  # more than the slot holds: refused as a whole
+    assert s3.s3_kv_fill_batch(rig.a, 1, rig.ids, bad_rows, kd, vd, rig.stream, slot_off=off_d, length=len_d,
+                               batch_n=batch_n, batch_idx=idx) == s3.S3_ERR_SLOT_FULL
+    assert s3.s3_kv_fill_batch(rig.a, 1, rig.ids, rows, kd, vd, rig.stream, slot_off=off_d, length=len_d,
+                               batch_n=batch_n, batch_idx=[99] * n) == s3.S3_ERR_INVALID
+    torch.cuda.synchronize()
+    assert (off_d.cpu().numpy() == -7).all() and not rig_read(rig, int(rig.ids[1]), 1, 0, 200).any()
+    assert s3.s3_kv_fill_batch(rig.a, 1, rig.ids, rows, kd, vd, rig.stream, slot_off=off_d, length=len_d,
+                               batch_n=batch_n, batch_idx=idx) == 0
+    torch.cuda.synchronize()
+    got_off, got_len = off_d.cpu().numpy(), len_d.cpu().numpy()
+    for i, sid in enumerate(rig.ids.tolist()):
+        assert got_off[idx[i]] == rig.offs[i] and got_len[idx[i]] == rows[i]
+        if rows[i]:
+            assert rig.o.fill(sid, 1, ks[i][:rows[i]], vs[i][:rows[i]]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, sid, 1, which, rig.caps[i]), rig.o.data[sid][1, which])
+            assert not rig_read(rig, sid, 0, which, rig.caps[i]).any()  # the other layer is untouched
+    untouched = sorted(set(range(batch_n)) - set(idx))
+    assert (got_off[untouched] == -7).all() and (got_len[untouched] == -7).all()
+    # without the batch arrays it is the fills alone
+    assert s3.s3_kv_fill_batch(rig.a, 0, rig.ids[:3], rows[:3], kd[:3], vd[:3], rig.stream) == 0
+    torch.cuda.synchronize()
+    assert np.array_equal(rig_read(rig, int(rig.ids[1]), 0, 0, 200), ks[1])
+    rig.close()
+
+
 def test_batch_patch_rewrites_only_the_named_entries():
     n = 100
     off = torch.arange(n, dtype=torch.int64, device=DEV) * 64
