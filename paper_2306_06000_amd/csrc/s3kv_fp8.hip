@@ -8,8 +8,8 @@
 // Attention: a wave's 128-bit load covers 1 KiB of consecutive arena bytes = 16 elements per lane,
 // D/16 lanes per head, 1024/D heads of one row (or, when a row has fewer heads, whole consecutive
 // rows, each lane group with its own online-softmax state).  Work list, near-equal chunks,
-// longest-first order, TS waves per item merging through LDS, chunk partials finished by
-// attn_merge_kernel: as in the kernel for shared K/V heads.
+// longest-first order, TS waves per item merging through LDS: as in the kernel for shared K/V heads;
+// chunks of one context merge inside the kernel (arrival counter), so no second kernel follows.
 #include "s3kv_device.h"
 
 typedef float f32x2v __attribute__((ext_vector_type(2)));
@@ -88,8 +88,14 @@ __global__ void __launch_bounds__(TS * 64) attn_fp8_kernel(const AttnArgs a) {
     const int n_hg = (a.H + GH - 1) / GH;
     const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
     const int64_t total = (int64_t)bv.total * n_hg;
-    if (blockIdx.x == 0 && a.len_out)
-        for (int b = threadIdx.x; b < a.n; b += TS * 64) a.len_out[b] = a.cur_len[b] + 1;
+    // the new lengths, and a zero output row for empty or refused contexts, by the workgroups in turn
+    for (int b = blockIdx.x; b < a.n; b += gridDim.x) {
+        if (a.len_out && threadIdx.x == 0) a.len_out[b] = a.cur_len[b] + 1;
+        if (bv.len[b] == 0) {
+            const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int e = threadIdx.x; e < a.H * D / 8; e += TS * 64) store_out8(a.out, a.out_dtype, ((int64_t)b * a.H * D / 8 + e) * 8, z);
+        }
+    }
 
     const int slot = lane / LPH, dl = lane % LPH;
     const int tsub = tpw > 1 ? slot / a.H : 0;
@@ -194,13 +200,30 @@ __global__ void __launch_bounds__(TS * 64) attn_fp8_kernel(const AttnArgs a) {
                 const int64_t e0 = ((int64_t)it.b * a.H + h) * D + dl * 16;
                 store_out8(a.out, a.out_dtype, e0, o0);
                 store_out8(a.out, a.out_dtype, e0 + 8, o1);
-            } else {
+            } else {  // a chunk of a longer context: the partial goes out with write-through stores
                 const int64_t pi = ((int64_t)it.b * a.max_chunks + it.c) * a.H + h;
                 float *pa = a.part_acc + pi * D + dl * 16;
-                if (dl == 0) a.part_ml[pi] = make_float2(mm, ll);
+                if (dl == 0) put_partial2<true>((float *)a.part_ml + 2 * pi, (f32x2){mm, ll});
 #pragma unroll
                 for (int v4 = 0; v4 < 4; v4++)
-                    ((f32x4 *)pa)[v4] = (f32x4){o[4 * v4], o[4 * v4 + 1], o[4 * v4 + 2], o[4 * v4 + 3]};
+                    put_partial4<true>(pa + 4 * v4, (f32x4){o[4 * v4], o[4 * v4 + 1], o[4 * v4 + 2], o[4 * v4 + 3]});
+            }
+        }
+        if (ts == 0 && it.nchunks > 1) {
+            // Chunks meet through an arrival counter per (sequence, head group), as in the fused multi-head
+            // step: whoever delivers the last chunk merges them.  With the default chunk of 1024 rows this is
+            // rare, which is what makes it cheaper than a merge launch after every attention launch.
+            __builtin_amdgcn_s_waitcnt(0);  // this wave's partial stores have completed
+            unsigned int *cnt = a.arrivals + (int64_t)it.b * n_hg + it.hgb;
+            unsigned int old = 0;
+            if (lane == 0) old = atomicAdd(cnt, 1u);
+            old = __builtin_amdgcn_readfirstlane(old);
+            if (old == (unsigned int)(it.nchunks - 1)) {
+                if (lane == 0) atomicExch(cnt, 0u);  // leave the counter clean for the next launch
+                if (h_ok && tsub == 0) {
+                    merge_chunks<D, true>(a, a.H, it.b, h, 2 * dl, it.nchunks);
+                    merge_chunks<D, true>(a, a.H, it.b, h, 2 * dl + 1, it.nchunks);
+                }
             }
         }
         __syncthreads();  // comb is reused by the next item

@@ -892,7 +892,7 @@ static int launch_gqa(s3_arena *a, const AttnCall &c) {
     return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, Hq);
 }
 
-// 8-bit cache rows: quantising append (own launch), attention over the codes, merge of chunk partials.
+// 8-bit cache rows: quantising append (own launch), then the attention kernel, which also merges chunks.
 static int launch_fp8(s3_arena *a, const AttnCall &c) {
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     int threads = 0;
@@ -903,13 +903,15 @@ static int launch_fp8(s3_arena *a, const AttnCall &c) {
         if (arc != S3_OK) return arc;
     }
     AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
-    int rc = place_scratch(a, args, 0);
+    const int n_hg = (H + 1024 / D - 1) / (1024 / D);  // head groups: 1024/D heads per 128-bit wave load of bytes
+    const size_t cnt_bytes = (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;
+    int rc = place_scratch(a, args, cnt_bytes);
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;
     rc = stride_grid(a, (const void *)fn, threads, dyn_lds, c.n > 128 ? 2 : 1, &blocks);
     if (rc != S3_OK) return rc;
-    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, H);
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, 0);  // the kernel merges by itself
 }
 
 // Shared by s3_decode_attention (partial kernel + merge kernel) and s3_decode_step (with_append: one
