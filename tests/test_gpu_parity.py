@@ -667,3 +667,58 @@ def test_c3_shape_small_arena_28_layers():
     w.seqs = w.seqs[:6]
     w.arena_bytes = 0
     run_trace(w, 1, attend_steps=[0])
+
+
+# ---------------------------------------------------------------- seeded random configurations
+@pytest.mark.parametrize("seed", range(24))
+def test_random_configuration_against_the_oracle(seed):
+    """A seeded draw over everything a caller can choose inside the documented limits: head shape and
+    sharing, types, batch size, ragged lengths (empty ones included), chunk size, kernel variant, length
+    classes and grid size; attention through s3_decode_attention and a decode step after it."""
+    rng = np.random.default_rng(1000 + seed)
+    D = int(rng.choice([64, 128, 256]))
+    dt = int(rng.choice([s3.S3_F16, s3.S3_BF16]))
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    group = int(rng.choice([1, 1, 2, 4, 5, 8, 16]))
+    H = Hkv * group
+    n = int(rng.choice([1, 2, 7, 33, 64, 65, 130]))
+    M = 1024
+    lens = [int(x) for x in rng.choice([0, 1, 2, 15, 16, 17, 63, 64, 65, 200, 511, 700, 1023], n)]
+    rig = Rig(1, H, D, dt, 64, M, [min(M, L + 1) for L in lens], seed=2000 + seed, Hkv=None if group == 1 else Hkv)
+    rig.fill(lens)
+    nv = n_variants(rig.a)
+    for _ in range(2):
+        assert s3.s3_kv_set_param(rig.a, "variant", int(rng.integers(-1, nv))) == 0
+        assert s3.s3_kv_set_param(rig.a, "chunk", int(rng.choice([0, 32, 96, 256, 1024]))) == 0
+        assert s3.s3_kv_set_param(rig.a, "classes", int(rng.integers(0, 9))) == 0
+        assert s3.s3_kv_set_param(rig.a, "grid_blocks", int(rng.choice([0, 1, 3, 64, 300, 2048]))) == 0
+        q, got = rig.attend(lens)
+        assert_close(got, rig.oracle_attend(q, lens), f"random {seed}: H{H} Hkv{Hkv} D{D} n{n}")
+        for b, L in enumerate(lens):
+            if L == 0:
+                assert not got[b].any()
+    # one decode step on the sequences that still have room
+    pos = [L for L in lens if L < M]
+    keep = [b for b, L in enumerate(lens) if L < M]
+    ids = rig.ids[keep]
+    m = len(keep)
+    kvh = Hkv if group > 1 else H
+    q = wl.normal_bits(rig.rng, (m, H, D), dt)
+    k = wl.normal_bits(rig.rng, (m, kvh, D), dt)
+    v = wl.normal_bits(rig.rng, (m, kvh, D), dt)
+    qd, kd, vd = (device_bits(x, TDT[dt], DEV) for x in (q, k, v))
+    off_d = torch.tensor(rig.offs[keep].tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    out = torch.full((m, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(m, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, m, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=ids, pos_host=pos) == 0
+    torch.cuda.synchronize()
+    assert len_out.cpu().tolist() == [p + 1 for p in pos]
+    for j, sid in enumerate(ids.tolist()):
+        assert rig.o.append(sid, 0, pos[j], k[j], v[j]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, sid, 0, which, pos[j] + 1), rig.o.rows(sid, 0, which, pos[j] + 1))
+    want = rig.o.attention(0, ids.tolist(), [p + 1 for p in pos], q, None, "f32", threads=8)
+    assert_close(out.cpu().numpy(), want, f"random {seed} step")
+    rig.close()
