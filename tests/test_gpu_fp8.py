@@ -247,6 +247,34 @@ def test_shared_heads_over_8_bit_rows_decode_step(H, Hkv, D, act):
     rig.close()
 
 
+@pytest.mark.parametrize("seed", range(16))
+def test_random_configuration_over_8_bit_rows(seed):
+    """A seeded draw over head shape and sharing, query type, batch, ragged lengths, chunk, kernel shape,
+    classes and grid size, for attention over e4m3 rows."""
+    rng = np.random.default_rng(3000 + seed)
+    D = int(rng.choice([64, 128, 256]))
+    act = int(rng.choice([s3.S3_F16, s3.S3_BF16]))
+    Hkv = int(rng.choice([1, 2, 3, 4, 8]))
+    group = int(rng.choice([1, 1, 2, 4, 5, 8, 16]))
+    H = Hkv * group
+    n = int(rng.choice([1, 2, 7, 33, 64, 65, 130]))
+    lens = [int(x) for x in rng.choice([0, 1, 2, 15, 16, 17, 63, 64, 65, 200, 511, 700, 1024], n)]
+    rig = Rig8(1, H, D, act, 64, 1024, [max(1, L) for L in lens], seed=4000 + seed, Hkv=None if group == 1 else Hkv)
+    rig.fill(lens)
+    nv = s3.s3_kv_get_param(rig.a, "n_variants")[1]
+    for _ in range(2):
+        assert s3.s3_kv_set_param(rig.a, "variant", int(rng.integers(-1, nv))) == 0
+        assert s3.s3_kv_set_param(rig.a, "chunk", int(rng.choice([0, 32, 96, 256, 1024]))) == 0
+        assert s3.s3_kv_set_param(rig.a, "classes", int(rng.integers(0, 9))) == 0
+        assert s3.s3_kv_set_param(rig.a, "grid_blocks", int(rng.choice([0, 1, 3, 64, 300, 2048]))) == 0
+        q, got = rig.attend(lens)
+        assert_close(got, rig.oracle_attend(q, lens), f"random e4m3 {seed}: H{H} Hkv{Hkv} D{D} n{n}")
+        for b, L in enumerate(lens):
+            if L == 0:
+                assert not got[b].any()
+    rig.close()
+
+
 def test_grow_and_evict_move_8_bit_rows_bit_exactly():
     H, D = 8, 128
     rig = Rig8(2, H, D, s3.S3_BF16, 64, 512, [64, 100, 64], seed=50)
