@@ -105,15 +105,14 @@ class DecodeEngine:
             s3.check(s3.s3_kv_batch_patch(self.n_active, self.slot_off_dev, self.len_dev, idx, self.off[idx],
                                           self.len[idx], self._stream_ptr()), "s3_kv_batch_patch")
         self._patch.clear()
-        if self._dirty:
+        if self._dirty:  # a new batch: the arrays keep this size; a batch that shrinks later uses a prefix
             self.slot_off_dev = self._upload(self.off)
             self.len_dev = self._upload(self.len)
             self.len_next = torch.empty_like(self.len_dev)
-            n = self.n_active
-            if self.out is None or self.out.shape[0] != n:
-                self.out = torch.empty((n, self.w.n_heads, self.w.head_dim), dtype=_TORCH_DT[self.out_dtype],
-                                       device=self.dev)
+            self.out_full = torch.empty((self.n_active, self.w.n_heads, self.w.head_dim),
+                                        dtype=_TORCH_DT[self.out_dtype], device=self.dev)
             self._dirty = False
+        self.out = self.out_full[:self.n_active]
 
     def _set_batch(self, recs):
         self.serial = np.array([r[0] for r in recs], np.int64)
@@ -183,14 +182,23 @@ class DecodeEngine:
             self._log("free", int(self.serial[i]), int(self.slot[i]))
             self.n_evicted += 1
         if drop:
-            keep = np.ones(self.n_active, bool)
-            keep[drop] = False
-            self._keep(keep)
+            self._remove(drop)
 
-    def _keep(self, mask):
-        for name in ("serial", "slot", "off", "cap", "len", "total"):
-            setattr(self, name, getattr(self, name)[mask])
-        self._dirty = True
+    def _remove(self, gone):
+        """Take entries out of the batch without re-uploading it: the last entry moves into each hole
+        (one patched entry of the device arrays per hole) and the batch becomes a shorter prefix."""
+        fields = ("serial", "slot", "off", "cap", "len", "total")
+        n = self.n_active
+        for i in sorted(gone, reverse=True):  # descending: the last entry is never a hole still to come
+            last = n - 1
+            if i != last:
+                for name in fields:
+                    getattr(self, name)[i] = getattr(self, name)[last]
+                self._patch.add(i)
+            self._patch.discard(last)
+            n -= 1
+        for name in fields:
+            setattr(self, name, getattr(self, name)[:n].copy())
 
     def launch_step(self, tensors, check_host=False):
         """append + attention for every layer on the current batch.  tensors(layer, n) ->
@@ -253,7 +261,7 @@ class DecodeEngine:
             if not in_place:
                 self._patch.update(new)
         if not keep.all():
-            self._keep(keep)
+            self._remove(np.nonzero(~keep)[0].tolist())
 
     def step(self, tensors, prefill, check_host=False):
         self.grow_full_slots()
