@@ -235,7 +235,7 @@ def main():
                    "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
                    "path": "quantising append + shared-kv matrix-core attention over 8-bit rows + merge per layer" if shared_kv and w.dtype == 3 else
                            "shared-kv attention kernel (+ append launch for the vector-ALU kernel) + merge per layer" if shared_kv else
-                           "quantising append kernel + attention kernel over 8-bit rows + merge per layer" if w.dtype == 3 else
+                           "one s3_decode_step kernel per layer (quantises and appends the new row, attends over 8-bit rows, merges)" if w.dtype == 3 else
                            "append+attention+merge kernels" if args.unfused else "one s3_decode_step kernel per layer",
                    "variant": s3.s3_kv_get_param(eng.arena, "variant")[1],
                    "chunk": s3.s3_kv_get_param(eng.arena, "chunk")[1]},

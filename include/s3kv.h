@@ -145,16 +145,17 @@ int s3_kv_append(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, 
 int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
                         const int32_t *cur_len, void *out, int32_t out_dtype, float scale, void *stream);
 
-/* One layer-step (multi-head 16-bit caches: in ONE kernel launch): exactly s3_kv_append(pos) followed by s3_decode_attention over
+/* One layer-step (multi-head caches, 16-bit or 8-bit rows: in ONE kernel launch): exactly s3_kv_append(pos) followed by s3_decode_attention over
  * cur_len[b] = pos[b] + 1 rows (the new token attends to itself as well; section 2.1), same results,
  * same host-side checks (slot_id / pos_host as in s3_kv_append), same treatment of bad device entries.
  * The wave that owns the new row takes it from k_new / v_new and writes it into the arena; the
  * workgroup that delivers the last chunk of a context merges the chunks, so no second kernel runs.
  *   len_out   DEVICE [n] int32 or NULL: receives pos[b] + 1, the positions of the next step; must not
  *             be the same array as pos (S3_ERR_INVALID) - alternate between two arrays. */
-/* (Shared key/value heads and 8-bit caches: the same call, results and checks, as two or three launches
- * on `stream`: the append (folded into the attention kernel when the matrix-core kernel is in use), the
- * attention kernel, and a merge of chunk partials.) */
+/* (Shared key/value heads: the same call, results and checks, as two or three launches on `stream`: the
+ * append (folded into the attention kernel when the matrix-core kernel runs over 16-bit rows), the
+ * attention kernel, and a merge of chunk partials.  An 8-bit cache rounds the new row to codes in the
+ * same kernel that attends over it.) */
 int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
                    const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
                    const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out, void *stream);

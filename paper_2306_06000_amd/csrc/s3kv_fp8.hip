@@ -9,7 +9,8 @@
 // D/16 lanes per head, 1024/D heads of one row (or, when a row has fewer heads, whole consecutive
 // rows, each lane group with its own online-softmax state).  Work list, near-equal chunks,
 // longest-first order, TS waves per item merging through LDS: as in the kernel for shared K/V heads;
-// chunks of one context merge inside the kernel (arrival counter), so no second kernel follows.
+// chunks of one context merge inside the kernel (arrival counter), so no second kernel follows, and in a
+// decode step the kernel quantises and appends the new row itself: one launch per step.
 #include "s3kv_device.h"
 
 typedef float f32x2v __attribute__((ext_vector_type(2)));
@@ -24,21 +25,17 @@ __device__ __forceinline__ void widen4_e4m3(const unsigned w, float (&f)[4]) {
     f[3] = hi[1];
 }
 
-// fp32 -> nearest e4m3 code with integer arithmetic only (ties to even, magnitudes from 448 up
-// saturate to 448 = 0x7e, NaN -> 0x7f): no dependence on a conversion instruction's rounding or
-// overflow mode.
-__device__ __forceinline__ unsigned quantize_e4m3(const float x) {
-    const unsigned u = __builtin_bit_cast(unsigned, x);
-    const unsigned sign = (u >> 24) & 0x80u, a = u & 0x7FFFFFFFu;
-    if (a > 0x7F800000u) return 0x7Fu;
-    if (a >= 0x43E00000u) return sign | 0x7Eu;  // |x| >= 448
-    if (a < 0x3C800000u) {                       // |x| < 2^-6: subnormal codes, spacing 2^-9 (8 -> the smallest normal)
-        const float mag = __builtin_bit_cast(float, a);
-        return sign | (unsigned)__builtin_rintf(mag * 512.f);
-    }
-    // normal: keep 3 fraction bits, round to nearest even; a carry out of the fraction raises the exponent
-    const unsigned r = a + 0x7FFFFu + ((a >> 20) & 1u);
-    return sign | ((r >> 20) - (120u << 3));
+// Two fp32 values -> their e4m3 codes in one half of a 32-bit word (v_cvt_pk_fp8_f32 rounds to the nearest
+// code, ties to even, subnormal codes included).  Magnitudes are clamped to 448 first, so nothing depends on
+// the instruction's overflow mode, and NaN is forced to 0x7f afterwards (the clamp turns it into a number).
+template <bool HI>
+__device__ __forceinline__ unsigned quantize2_e4m3(const float x0, const float x1, const unsigned old) {
+    const float c0 = fminf(fmaxf(x0, -448.f), 448.f), c1 = fminf(fmaxf(x1, -448.f), 448.f);
+    unsigned w = (unsigned)__builtin_amdgcn_cvt_pk_fp8_f32(c0, c1, (int)old, HI);
+    constexpr unsigned S = HI ? 16u : 0u;
+    if (x0 != x0) w = (w & ~(0xFFu << S)) | (0x7Fu << S);
+    if (x1 != x1) w = (w & ~(0xFF00u << S)) | (0x7F00u << S);
+    return w;
 }
 
 template <int ACT>
@@ -46,6 +43,20 @@ __device__ __forceinline__ float widen16(const unsigned short h) {
     if (ACT == S3_F16) return (float)__builtin_bit_cast(_Float16, h);
     const unsigned w = (unsigned)h << 16;
     return __builtin_bit_cast(float, w);
+}
+
+// 16 consecutive 16-bit elements (two 128-bit words) -> their 16 codes in element order.
+template <int ACT>
+__device__ __forceinline__ u32x4 quantize16(const u32x4 lo, const u32x4 hi) {
+    u32x4 out;
+#pragma unroll
+    for (int w = 0; w < 4; w++) {
+        const unsigned a = w < 2 ? lo[2 * w] : hi[2 * w - 4], c = w < 2 ? lo[2 * w + 1] : hi[2 * w - 3];
+        const unsigned lo2 = quantize2_e4m3<false>(widen16<ACT>((unsigned short)(a & 0xFFFFu)),
+                                                   widen16<ACT>((unsigned short)(a >> 16)), 0u);
+        out[w] = quantize2_e4m3<true>(widen16<ACT>((unsigned short)(c & 0xFFFFu)), widen16<ACT>((unsigned short)(c >> 16)), lo2);
+    }
+    return out;
 }
 
 // grid (n, 2): block (b, which) quantises one new row of H*D 16-bit elements into row off+pos.
@@ -61,17 +72,7 @@ __global__ void __launch_bounds__(256) append_fp8_kernel(char *kplane, char *vpl
     char *dst = (blockIdx.y ? vplane : kplane) + (off + p) * (int64_t)row_elems;
     for (int i = threadIdx.x; i < row_elems / 16; i += 256) {  // 16 elements: 32 bytes in, 16 out
         const u32x4 lo = *(const u32x4 *)(src + (int64_t)i * 32), hi = *(const u32x4 *)(src + (int64_t)i * 32 + 16);
-        u32x4 out;
-#pragma unroll
-        for (int w = 0; w < 4; w++) {
-            const unsigned a = w < 2 ? lo[2 * w] : hi[2 * w - 4], c = w < 2 ? lo[2 * w + 1] : hi[2 * w - 3];
-            const unsigned q0 = quantize_e4m3(widen16<ACT>((unsigned short)(a & 0xFFFFu)));
-            const unsigned q1 = quantize_e4m3(widen16<ACT>((unsigned short)(a >> 16)));
-            const unsigned q2 = quantize_e4m3(widen16<ACT>((unsigned short)(c & 0xFFFFu)));
-            const unsigned q3 = quantize_e4m3(widen16<ACT>((unsigned short)(c >> 16)));
-            const unsigned packed = q0 | (q1 << 8) | (q2 << 16) | (q3 << 24);
-            out[w] = packed;
-        }
+        const u32x4 out = quantize16<ACT>(lo, hi);
         *(u32x4 *)(dst + (int64_t)i * 16) = out;
     }
 }
@@ -106,8 +107,14 @@ __global__ void __launch_bounds__(TS * 64) attn_fp8_kernel(const AttnArgs a) {
         const bool h_ok = h < a.H;
         const int hc = h_ok ? h : a.H - 1;
         const int start = it.c * it.clen, end = min(it.len, start + it.clen);
-        const int per = (end - start + TS - 1) / TS;
-        const int j0 = min(end, start + ts * per), j1 = min(end, j0 + per);
+        // decode step: row len-1 is still a 16-bit row in k_new / v_new; the chunk that ends with it
+        // streams the rows before it and takes the new row in its last wave (below)
+        const bool has_new = a.k_new != nullptr && end == it.len;
+        const int end_mem = has_new ? end - 1 : end;
+        // the new row costs its wave one more memory round trip, about what a batch of U rows costs: its
+        // share of the streamed rows is shorter by that much
+        const int per = (end_mem - start + (has_new ? U : 0) + TS - 1) / TS;
+        const int j0 = min(end_mem, start + ts * per), j1 = min(end_mem, j0 + per);
         const char *kp = a.kplane + it.off * (int64_t)rs32 + hc * D + dl * 16;
         const char *vp = a.vplane + it.off * (int64_t)rs32 + hc * D + dl * 16;
         float q[16];
@@ -169,6 +176,42 @@ __global__ void __launch_bounds__(TS * 64) attn_fp8_kernel(const AttnArgs a) {
             }
             m = mn;
         }
+        if (has_new && ts == TS - 1) {
+            // The new row: rounded to codes exactly as the append kernel rounds it, written to the arena by
+            // the lanes that own its bytes, and attended over as the codes widen (what a later step reads).
+            const int64_t in_byte = (((int64_t)it.b * a.H + hc) * D + dl * 16) * 2;
+            const u32x4 kc = quantize16<ACT>(*(const u32x4 *)(a.k_new + in_byte), *(const u32x4 *)(a.k_new + in_byte + 16));
+            const u32x4 vc = quantize16<ACT>(*(const u32x4 *)(a.v_new + in_byte), *(const u32x4 *)(a.v_new + in_byte + 16));
+            if (h_ok && tsub == 0) {
+                const int64_t row_byte = (it.off + it.len - 1) * (int64_t)rs32 + h * D + dl * 16;
+                *(u32x4 *)(a.kplane + row_byte) = kc;
+                *(u32x4 *)(a.vplane + row_byte) = vc;
+            }
+            float d = 0.f;
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                float f[4];
+                const unsigned word = kc[w];
+                widen4_e4m3(word, f);
+#pragma unroll
+                for (int e = 0; e < 4; e++) d = fmaf(q[4 * w + e], f[e], d);
+            }
+            d = group_sum<LPH>(d);
+            const float s_new = tsub == 0 ? d : -INFINITY;  // one row: the first lane group's
+            const float mn = fmaxf(m, s_new);
+            const float alpha = (mn == -INFINITY) ? 1.f : fast_exp2(m - mn);
+            const float p = (mn == -INFINITY) ? 0.f : fast_exp2(s_new - mn);
+            l = l * alpha + p;
+#pragma unroll
+            for (int w = 0; w < 4; w++) {
+                float f[4];
+                const unsigned word = vc[w];
+                widen4_e4m3(word, f);
+#pragma unroll
+                for (int e = 0; e < 4; e++) acc[4 * w + e] = fmaf(p, f[e], acc[4 * w + e] * alpha);
+            }
+            m = mn;
+        }
         comb[ts][0][lane] = m;
         comb[ts][1][lane] = l;
 #pragma unroll
@@ -178,7 +221,7 @@ __global__ void __launch_bounds__(TS * 64) attn_fp8_kernel(const AttnArgs a) {
             float o[16], mm = -INFINITY, ll = 0.f;
 #pragma unroll
             for (int e = 0; e < 16; e++) o[e] = 0.f;
-            // a chunk's rows start at wave 0, lane group 0, so the maximum is finite
+            // a chunk has at least one row, so the maximum over its waves and lane groups is finite
             for (int t = 0; t < TS; t++)
                 for (int g = 0; g < tpw; g++) mm = fmaxf(mm, comb[t][0][lane + g * a.H * LPH]);
             for (int t = 0; t < TS; t++)

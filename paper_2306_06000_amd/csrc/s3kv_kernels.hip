@@ -856,7 +856,7 @@ static int launch_attn_kernels(s3_arena *a, attn_fn fn, int blocks, int threads,
 }
 
 // Shared key/value heads.  Vector-ALU kernel: append as its own launch, attention, merge.  Matrix-core
-// kernel: attention (which appends the new row itself), merge; over 8-bit rows: quantising append,
+// kernel: attention (which appends the new row itself), merge; over 8-bit rows: quantising append launch,
 // attention, merge.
 static int launch_gqa(s3_arena *a, const AttnCall &c) {
     const int D = a->cfg.head_dim, Hq = a->cfg.n_heads, Hkv = a->cfg.n_kv_heads;
@@ -892,16 +892,13 @@ static int launch_gqa(s3_arena *a, const AttnCall &c) {
     return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, Hq);
 }
 
-// 8-bit cache rows: quantising append (own launch), then the attention kernel, which also merges chunks.
+// 8-bit cache rows: one kernel, which in a decode step also quantises and appends the new row, merges
+// chunks and publishes the new lengths.
 static int launch_fp8(s3_arena *a, const AttnCall &c) {
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     int threads = 0;
     attn_fn fn = s3i_pick_fp8(a->cfg.act_dtype, D, a->variant, &threads);
     if (!fn) return S3_ERR_INVALID;
-    if (c.with_append) {
-        const int arc = launch_append(a, c.layer, c.n, c.slot_off, c.len_or_pos, c.k_new, c.v_new, c.stream);
-        if (arc != S3_OK) return arc;
-    }
     AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
     const int n_hg = (H + 1024 / D - 1) / (1024 / D);  // head groups: 1024/D heads per 128-bit wave load of bytes
     const size_t cnt_bytes = (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;

@@ -201,6 +201,47 @@ def test_decode_step_quantises_appends_and_attends(act):
     rig.close()
 
 
+@pytest.mark.parametrize("act", [s3.S3_F16, s3.S3_BF16])
+@pytest.mark.parametrize("D", [64, 128, 256])
+def test_decode_step_rounds_finite_special_values_like_the_append(D, act):
+    """The decode step rounds the new row inside the attention kernel: midpoints between codes, subnormal
+    codes, values at and beyond the largest code must give the oracle's codes there too."""
+    H = 2048 // D
+    pos = [0, 3, 64, 700]
+    rig = Rig8(1, H, D, act, 64, 1024, [p + 1 for p in pos], seed=45 + D)
+    rig.fill(pos)
+    n = len(pos)
+    vals = orc.widen(np.arange(0x7f, dtype=np.uint16), orc.E4M3, "f64")
+    mids = (vals[:-1] + vals[1:]) / 2
+    special = np.concatenate([mids, -mids, vals, -vals, [0.0, -0.0, 448.0, 464.0, 465.0, 1e4, 65504.0, -1e4, 2.0 ** -10,
+                                                         3 * 2.0 ** -11, 2.0 ** -11, 6e-8, -6e-8, 2.0 ** -9 * 0.75]])
+    x = (rig.rng.standard_normal((2, n, H, D)) * rig.rng.choice([0.01, 1.0, 30.0], (2, n, H, 1))).astype(np.float32)
+    assert special.size <= H * D
+    for b in range(n):
+        x[0, b].reshape(-1)[:special.size] = np.roll(special, 7 * b).astype(np.float32)
+        x[1, b].reshape(-1)[-special.size:] = np.roll(special, 3 * b).astype(np.float32)
+    kb, vb = wl.to_bits(x[0], act), wl.to_bits(x[1], act)
+    q = wl.normal_bits(rig.rng, (n, H, D), act)
+    qd, kd, vd = (device_bits(t, TDT[act], DEV) for t in (q, kb, vb))
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=rig.ids, pos_host=pos) == 0
+    torch.cuda.synchronize()
+    assert len_out.cpu().tolist() == [p + 1 for p in pos]
+    for b, sid in enumerate(rig.ids.tolist()):
+        assert rig.o.append(sid, 0, pos[b], kb[b], vb[b]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig.read(sid, 0, which, pos[b] + 1), rig.o.rows(sid, 0, which, pos[b] + 1).astype(np.uint8)), (b, which)
+    got = out.cpu().numpy()
+    want = rig.oracle_attend(q, [p + 1 for p in pos])
+    assert np.isfinite(got).all()
+    assert np.linalg.norm(got - want) <= 1e-3 * np.linalg.norm(want)
+    rig.close()
+
+
 SHARED8 = [(32, 8, 128), (16, 1, 256), (8, 1, 64), (8, 2, 64), (12, 4, 128), (6, 3, 256), (64, 8, 128), (40, 2, 128), (9, 3, 64)]
 
 
