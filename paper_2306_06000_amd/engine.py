@@ -8,6 +8,10 @@ Per decode step (iteration-level scheduling, section 3 of the S3 paper):
   3. attention over the len rows now cached (append-then-attend: the new token attends to itself);
   4. sequences that reached their true total length are freed; with refill on, the next
      candidate of the pool is admitted into the freed room and its prompt rows are written.
+When a reservation cannot be doubled because no extent is large enough (supervisor paragraph of
+section 3): if the free space is merely fragmented the arena is compacted and the doubling repeated;
+otherwise the sequence's rows go to pinned host memory, its slot is freed, and it comes back with the
+doubled reservation as soon as a finished sequence has made room (before any newcomer).
 The event log lets a test replay the same decisions on the CPU oracle and compare every id,
 offset and capacity bit for bit.  Host-side state is kept in numpy arrays so that a step costs
 a few vector operations however large the batch is.
@@ -23,9 +27,16 @@ _TORCH_DT = {s3.S3_F16: torch.float16, s3.S3_BF16: torch.bfloat16, s3.S3_F32: to
 
 
 class DecodeEngine:
-    def __init__(self, w, arena_tokens=None, device="cuda:0", out_dtype=s3.S3_F32, log_events=True, fused=True):
+    def __init__(self, w, arena_tokens=None, device="cuda:0", out_dtype=s3.S3_F32, log_events=True, fused=True,
+                 on_nomem="swap"):
         self.w = w
         self.fused = fused  # True: one s3_decode_step launch per layer; False: append + attention calls
+        # "swap": compact, else evict to the host and re-admit later (the paper's supervisor); "drop": free
+        self.on_nomem = on_nomem
+        self.swapped = []     # evicted sequences waiting for room, oldest first
+        self._host_keep = []  # (event, pinned buffer): buffers of restores the stream may still be reading
+        self.n_swapped_out = self.n_swapped_in = self.n_compactions = 0
+        self.capacity = 0     # entries the device arrays can hold (the largest batch so far)
         self.dev = torch.device(device)
         self.cfg = s3.make_config(w.n_layers, w.n_heads, w.head_dim, w.dtype, w.granule, w.max_len, w.n_kv_heads, max(w.act_dtype, 0))
         self.bpt = s3.s3_kv_bytes_per_token(self.cfg)
@@ -93,11 +104,10 @@ class DecodeEngine:
                                 cap=int(self.cap[i]), len=int(self.len[i]), total=int(self.total[i]))
                 for i in range(self.n_active)]
 
-    def _upload(self, arr):
+    def _pinned(self, arr):
         # torch's pinned-memory allocator does not reuse a block before the copy that reads it has
         # completed, so the staging tensor needs no lifetime management here
-        host = torch.from_numpy(arr.copy()).pin_memory()
-        return host.to(self.dev, non_blocking=True)
+        return torch.from_numpy(arr.copy()).pin_memory()
 
     def _sync_arrays(self):
         if not self._dirty and self._patch:
@@ -105,14 +115,19 @@ class DecodeEngine:
             s3.check(s3.s3_kv_batch_patch(self.n_active, self.slot_off_dev, self.len_dev, idx, self.off[idx],
                                           self.len[idx], self._stream_ptr()), "s3_kv_batch_patch")
         self._patch.clear()
-        if self._dirty:  # a new batch: the arrays keep this size; a batch that shrinks later uses a prefix
-            self.slot_off_dev = self._upload(self.off)
-            self.len_dev = self._upload(self.len)
-            self.len_next = torch.empty_like(self.len_dev)
-            self.out_full = torch.empty((self.n_active, self.w.n_heads, self.w.head_dim),
-                                        dtype=_TORCH_DT[self.out_dtype], device=self.dev)
+        n = self.n_active
+        if self._dirty:  # a new batch (or every offset changed): upload; a batch that shrinks later uses a prefix
+            if n > self.capacity or self.slot_off_dev is None:
+                self.capacity = max(n, self.capacity)
+                self.slot_off_dev = torch.empty(self.capacity, dtype=torch.int64, device=self.dev)
+                self.len_dev = torch.empty(self.capacity, dtype=torch.int32, device=self.dev)
+                self.len_next = torch.empty_like(self.len_dev)
+                self.out_full = torch.empty((self.capacity, self.w.n_heads, self.w.head_dim),
+                                            dtype=_TORCH_DT[self.out_dtype], device=self.dev)
+            self.slot_off_dev[:n].copy_(self._pinned(self.off), non_blocking=True)
+            self.len_dev[:n].copy_(self._pinned(self.len), non_blocking=True)
             self._dirty = False
-        self.out = self.out_full[:self.n_active]
+        self.out = self.out_full[:n]
 
     def _set_batch(self, recs):
         self.serial = np.array([r[0] for r in recs], np.int64)
@@ -165,24 +180,75 @@ class DecodeEngine:
         full = np.nonzero(self.len == self.cap)[0]
         if full.size == 0:
             return
-        drop = []
+        drop, out = [], []
         for i in full.tolist():
-            st, off, cap = s3.s3_kv_grow(self.arena, int(self.slot[i]), int(self.len[i]), self._stream_ptr())
-            self._log("grow", int(self.serial[i]), int(self.slot[i]), int(self.len[i]), st, off, cap)
+            st, off, cap = self._grow(i)
+            if st == s3.S3_ERR_NOMEM and self.on_nomem == "swap" and self._compact_for(min(2 * int(self.cap[i]), self.w.max_len)):
+                st, off, cap = self._grow(i)
             if st == s3.S3_OK:
                 self.off[i], self.cap[i] = off, cap
                 self.n_grown += 1
                 self._patch.add(i)
+            elif st == s3.S3_ERR_NOMEM and self.on_nomem == "swap":
+                out.append(i)
             elif st in (s3.S3_ERR_NOMEM, s3.S3_ERR_MAXLEN):
-                drop.append(i)  # cannot continue on the device (the paper evicts such a sequence to the host)
+                drop.append(i)  # cannot continue: at the maximum length (or no host swap wanted)
             else:
                 s3.check(st, "s3_kv_grow")
+        for i in out:
+            self._evict(i)
         for i in drop:
             s3.check(s3.s3_kv_free(self.arena, int(self.slot[i])), "s3_kv_free")
             self._log("free", int(self.serial[i]), int(self.slot[i]))
             self.n_evicted += 1
-        if drop:
-            self._remove(drop)
+        if drop or out:
+            self._remove(drop + out)
+
+    def _grow(self, i):
+        st, off, cap = s3.s3_kv_grow(self.arena, int(self.slot[i]), int(self.len[i]), self._stream_ptr())
+        self._log("grow", int(self.serial[i]), int(self.slot[i]), int(self.len[i]), st, off, cap)
+        return st, off, cap
+
+    def _compact_for(self, want):
+        """Free space that is only fragmented: close the holes (every live slot belongs to the batch).
+        True if an extent of `want` tokens exists afterwards."""
+        st, used, free, largest, total = s3.s3_kv_stats(self.arena)
+        s3.check(st, "s3_kv_stats")
+        if free < want or largest >= want:
+            return False
+        st, new_off, moved = s3.s3_kv_compact(self.arena, self.slot, self.len, self._stream_ptr())
+        s3.check(st, "s3_kv_compact")
+        self._log("compact", self.slot.tolist(), new_off.tolist(), moved)
+        self.off[:] = new_off
+        self.n_compactions += 1
+        self._dirty = True
+        return True
+
+    def _evict(self, i):
+        """Rows of batch entry i to pinned host memory; the slot is freed (the entry is removed by the caller)."""
+        length, sid = int(self.len[i]), int(self.slot[i])
+        host = torch.empty(s3.s3_kv_evict_bytes(self.arena, length), dtype=torch.uint8, pin_memory=True)
+        s3.check(s3.s3_kv_evict(self.arena, sid, length, host, self._stream_ptr()), "s3_kv_evict")
+        self._log("evict", int(self.serial[i]), sid, length)
+        self.swapped.append(SimpleNamespace(serial=int(self.serial[i]), len=length, total=int(self.total[i]),
+                                            want=min(2 * int(self.cap[i]), self.w.max_len), host=host))
+        self.n_swapped_out += 1
+
+    def _restore_oldest(self):
+        """Try to bring the longest-waiting evicted sequence back with its doubled reservation.
+        -> (serial, slot, off, cap, len, total) or None (no room yet)."""
+        rec = self.swapped[0]
+        st, sid, off, cap = s3.s3_kv_restore(self.arena, rec.want, rec.len, rec.host, self._stream_ptr())
+        self._log("restore", rec.serial, rec.want, rec.len, st, sid, off, cap)
+        if st == s3.S3_ERR_NOMEM:
+            return None
+        s3.check(st, "s3_kv_restore")
+        self.swapped.pop(0)
+        ev = torch.cuda.Event()
+        ev.record(torch.cuda.current_stream(self.dev))
+        self._host_keep = [(e, h) for e, h in self._host_keep if not e.query()] + [(ev, rec.host)]
+        self.n_swapped_in += 1
+        return (rec.serial, sid, off, cap, rec.len, rec.total)
 
     def _remove(self, gone):
         """Take entries out of the batch without re-uploading it: the last entry moves into each hole
@@ -229,8 +295,8 @@ class DecodeEngine:
 
     def retire_and_refill(self, prefill):
         done = np.nonzero(self.len >= self.total)[0]
-        if done.size == 0:
-            return
+        if done.size == 0 and not (self.swapped and self.n_active == 0):
+            return  # nothing was freed (a batch that is entirely on the host must come back, though)
         keep = np.ones(self.n_active, bool)
         for i in done.tolist():
             s3.check(s3.s3_kv_free(self.arena, int(self.slot[i])), "s3_kv_free")
@@ -238,10 +304,17 @@ class DecodeEngine:
             self.n_retired += 1
             keep[i] = False
         new = []  # batch entries that received a newcomer
-        if self.w.refill:
-            for i in done.tolist():
-                if self.pool_pos >= len(self.w.pool):
-                    break
+        room = True  # an evicted sequence comes back before any newcomer; one refusal ends the attempts of this step
+        for i in done.tolist():
+            if self.swapped and room:
+                got = self._restore_oldest()
+                room = got is not None
+                if got:
+                    (self.serial[i], self.slot[i], self.off[i], self.cap[i], self.len[i], self.total[i]) = got
+                    keep[i] = True
+                    self._patch.add(i)
+                    continue
+            if self.w.refill and self.pool_pos < len(self.w.pool):
                 got = self.admit([self.w.pool[self.pool_pos]], prefill, fill=False)
                 self.pool_pos += 1
                 if got:
@@ -262,6 +335,17 @@ class DecodeEngine:
                 self._patch.update(new)
         if not keep.all():
             self._remove(np.nonzero(~keep)[0].tolist())
+        while self.swapped and room and self.n_active < self.capacity:
+            got = self._restore_oldest()
+            room = got is not None
+            if got:
+                self._append_entry(got)
+
+    def _append_entry(self, rec):
+        for name, v in zip(("serial", "slot", "off", "cap", "len", "total"), rec):
+            arr = getattr(self, name)
+            setattr(self, name, np.append(arr, np.asarray([v], arr.dtype)))
+        self._patch.add(self.n_active - 1)
 
     def step(self, tensors, prefill, check_host=False):
         self.grow_full_slots()

@@ -65,6 +65,7 @@ class OracleReplay:
                               act_dtype=None if w.act_dtype < 0 else w.act_dtype)
         self.sid = {}   # serial -> slot id
         self.len = {}   # serial -> rows cached
+        self.blobs = {} # serial -> rows of a sequence that is on the host
         self.step_idx = 0
 
     def replay(self, events, attend_steps=(), threads=8, precision="f32"):
@@ -90,6 +91,24 @@ class OracleReplay:
                 assert length == self.len[serial] == o.slots[sid][1]  # grown exactly when full
                 got = o.grow(sid, length)
                 assert got == (st, off, cap), ("grow", serial, got, (st, off, cap))
+            elif kind == "compact":
+                _, ids, new_off, moved = ev
+                offs, want_moved = o.compact()
+                assert [offs[i] for i in ids] == new_off and moved == want_moved, ("compact", moved, want_moved)
+            elif kind == "evict":
+                _, serial, sid, length = ev
+                assert self.sid.pop(serial) == sid and length == self.len[serial]
+                st, blob = o.evict(sid, length)
+                assert st == orc.OK
+                self.blobs[serial] = blob
+            elif kind == "restore":
+                _, serial, want, length, st, sid, off, cap = ev
+                assert length == self.len[serial]
+                got = o.restore(want, self.blobs[serial])
+                assert got == (st, sid, off, cap), ("restore", serial, got, (st, sid, off, cap))
+                if st == orc.OK:
+                    self.sid[serial] = sid
+                    del self.blobs[serial]
             elif kind == "free":
                 _, serial, sid = ev
                 assert self.sid.pop(serial) == sid

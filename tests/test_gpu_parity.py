@@ -669,6 +669,58 @@ def test_c3_shape_small_arena_28_layers():
     run_trace(w, 1, attend_steps=[0])
 
 
+def tight_workload(seed, n=12, n_layers=2, H=4, D=64, dtype=wl.F16, steps=260):
+    """Under-predicted sequences in an arena that cannot hold all their doubled reservations: the
+    doubling runs out of room, which is the supervisor's case (section 3)."""
+    rng = np.random.default_rng(seed)
+
+    def draw():
+        p, o = int(rng.integers(20, 60)), int(rng.integers(90, 240))
+        return wl.Seq(prompt=p, output=o, predicted=p + int(rng.integers(4, 40)))
+
+    return wl.Workload(f"tight-{seed}", 40 + seed, n_layers, H, D, dtype, 32, 512, n, steps, [draw() for _ in range(n)],
+                       [draw() for _ in range(3 * n)], True)
+
+
+@pytest.mark.parametrize("seed,arena_tokens", [(1, 1536), (2, 1280), (3, 2048)])
+def test_supervisor_path_compacts_evicts_and_readmits(seed, arena_tokens):
+    """Mispredictions in a tight arena: a doubling that finds no extent first compacts (when the free
+    space is only fragmented), else the sequence goes to pinned host memory and returns with the doubled
+    reservation once a finished sequence has made room.  Every id, offset and capacity the library
+    answered, the rows of every live slot and the attention outputs must equal the oracle's replay."""
+    from paper_2306_06000_amd.engine import DecodeEngine
+
+    w = tight_workload(seed)
+    eng = DecodeEngine(w, arena_tokens=arena_tokens)
+    prefill, tensors_for = make_sources(w, eng)
+    eng.start(prefill, stop_when_full=True)
+    attend = sorted({0, 60, 130, 200, w.steps - 1})
+    got = {}
+    for t in range(w.steps):
+        if eng.n_active == 0 and not eng.swapped:
+            break
+        out = eng.step(tensors_for(t), prefill, check_host=True)
+        if t in attend and out is not None:
+            got[t] = out.float().cpu().numpy()
+    kinds = [e[0] for e in eng.events]
+    print(f"tight {seed}: grows {eng.n_grown} compactions {eng.n_compactions} out {eng.n_swapped_out} in {eng.n_swapped_in} "
+          f"still on host {len(eng.swapped)} batch {eng.n_active}")
+    rep = OracleReplay(w, eng.arena_tokens)
+    outs = rep.replay(eng.events, attend_steps=set(got))
+    for t in got:
+        assert_close(got[t], outs[t][2], f"{w.name} step {t}")
+    for a in eng.active:
+        sid = rep.sid[a.serial]
+        assert sid == a.slot and rep.o.slots[sid] == [a.off, a.cap] and rep.len[a.serial] == a.len
+        for layer in range(w.n_layers):
+            for which in (0, 1):
+                assert np.array_equal(eng.read_slot(a, layer, which), rep.o.rows(sid, layer, which, a.len))
+    assert s3.s3_kv_stats(eng.arena) == (0, *rep.o.stats())
+    assert eng.n_swapped_out >= 1 and eng.n_swapped_in >= 1 and "restore" in kinds
+    assert {r.serial for r in eng.swapped} == set(rep.blobs)
+    eng.close()
+
+
 # ---------------------------------------------------------------- seeded random configurations
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_against_the_oracle(seed):
