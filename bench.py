@@ -43,6 +43,9 @@ def parse():
                     "default is the configuration the metric is quoted on")
     ap.add_argument("--unfused", action="store_true", help="append + attention + merge kernels instead of one")
     ap.add_argument("--drain", action="store_true", help="finished sequences are not replaced: the batch shrinks")
+    ap.add_argument("--on-nomem", choices=("swap", "drop"), default="swap", help="a reservation that cannot be doubled: "
+                    "swap = compaction or eviction to the host and later re-admission (the paper's supervisor; default), "
+                    "drop = the sequence leaves the batch")
     ap.add_argument("--flush-mb", type=int, default=0, help="diagnostic: overwrite a buffer of this many MB between "
                     "steps so that the memory-side cache holds none of the previous step's rows; every launch is "
                     "then bracketed and only roofline.* is meaningful (value includes the flushes)")
@@ -175,7 +178,7 @@ def main():
     shared_kv = w.kv_heads < w.n_heads  # not one of the paper's models: measured as a widening, not the headline
     steps = args.steps if args.steps is not None else DEFAULT_STEPS[args.workload][0]
     warmup = args.warmup if args.warmup is not None else DEFAULT_STEPS[args.workload][1]
-    eng = DecodeEngine(w, log_events=False, fused=not args.unfused)
+    eng = DecodeEngine(w, log_events=False, fused=not args.unfused, on_nomem=args.on_nomem)
     if args.variant >= 0:
         s3.check(s3.s3_kv_set_param(eng.arena, "variant", args.variant))
     if args.chunk:
@@ -231,6 +234,8 @@ def main():
                    "mean_context_at_start": round(float(lens_at_start.mean()), 1),
                    "batch_at_end": int(eng.n_active), "refill": bool(w.refill),
                    "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,
+                   "swapped_out": eng.n_swapped_out, "swapped_in": eng.n_swapped_in, "compactions": eng.n_compactions,
+                   "dropped": eng.n_evicted, "on_nomem": args.on_nomem,
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
                    "algorithmic_GB_per_step": round(total_bytes / args.steps / 1e9, 4),
                    "path": "quantising append + shared-kv matrix-core attention over 8-bit rows + merge per layer" if shared_kv and w.dtype == 3 else

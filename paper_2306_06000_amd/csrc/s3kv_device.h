@@ -59,8 +59,7 @@ __device__ __forceinline__ float group_sum(float v) {
     v = dpp_sum_step<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2
     if (LANES >= 8) v = dpp_sum_step<0x141>(v);  // row_half_mirror: the other quad of each 8
     if (LANES >= 16) v = dpp_sum_step<0x140>(v);  // row_mirror: the other 8 of each 16
-    if (LANES >= 32)
-    {
+    if (LANES >= 32) {
         const int bits = __builtin_bit_cast(int, v);
         const int other = __builtin_amdgcn_ds_swizzle(bits, 0x401F);  // lane ^ 16
         v += __builtin_bit_cast(float, other);

@@ -118,7 +118,7 @@ struct FillArgs {
     char *kdst[S3_FILL_MAX];
     char *vdst[S3_FILL_MAX];
     int64_t off[S3_FILL_MAX];
-    uint32_t n16[S3_FILL_MAX];
+    uint64_t n16[S3_FILL_MAX];  // 16-byte pieces of one plane's rows (max_len rows of up to 64 KiB reach 2^32)
     int32_t idx[S3_FILL_MAX];
     int32_t rows[S3_FILL_MAX];
 };
@@ -163,7 +163,7 @@ extern "C" int s3_kv_fill_batch(s3_arena *a, int32_t layer, int32_t n_new, const
             f.vsrc[i] = (const char *)v_rows[first + i];
             f.kdst[i] = a->plane(layer, 0) + s->off * a->row_bytes;
             f.vdst[i] = a->plane(layer, 1) + s->off * a->row_bytes;
-            f.n16[i] = (uint32_t)n16;
+            f.n16[i] = n16;
             f.off[i] = s->off;
             f.idx[i] = patch ? batch_idx[first + i] : 0;
             f.rows[i] = n_rows[first + i];
@@ -587,7 +587,6 @@ static const Variant kVariants[] = {
 #undef X
 };
 int s3i_num_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0])); }
-
 
 template <int DT, int D, bool FUSED>
 static attn_fn pick_variant(int v) {

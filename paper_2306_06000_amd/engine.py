@@ -27,6 +27,8 @@ _TORCH_DT = {s3.S3_F16: torch.float16, s3.S3_BF16: torch.bfloat16, s3.S3_F32: to
 
 
 class DecodeEngine:
+    COMPACT_RATIO = 48  # live tokens per token of the wanted slot up to which compaction is preferred to a swap
+
     def __init__(self, w, arena_tokens=None, device="cuda:0", out_dtype=s3.S3_F32, log_events=True, fused=True,
                  on_nomem="swap"):
         self.w = w
@@ -35,6 +37,9 @@ class DecodeEngine:
         self.on_nomem = on_nomem
         self.swapped = []     # evicted sequences waiting for room, oldest first
         self._host_keep = []  # (event, pinned buffer): buffers of restores the stream may still be reading
+        self._host_free = []  # pinned buffers ready for reuse
+        self._side = None     # stream the evictions copy on, beside the decode steps
+        self._evict_done = [] # events of evictions whose freed rows the main stream must not overwrite yet
         self.n_swapped_out = self.n_swapped_in = self.n_compactions = 0
         self.capacity = 0     # entries the device arrays can hold (the largest batch so far)
         self.dev = torch.device(device)
@@ -50,6 +55,9 @@ class DecodeEngine:
         self.arena_mem = torch.empty(self.arena_tokens * self.bpt, dtype=torch.uint8, device=self.dev)
         st, self.arena = s3.s3_kv_arena_init(self.cfg, self.arena_mem, self.arena_mem.numel())
         s3.check(st, "s3_kv_arena_init")
+        if on_nomem == "swap":  # pinning is slow: two buffers that hold any sequence are pinned up front
+            self._side = torch.cuda.Stream(self.dev)
+            self._host_free = [torch.empty(w.max_len * self.bpt, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
         self.out_dtype = out_dtype
         self.events = [] if log_events else None
         self.next_serial = 0
@@ -84,6 +92,13 @@ class DecodeEngine:
 
     def _stream_ptr(self):
         return torch.cuda.current_stream(self.dev).cuda_stream
+
+    def _guard_freed_rows(self):
+        """Before anything on the main stream may write into space an eviction has freed (a fill, the copy of
+        a doubling, a compaction, a reload): wait until the eviction's copies to the host have read it."""
+        for ev in self._evict_done:
+            torch.cuda.current_stream(self.dev).wait_event(ev)
+        self._evict_done.clear()
 
     def kv_dtype_torch(self):
         """torch type of cache rows handed to fill (8-bit caches: raw codes)."""
@@ -145,6 +160,7 @@ class DecodeEngine:
         prefill(serial, layer, rows) -> (k_rows, v_rows) device tensors [rows][H][D].
         Returns (serial, slot, off, cap, len, total) of the admitted ones."""
         preds = [s.predicted for s in seqs]
+        self._guard_freed_rows()
         rc, ids, offs, caps = s3.s3_kv_alloc(self.arena, preds)
         s3.check(rc, "s3_kv_alloc")
         admitted = []
@@ -205,6 +221,7 @@ class DecodeEngine:
             self._remove(drop + out)
 
     def _grow(self, i):
+        self._guard_freed_rows()
         st, off, cap = s3.s3_kv_grow(self.arena, int(self.slot[i]), int(self.len[i]), self._stream_ptr())
         self._log("grow", int(self.serial[i]), int(self.slot[i]), int(self.len[i]), st, off, cap)
         return st, off, cap
@@ -216,6 +233,11 @@ class DecodeEngine:
         s3.check(st, "s3_kv_stats")
         if free < want or largest >= want:
             return False
+        # Compaction moves up to every live row through HBM; swapping one sequence moves its rows over the
+        # host link twice, some fifty times slower per byte: compact only while that is the cheaper of the two.
+        if used > self.COMPACT_RATIO * want:
+            return False
+        self._guard_freed_rows()
         st, new_off, moved = s3.s3_kv_compact(self.arena, self.slot, self.len, self._stream_ptr())
         s3.check(st, "s3_kv_compact")
         self._log("compact", self.slot.tolist(), new_off.tolist(), moved)
@@ -227,17 +249,41 @@ class DecodeEngine:
     def _evict(self, i):
         """Rows of batch entry i to pinned host memory; the slot is freed (the entry is removed by the caller)."""
         length, sid = int(self.len[i]), int(self.slot[i])
-        host = torch.empty(s3.s3_kv_evict_bytes(self.arena, length), dtype=torch.uint8, pin_memory=True)
-        s3.check(s3.s3_kv_evict(self.arena, sid, length, host, self._stream_ptr()), "s3_kv_evict")
+        host = self._host_buffer(s3.s3_kv_evict_bytes(self.arena, length))
+        # the copies run on a side stream, after everything the main stream has enqueued so far, and overlap
+        # with the decode steps that follow (those touch live slots only)
+        main = torch.cuda.current_stream(self.dev)
+        ready, done = torch.cuda.Event(), torch.cuda.Event()
+        ready.record(main)
+        self._side.wait_event(ready)
+        s3.check(s3.s3_kv_evict(self.arena, sid, length, host, self._side.cuda_stream), "s3_kv_evict")
+        done.record(self._side)
+        self._evict_done.append(done)
         self._log("evict", int(self.serial[i]), sid, length)
         self.swapped.append(SimpleNamespace(serial=int(self.serial[i]), len=length, total=int(self.total[i]),
                                             want=min(2 * int(self.cap[i]), self.w.max_len), host=host))
         self.n_swapped_out += 1
 
+    def _host_buffer(self, nbytes):
+        """Pinned staging memory for one evicted sequence: a buffer whose reload has completed is reused
+        (pinning memory costs far more than the copy it serves)."""
+        still = []
+        for e, h in self._host_keep:
+            if e.query():
+                self._host_free.append(h)
+            else:
+                still.append((e, h))
+        self._host_keep = still
+        for k, h in enumerate(self._host_free):
+            if h.numel() >= nbytes:
+                return self._host_free.pop(k)
+        return torch.empty(self.w.max_len * self.bpt, dtype=torch.uint8, pin_memory=True)
+
     def _restore_oldest(self):
         """Try to bring the longest-waiting evicted sequence back with its doubled reservation.
         -> (serial, slot, off, cap, len, total) or None (no room yet)."""
         rec = self.swapped[0]
+        self._guard_freed_rows()  # also: the rows of `rec` have reached its host buffer
         st, sid, off, cap = s3.s3_kv_restore(self.arena, rec.want, rec.len, rec.host, self._stream_ptr())
         self._log("restore", rec.serial, rec.want, rec.len, st, sid, off, cap)
         if st == s3.S3_ERR_NOMEM:
@@ -246,7 +292,7 @@ class DecodeEngine:
         self.swapped.pop(0)
         ev = torch.cuda.Event()
         ev.record(torch.cuda.current_stream(self.dev))
-        self._host_keep = [(e, h) for e, h in self._host_keep if not e.query()] + [(ev, rec.host)]
+        self._host_keep.append((ev, rec.host))
         self.n_swapped_in += 1
         return (rec.serial, sid, off, cap, rec.len, rec.total)
 
