@@ -35,7 +35,7 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time the attention kernel with events")
     ap.add_argument("--event-every", type=int, default=16,
-                    help="bracket every k-th attention launch with HIP events (each bracket costs a few us)")
+                    help="every k-th attention launch carries start/stop events (an evented launch costs a few us)")
     ap.add_argument("--c3-bytes", type=float, default=200e9)
     ap.add_argument("--heads", type=str, default="", help="c5 only: query heads, kv heads, head dim as Q,KV,D")
     ap.add_argument("--kv8", action="store_true", help="c5 only: e4m3 cache rows (bf16 queries) on top of the shared heads")

@@ -265,15 +265,15 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *   "grid_blocks"  workgroups launched (0 = library default)
  *   "variant"      kernel variant index, -1 = default (see get "n_variants"; arenas with shared
  *                  key/value heads have their own, shorter, list)
- *   "profile"      k > 0: bracket every k-th attention launch (counted from this call) with HIP events
- *                  on its stream; 0: off; both reset the sums
+ *   "profile"      k > 0: every k-th attention launch (counted from this call) carries HIP events that
+ *                  take the kernel's own start and end times (hipExtLaunchKernel); 0: off; both reset the sums
  * get names: the above plus "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,
  * 2 shared-K/V matrix-core kernel, 3 kernel for 8-bit rows, 4 matrix-core kernel over 8-bit rows with
  * shared heads: what the next attention launch uses), "n_variants", "n_grows",
  * "live_slots", "scratch_bytes", "num_cus" and,
  * after "profile" k, "profile_launches", "profile_partial_ns", "profile_merge_ns" (sums over the
  * timed launches since the last reset) and "profile_p10_ns", "profile_p50_ns", "profile_p90_ns"
- * (nearest-rank percentiles of the attention kernel's bracketed duration); reading them waits for
+ * (nearest-rank percentiles of the attention kernel's duration); reading them waits for
  * the recorded events.
  * Returns S3_ERR_INVALID for an unknown name or a value out of range. */
 int s3_kv_set_param(s3_arena *a, const char *name /*HOST*/, int64_t value);

@@ -21,6 +21,7 @@
 // in the epilogue wave of whichever workgroup delivers the last chunk.  Score s_j = q.K_j * scale
 // as in the section 2.1 equation of the S3 paper; softmax is max-subtracted; everything after the
 // 16-bit loads is fp32.
+#include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
@@ -834,11 +835,16 @@ static int launch_attn_kernels(s3_arena *a, attn_fn fn, int blocks, int threads,
             const int prc = prof_next_event(a, &ev[i]);
             if (prc != S3_OK) return prc;
         }
-        HIP_TRY(hipEventRecord(ev[0], (hipStream_t)stream));
+        // the events take the kernel's own start and end times (not the times at which markers around it
+        // pass through the queue), so the duration is the one a profiler reports for the dispatch
+        AttnArgs copy = args;
+        void *kargs[] = {(void *)&copy};
+        HIP_TRY(hipExtLaunchKernel((const void *)fn, dim3((unsigned)blocks), dim3((unsigned)threads), kargs, dyn_lds,
+                                   (hipStream_t)stream, ev[0], ev[1], 0));
+    } else {
+        hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)threads), dyn_lds, (hipStream_t)stream, args);
+        HIP_TRY(hipGetLastError());
     }
-    hipLaunchKernelGGL(fn, dim3((unsigned)blocks), dim3((unsigned)threads), dyn_lds, (hipStream_t)stream, args);
-    HIP_TRY(hipGetLastError());
-    if (timed) HIP_TRY(hipEventRecord(ev[1], (hipStream_t)stream));
     if (merge_heads > 0) {
         const int D = a->cfg.head_dim;
         AttnArgs margs = args;
@@ -847,10 +853,17 @@ static int launch_attn_kernels(s3_arena *a, attn_fn fn, int blocks, int threads,
         const unsigned mblocks = (unsigned)(((int64_t)args.n * ((merge_heads + GH - 1) / GH) + 3) / 4);
         void (*mfn)(const AttnArgs) =
             D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
-        hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, margs);
-        HIP_TRY(hipGetLastError());
+        if (timed) {
+            void *kargs[] = {(void *)&margs};
+            HIP_TRY(hipExtLaunchKernel((const void *)mfn, dim3(mblocks), dim3(256), kargs, 0, (hipStream_t)stream, nullptr,
+                                       ev[2], 0));
+        } else {
+            hipLaunchKernelGGL(mfn, dim3(mblocks), dim3(256), 0, (hipStream_t)stream, margs);
+            HIP_TRY(hipGetLastError());
+        }
+    } else if (timed) {
+        HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
     }
-    if (timed) HIP_TRY(hipEventRecord(ev[2], (hipStream_t)stream));
     return S3_OK;
 }
 
