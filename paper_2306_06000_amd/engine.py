@@ -30,8 +30,12 @@ class DecodeEngine:
     COMPACT_RATIO = 48  # live tokens per token of the wanted slot up to which compaction is preferred to a swap
 
     def __init__(self, w, arena_tokens=None, device="cuda:0", out_dtype=s3.S3_F32, log_events=True, fused=True,
-                 on_nomem="swap"):
+                 on_nomem="swap", admission="fifo"):
         self.w = w
+        # "fifo": candidates in pool order, each admitted iff it fits; "dff": the library's scheduler picks
+        # them, largest reservation first, from everything that waits (section 3, scheduler paragraph)
+        self.admission = admission
+        self.sched = None
         self.fused = fused  # True: one s3_decode_step launch per layer; False: append + attention calls
         # "swap": compact, else evict to the host and re-admit later (the paper's supervisor); "drop": free
         self.on_nomem = on_nomem
@@ -55,6 +59,12 @@ class DecodeEngine:
         self.arena_mem = torch.empty(self.arena_tokens * self.bpt, dtype=torch.uint8, device=self.dev)
         st, self.arena = s3.s3_kv_arena_init(self.cfg, self.arena_mem, self.arena_mem.numel())
         s3.check(st, "s3_kv_arena_init")
+        if admission == "dff":
+            st, self.sched = s3.s3_sched_create(self.arena)
+            s3.check(st, "s3_sched_create")
+            self._requests = list(w.seqs) + list(w.pool)  # request id = position in this list
+            for rid, r in enumerate(self._requests):
+                s3.check(s3.s3_sched_submit(self.sched, rid, r.predicted), "s3_sched_submit")
         if on_nomem == "swap":  # pinning is slow: two buffers that hold any sequence are pinned up front
             self._side = torch.cuda.Stream(self.dev)
             self._host_free = [torch.empty(w.max_len * self.bpt, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
@@ -83,6 +93,9 @@ class DecodeEngine:
     def close(self):
         if self.arena is not None:
             torch.cuda.synchronize(self.dev)
+            if self.sched is not None:
+                s3.s3_sched_destroy(self.sched)
+                self.sched = None
             s3.s3_kv_arena_destroy(self.arena)
             self.arena = None
 
@@ -179,9 +192,33 @@ class DecodeEngine:
             admitted.append((serial, sid, off, cap, rows, s.total))
         return admitted
 
+    def admit_scheduled(self, max_out, prefill, fill=True):
+        """Let the scheduler admit up to max_out waiting requests (decreasing first fit).  Same return value
+        as admit()."""
+        if max_out <= 0 or s3.s3_sched_pool_size(self.sched) == 0:
+            return []
+        self._guard_freed_rows()
+        rc, rids, sids, offs, caps = s3.s3_sched_admit(self.sched, max_out)
+        s3.check(rc, "s3_sched_admit")
+        serials = list(range(self.next_serial, self.next_serial + len(rids)))
+        self.next_serial += len(rids)
+        self._log("sched_admit", max_out, serials, rids.tolist(), sids.tolist(), offs.tolist(), caps.tolist())
+        admitted = []
+        for serial, rid, sid, off, cap in zip(serials, rids.tolist(), sids.tolist(), offs.tolist(), caps.tolist()):
+            r = self._requests[rid]
+            for layer in range(self.w.n_layers if fill else 0):
+                k_rows, v_rows = prefill(serial, layer, r.start)
+                s3.check(s3.s3_kv_fill(self.arena, sid, layer, 0, r.start, k_rows, v_rows, self._stream_ptr()),
+                         "s3_kv_fill")
+            self._log("fill", serial, sid, r.start)
+            admitted.append((serial, sid, off, cap, r.start, r.total))
+        return admitted
+
     def start(self, prefill, stop_when_full=False):
         recs = []
-        if stop_when_full:  # admit candidates one by one until the arena refuses one
+        if self.admission == "dff":
+            recs = self.admit_scheduled(self.w.batch, prefill)
+        elif stop_when_full:  # admit candidates one by one until the arena refuses one
             for s in self.w.seqs:
                 got = self.admit([s], prefill)
                 if not got:
@@ -360,13 +397,19 @@ class DecodeEngine:
                     keep[i] = True
                     self._patch.add(i)
                     continue
-            if self.w.refill and self.pool_pos < len(self.w.pool):
+            if self.admission == "fifo" and self.w.refill and self.pool_pos < len(self.w.pool):
                 got = self.admit([self.w.pool[self.pool_pos]], prefill, fill=False)
                 self.pool_pos += 1
                 if got:
                     (self.serial[i], self.slot[i], self.off[i], self.cap[i], self.len[i], self.total[i]) = got[0]
                     keep[i] = True
                     new.append(i)
+        if self.admission == "dff" and self.w.refill:  # one scheduler pass for all entries that are still open
+            holes = np.nonzero(~keep)[0].tolist()
+            for i, got in zip(holes, self.admit_scheduled(len(holes), prefill, fill=False)):
+                (self.serial[i], self.slot[i], self.off[i], self.cap[i], self.len[i], self.total[i]) = got
+                keep[i] = True
+                new.append(i)
         if new:
             # the prompt rows of all newcomers of this step in one launch per layer; if the batch keeps its
             # shape, the first launch also writes their entries of the device arrays

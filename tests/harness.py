@@ -66,6 +66,7 @@ class OracleReplay:
         self.sid = {}   # serial -> slot id
         self.len = {}   # serial -> rows cached
         self.blobs = {} # serial -> rows of a sequence that is on the host
+        self.sched = None
         self.step_idx = 0
 
     def replay(self, events, attend_steps=(), threads=8, precision="f32"):
@@ -91,6 +92,16 @@ class OracleReplay:
                 assert length == self.len[serial] == o.slots[sid][1]  # grown exactly when full
                 got = o.grow(sid, length)
                 assert got == (st, off, cap), ("grow", serial, got, (st, off, cap))
+            elif kind == "sched_admit":
+                _, max_out, serials, rids, sids, offs, caps = ev
+                if self.sched is None:  # every request waits in the scheduler from the start
+                    self.sched = orc.SchedulerOracle(o)
+                    for rid, r in enumerate(list(w.seqs) + list(w.pool)):
+                        self.sched.submit(rid, r.predicted)
+                got = self.sched.admit(max_out)
+                assert got == list(zip(rids, sids, offs, caps)), ("sched_admit", got, ev)
+                for serial, sid in zip(serials, sids):
+                    self.sid[serial] = sid
             elif kind == "compact":
                 _, ids, new_off, moved = ev
                 offs, want_moved = o.compact()

@@ -522,10 +522,10 @@ def test_batch_patch_rewrites_only_the_named_entries():
 
 
 # ---------------------------------------------------------------- traces
-def run_trace(w, steps, attend_steps, arena_tokens=None, variant=None, chunk=None, sample=None, fused=True):
+def run_trace(w, steps, attend_steps, arena_tokens=None, variant=None, chunk=None, sample=None, fused=True, admission="fifo"):
     from paper_2306_06000_amd.engine import DecodeEngine
 
-    eng = DecodeEngine(w, arena_tokens=arena_tokens, fused=fused)
+    eng = DecodeEngine(w, arena_tokens=arena_tokens, fused=fused, admission=admission)
     if variant is not None:
         s3.s3_kv_set_param(eng.arena, "variant", variant)
     if chunk is not None:
@@ -682,8 +682,17 @@ def tight_workload(seed, n=12, n_layers=2, H=4, D=64, dtype=wl.F16, steps=260):
                        [draw() for _ in range(3 * n)], True)
 
 
-@pytest.mark.parametrize("seed,arena_tokens", [(1, 1536), (2, 1280), (3, 2048)])
-def test_supervisor_path_compacts_evicts_and_readmits(seed, arena_tokens):
+def test_c1_trace_with_the_scheduler_admitting():
+    """The batch is chosen by the library's scheduler (largest reservation first, from the initial
+    candidates and the refill pool together) instead of in arrival order; the oracle's scheduler must
+    pick the same requests and get the same slots at every iteration."""
+    w = wl.c1(batch=24, steps=64)
+    run_trace(w, w.steps, attend_steps=[0, 30, 63], admission="dff")  # the longest come first: few finish here;
+    # refills through the scheduler are exercised by the tight-arena trace below
+
+
+@pytest.mark.parametrize("seed,arena_tokens,admission", [(1, 1536, "fifo"), (2, 1280, "fifo"), (3, 2048, "fifo"), (1, 1536, "dff")])
+def test_supervisor_path_compacts_evicts_and_readmits(seed, arena_tokens, admission):
     """Mispredictions in a tight arena: a doubling that finds no extent first compacts (when the free
     space is only fragmented), else the sequence goes to pinned host memory and returns with the doubled
     reservation once a finished sequence has made room.  Every id, offset and capacity the library
@@ -691,7 +700,7 @@ def test_supervisor_path_compacts_evicts_and_readmits(seed, arena_tokens):
     from paper_2306_06000_amd.engine import DecodeEngine
 
     w = tight_workload(seed)
-    eng = DecodeEngine(w, arena_tokens=arena_tokens)
+    eng = DecodeEngine(w, arena_tokens=arena_tokens, admission=admission)
     prefill, tensors_for = make_sources(w, eng)
     eng.start(prefill, stop_when_full=True)
     attend = sorted({0, 60, 130, 200, w.steps - 1})
