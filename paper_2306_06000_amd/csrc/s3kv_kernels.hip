@@ -930,8 +930,9 @@ static int launch_attention(s3_arena *a, const AttnCall &c) {
     if (a->cfg.kv_dtype == S3_E4M3) return launch_fp8(a, c);
     const int D = a->cfg.head_dim, H = a->cfg.n_heads;
     // Defaults from sweeps on MI355X: large chunks keep most contexts in one piece (no cross-workgroup
-    // merge), eight waves share an item's rows evenly.
-    const int variant = a->variant >= 0 ? a->variant : 1;
+    // merge), eight waves share an item's rows evenly, each with two batches of two rows in flight
+    // alternately (1 % ahead of one batch of four rows on the ragged batch of 64, level on the others).
+    const int variant = a->variant >= 0 ? a->variant : 12;
     const Variant &vr = kVariants[variant];
     const bool fused = c.with_append;
     attn_fn fn = fused ? pick_kernel<true>(a->cfg.kv_dtype, D, variant) : pick_kernel<false>(a->cfg.kv_dtype, D, variant);
