@@ -111,9 +111,9 @@ __global__ void __launch_bounds__(TS * 64) attn_fp8_kernel(const AttnArgs a) {
         // streams the rows before it and takes the new row in its last wave (below)
         const bool has_new = a.k_new != nullptr && end == it.len;
         const int end_mem = has_new ? end - 1 : end;
-        // the new row costs its wave one more memory round trip, about what a batch of U rows costs: its
+        // the new row costs its wave one more memory round trip, about what a batch of four rows costs: its
         // share of the streamed rows is shorter by that much
-        const int per = (end_mem - start + (has_new ? U : 0) + TS - 1) / TS;
+        const int per = (end_mem - start + (has_new ? 4 : 0) + TS - 1) / TS;
         const int j0 = min(end_mem, start + ts * per), j1 = min(end_mem, j0 + per);
         const char *kp = a.kplane + it.off * (int64_t)rs32 + hc * D + dl * 16;
         const char *vp = a.vplane + it.off * (int64_t)rs32 + hc * D + dl * 16;
@@ -292,7 +292,7 @@ static attn_fn pick_fp8_shape(int shape) {
 }
 
 attn_fn s3i_pick_fp8(int act, int d, int shape, int *threads) {
-    if (shape < 0 || shape >= s3i_num_fp8_shapes()) shape = 0;
+    if (shape < 0 || shape >= s3i_num_fp8_shapes()) shape = 2;  // measured best on MI355X: eight waves, two rows per round
     *threads = kFp8Shapes[shape].ts * 64;
     if (act == S3_F16) {
         if (d == 64) return pick_fp8_shape<S3_F16, 64>(shape);
