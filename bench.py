@@ -1,12 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the decode hot path (grow check, append, ragged attention, retire/refill) on ONE
-MI355X, through the C ABI of libs3kv.so, on the synthetic workload C1 of the benchmark spec
-(GPT-J-shaped layer, batch 64, 128 consecutive decode steps) unless --workload says otherwise.
+MI355X, through the C ABI of libs3kv.so, on the synthetic workload C1 (GPT-J-shaped layer, batch 64,
+128 consecutive decode steps: the configuration the headline metric is quoted on) unless --workload
+says otherwise.
 
 Prints ONE JSON line.  `value` is algorithmic bytes moved per second over the whole timed
 region (all kernels, host bookkeeping included), inputs resident in HBM.  `roofline` is for the
-dominant kernel (the split attention kernel), timed with HIP events on the launch stream inside
-the same timed region.  `cpu_baseline` is the CPU oracle timed on this machine's host cores on a
+dominant kernel (the attention kernel of the workload's cache type), timed with HIP events bound to
+the kernel's own start and end, inside the same timed region.  `cpu_baseline` is the CPU oracle timed on this machine's host cores on a
 bounded sample of the same workload.
 """
 import argparse
