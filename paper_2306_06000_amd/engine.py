@@ -65,9 +65,10 @@ class DecodeEngine:
             self._requests = list(w.seqs) + list(w.pool)  # request id = position in this list
             for rid, r in enumerate(self._requests):
                 s3.check(s3.s3_sched_submit(self.sched, rid, r.predicted), "s3_sched_submit")
-        if on_nomem == "swap":  # pinning is slow: two buffers that hold any sequence are pinned up front
+        if on_nomem == "swap":  # pinning is slow: eight buffers of a quarter of the longest sequence are pinned up front
             self._side = torch.cuda.Stream(self.dev)
-            self._host_free = [torch.empty(w.max_len * self.bpt, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
+            quarter = max(w.granule, w.max_len // 4) * self.bpt
+            self._host_free = [torch.empty(quarter, dtype=torch.uint8, pin_memory=True) for _ in range(8)]
         self.out_dtype = out_dtype
         self.events = [] if log_events else None
         self.next_serial = 0
@@ -311,10 +312,10 @@ class DecodeEngine:
             else:
                 still.append((e, h))
         self._host_keep = still
-        for k, h in enumerate(self._host_free):
-            if h.numel() >= nbytes:
-                return self._host_free.pop(k)
-        return torch.empty(self.w.max_len * self.bpt, dtype=torch.uint8, pin_memory=True)
+        fits = [k for k, h in enumerate(self._host_free) if h.numel() >= nbytes]
+        if fits:  # the smallest that fits
+            return self._host_free.pop(min(fits, key=lambda k: self._host_free[k].numel()))
+        return torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
 
     def _restore_oldest(self):
         """Try to bring the longest-waiting evicted sequence back with its doubled reservation.
