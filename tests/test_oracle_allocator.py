@@ -35,9 +35,9 @@ def test_bytes_per_token_and_max_length_reservation_match_the_paper():
     g = golden_bytes()
     o = neox(0)
     assert o.bytes_per_token == g["bytes_per_token"] == 4 * g["n_layers"] * g["hidden"]
-    assert abs(o.bytes_per_token / 2**20 - 1.0) < 0.05  # "1MB per token"
+    assert abs(o.bytes_per_token / 2**20 - 1.0) < 0.05  # the paper rounds this to 1 MB per token
     assert o.bytes_per_token * g["max_len"] == g["bytes_per_max_reservation"]
-    assert round(g["bytes_per_max_reservation"] / 1e9, 1) == 2.2  # "2.2GB per sequence"
+    assert round(g["bytes_per_max_reservation"] / 1e9, 1) == 2.2  # the paper rounds this to 2.2 GB per sequence
 
 
 @pytest.mark.parametrize("key_bytes,key_batch", [("free_bytes_decimal", "max_batch_decimal"),
