@@ -261,7 +261,8 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
 
 /* Launch-shape knobs of the attention kernels and measurement switches.  set names:
  *   "chunk"        tokens per split-K chunk (multiple of 32, 32..2048; 0 = library default)
- *   "classes"      length classes of the longest-first work order (1..8; 0 = library default)
+ *   "classes"      length classes of the longest-first work order (1..8; 0 = library default); a batch of
+ *                  thousands of sequences keeps as many as fit the workgroup's memory
  *   "grid_blocks"  workgroups launched (0 = library default)
  *   "variant"      kernel variant index, -1 = default (see get "n_variants"; arenas with shared
  *                  key/value heads have their own, shorter, list)

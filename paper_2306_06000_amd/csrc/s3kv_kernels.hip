@@ -761,6 +761,8 @@ struct AttnCall {
     int32_t *len_out;
 };
 
+static size_t batch_view_lds(int n, int ncls);
+
 // Kernel arguments every attention kernel shares.  row_heads: heads of a cached row; q_heads: heads of q / out.
 static AttnArgs common_args(const s3_arena *a, const AttnCall &c, int row_heads, int q_heads, int chunk) {
     AttnArgs args;
@@ -783,6 +785,9 @@ static AttnArgs common_args(const s3_arena *a, const AttnCall &c, int row_heads,
     // short, the tail matters); for large batches the extra prologue work per class costs more than
     // the order gains.  Measured on MI355X.
     args.ncls = a->ncls > 0 ? a->ncls : c.n <= 128 ? 4 : c.n <= 256 ? 2 : 1;
+    // the view must fit LDS beside the kernels' own buffers (up to 41 KiB) whatever the caller asked for:
+    // a batch of thousands keeps fewer classes
+    while (args.ncls > 1 && batch_view_lds(c.n, args.ncls) > (size_t)96 * 1024) args.ncls--;
     args.out_dtype = c.out_dtype;
     args.max_len = a->cfg.max_len;
     args.len_add = c.with_append ? 1 : 0;

@@ -734,6 +734,50 @@ def test_supervisor_path_compacts_evicts_and_readmits(seed, arena_tokens, admiss
     eng.close()
 
 
+@pytest.mark.parametrize("H,Hkv", [(2, None), (4, 1)])
+def test_largest_batch_one_call_takes(H, Hkv):
+    """4095 sequences in one call (the documented maximum; one more is refused), short ragged contexts,
+    attention and a decode step, with the default work order and with eight length classes requested
+    (the library keeps as many as fit its workgroup memory).  Multi-head kernels, and the matrix-core
+    kernel for shared heads."""
+    n, D, dt = 4095, 64, s3.S3_F16
+    rng = np.random.default_rng(77)
+    lens = [int(x) for x in rng.integers(0, 48, n)]
+    lens[:4] = [0, 1, 47, 33]
+    rig = Rig(1, H, D, dt, 64, 64, [64] * n, seed=78, Hkv=Hkv)
+    kvh = Hkv or H
+    rig.fill(lens)
+    for classes in (0, 8):
+        assert s3.s3_kv_set_param(rig.a, "classes", classes) == 0
+        q, got = rig.attend(lens)
+        assert_close(got, rig.oracle_attend(q, lens), f"batch of {n}, classes {classes}")
+    q = wl.normal_bits(rig.rng, (n, H, D), dt)
+    k = wl.normal_bits(rig.rng, (n, kvh, D), dt)
+    v = wl.normal_bits(rig.rng, (n, kvh, D), dt)
+    qd, kd, vd = (device_bits(x, TDT[dt], DEV) for x in (q, k, v))
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream) == 0
+    torch.cuda.synchronize()
+    assert len_out.cpu().tolist() == [L + 1 for L in lens]
+    for b, sid in enumerate(rig.ids.tolist()):
+        assert rig.o.append(sid, 0, lens[b], k[b], v[b]) == 0
+    want = rig.o.attention(0, rig.ids.tolist(), [L + 1 for L in lens], q, None, "f32", threads=8)
+    assert_close(out.cpu().numpy(), want, f"decode step on a batch of {n}")
+    for b in (0, 1, 2, 3, n - 1):
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, int(rig.ids[b]), 0, which, lens[b] + 1), rig.o.rows(int(rig.ids[b]), 0, which, lens[b] + 1))
+    # one more sequence than a call takes
+    big = torch.zeros(n + 1, dtype=torch.int64, device=DEV)
+    big_len = torch.zeros(n + 1, dtype=torch.int32, device=DEV)
+    q1 = torch.zeros((n + 1, H, D), dtype=torch.float16, device=DEV)
+    o1 = torch.zeros((n + 1, H, D), dtype=torch.float32, device=DEV)
+    assert s3.s3_decode_attention(rig.a, 0, n + 1, q1, big, big_len, o1, s3.S3_F32, 0.0, rig.stream) == s3.S3_ERR_INVALID
+    rig.close()
+
+
 # ---------------------------------------------------------------- seeded random configurations
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_against_the_oracle(seed):
