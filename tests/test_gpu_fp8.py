@@ -316,6 +316,42 @@ def test_random_configuration_over_8_bit_rows(seed):
     rig.close()
 
 
+def test_8_bit_contexts_up_to_a_long_maximum_length():
+    """max_len = 16384 over e4m3 rows: a full context, one a row short of it and short ones; 128 chunks per
+    context (chunk 128) merge inside the kernel; the decode step rounds and appends the last row of the
+    nearly full slot."""
+    H, D, act, M = 4, 128, s3.S3_BF16, 16384
+    lens = [M, M - 1, 1, 700, 0, 5000]
+    rig = Rig8(1, H, D, act, 128, M, [max(1, L) for L in lens], seed=89)
+    rig.fill(lens)
+    for chunk in (0, 128, 2048):
+        assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+        q, got = rig.attend(lens)
+        assert_close(got, rig.oracle_attend(q, lens), f"long e4m3 contexts, chunk {chunk}")
+    assert s3.s3_kv_set_param(rig.a, "chunk", 0) == 0
+    keep = [1, 2, 3, 5]
+    ids = rig.ids[keep]
+    pos = [lens[b] for b in keep]
+    m = len(keep)
+    q, k, v = (wl.normal_bits(rig.rng, (m, H, D), act) for _ in range(3))
+    qd, kd, vd = (device_bits(x, TDT[act], DEV) for x in (q, k, v))
+    off_d = torch.tensor(rig.offs[keep].tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    out = torch.full((m, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(m, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, m, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=ids, pos_host=pos) == 0
+    torch.cuda.synchronize()
+    assert len_out.cpu().tolist() == [p + 1 for p in pos]
+    for j, sid in enumerate(ids.tolist()):
+        assert rig.o.append(sid, 0, pos[j], k[j], v[j]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig.read(sid, 0, which, pos[j] + 1), rig.o.rows(sid, 0, which, pos[j] + 1).astype(np.uint8))
+    want = rig.o.attention(0, ids.tolist(), [p + 1 for p in pos], q, None, "f32", threads=8)
+    assert_close(out.cpu().numpy(), want, "e4m3 decode step at the maximum length")
+    rig.close()
+
+
 def test_grow_and_evict_move_8_bit_rows_bit_exactly():
     H, D = 8, 128
     rig = Rig8(2, H, D, s3.S3_BF16, 64, 512, [64, 100, 64], seed=50)

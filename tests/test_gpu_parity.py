@@ -778,6 +778,51 @@ def test_largest_batch_one_call_takes(H, Hkv):
     rig.close()
 
 
+@pytest.mark.parametrize("H,Hkv", [(2, None), (8, 2)])
+def test_contexts_up_to_a_long_maximum_length(H, Hkv):
+    """max_len = 16384: one context that fills it, one a row short of it, short ones beside them; up to
+    128 chunks per context merge (chunk 128) and the default chunking; a decode step appends the last
+    row of the nearly full slot."""
+    D, dt, M = 128, s3.S3_BF16, 16384
+    lens = [M, M - 1, 1, 700, 0, 5000]
+    rig = Rig(1, H, D, dt, 128, M, [max(1, L) for L in lens], seed=88, Hkv=Hkv)
+    kvh = Hkv or H
+    rig.fill(lens)
+    assert s3.s3_kv_set_param(rig.a, "chunk", 4096) == s3.S3_ERR_INVALID  # 2048 is the largest chunk
+    for chunk in (0, 128, 2048):
+        assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+        q, got = rig.attend(lens)
+        assert_close(got, rig.oracle_attend(q, lens), f"long contexts, chunk {chunk}")
+    assert s3.s3_kv_set_param(rig.a, "chunk", 0) == 0
+    keep = [1, 2, 3, 5]  # the ones with room for one more row
+    ids = rig.ids[keep]
+    pos = [lens[b] for b in keep]
+    m = len(keep)
+    q = wl.normal_bits(rig.rng, (m, H, D), dt)
+    k = wl.normal_bits(rig.rng, (m, kvh, D), dt)
+    v = wl.normal_bits(rig.rng, (m, kvh, D), dt)
+    qd, kd, vd = (device_bits(x, TDT[dt], DEV) for x in (q, k, v))
+    off_d = torch.tensor(rig.offs[keep].tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(pos, dtype=torch.int32, device=DEV)
+    out = torch.full((m, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(m, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, m, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=ids, pos_host=pos) == 0
+    torch.cuda.synchronize()
+    assert len_out.cpu().tolist() == [p + 1 for p in pos]
+    for j, sid in enumerate(ids.tolist()):
+        assert rig.o.append(sid, 0, pos[j], k[j], v[j]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, sid, 0, which, pos[j] + 1), rig.o.rows(sid, 0, which, pos[j] + 1))
+    want = rig.o.attention(0, ids.tolist(), [p + 1 for p in pos], q, None, "f32", threads=8)
+    assert_close(out.cpu().numpy(), want, "decode step at the maximum length")
+    # the full slot takes no further row
+    full = torch.tensor([int(rig.offs[0])], dtype=torch.int64, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, 1, full, torch.tensor([M], dtype=torch.int32, device=DEV), qd, kd, vd, out, s3.S3_F32,
+                             0.0, len_out, rig.stream, slot_id=rig.ids[:1], pos_host=[M]) == s3.S3_ERR_SLOT_FULL
+    rig.close()
+
+
 # ---------------------------------------------------------------- seeded random configurations
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_against_the_oracle(seed):
