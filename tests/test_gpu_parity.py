@@ -823,6 +823,22 @@ def test_contexts_up_to_a_long_maximum_length(H, Hkv):
     rig.close()
 
 
+@pytest.mark.parametrize("H,D", [(96, 128), (128, 256)])
+def test_wide_rows(H, D):
+    """Rows of 24 KiB (96 heads of 128, the largest model of table 1) and 64 KiB: many head groups per
+    sequence, byte offsets beyond 32 bits inside the arena."""
+    dt = s3.S3_F16
+    lens = [0, 1, 100, 513, 64]
+    rig = Rig(2, H, D, dt, 64, 1024, [max(1, L + 1) for L in lens], seed=93, arena_tokens=70000)
+    assert 3 * rig.N * H * D * 2 > 2 ** 32  # the planes of layer 1 start beyond 4 GiB
+    rig.fill(lens, layer=1)
+    for chunk in (0, 96):
+        assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+        q, got = rig.attend(lens, layer=1)
+        assert_close(got, rig.oracle_attend(q, lens, layer=1), f"wide rows {H}x{D} chunk {chunk}")
+    rig.close()
+
+
 # ---------------------------------------------------------------- seeded random configurations
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_against_the_oracle(seed):
