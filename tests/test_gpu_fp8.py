@@ -28,14 +28,14 @@ def need_gpu_and_lib():
 class Rig8:
     """A small 8-bit arena with hand-placed sequences, mirrored in the oracle."""
 
-    def __init__(self, n_layers, H, D, act, G, M, preds, seed, Hkv=None):
+    def __init__(self, n_layers, H, D, act, G, M, preds, seed, Hkv=None, arena_tokens=None):
         self.n_layers, self.Hq, self.D, self.act = n_layers, H, D, act
         self.H = Hkv or H  # heads of a cached row
         self.cfg = s3.make_config(n_layers, H, D, s3.S3_E4M3, G, M, 0 if Hkv is None else Hkv, act)
         bpt = s3.s3_kv_bytes_per_token(self.cfg)
         assert bpt == 2 * n_layers * self.H * D
         caps = [min(M, max(G, -(-p // G) * G)) for p in preds]
-        self.N = sum(caps) + 3 * M
+        self.N = arena_tokens or (sum(caps) + 3 * M)
         self.mem = torch.zeros(self.N * bpt, dtype=torch.uint8, device=DEV)
         st, self.a = s3.s3_kv_arena_init(self.cfg, self.mem, self.mem.numel())
         assert st == 0
@@ -349,6 +349,38 @@ def test_8_bit_contexts_up_to_a_long_maximum_length():
             assert np.array_equal(rig.read(sid, 0, which, pos[j] + 1), rig.o.rows(sid, 0, which, pos[j] + 1).astype(np.uint8))
     want = rig.o.attention(0, ids.tolist(), [p + 1 for p in pos], q, None, "f32", threads=8)
     assert_close(out.cpu().numpy(), want, "e4m3 decode step at the maximum length")
+    rig.close()
+
+
+def test_8_bit_slot_whose_rows_lie_beyond_4_gib_of_its_plane():
+    """32 KiB rows of codes, slots that start more than 4 GiB into the plane; a decode step there."""
+    H, D, act = 128, 256, s3.S3_F16
+    row_bytes = H * D
+    filler = 2 ** 32 // row_bytes + 500
+    rig = Rig8(1, H, D, act, 64, 2 * 2 ** 32 // row_bytes, [filler, 100, 64], seed=96, arena_tokens=filler + 4000)
+    assert int(rig.offs[1]) * row_bytes > 2 ** 32
+    ids, offs, lens = rig.ids[1:], rig.offs[1:], [100, 63]
+    for sid, L in zip(ids.tolist(), lens):
+        k = wl.normal_bits(rig.rng, (L, H, D), wl.E4M3)
+        v = wl.normal_bits(rig.rng, (L, H, D), wl.E4M3)
+        assert rig.o.fill(sid, 0, k, v) == 0
+        assert s3.s3_kv_fill(rig.a, sid, 0, 0, L, device_bits(k, None, DEV), device_bits(v, None, DEV), rig.stream) == 0
+    n = 2
+    q, k, v = (wl.normal_bits(rig.rng, (n, H, D), act) for _ in range(3))
+    qd, kd, vd = (device_bits(x, TDT[act], DEV) for x in (q, k, v))
+    off_d = torch.tensor(offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=ids, pos_host=lens) == 0
+    torch.cuda.synchronize()
+    for j, sid in enumerate(ids.tolist()):
+        assert rig.o.append(sid, 0, lens[j], k[j], v[j]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig.read(sid, 0, which, lens[j] + 1), rig.o.rows(sid, 0, which, lens[j] + 1).astype(np.uint8))
+    want = rig.o.attention(0, ids.tolist(), [L + 1 for L in lens], q, None, "f32", threads=8)
+    assert_close(out.cpu().numpy(), want, "e4m3 rows beyond 4 GiB")
     rig.close()
 
 

@@ -839,6 +839,48 @@ def test_wide_rows(H, D):
     rig.close()
 
 
+@pytest.mark.parametrize("Hkv", [None, 32])
+def test_slot_whose_rows_lie_beyond_4_gib_of_its_plane(Hkv):
+    """64 KiB rows (16 KiB with shared heads), slots that start more than 4 GiB into the plane: every row
+    address needs more than 32 bits relative to the plane.  A doubling (whose copy also lands up there) and
+    a decode step, for the multi-head and the matrix-core kernel."""
+    H, D, dt = 128, 256, s3.S3_F16
+    row_bytes = (Hkv or H) * D * 2
+    filler = 2 ** 32 // row_bytes + 500
+    M = 2 * 2 ** 32 // row_bytes
+    rig = Rig(1, H, D, dt, 64, M, [filler, 100, 64], seed=95, arena_tokens=filler + 4000, Hkv=Hkv)  # slot 0 is only a filler
+    assert int(rig.offs[1]) * row_bytes > 2 ** 32
+    H_rows = Hkv or H
+    ids, offs = rig.ids[1:], rig.offs[1:]
+    lens = [100, 64]
+    for sid, L in zip(ids.tolist(), lens):
+        k = wl.normal_bits(rig.rng, (L, H_rows, D), dt)
+        v = wl.normal_bits(rig.rng, (L, H_rows, D), dt)
+        assert rig.o.fill(sid, 0, k, v) == 0
+        assert s3.s3_kv_fill(rig.a, sid, 0, 0, L, device_bits(k, TDT[dt], DEV), device_bits(v, TDT[dt], DEV), rig.stream) == 0
+    st, off2, cap2 = s3.s3_kv_grow(rig.a, int(ids[1]), 64, rig.stream)  # 64 -> 128 rows: lands behind the first one
+    assert (st, off2, cap2) == rig.o.grow(int(ids[1]), 64) and off2 * row_bytes > 2 ** 32
+    offs = np.array([int(offs[0]), off2], np.int64)
+    n = 2
+    q = wl.normal_bits(rig.rng, (n, H, D), dt)
+    k, v = (wl.normal_bits(rig.rng, (n, H_rows, D), dt) for _ in range(2))
+    qd, kd, vd = (device_bits(x, TDT[dt], DEV) for x in (q, k, v))
+    off_d = torch.tensor(offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, qd, kd, vd, out, s3.S3_F32, 0.0, len_out, rig.stream,
+                             slot_id=ids, pos_host=lens) == 0
+    torch.cuda.synchronize()
+    for j, sid in enumerate(ids.tolist()):
+        assert rig.o.append(sid, 0, lens[j], k[j], v[j]) == 0
+        for which in (0, 1):
+            assert np.array_equal(rig_read(rig, sid, 0, which, lens[j] + 1), rig.o.rows(sid, 0, which, lens[j] + 1))
+    want = rig.o.attention(0, ids.tolist(), [L + 1 for L in lens], q, None, "f32", threads=8)
+    assert_close(out.cpu().numpy(), want, "rows beyond 4 GiB")
+    rig.close()
+
+
 # ---------------------------------------------------------------- seeded random configurations
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_against_the_oracle(seed):
