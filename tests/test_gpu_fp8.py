@@ -384,6 +384,41 @@ def test_8_bit_slot_whose_rows_lie_beyond_4_gib_of_its_plane():
     rig.close()
 
 
+@pytest.mark.parametrize("H,Hkv", [(4, None), (8, 2)])
+def test_8_bit_step_refuses_full_slots_and_skips_bad_entries(H, Hkv):
+    """The decode step over 8-bit rows (which appends inside the attention kernel, or with the quantising
+    append before the matrix-core kernel) writes nothing for a refused call or a device entry that would
+    leave the arena: zero output row, arena untouched except the valid neighbour's new row."""
+    D, act = 128, s3.S3_F16
+    lens = [64, 10]
+    rig = Rig8(1, H, D, act, 64, 256, [64, 64], seed=23, Hkv=Hkv, arena_tokens=1024)
+    rig.fill(lens)
+    n, kvh = 2, Hkv or H
+    q = device_bits(wl.normal_bits(rig.rng, (n, H, D), act), TDT[act], DEV)
+    k, v = (device_bits(wl.normal_bits(rig.rng, (n, kvh, D), act), TDT[act], DEV) for _ in range(2))
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.zeros((n, H, D), dtype=torch.float32, device=DEV)
+    snap = rig.mem.clone()
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, None, rig.stream,
+                             slot_id=rig.ids, pos_host=lens) == s3.S3_ERR_SLOT_FULL
+    torch.cuda.synchronize()
+    assert torch.equal(snap, rig.mem)
+    for bad in ([rig.N - 5, int(rig.offs[1])], [-1, int(rig.offs[1])]):
+        bad_off = torch.tensor(bad, dtype=torch.int64, device=DEV)
+        out.fill_(float("nan"))
+        assert s3.s3_decode_step(rig.a, 0, n, bad_off, pos_d, q, k, v, out, s3.S3_F32, 0.0, None, rig.stream) == 0
+        torch.cuda.synchronize()
+        got = out.cpu().numpy()
+        assert not got[0].any() and np.isfinite(got[1]).all()
+        changed = (snap != rig.mem).nonzero().flatten().cpu().numpy()
+        row_bytes = kvh * D
+        lo = (int(rig.offs[1]) + lens[1]) * row_bytes  # the valid neighbour's new K row; its V row is one plane on
+        plane = rig.N * row_bytes
+        assert changed.size and all(lo <= c % plane < lo + row_bytes for c in changed.tolist())
+    rig.close()
+
+
 def test_grow_and_evict_move_8_bit_rows_bit_exactly():
     H, D = 8, 128
     rig = Rig8(2, H, D, s3.S3_BF16, 64, 512, [64, 100, 64], seed=50)
