@@ -369,15 +369,19 @@ def test_fused_step_equals_append_then_attention_bit_for_bit():
         r.close()
 
 
-def test_fused_step_refuses_full_slots_and_skips_bad_entries():
+@pytest.mark.parametrize("H,Hkv", [(4, None), (8, 2), (4, 2)])
+def test_fused_step_refuses_full_slots_and_skips_bad_entries(H, Hkv):
+    """Multi-head step kernel, matrix-core kernel (appends inside) and vector-ALU shared-head kernel
+    (append launch before it)."""
     lens = [64, 10]
-    rig = Rig(1, 4, 128, s3.S3_F16, 64, 256, [64, 64], seed=23, arena_tokens=1024)
+    rig = Rig(1, H, 128, s3.S3_F16, 64, 256, [64, 64], seed=23, arena_tokens=1024, Hkv=Hkv)
     rig.fill(lens)
-    n = 2
-    q, k, v = (device_bits(wl.normal_bits(rig.rng, (n, 4, 128), 0), torch.float16, DEV) for _ in range(3))
+    n, kvh = 2, Hkv or H
+    q = device_bits(wl.normal_bits(rig.rng, (n, H, 128), 0), torch.float16, DEV)
+    k, v = (device_bits(wl.normal_bits(rig.rng, (n, kvh, 128), 0), torch.float16, DEV) for _ in range(2))
     off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
     pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
-    out = torch.zeros((n, 4, 128), dtype=torch.float32, device=DEV)
+    out = torch.zeros((n, H, 128), dtype=torch.float32, device=DEV)
     snap = rig.mem.clone()
     assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, None, rig.stream,
                              slot_id=rig.ids, pos_host=lens) == s3.S3_ERR_SLOT_FULL
