@@ -26,7 +26,13 @@
  * void*; NULL is the default stream).  Host-side bookkeeping (slot table, free
  * list) changes immediately; device work is ordered by the stream.  An arena is
  * not thread-safe: serialise calls on one arena (different arenas may be used from
- * different threads).
+ * different threads); attention launches of one arena share its scratch and must not
+ * overlap on the device either (one stream, or ordered streams).
+ *
+ * Graphs.  s3_decode_attention / s3_decode_step only enqueue kernels once the library's
+ * scratch is large enough for the batch (it grows, with a device synchronisation and an
+ * allocation, on the first call with a larger batch): after one eager call with the same
+ * arguments' shapes the launches may be recorded into a HIP graph and replayed.
  *
  * Error behaviour of device arrays.  slot_off/pos/cur_len live in device memory
  * and cannot be checked by the host without a sync, so the kernels themselves

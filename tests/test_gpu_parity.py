@@ -885,6 +885,49 @@ def test_slot_whose_rows_lie_beyond_4_gib_of_its_plane(Hkv):
     rig.close()
 
 
+@pytest.mark.parametrize("H,Hkv,chunk", [(16, None, 0), (16, None, 64), (32, 8, 0)])
+def test_decode_step_recorded_in_a_graph_replays_exactly(H, Hkv, chunk):
+    """A decode step whose launches were recorded into a HIP graph (after one eager call, so that the
+    library's scratch exists and nothing allocates during the recording) gives the eager result on every
+    replay, with other work in between: the arrival counters of the chunk merge clean up after themselves."""
+    D, dt = 128, s3.S3_BF16
+    lens = [0, 1, 63, 200, 511, 700, 64, 5]
+    rig = Rig(1, H, D, dt, 64, 1024, [L + 1 for L in lens], seed=97, Hkv=Hkv)
+    rig.fill(lens)
+    assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+    n, kvh = len(lens), Hkv or H
+    q = device_bits(wl.normal_bits(rig.rng, (n, H, D), dt), TDT[dt], DEV)
+    k, v = (device_bits(wl.normal_bits(rig.rng, (n, kvh, D), dt), TDT[dt], DEV) for _ in range(2))
+    off_d = torch.tensor(rig.offs.tolist(), dtype=torch.int64, device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    eager = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, q, k, v, eager, s3.S3_F32, 0.0, len_out, rig.stream) == 0
+    torch.cuda.synchronize()
+    want = eager.clone()
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        st = s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, len_out,
+                               torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    for rep in range(4):
+        out.fill_(float("nan"))
+        len_out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
+        assert len_out.cpu().tolist() == [L + 1 for L in lens]
+        # the program's own eager work between replays, on the same arena
+        again = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+        assert s3.s3_decode_step(rig.a, 0, n, off_d, pos_d, q, k, v, again, s3.S3_F32, 0.0, len_out, rig.stream) == 0
+        torch.cuda.synchronize()
+        assert torch.equal(again, want)
+    rig.close()
+
+
 # ---------------------------------------------------------------- seeded random configurations
 @pytest.mark.parametrize("seed", range(24))
 def test_random_configuration_against_the_oracle(seed):
