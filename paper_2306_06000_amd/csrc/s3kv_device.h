@@ -172,6 +172,22 @@ __device__ __forceinline__ int wave_inclusive_scan(int v) {
     return v;
 }
 
+// Maximum of a non-negative value over the 64 lanes, same DPP ladder (lanes shifted in from outside a
+// row read as 0, the identity here); every lane gets the result.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_max_step(int v) {
+    return max(v, __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false));
+}
+__device__ __forceinline__ int wave_max_nonneg(int v) {
+    v = dpp_max_step<0x111, 0xF>(v);
+    v = dpp_max_step<0x112, 0xF>(v);
+    v = dpp_max_step<0x114, 0xF>(v);
+    v = dpp_max_step<0x118, 0xF>(v);
+    v = dpp_max_step<0x142, 0xA>(v);
+    v = dpp_max_step<0x143, 0xC>(v);
+    return __builtin_amdgcn_readlane(v, 63);
+}
+
 // LDS picture of the batch built by every workgroup at kernel start (dynamic shared memory):
 //   off[n] (int64), len[n] (int32, 0 for refused entries), pre[ncls][n + 1] (int32)
 struct BatchView {
@@ -185,6 +201,47 @@ __device__ __forceinline__ size_t batch_view_bytes(int n, int ncls) {
     return (size_t)n * 8 + (size_t)((n + 1) & ~1) * 4 + (size_t)ncls * (n + 1) * 4;
 }
 
+// The one-wave build of the view: lane l owns entries l*E .. l*E+E-1 (n <= 64*E).
+template <int E>
+__device__ __forceinline__ void one_wave_view(const AttnArgs &a, int64_t *off_s, int *len_s, int *pre) {
+    const int lane = threadIdx.x & 63;
+    const int ncls = a.ncls, chunk = a.chunk, n = a.n;
+    int len[E], cls[E], cnt[E];
+    int mx = 0;
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+        const int b = lane * E + e;
+        len[e] = 0;
+        if (b < n) {
+            len[e] = checked_len(a, b);
+            len_s[b] = len[e];
+            off_s[b] = a.slot_off[b];
+        }
+        mx = max(mx, len[e]);
+    }
+    mx = wave_max_nonneg(mx);
+#pragma unroll
+    for (int e = 0; e < E; e++) {
+        cls[e] = class_of(len[e], mx, ncls);
+        cnt[e] = (len[e] + chunk - 1) / chunk;
+    }
+    for (int c = 0; c < ncls; c++) {
+        int loc[E], lsum = 0;
+#pragma unroll
+        for (int e = 0; e < E; e++) {
+            loc[e] = lsum;
+            if (cls[e] == c) lsum += cnt[e];
+        }
+        const int incl = wave_inclusive_scan(lsum);
+#pragma unroll
+        for (int e = 0; e < E; e++) {
+            const int b = lane * E + e;
+            if (b < n) pre[c * (n + 1) + b] = incl - lsum + loc[e];
+        }
+        if (lane == 63) pre[c * (n + 1) + n] = incl;
+    }
+}
+
 // One pass over the device arrays (each entry is read from global memory once and checked once),
 // then class-wise exclusive prefix sums of the chunk counts.
 __device__ __forceinline__ BatchView build_batch_view(const AttnArgs &a, char *dyn, int *wave_sums) {
@@ -194,44 +251,18 @@ __device__ __forceinline__ BatchView build_batch_view(const AttnArgs &a, char *d
     int64_t *off_s = (int64_t *)dyn;
     int *len_s = (int *)(dyn + (size_t)n * 8);
     int *pre = len_s + ((n + 1) & ~1);
-    constexpr int EMAX = 8;  // entries per lane of the one-wave build
-    if (n <= 64 * EMAX) {
+    if (n <= 64 * 8) {
         // Batches of up to 512 sequences: wave 0 builds the whole view by itself (lane l takes entries
         // l*E .. l*E+E-1; a serial prefix inside the lane, one DPP scan across lanes per class) and the
         // workgroup meets at ONE barrier.  The general path below needs four barriers and LDS round trips
         // between them, which cost every workgroup of a small launch about 1.5 us before its first load.
+        // E is a compile-time constant per batch size class: the per-entry work (two integer divisions) is
+        // not spent on entries a small batch does not have.
         if (wave == 0) {
-            const int E = (n + 63) >> 6;
-            int len[EMAX];
-            int mx = 0;
-#pragma unroll
-            for (int e = 0; e < EMAX; e++) {
-                const int b = lane * E + e;
-                len[e] = 0;
-                if (e < E && b < n) {
-                    len[e] = checked_len(a, b);
-                    len_s[b] = len[e];
-                    off_s[b] = a.slot_off[b];
-                }
-                mx = max(mx, len[e]);
-            }
-#pragma unroll
-            for (int d = 32; d >= 1; d >>= 1) mx = max(mx, __shfl_xor(mx, d));
-            for (int c = 0; c < ncls; c++) {
-                int loc[EMAX], lsum = 0;
-#pragma unroll
-                for (int e = 0; e < EMAX; e++) {
-                    loc[e] = lsum;
-                    if (class_of(len[e], mx, ncls) == c) lsum += (len[e] + chunk - 1) / chunk;
-                }
-                const int incl = wave_inclusive_scan(lsum);
-#pragma unroll
-                for (int e = 0; e < EMAX; e++) {
-                    const int b = lane * E + e;
-                    if (e < E && b < n) pre[c * (n + 1) + b] = incl - lsum + loc[e];
-                }
-                if (lane == 63) pre[c * (n + 1) + n] = incl;
-            }
+            if (n <= 64) one_wave_view<1>(a, off_s, len_s, pre);
+            else if (n <= 128) one_wave_view<2>(a, off_s, len_s, pre);
+            else if (n <= 256) one_wave_view<4>(a, off_s, len_s, pre);
+            else one_wave_view<8>(a, off_s, len_s, pre);
         }
         __syncthreads();
         BatchView v;
