@@ -33,6 +33,7 @@ def parse():
     ap.add_argument("--variant", type=int, default=-1)
     ap.add_argument("--chunk", type=int, default=0)
     ap.add_argument("--grid-blocks", type=int, default=0)
+    ap.add_argument("--classes", type=int, default=0, help="length classes of the longest-first work order (0: library default)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="do not time the attention kernel with events")
     ap.add_argument("--event-every", type=int, default=16,
@@ -186,6 +187,8 @@ def main():
         s3.check(s3.s3_kv_set_param(eng.arena, "chunk", args.chunk))
     if args.grid_blocks:
         s3.check(s3.s3_kv_set_param(eng.arena, "grid_blocks", args.grid_blocks))
+    if args.classes:
+        s3.check(s3.s3_kv_set_param(eng.arena, "classes", args.classes))
     prefill, tensors, _keep = make_device_sources(w, eng, torch)
     eng.start(prefill, stop_when_full=(args.workload == "c3"))
     torch.cuda.synchronize()

@@ -900,6 +900,7 @@ static int launch_gqa(s3_arena *a, const AttnCall &c) {
                       : mfma     ? 128  // one wave per item: short items keep every SIMD busy
                       : (int64_t)c.n * per_seq >= 2048 ? 1024 : (int64_t)c.n * per_seq >= 512 ? 512 : 256;
     AttnArgs args = common_args(a, c, Hkv, Hq, chunk);
+    if (mfma && a->ncls <= 0) args.ncls = 1;  // items of at most 128 rows are all alike: no order to gain from (measured)
     int rc = place_scratch(a, args, 0);
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
