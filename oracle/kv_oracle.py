@@ -205,6 +205,11 @@ class KVOracle:
         cap = max(g, cap)
         return min(self.M, cap)
 
+    def grown_capacity(self, cap):
+        """Reservation of a sequence that used up `cap` tokens and is not finished: twice the memory
+        (section 3, supervisor paragraph), never more than the maximum sequence length."""
+        return min(2 * int(cap), self.M)
+
     def _first_fit(self, cap):
         for i, (off, size) in enumerate(self.free_list):
             if size >= cap:
@@ -282,7 +287,7 @@ class KVOracle:
             return ERR_INVALID, -1, 0
         if cap >= self.M:
             return ERR_MAXLEN, -1, 0
-        new_cap = min(2 * cap, self.M)
+        new_cap = self.grown_capacity(cap)
         new_off = self._carve(new_cap)  # the old extent is still reserved here
         if new_off < 0:
             return ERR_NOMEM, -1, 0

@@ -298,3 +298,162 @@ def test_compact_closes_every_hole_and_keeps_rows():
     check_invariants(o)
     assert o.compact() == (new, 0)  # idempotent
     assert o.alloc_one(64)[1] == 1344
+
+
+# ---------------------------------------------------------------- eviction to the host and re-admission
+# Section 3, supervisor paragraph: a sequence that ran out of room is moved out of the cache (to the request
+# pool in host memory), its memory is given back, and it is re-admitted later with a doubled reservation.
+def _filled(o, rng, pred, rows):
+    sid, off, cap = o.alloc_one(pred)
+    data = wl.normal_bits(rng, (o.n_layers, 2, rows, o.Hkv, o.D), orc.F16)
+    for layer in range(o.n_layers):
+        assert o.fill(sid, layer, data[layer, 0], data[layer, 1]) == orc.OK
+    return sid, off, cap, data
+
+
+def test_evict_returns_a_copy_that_survives_free_and_reuse_of_the_extent():
+    o = orc.KVOracle(3, 2, 8, orc.F16, 64, 2048, 1024 * 3 * 2 * 2 * 8 * 2)
+    assert o.N == 1024
+    rng = np.random.default_rng(10)
+    a, a_off, a_cap, a_rows = _filled(o, rng, 128, 128)
+    b, b_off, b_cap, b_rows = _filled(o, rng, 64, 40)
+    st, blob = o.evict(a, 100)
+    assert st == orc.OK and blob.shape == (3, 2, 100, 2, 8)
+    assert np.array_equal(blob, a_rows[:, :, :100])
+    # the slot is gone and exactly its extent is free again (the hole in front of b, the tail behind it)
+    assert a not in o.slots and a not in o.data
+    assert o.free_list == [[a_off, a_cap], [b_off + b_cap, 1024 - b_off - b_cap]]
+    assert o.stats() == (b_cap, 1024 - b_cap, 1024 - b_off - b_cap, 1024)
+    # a newcomer takes the same extent (first fit) and the same id, and is filled with other rows: the
+    # evicted rows are a copy, not a view of storage that was given back
+    c, c_off, c_cap, c_rows = _filled(o, rng, 128, 128)
+    assert (c, c_off, c_cap) == (a, a_off, a_cap)
+    assert not np.array_equal(c_rows[:, :, :100], a_rows[:, :, :100])
+    assert np.array_equal(blob, a_rows[:, :, :100])
+    assert np.array_equal(o.data[b][:, :, :40], b_rows)
+
+
+def test_evict_refuses_bad_arguments_and_changes_nothing():
+    o = orc.KVOracle(1, 1, 8, orc.F16, 64, 2048, 512 * 32)
+    rng = np.random.default_rng(11)
+    a, _, cap, rows = _filled(o, rng, 64, 64)
+    snap = ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()})
+    assert o.evict(a + 1, 1) == (orc.ERR_INVALID, None)
+    assert o.evict(a, cap + 1) == (orc.ERR_INVALID, None)
+    assert o.evict(a, -1) == (orc.ERR_INVALID, None)
+    assert ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()}) == snap
+    assert np.array_equal(o.data[a][:, :, :64], rows)
+    st, blob = o.evict(a, 0)  # nothing cached yet: an empty copy, the slot is still given back
+    assert st == orc.OK and blob.shape[2] == 0 and o.free_list == [[0, 512]]
+
+
+def test_restore_places_first_fit_and_writes_rows_0_to_len_of_every_plane_only():
+    o = orc.KVOracle(2, 2, 8, orc.F16, 64, 2048, 2048 * 2 * 2 * 2 * 8 * 2)
+    assert o.N == 2048
+    bm = BitmapAllocator(2048, 64, 2048)
+    rng = np.random.default_rng(12)
+    ids = []
+    for pred, rows in ((64, 64), (200, 150), (64, 10), (300, 300), (128, 100)):
+        sid, off, cap, data = _filled(o, rng, pred, rows)
+        assert (sid, off, cap) == bm.alloc(pred)
+        ids.append((sid, data))
+    victim, victim_rows = ids[1]  # 256 tokens at offset 64
+    st, blob = o.evict(victim, 150)
+    bm.free(victim)
+    assert st == orc.OK
+    assert o.free(ids[2][0]) == orc.OK  # the 64-token slot behind it: the two holes merge to 320 tokens
+    bm.free(ids[2][0])
+    assert {k: tuple(v) for k, v in o.slots.items()} == bm.slots
+    others = {sid: o.data[sid].copy() for sid in o.slots}
+    # predicted < rows held: refused, nothing changes
+    snap = ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()})
+    assert o.restore(149, blob) == (orc.ERR_INVALID, -1, -1, 0)
+    assert ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()}) == snap
+    # the doubled reservation (512) does not fit the 320-token hole: first fit puts it behind the last slot
+    got = o.restore(512, blob)
+    want = bm.alloc(512)
+    assert got == (orc.OK,) + want and want[1] == 64 + 256 + 64 + 320 + 128
+    sid = got[1]
+    assert sid == victim  # smallest unused id
+    assert o.data[sid].shape == (2, 2, 512, 2, 8)
+    assert np.array_equal(o.data[sid][:, :, :150], victim_rows)
+    assert not o.data[sid][:, :, 150:].any()  # rows beyond the restored length are untouched (fresh)
+    for other, before in others.items():
+        assert np.array_equal(o.data[other], before)
+    check_invariants(o)
+    # a reservation that does fit the hole goes to its lowest offset
+    st, blob2 = o.evict(sid, 150)
+    bm.free(sid)
+    got = o.restore(300, blob2)
+    assert got == (orc.OK,) + bm.alloc(300) and got[2] == 64 and got[3] == 320
+    assert np.array_equal(o.data[got[1]][:, :, :150], victim_rows)
+
+
+def test_restore_nomem_leaves_state_unchanged():
+    o = orc.KVOracle(1, 1, 8, orc.F16, 64, 2048, 256 * 32)
+    rng = np.random.default_rng(13)
+    a, _, _, rows = _filled(o, rng, 128, 128)
+    b, _, _, _ = _filled(o, rng, 64, 64)
+    st, blob = o.evict(a, 128)
+    assert st == orc.OK
+    snap = ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()})
+    assert o.restore(256, blob) == (orc.ERR_NOMEM, -1, -1, 0)  # 128 + 64 tokens free, in two pieces
+    assert ([list(x) for x in o.free_list], {k: list(v) for k, v in o.slots.items()}) == snap
+    assert o.free(b) == orc.OK
+    assert o.restore(256, blob) == (orc.OK, 0, 0, 256)
+    assert np.array_equal(o.data[0][:, :, :128], rows)
+
+
+def test_random_trace_with_evictions_agrees_with_bitmap_allocator():
+    rng = np.random.default_rng(14)
+    tokens, G, M = 64 * 120, 64, 1024
+    o = orc.KVOracle(1, 1, 4, orc.F16, G, M, tokens * 16)
+    assert o.N == tokens
+    bm = BitmapAllocator(tokens, G, M)
+    live, held, away = [], {}, []  # ids in the cache, their rows, (rows, reservation owed) on the host
+    for _ in range(4000):
+        r = rng.random()
+        if r < 0.4 or not live:
+            pred = int(rng.integers(1, 700))
+            got = o.alloc_one(pred)
+            assert got == bm.alloc(pred)
+            if got[0] >= 0:
+                rows = int(rng.integers(0, got[2] + 1))
+                k = wl.normal_bits(rng, (rows, 1, 4), orc.F16)
+                assert o.fill(got[0], 0, k, k[::-1]) == orc.OK
+                live.append(got[0])
+                held[got[0]] = k
+        elif r < 0.6:
+            sid = live.pop(int(rng.integers(len(live))))
+            assert o.free(sid) == orc.OK
+            bm.free(sid)
+            del held[sid]
+        elif r < 0.8:
+            sid = live.pop(int(rng.integers(len(live))))
+            k = held.pop(sid)
+            cap = o.slots[sid][1]
+            st, blob = o.evict(sid, k.shape[0])
+            bm.free(sid)
+            assert st == orc.OK and np.array_equal(blob[0, 0], k) and np.array_equal(blob[0, 1], k[::-1])
+            away.append((blob, k, o.grown_capacity(cap)))
+        elif away:
+            blob, k, owed = away[0]
+            got = o.restore(owed, blob)
+            want = bm.alloc(owed)
+            assert got[1:] == want and got[0] == (orc.OK if want[0] >= 0 else orc.ERR_NOMEM)
+            if got[0] == orc.OK:
+                away.pop(0)
+                live.append(got[1])
+                held[got[1]] = k
+                assert o.slots[got[1]][1] == owed
+        check_invariants(o)
+        assert {k_: tuple(v) for k_, v in o.slots.items()} == bm.slots
+        for sid, k in held.items():
+            assert np.array_equal(o.data[sid][0, 0, :k.shape[0]], k) and np.array_equal(o.data[sid][0, 1, :k.shape[0]], k[::-1])
+
+
+def test_reservation_owed_after_running_out_of_room_is_doubled_up_to_the_maximum():
+    o = orc.KVOracle(1, 1, 8, orc.F16, 64, 320, 10**6, store=False)
+    assert [o.grown_capacity(c) for c in (64, 128, 192, 256, 320)] == [128, 256, 320, 320, 320]
+    sid, _, cap = o.alloc_one(130)
+    assert o.grow(sid, 0)[2] == o.grown_capacity(cap) == 320

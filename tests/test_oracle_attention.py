@@ -446,3 +446,64 @@ def test_split_merge_identity(chunk):
         e = np.exp(sc - m)
         parts.append((m, e.sum(), e @ vf[j0:j0 + chunk]))
     assert np.allclose(orc.merge_partials(parts), whole[0, 0], atol=1e-12)
+
+
+# ---------------------------------------------------------------- the store's attention wrapper
+def test_kv_oracle_attention_reads_the_key_plane_for_scores_and_the_value_plane_for_the_sum():
+    """Closed form: when all cached keys of a head are identical the weights are uniform and the output is
+    the mean of that head's cached values (section 2.1 equation).  Every (layer, plane, sequence) of the
+    store holds its own constant, so an output names the plane, layer and sequence it was read from."""
+    dtype = orc.F16
+    o = orc.KVOracle(3, 2, 8, dtype, 64, 256, 10**7)
+    rng = np.random.default_rng(30)
+    const = lambda layer, plane, sid: 1.0 + layer + 0.25 * plane + 0.03125 * sid  # exact in fp16
+    ids = [o.alloc_one(p)[0] for p in (64, 128, 64)]
+    for sid in ids:
+        cap = o.slots[sid][1]
+        for layer in range(3):
+            k = np.full((cap, 2, 8), const(layer, 0, sid), np.float32)
+            v = np.full((cap, 2, 8), const(layer, 1, sid), np.float32)
+            assert o.fill(sid, layer, bits(k, dtype), bits(v, dtype)) == orc.OK
+    q = wl.normal_bits(rng, (3, 2, 8), dtype)
+    order, lens = [ids[2], ids[0], ids[1]], [5, 64, 17]  # batch order differs from id order
+    for layer in range(3):
+        for precision, tol in (("f32", 1e-6), ("f64", 1e-12)):
+            out = o.attention(layer, order, lens, q, None, precision, 2)
+            for b, sid in enumerate(order):
+                assert np.allclose(out[b], const(layer, 1, sid), atol=tol), (layer, b)
+
+
+def test_kv_oracle_attention_equals_attention_ragged_on_hand_built_lists():
+    """Random rows, ragged lengths shorter than what is stored, rows written by fill and by append: the
+    wrapper must hand exactly the sequences' own key and value rows of that layer, in batch order."""
+    import torch
+
+    for dtype, H, Hkv in ((orc.F16, 4, 4), (orc.BF16, 4, 2)):
+        D, n_layers = 16, 2
+        o = orc.KVOracle(n_layers, H, D, dtype, 64, 256, 10**7, n_kv_heads=Hkv)
+        rng = np.random.default_rng(31)
+        ids, kept = [], {}
+        for pred, rows in ((64, 20), (128, 100), (64, 63)):
+            sid = o.alloc_one(pred)[0]
+            ids.append(sid)
+            for layer in range(n_layers):
+                k = wl.normal_bits(rng, (rows + 1, Hkv, D), dtype)
+                v = wl.normal_bits(rng, (rows + 1, Hkv, D), dtype)
+                assert o.fill(sid, layer, k[:rows], v[:rows]) == orc.OK
+                assert o.append(sid, layer, rows, k[rows], v[rows]) == orc.OK
+                kept[sid, layer] = (k, v)
+        order = [ids[1], ids[2], ids[0]]
+        lens = [101, 40, 21]
+        q = wl.normal_bits(rng, (3, H, D), dtype)
+        for layer in range(n_layers):
+            out = o.attention(layer, order, lens, q, 0.3, "f64", 1)
+            want, _ = orc.attention_ragged(q, [kept[s, layer][0] for s in order], [kept[s, layer][1] for s in order],
+                                           lens, dtype, 0.3, "f64")
+            assert np.array_equal(out, want)
+            for b, sid in enumerate(order):  # and against the library routine, on the rows kept here
+                L, g = lens[b], H // Hkv
+                tq = torch.from_numpy(np_widen(q[b], dtype)).reshape(1, H, 1, D)
+                tk = torch.from_numpy(np_widen(kept[sid, layer][0][:L], dtype)).permute(1, 0, 2).repeat_interleave(g, 0)
+                tv = torch.from_numpy(np_widen(kept[sid, layer][1][:L], dtype)).permute(1, 0, 2).repeat_interleave(g, 0)
+                ref = torch.nn.functional.scaled_dot_product_attention(tq, tk[None], tv[None], scale=0.3).reshape(H, D)
+                assert np.allclose(out[b], ref.numpy(), atol=1e-12)
