@@ -68,7 +68,8 @@ typedef enum {
 typedef struct {
     int32_t n_layers;  /* l: transformer layers whose K and V the arena holds            */
     int32_t n_heads;   /* H                                                              */
-    int32_t head_dim;  /* D: 64, 128 or 256                                              */
+    int32_t head_dim;  /* D: 64, 128 or 256; 96 for multi-head 16-bit caches (n_kv_heads 0 or
+                          n_heads, kv_dtype S3_F16 / S3_BF16)                            */
     int32_t kv_dtype;  /* s3_dtype of the cache rows (and, if 16-bit, of q, k_new, v_new):
                           S3_F16, S3_BF16 or S3_E4M3                                     */
     int32_t granule;   /* G: capacities are multiples of G tokens (> 0)                  */
@@ -87,6 +88,17 @@ typedef struct {
  * (section 2.1: 4*l*d_h bytes in half precision).  Returns the byte count, or
  * S3_ERR_INVALID (< 0) for a bad config. */
 int64_t s3_kv_bytes_per_token(const s3_kv_config *cfg /*HOST*/);
+
+/* The reservation rules as plain functions of a configuration (HOST integers; no arena needed).
+ *   s3_kv_capacity_for     tokens reserved for a sequence predicted to reach predicted_len tokens in total
+ *                          (sections 1 and 2.3: reserve what is predicted, not the maximum):
+ *                          min(M, max(G, round_up(predicted_len, G)))
+ *   s3_kv_grown_capacity   reservation owed to a sequence that used up `cap` tokens and is not finished
+ *                          (section 3, supervisor paragraph: twice the memory): min(2*cap, M).  It is what
+ *                          s3_kv_grow reserves, and what an evicted sequence is re-admitted with.
+ * Both return S3_ERR_INVALID (< 0) for a bad config or a negative argument. */
+int32_t s3_kv_capacity_for(const s3_kv_config *cfg /*HOST*/, int32_t predicted_len);
+int32_t s3_kv_grown_capacity(const s3_kv_config *cfg /*HOST*/, int32_t cap);
 
 /* Create the bookkeeping for one arena over caller-owned device memory.
  *   dev_base  DEVICE, 256-byte aligned, dev_bytes long; stays owned by the caller and must
@@ -165,6 +177,12 @@ int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, co
 int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
                    const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
                    const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out, void *stream);
+
+/* Size the arena's own scratch (chunk partials, arrival counters) once, for batches of up to max_batch
+ * sequences at the current "chunk" setting, so that s3_decode_attention / s3_decode_step never allocate or
+ * synchronise afterwards (they still grow it on demand for a larger batch or a smaller chunk).  Allocates
+ * with hipMalloc and synchronises the device if the scratch must grow.  max_batch in [1, 4095]. */
+int s3_kv_reserve_scratch(s3_arena *a, int32_t max_batch);
 
 /* A sequence used up its reservation and is not finished: double it (section 3, supervisor
  * paragraph).  new capacity = min(2*cap, M); the new slot is placed first-fit while the old one is
@@ -272,9 +290,13 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *   "grid_blocks"  workgroups launched (0 = library default)
  *   "variant"      kernel variant index, -1 = default (see get "n_variants"; arenas with shared
  *                  key/value heads have their own, shorter, list)
+ *   "merge_sync"   how chunks of one context that meet inside ONE launch (s3_decode_step on multi-head
+ *                  caches, 8-bit rows) are ordered across workgroups: 0 (default) write-through partial
+ *                  stores, a drained memory counter and a relaxed counter increment; 1 device-scope
+ *                  release / acquire fences around the increment (slower; same results)
  *   "profile"      k > 0: every k-th attention launch (counted from this call) carries HIP events that
  *                  take the kernel's own start and end times (hipExtLaunchKernel); 0: off; both reset the sums
- * get names: the above plus "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,
+ * get names: the above plus "default_variant", "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,
  * 2 shared-K/V matrix-core kernel, 3 kernel for 8-bit rows, 4 matrix-core kernel over 8-bit rows with
  * shared heads: what the next attention launch uses), "n_variants", "n_grows",
  * "live_slots", "scratch_bytes", "num_cus" and,

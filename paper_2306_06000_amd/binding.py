@@ -30,6 +30,9 @@ _pi32, _pi64 = ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
 
 SIGNATURES = {
     "s3_kv_bytes_per_token": (_i64, [ctypes.POINTER(s3_kv_config)]),
+    "s3_kv_capacity_for": (_i32, [ctypes.POINTER(s3_kv_config), _i32]),
+    "s3_kv_grown_capacity": (_i32, [ctypes.POINTER(s3_kv_config), _i32]),
+    "s3_kv_reserve_scratch": (ctypes.c_int, [_vp, _i32]),
     "s3_kv_arena_init": (ctypes.c_int, [ctypes.POINTER(_vp), ctypes.POINTER(s3_kv_config), _vp, ctypes.c_size_t]),
     "s3_kv_arena_destroy": (None, [_vp]),
     "s3_kv_alloc": (ctypes.c_int, [_vp, _i32, _pi32, _pi32, _pi64, _pi32]),
@@ -110,6 +113,18 @@ def make_config(n_layers, n_heads, head_dim, kv_dtype, granule, max_len, n_kv_he
 
 def s3_kv_bytes_per_token(cfg):
     return int(lib().s3_kv_bytes_per_token(ctypes.byref(cfg)))
+
+
+def s3_kv_capacity_for(cfg, predicted_len):
+    return int(lib().s3_kv_capacity_for(ctypes.byref(cfg), int(predicted_len)))
+
+
+def s3_kv_grown_capacity(cfg, cap):
+    return int(lib().s3_kv_grown_capacity(ctypes.byref(cfg), int(cap)))
+
+
+def s3_kv_reserve_scratch(arena, max_batch):
+    return lib().s3_kv_reserve_scratch(arena, int(max_batch))
 
 
 def s3_kv_arena_init(cfg, dev_base, dev_bytes):

@@ -6,8 +6,12 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libs3kv.so")
-SOURCES = ["s3kv_kernels.hip", "s3kv_gqa.hip", "s3kv_gqa_mfma.hip", "s3kv_fp8.hip", "s3kv_alloc.cpp", "s3kv_sched.cpp"]
-HEADERS = ["s3kv_internal.h", "s3kv_device.h"]
+# (source, extra defines, object name); the multi-head attention kernels are one object per head dimension
+HEAD_DIMS = (64, 96, 128, 256)
+UNITS = [("s3kv_attn_inst.hip", [f"-DS3_INST_D={d}"], f"s3kv_attn_d{d}.o") for d in HEAD_DIMS] + [
+    (s, [], s + ".o") for s in ("s3kv_kernels.hip", "s3kv_gqa.hip", "s3kv_gqa_mfma.hip", "s3kv_fp8.hip", "s3kv_alloc.cpp",
+                                "s3kv_sched.cpp")]
+HEADERS = ["s3kv_internal.h", "s3kv_device.h", "s3kv_attn.h"]
 
 
 def _hipcc() -> str:
@@ -21,7 +25,7 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
     """Compile every source to an object (in parallel, one hipcc each), then link the shared library."""
     from concurrent.futures import ThreadPoolExecutor
 
-    srcs = [os.path.join(CSRC, s) for s in SOURCES]
+    srcs = sorted({os.path.join(CSRC, u[0]) for u in UNITS})
     deps = srcs + [os.path.join(CSRC, h) for h in HEADERS] + [os.path.join(ROOT, "include", "s3kv.h")]
     if not force and os.path.exists(LIB) and all(os.path.getmtime(LIB) >= os.path.getmtime(d) for d in deps):
         return LIB
@@ -46,9 +50,10 @@ def build_lib(force: bool = True, verbose: bool = False) -> str:
         if verbose and out.strip():
             print(out, flush=True)
 
-    objs = [os.path.join(objdir, os.path.basename(s) + ".o") for s in srcs]
-    with ThreadPoolExecutor(max_workers=min(len(srcs), int(os.environ.get("MAX_JOBS", "8")))) as pool:
-        list(pool.map(lambda so: run([_hipcc()] + flags + ["-c", "-x", "hip", so[0], "-o", so[1]]), zip(srcs, objs)))
+    objs = [os.path.join(objdir, u[2]) for u in UNITS]
+    with ThreadPoolExecutor(max_workers=min(len(UNITS), int(os.environ.get("MAX_JOBS", "8")))) as pool:
+        list(pool.map(lambda u: run([_hipcc()] + flags + u[1] + ["-c", "-x", "hip", os.path.join(CSRC, u[0]), "-o",
+                                                              os.path.join(objdir, u[2])]), UNITS))
     tmp = LIB + ".tmp"
     run([_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp])
     os.replace(tmp, LIB)

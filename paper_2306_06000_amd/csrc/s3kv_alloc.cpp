@@ -40,11 +40,13 @@ extern "C" const char *s3_status_str(int status) {
 static bool config_ok(const s3_kv_config *c) {
     if (!c) return false;
     if (c->n_layers <= 0 || c->n_heads <= 0) return false;
-    if (c->head_dim != 64 && c->head_dim != 128 && c->head_dim != 256) return false;
+    if (c->head_dim != 64 && c->head_dim != 96 && c->head_dim != 128 && c->head_dim != 256) return false;
     if (c->kv_dtype != S3_F16 && c->kv_dtype != S3_BF16 && c->kv_dtype != S3_E4M3) return false;
     if (c->kv_dtype == S3_E4M3 && c->act_dtype != S3_F16 && c->act_dtype != S3_BF16) return false;  // 16-bit activations
     if (c->granule <= 0 || c->max_len <= 0 || c->max_len % c->granule != 0) return false;
     if (c->n_kv_heads < 0 || (c->n_kv_heads > 0 && (c->n_kv_heads > c->n_heads || c->n_heads % c->n_kv_heads))) return false;
+    // 96-wide heads (the 64 x 96 model of the paper's table 1): multi-head 16-bit caches only
+    if (c->head_dim == 96 && (c->kv_dtype == S3_E4M3 || (c->n_kv_heads > 0 && c->n_kv_heads != c->n_heads))) return false;
     return true;
 }
 
@@ -81,13 +83,22 @@ extern "C" int s3_kv_arena_init(s3_arena **out, const s3_kv_config *cfg, void *d
     return S3_OK;
 }
 
-int32_t s3i_capacity_for(const s3_arena *a, int32_t predicted_len) {
-    const int64_t g = a->cfg.granule;
+extern "C" int32_t s3_kv_capacity_for(const s3_kv_config *cfg, int32_t predicted_len) {
+    if (!config_ok(cfg) || predicted_len < 0) return S3_ERR_INVALID;
+    const int64_t g = cfg->granule;
     int64_t cap = ((int64_t)predicted_len + g - 1) / g * g;
     if (cap < g) cap = g;
-    if (cap > a->cfg.max_len) cap = a->cfg.max_len;
+    if (cap > cfg->max_len) cap = cfg->max_len;
     return (int32_t)cap;
 }
+
+extern "C" int32_t s3_kv_grown_capacity(const s3_kv_config *cfg, int32_t cap) {
+    if (!config_ok(cfg) || cap < 0) return S3_ERR_INVALID;
+    const int64_t twice = 2 * (int64_t)cap;
+    return (int32_t)(twice > cfg->max_len ? cfg->max_len : twice);
+}
+
+int32_t s3i_capacity_for(const s3_arena *a, int32_t predicted_len) { return s3_kv_capacity_for(&a->cfg, predicted_len); }
 
 int64_t s3i_carve(s3_arena *a, int64_t cap) {
     for (auto it = a->free_ext.begin(); it != a->free_ext.end(); ++it) {
@@ -182,8 +193,7 @@ extern "C" int s3_kv_grow(s3_arena *a, int32_t slot_id, int32_t len, int64_t *ne
     if (s->cap >= a->cfg.max_len) return S3_ERR_MAXLEN;
     const int64_t old_off = s->off;
     const int32_t old_cap = s->cap;
-    int64_t cap2 = 2 * (int64_t)old_cap;
-    if (cap2 > a->cfg.max_len) cap2 = a->cfg.max_len;
+    const int64_t cap2 = s3_kv_grown_capacity(&a->cfg, old_cap);
     const int64_t off2 = s3i_carve(a, cap2);  // the old extent is still reserved: no overlap possible
     if (off2 < 0) return S3_ERR_NOMEM;
     if (a->base && len > 0) {
@@ -306,6 +316,11 @@ extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
         a->variant = (int32_t)value;
         return S3_OK;
     }
+    if (!strcmp(name, "merge_sync")) {
+        if (value != 0 && value != 1) return S3_ERR_INVALID;
+        a->merge_sync = (int32_t)value;
+        return S3_OK;
+    }
     if (!strcmp(name, "profile")) {  // k > 0: time every k-th attention launch with events; 0: off; both reset
         if (value < 0 || value > 1000000) return S3_ERR_INVALID;
         if (!a->base) return S3_ERR_INVALID;
@@ -323,7 +338,9 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
     else if (!strcmp(name, "grid_blocks")) *value = a->grid_blocks;
     else if (!strcmp(name, "classes")) *value = a->ncls;
     else if (!strcmp(name, "variant")) *value = a->variant;
+    else if (!strcmp(name, "merge_sync")) *value = a->merge_sync;
     else if (!strcmp(name, "n_variants")) *value = s3i_variants_of(a);
+    else if (!strcmp(name, "default_variant")) *value = s3i_kernel_kind(a) == 0 ? s3i_default_variant() : -1;
     else if (!strcmp(name, "kernel_kind")) *value = s3i_kernel_kind(a);
     else if (!strcmp(name, "n_grows")) *value = a->n_grows;
     else if (!strcmp(name, "live_slots")) *value = (int64_t)a->slots.size() - (int64_t)a->dead_ids.size();

@@ -35,6 +35,7 @@ struct AttnArgs {
     const char *v_new;
     int32_t *len_out;        // may be null
     unsigned int *arrivals;  // [n][n_hgb] chunk-arrival counters, zero between launches
+    int32_t merge_sync;      // how chunks that meet inside one launch are ordered: see chunk_arrived()
 };
 
 __device__ __forceinline__ int checked_len(const AttnArgs &a, int b) {
@@ -370,6 +371,31 @@ template <bool COHERENT>
 __device__ __forceinline__ f32x2 get_partial2(const float *p) {
     if (COHERENT) return *(const volatile f32x2 *)p;
     return *(const f32x2 *)p;
+}
+
+// A wave has written its chunk's partial: count the chunk on the context's arrival counter.  Returns true
+// (to every lane) in the wave that delivered the LAST chunk of the context; that wave then merges the chunks,
+// and the counter is back at zero for the next launch.  Called by whole waves in uniform control flow.
+// Two orderings of "my partial is visible before my count, the others' partials are visible after theirs":
+//   merge_sync 0  the partials are written and read with the write-through / cache-bypassing accesses above,
+//                 so they are at the memory side once this wave's vector-memory counter has drained
+//                 (s_waitcnt 0); the counter is a relaxed device-scope atomic.  This rests on `volatile`
+//                 vector accesses being emitted with the sc0 sc1 cache bits on gfx950 (a host-side test
+//                 compiles these helpers and checks the bits in the emitted code).
+//   merge_sync 1  the same accesses, ordered by the memory model instead: a device-scope release fence
+//                 before the count and an acquire fence in the wave that merges (L2 write-back and
+//                 invalidate on this device, which cost far more than the partials themselves).
+__device__ __forceinline__ bool chunk_arrived(const AttnArgs &a, unsigned int *cnt, int nchunks) {
+    const int lane = threadIdx.x & 63;
+    if (a.merge_sync) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+    else __builtin_amdgcn_s_waitcnt(0);  // this wave's partial stores have completed
+    unsigned int old = 0;
+    if (lane == 0) old = atomicAdd(cnt, 1u);
+    old = __builtin_amdgcn_readfirstlane(old);
+    if (old != (unsigned int)(nchunks - 1)) return false;
+    if (lane == 0) atomicExch(cnt, 0u);  // leave the counter clean for the next launch
+    if (a.merge_sync) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+    return true;
 }
 
 // Merge the chunk partials of (sequence b, head h) for this lane's 8-element slice and store the

@@ -256,13 +256,8 @@ __global__ void __launch_bounds__(TS * 64) attn_fp8_kernel(const AttnArgs a) {
             // Chunks meet through an arrival counter per (sequence, head group), as in the fused multi-head
             // step: whoever delivers the last chunk merges them.  With the default chunk of 1024 rows this is
             // rare, which is what makes it cheaper than a merge launch after every attention launch.
-            __builtin_amdgcn_s_waitcnt(0);  // this wave's partial stores have completed
             unsigned int *cnt = a.arrivals + (int64_t)it.b * n_hg + it.hgb;
-            unsigned int old = 0;
-            if (lane == 0) old = atomicAdd(cnt, 1u);
-            old = __builtin_amdgcn_readfirstlane(old);
-            if (old == (unsigned int)(it.nchunks - 1)) {
-                if (lane == 0) atomicExch(cnt, 0u);  // leave the counter clean for the next launch
+            if (chunk_arrived(a, cnt, it.nchunks)) {
                 if (h_ok && tsub == 0) {
                     merge_chunks<D, true>(a, a.H, it.b, h, 2 * dl, it.nchunks);
                     merge_chunks<D, true>(a, a.H, it.b, h, 2 * dl + 1, it.nchunks);

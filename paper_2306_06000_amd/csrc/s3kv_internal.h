@@ -47,6 +47,7 @@ struct s3_arena {
     int32_t ncls = 0;  // length classes of the work order (0: library default)
     int32_t grid_blocks = 0;
     int32_t variant = -1;
+    int32_t merge_sync = 0;  // ordering of chunks that meet inside one launch (0: write-through partials, 1: fences)
     int32_t num_cus = 0;
 
     char *plane(int32_t layer, int32_t which) const {
@@ -65,6 +66,7 @@ void s3i_set_hip_error(const char *what, int code, const char *text);
 int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src_plane_stride,
                            size_t dst_plane_stride, int planes, void *stream);
 int s3i_num_variants();    // kernel variants of the multi-head attention kernels
+int s3i_default_variant(); // the one an arena uses unless told otherwise
 int s3i_num_gqa_shapes();  // shapes of the shared-K/V (grouped-query) attention kernel
 int s3i_num_fp8_shapes();  // shapes of the attention kernel for 8-bit cache rows
 // Which attention kernel family the arena's next launch uses: 0 multi-head, 1 shared-K/V on the vector

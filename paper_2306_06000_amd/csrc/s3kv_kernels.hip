@@ -1,32 +1,20 @@
-// HIP kernels and launch code of libs3kv for gfx950 (MI355X): append, ragged decode-step attention
-// for multi-head 16-bit caches (split over the sequence axis + merge), plane copies (grow / fill /
-// read-back), and the host side of every attention call.  The kernels for shared key/value heads
-// and for 8-bit rows live in s3kv_gqa.hip, s3kv_gqa_mfma.hip and s3kv_fp8.hip and are launched
-// from here; the device helpers all of them share are in s3kv_device.h.
+// Launch code of libs3kv for gfx950 (MI355X) and its small kernels: append, plane copies (grow / fill /
+// read-back), batch patches, the bandwidth probe, and the host side of every attention call.  The attention
+// kernels live in s3kv_attn.h (multi-head 16-bit caches; instantiated per head dimension by
+// s3kv_attn_inst.hip), s3kv_gqa.hip, s3kv_gqa_mfma.hip (shared key/value heads) and s3kv_fp8.hip (8-bit
+// rows) and are launched from here; the device helpers all of them share are in s3kv_device.h.
 //
 // Arena layout.  Plane p = 2*layer + (0: K, 1: V) holds N token rows of H*D elements (H = cached
 // heads), token-major: element (token t, head h, d) of a plane sits at ((t*H + h)*D + d).  A slot
 // is the row range [off, off+cap) in EVERY plane, so one sequence's rows of one plane are one
 // contiguous run and the attention kernels stream them with 128-bit loads.
-//
-// Attention work decomposition.  The method is bound by HBM bandwidth (about one flop per byte),
-// so the unit of parallelism is bytes, not sequences: every context is cut into near-equal chunks
-// of at most `chunk` tokens and the (chunk, head-group) pairs of the whole ragged batch form one
-// flat work list, longest contexts first, that a fixed grid walks with a stride.  A wavefront
-// covers GH = 512/D adjacent heads of one token per 128-bit load (64 lanes x 16 B = 1 KiB of
-// contiguous memory); the D/8 lanes of a head reduce their dot product with DPP row operations,
-// keep a running maximum and sum in fp32, and accumulate their 8-element slice of the output.
-// The TS waves of a workgroup that share a head group split the chunk's tokens and merge through
-// LDS; chunks of one context merge in a second kernel (s3_decode_attention) or, in the fused step,
-// in the epilogue wave of whichever workgroup delivers the last chunk.  Score s_j = q.K_j * scale
-// as in the section 2.1 equation of the S3 paper; softmax is max-subtracted; everything after the
-// 16-bit loads is fp32.
 #include <hip/hip_ext.h>
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
 #include <string.h>
 
+#include <map>
 #include <mutex>
 
 #include "s3kv_internal.h"
@@ -264,355 +252,38 @@ __global__ void __launch_bounds__(256) append_kernel(char *kplane, char *vplane,
 }
 
 // ------------------------------------------------------------------------------------------
-// attention
+// attention: kernel choice and launchers
 // ------------------------------------------------------------------------------------------
-// One wave's share of an item: tokens [j0, j1) of head group hg, online softmax in fp32.
-// DT: element type of q/K/V.  D: head_dim.  U: tokens per load batch.  NT: non-temporal loads.
-// FUSED: row len-1 is still only in k_new / v_new: it is taken from there and, by the wave whose
-// range holds it, written into the arena (the append).
-// PF: software pipelining - the loads of the next batch of U tokens are issued before the current
-// batch is reduced, so the wave always has loads in flight (two register sets, used alternately).
-template <int DT, int D, int U, bool NT, bool FUSED>
-struct TokenStream {
-    static constexpr int LPH = D / 8;    // lanes per head
-    static constexpr int GH = 64 / LPH;  // heads per wave
-    const char *kp, *vp, *knew, *vnew;
-    int64_t rstride;
-    int jnew, j1;
-    float scale_log2e;
-    u32x4 qv;
+// Multi-head kernels, one translation unit per head dimension (s3kv_attn_inst.hip).
+attn_fn s3i_pick_mha_d64(int dt, int variant, bool fused);
+attn_fn s3i_pick_mha_d96(int dt, int variant, bool fused);
+attn_fn s3i_pick_mha_d128(int dt, int variant, bool fused);
+attn_fn s3i_pick_mha_d256(int dt, int variant, bool fused);
+attn_fn s3i_pick_merge_d64();
+attn_fn s3i_pick_merge_d96();
+attn_fn s3i_pick_merge_d128();
+attn_fn s3i_pick_merge_d256();
+int s3i_default_variant();
+int s3i_variant_threads(int variant, bool fused);
 
-    __device__ __forceinline__ void load(int j, u32x4 (&kk)[U], u32x4 (&vv)[U]) const {
-#pragma unroll
-        for (int u = 0; u < U; u++) {
-            const int jj = min(j + u, j1 - 1);
-            const char *src = kp + (int64_t)jj * rstride;
-            if (FUSED) src = (jj == jnew) ? knew : src;
-            kk[u] = load16<NT>(src);
-        }
-#pragma unroll
-        for (int u = 0; u < U; u++) {
-            const int jj = min(j + u, j1 - 1);
-            const char *src = vp + (int64_t)jj * rstride;
-            if (FUSED) src = (jj == jnew) ? vnew : src;
-            vv[u] = load16<NT>(src);
-        }
-    }
-
-    __device__ __forceinline__ void reduce(int j, const u32x4 (&kk)[U], const u32x4 (&vv)[U], float &m, float &l,
-                                           float (&acc)[8]) const {
-        float s[U];
-#pragma unroll
-        for (int u = 0; u < U; u++) s[u] = dot8<DT>(qv, kk[u]);
-#pragma unroll
-        for (int u = 0; u < U; u++) s[u] = group_sum<LPH>(s[u]);
-        float mb = -INFINITY;
-#pragma unroll
-        for (int u = 0; u < U; u++) {
-            s[u] = (j + u < j1) ? s[u] * scale_log2e : -INFINITY;
-            mb = fmaxf(mb, s[u]);
-        }
-        const float mn = fmaxf(m, mb);  // finite: the batch holds at least one real token
-        const float alpha = fast_exp2(m - mn);
-        l *= alpha;
-#pragma unroll
-        for (int i = 0; i < 8; i++) acc[i] *= alpha;
-#pragma unroll
-        for (int u = 0; u < U; u++) {
-            const float p = fast_exp2(s[u] - mn);
-            l += p;
-            axpy8<DT>(acc, p, vv[u]);
-        }
-        m = mn;
-    }
-};
-
-template <int DT, int D, int U, bool NT, bool FUSED, bool PF>
-__device__ __forceinline__ void wave_tokens(const AttnArgs &a, const Item &it, int hg, int j0, int j1, float &m,
-                                            float &l, float (&acc)[8]) {
-    typedef TokenStream<DT, D, U, NT, FUSED> TS_t;
-    const int lane = threadIdx.x & 63;
-    const int g = lane / TS_t::LPH, dl = lane % TS_t::LPH;
-    const int h = hg * TS_t::GH + g;
-    const bool h_ok = h < a.H;
-    const int hc = h_ok ? h : a.H - 1;
-    const int64_t rstride = (int64_t)a.H * D * 2;
-    const int64_t lane_byte = ((int64_t)hc * D + dl * 8) * 2;
-    const int64_t in_byte = ((int64_t)it.b * a.H * D) * 2 + lane_byte;  // this lane's slice of row b of q/k_new/v_new
-    TS_t st;
-    st.kp = a.kplane + it.off * rstride + lane_byte;
-    st.vp = a.vplane + it.off * rstride + lane_byte;
-    st.knew = FUSED ? a.k_new + in_byte : nullptr;
-    st.vnew = FUSED ? a.v_new + in_byte : nullptr;
-    st.rstride = rstride;
-    st.jnew = FUSED ? it.len - 1 : -1;
-    st.j1 = j1;
-    st.scale_log2e = a.scale_log2e;
-    st.qv = *(const u32x4 *)(a.q + in_byte);
-
-    m = -INFINITY;
-    l = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; i++) acc[i] = 0.f;
-    if (!PF) {
-        for (int j = j0; j < j1; j += U) {
-            u32x4 kk[U], vv[U];
-            st.load(j, kk, vv);
-            st.reduce(j, kk, vv, m, l, acc);
-        }
-    } else if (j0 < j1) {
-        u32x4 ka[U], va[U], kb[U], vb[U];
-        st.load(j0, ka, va);
-        for (int j = j0; j < j1; j += 2 * U) {
-            const bool more = j + U < j1;
-            if (more) st.load(j + U, kb, vb);
-            st.reduce(j, ka, va, m, l, acc);
-            if (more) {
-                if (j + 2 * U < j1) st.load(j + 2 * U, ka, va);
-                st.reduce(j + U, kb, vb, m, l, acc);
-            }
-        }
-    }
-    if (FUSED && h_ok && j0 <= st.jnew && st.jnew < j1) {  // the append: this wave owns the new row's slice
-        *(u32x4 *)(a.kplane + (it.off + st.jnew) * rstride + lane_byte) = *(const u32x4 *)(a.k_new + in_byte);
-        *(u32x4 *)(a.vplane + (it.off + st.jnew) * rstride + lane_byte) = *(const u32x4 *)(a.v_new + in_byte);
-    }
-}
-
-// Merge TS token splits (rows first..first+TS-1 of comb) lane by lane.
-template <int TS>
-__device__ __forceinline__ void combine_splits(const float (*comb)[10][64], int first, int lane, float &m, float &l,
-                                               float (&acc)[8]) {
-    m = comb[first][0][lane];
-    for (int t = 1; t < TS; t++) m = fmaxf(m, comb[first + t][0][lane]);
-    l = 0.f;
-#pragma unroll
-    for (int i = 0; i < 8; i++) acc[i] = 0.f;
-    for (int t = 0; t < TS; t++) {  // split 0 is never empty, so m is finite; empty splits weigh exp2(-inf) = 0
-        const float wt = fast_exp2(comb[first + t][0][lane] - m);
-        l += wt * comb[first + t][1][lane];
-#pragma unroll
-        for (int i = 0; i < 8; i++) acc[i] += wt * comb[first + t][2 + i][lane];
-    }
-}
-
-// Write one (chunk, head) result: the final output row slice if the context has a single chunk,
-// else the partial (max, sum, weighted sum).
-template <int D, bool COHERENT>
-__device__ __forceinline__ void emit_chunk(const AttnArgs &a, const Item &it, int h, int dl, float m, float l,
-                                           const float (&acc)[8]) {
-    if (it.nchunks == 1) {
-        const float inv = 1.f / l;
-        float o[8];
-#pragma unroll
-        for (int i = 0; i < 8; i++) o[i] = acc[i] * inv;
-        store_out8(a.out, a.out_dtype, ((int64_t)it.b * a.H + h) * D + dl * 8, o);
-        return;
-    }
-    const int64_t pi = ((int64_t)it.b * a.max_chunks + it.c) * a.H + h;
-    float *pml = (float *)a.part_ml + 2 * pi;
-    float *pa = a.part_acc + pi * D + dl * 8;
-    if (dl == 0) put_partial2<COHERENT>(pml, (f32x2){m, l});
-    put_partial4<COHERENT>(pa, (f32x4){acc[0], acc[1], acc[2], acc[3]});
-    put_partial4<COHERENT>(pa + 4, (f32x4){acc[4], acc[5], acc[6], acc[7]});
-}
-
-// Attention only (s3_decode_attention): TS*HS waves; the TS waves of a head group split the chunk's
-// tokens and merge through LDS; multi-chunk contexts are finished by attn_merge_kernel.
-template <int DT, int D, int TS, int HS, int U, bool NT, bool PF>
-__global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArgs a) {
-    constexpr int LPH = D / 8;
-    constexpr int GH = 64 / LPH;
-    constexpr int NW = TS * HS;
-    extern __shared__ __align__(16) char dyn_lds[];  // the batch view
-    __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
-    __shared__ float comb[TS > 1 ? NW : 1][10][64];
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int ts = wave % TS, hs = wave / TS;
-    const int n_hg = (a.H + GH - 1) / GH;
-    const int n_hgb = (n_hg + HS - 1) / HS;
-    const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
-    const int64_t total = (int64_t)bv.total * n_hgb;
-
-    for (int64_t item = blockIdx.x; item < total; item += gridDim.x) {
-        const Item it = decode_item(a, bv, item, n_hgb);
-        const int hg = it.hgb * HS + hs;
-        int j0, j1;
-        split_rows(it, ts, TS, j0, j1);
-        float m, l, acc[8];
-        wave_tokens<DT, D, U, NT, false, PF>(a, it, hg, j0, j1, m, l, acc);
-        if (TS > 1) {
-            comb[wave][0][lane] = m;
-            comb[wave][1][lane] = l;
-#pragma unroll
-            for (int i = 0; i < 8; i++) comb[wave][2 + i][lane] = acc[i];
-            __syncthreads();
-            if (ts == 0) combine_splits<TS>(comb, wave, lane, m, l, acc);
-        }
-        const int h = hg * GH + lane / LPH;
-        if (ts == 0 && h < a.H) emit_chunk<D, false>(a, it, h, lane % LPH, m, l, acc);
-        if (TS > 1) __syncthreads();  // comb is reused by the next item
-    }
-}
-
-// The whole layer-step in one launch (s3_decode_step): TS*HS compute waves plus ONE epilogue wave.
-// Compute waves stream their token shares (taking the new row from k_new / v_new and appending it),
-// drop (max, sum, weighted sum) into one of two LDS buffers and move on to the next item after a
-// single barrier.  The epilogue wave merges the splits, writes the output or the chunk partial,
-// announces the chunk on the context's arrival counter and, if it delivered the last chunk, merges
-// the chunks; all its memory latencies overlap with the compute waves' next item.  len_out and the
-// zero rows of empty contexts are published by the workgroups in turn.
-template <int DT, int D, int TS, int HS, int U, bool NT, bool PF>
-__global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const AttnArgs a) {
-    constexpr int LPH = D / 8;
-    constexpr int GH = 64 / LPH;
-    constexpr int NWC = TS * HS;  // compute waves
-    extern __shared__ __align__(16) char dyn_lds[];  // the batch view
-    __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
-    __shared__ float comb[2][NWC][10][64];
-
-    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const bool epilogue = wave == NWC;
-    const int ts = wave % TS, hs = wave / TS;
-    const int n_hg = (a.H + GH - 1) / GH;
-    const int n_hgb = (n_hg + HS - 1) / HS;
-    const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
-    const int64_t total = (int64_t)bv.total * n_hgb;
-
-    // Housekeeping that belongs to no item, spread over the workgroups (sequence b goes to workgroup
-    // b mod grid) so that none of them starts its first item late: the new lengths, and a zero output
-    // row for empty or refused contexts.
-    for (int b = blockIdx.x; b < a.n; b += gridDim.x) {
-        if (a.len_out && threadIdx.x == 0) a.len_out[b] = a.cur_len[b] + 1;
-        if (bv.len[b] == 0) {
-            const int per_row = a.H * D / 8;
-            const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-            for (int e = threadIdx.x; e < per_row; e += (NWC + 1) * 64) store_out8(a.out, a.out_dtype, ((int64_t)b * per_row + e) * 8, z);
-        }
-    }
-
-    int parity = 0;
-    for (int64_t item = blockIdx.x; item < total; item += gridDim.x, parity ^= 1) {
-        const Item it = decode_item(a, bv, item, n_hgb);
-        if (!epilogue) {
-            int j0, j1;
-            split_rows(it, ts, TS, j0, j1);
-            float m, l, acc[8];
-            wave_tokens<DT, D, U, NT, true, PF>(a, it, it.hgb * HS + hs, j0, j1, m, l, acc);
-            comb[parity][wave][0][lane] = m;
-            comb[parity][wave][1][lane] = l;
-#pragma unroll
-            for (int i = 0; i < 8; i++) comb[parity][wave][2 + i][lane] = acc[i];
-        }
-        // The only barrier of an item.  Buffer `parity` is next written two items later, after the
-        // barrier of item+1, which the epilogue wave reaches only when it is done reading it.
-        __syncthreads();
-        if (epilogue) {
-            for (int s = 0; s < HS; s++) {
-                const int h = (it.hgb * HS + s) * GH + lane / LPH;
-                if (h < a.H) {
-                    float m, l, acc[8];
-                    combine_splits<TS>(comb[parity], s * TS, lane, m, l, acc);
-                    emit_chunk<D, true>(a, it, h, lane % LPH, m, l, acc);
-                }
-            }
-            if (it.nchunks > 1) {
-                __builtin_amdgcn_s_waitcnt(0);  // this wave's partial stores have completed
-                unsigned int *cnt = a.arrivals + (int64_t)it.b * n_hgb + it.hgb;
-                unsigned int old = 0;
-                if (lane == 0) old = atomicAdd(cnt, 1u);
-                old = __builtin_amdgcn_readfirstlane(old);
-                if (old == (unsigned int)(it.nchunks - 1)) {  // every chunk of this context has arrived
-                    if (lane == 0) atomicExch(cnt, 0u);        // leave the counter clean for the next launch
-                    for (int s = 0; s < HS; s++) {
-                        const int h = (it.hgb * HS + s) * GH + lane / LPH;
-                        if (h < a.H) merge_chunks<D, true>(a, a.H, it.b, h, lane % LPH, it.nchunks);
-                    }
-                }
-            }
-        }
-    }
-}
-
-// One wave per (sequence, head group): merge the chunk partials of contexts longer than one
-// chunk; write zeros for empty contexts; leave single-chunk contexts (already final) alone.
-template <int D>
-__global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
-    constexpr int LPH = D / 8;
-    constexpr int GH = 64 / LPH;
-    const int lane = threadIdx.x & 63;
-    const int n_hg = (a.H + GH - 1) / GH;
-    const int64_t wid = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
-    if (wid >= (int64_t)a.n * n_hg) return;
-    const int b = (int)(wid / n_hg), hg = (int)(wid % n_hg);
-    const int h = hg * GH + lane / LPH, dl = lane % LPH;
-    if (h >= a.H) return;
-    const int nchunks = chunks_of(a, b, a.chunk);
-    if (nchunks == 1) return;
-    if (nchunks > 1) {
-        merge_chunks<D, false>(a, a.H, b, h, dl, nchunks);
-        return;
-    }
-    const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
-    store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, z);
-}
-
-// ------------------------------------------------------------------------------------------
-// variant table and launchers
-// ------------------------------------------------------------------------------------------
-struct Variant {
-    int ts, hs, u, nt, pf;
-};
-// (index, TS, HS, U, NT, PF)
-#define S3_VARIANTS(X)            \
-    X(0, 4, 1, 4, true, false)    \
-    X(1, 8, 1, 4, true, false)    \
-    X(2, 4, 2, 4, true, false)    \
-    X(3, 1, 4, 4, true, false)    \
-    X(4, 8, 1, 8, true, false)    \
-    X(5, 2, 4, 4, true, false)    \
-    X(6, 1, 8, 4, true, false)    \
-    X(7, 4, 1, 2, true, false)    \
-    X(8, 4, 1, 4, false, false)   \
-    X(9, 4, 1, 8, true, false)    \
-    X(10, 4, 2, 8, true, false)   \
-    X(11, 7, 1, 4, true, true)    \
-    X(12, 8, 1, 2, true, true)    \
-    X(13, 15, 1, 2, true, true)   \
-    X(14, 3, 1, 4, true, true)    \
-    X(15, 2, 1, 8, true, false)
-static const Variant kVariants[] = {
-#define X(i, ts, hs, u, nt, pf) {ts, hs, u, nt, pf},
-    S3_VARIANTS(X)
-#undef X
-};
-int s3i_num_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0])); }
-
-template <int DT, int D, bool FUSED>
-static attn_fn pick_variant(int v) {
-    switch (v) {
-#define X(i, ts, hs, u, nt, pf) \
-    case i: return FUSED ? (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt, pf> : (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt, pf>;
-        S3_VARIANTS(X)
-#undef X
+static attn_fn pick_kernel(int dt, int d, int variant, bool fused) {
+    switch (d) {
+        case 64: return s3i_pick_mha_d64(dt, variant, fused);
+        case 96: return s3i_pick_mha_d96(dt, variant, fused);
+        case 128: return s3i_pick_mha_d128(dt, variant, fused);
+        case 256: return s3i_pick_mha_d256(dt, variant, fused);
         default: return nullptr;
     }
 }
 
-template <bool FUSED>
-static attn_fn pick_kernel(int dt, int d, int v) {
-    if (dt == S3_F16) {
-        if (d == 64) return pick_variant<S3_F16, 64, FUSED>(v);
-        if (d == 128) return pick_variant<S3_F16, 128, FUSED>(v);
-        if (d == 256) return pick_variant<S3_F16, 256, FUSED>(v);
-    } else if (dt == S3_BF16) {
-        if (d == 64) return pick_variant<S3_BF16, 64, FUSED>(v);
-        if (d == 128) return pick_variant<S3_BF16, 128, FUSED>(v);
-        if (d == 256) return pick_variant<S3_BF16, 256, FUSED>(v);
-    }
-    return nullptr;
+static attn_fn pick_merge(int d) {
+    return d == 64 ? s3i_pick_merge_d64() : d == 96 ? s3i_pick_merge_d96() : d == 128 ? s3i_pick_merge_d128()
+                                                                                       : s3i_pick_merge_d256();
 }
+
+// Heads that one 128-bit wave load of 16-bit elements covers: 512/D, except that a 96-wide head takes a
+// group of sixteen lanes of which twelve are used (four heads per load).
+static int heads_per_load(int d) { return d == 96 ? 4 : 512 / d; }
 
 static int ensure_scratch(s3_arena *a, size_t need) {
     if (need <= a->scratch_bytes) return S3_OK;
@@ -794,6 +465,7 @@ static AttnArgs common_args(const s3_arena *a, const AttnCall &c, int row_heads,
     const float scale = c.scale > 0.f ? c.scale : 1.0f / sqrtf((float)a->cfg.head_dim);
     args.scale_log2e = scale * 1.4426950408889634f;
     args.len_out = c.with_append ? c.len_out : nullptr;
+    args.merge_sync = a->merge_sync;
     return args;
 }
 
@@ -808,6 +480,36 @@ static int place_scratch(s3_arena *a, AttnArgs &args, size_t cnt_bytes) {
     args.part_acc = (float *)((char *)a->scratch + cnt_bytes);
     args.part_ml = (float2 *)((char *)a->scratch + cnt_bytes + acc_bytes);
     return S3_OK;
+}
+
+// Bytes of the arrival counters at the head of the scratch: one per (sequence, head group), for the largest
+// batch a call takes, so that the partials behind them never move with the batch size.
+static size_t counters_bytes(int n_hg) {
+    return (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;
+}
+
+// Scratch an attention call over n sequences needs at most: the launchers' layout with the smallest chunk
+// they may choose for any batch size (or the chunk the caller fixed).
+static size_t scratch_need(const s3_arena *a, int n) {
+    const int D = a->cfg.head_dim, Hq = a->cfg.n_heads;
+    const int kind = s3i_kernel_kind(a);
+    int chunk = a->chunk;
+    size_t cnt_bytes = 0;
+    if (kind == 0 || kind == 3) {  // kernels that merge chunks themselves carry counters
+        if (chunk <= 0) chunk = 1024;
+        const int gh = kind == 3 ? 1024 / D : heads_per_load(D);
+        cnt_bytes = counters_bytes((Hq + gh - 1) / gh);
+    } else if (chunk <= 0) {
+        chunk = (kind == 2 || kind == 4) ? 128 : 256;
+    }
+    const size_t max_chunks = (size_t)(a->cfg.max_len + chunk - 1) / chunk;
+    const size_t n_part = (size_t)n * max_chunks * Hq;
+    return cnt_bytes + n_part * ((size_t)D * sizeof(float) + sizeof(float2));
+}
+
+extern "C" int s3_kv_reserve_scratch(s3_arena *a, int32_t max_batch) {
+    if (!a || !a->base || max_batch < 1 || max_batch > S3_MAX_BATCH) return S3_ERR_INVALID;
+    return ensure_scratch(a, scratch_need(a, max_batch));
 }
 
 static size_t batch_view_lds(int n, int ncls) {
@@ -853,11 +555,10 @@ static int launch_attn_kernels(s3_arena *a, attn_fn fn, int blocks, int threads,
     if (merge_heads > 0) {
         const int D = a->cfg.head_dim;
         AttnArgs margs = args;
-        margs.H = merge_heads;  // the merge kernel indexes partials and output by head of q, 512/D heads per wave
-        const int GH = 512 / D;
+        margs.H = merge_heads;  // the merge kernel indexes partials and output by head of q
+        const int GH = heads_per_load(D);
         const unsigned mblocks = (unsigned)(((int64_t)args.n * ((merge_heads + GH - 1) / GH) + 3) / 4);
-        void (*mfn)(const AttnArgs) =
-            D == 64 ? attn_merge_kernel<64> : D == 128 ? attn_merge_kernel<128> : attn_merge_kernel<256>;
+        attn_fn mfn = pick_merge(D);
         if (timed) {
             void *kargs[] = {(void *)&margs};
             HIP_TRY(hipExtLaunchKernel((const void *)mfn, dim3(mblocks), dim3(256), kargs, 0, (hipStream_t)stream, nullptr,
@@ -919,8 +620,7 @@ static int launch_fp8(s3_arena *a, const AttnCall &c) {
     if (!fn) return S3_ERR_INVALID;
     AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
     const int n_hg = (H + 1024 / D - 1) / (1024 / D);  // head groups: 1024/D heads per 128-bit wave load of bytes
-    const size_t cnt_bytes = (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;
-    int rc = place_scratch(a, args, cnt_bytes);
+    int rc = place_scratch(a, args, counters_bytes(n_hg));
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;
@@ -938,19 +638,17 @@ static int launch_attention(s3_arena *a, const AttnCall &c) {
     // Defaults from sweeps on MI355X: large chunks keep most contexts in one piece (no cross-workgroup
     // merge), eight waves share an item's rows evenly, each with two batches of two rows in flight
     // alternately (1 % ahead of one batch of four rows on the ragged batch of 64, level on the others).
-    const int variant = a->variant >= 0 ? a->variant : 12;
-    const Variant &vr = kVariants[variant];
+    const int variant = a->variant >= 0 ? a->variant : s3i_default_variant();
     const bool fused = c.with_append;
-    attn_fn fn = fused ? pick_kernel<true>(a->cfg.kv_dtype, D, variant) : pick_kernel<false>(a->cfg.kv_dtype, D, variant);
+    attn_fn fn = pick_kernel(a->cfg.kv_dtype, D, variant, fused);
     if (!fn) return S3_ERR_INVALID;
-    const int GH = 512 / D;
+    const int GH = heads_per_load(D);
     const int n_hg = (H + GH - 1) / GH;
     AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
     args.len_out = c.len_out;
-    const size_t cnt_bytes = (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;
-    int rc = place_scratch(a, args, cnt_bytes);
+    int rc = place_scratch(a, args, counters_bytes(n_hg));
     if (rc != S3_OK) return rc;
-    const int threads = (vr.ts * vr.hs + (fused ? 1 : 0)) * 64;  // the fused kernel adds an epilogue wave
+    const int threads = s3i_variant_threads(variant, fused);  // the fused kernel adds an epilogue wave
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;
     rc = stride_grid(a, (const void *)fn, threads, dyn_lds, c.n > 128 ? 2 : 1, &blocks);  // large batches: two rounds balance better

@@ -53,7 +53,7 @@ class DecodeEngine:
             if w.arena_bytes:
                 arena_tokens = w.arena_bytes // self.bpt
             else:
-                caps = [min(w.max_len, -(-max(s.predicted, 1) // w.granule) * w.granule) for s in w.seqs]
+                caps = [s3.s3_kv_capacity_for(self.cfg, s.predicted) for s in w.seqs]
                 arena_tokens = int(1.5 * sum(caps)) + 2 * w.max_len
         self.arena_tokens = int(arena_tokens)
         self.arena_mem = torch.empty(self.arena_tokens * self.bpt, dtype=torch.uint8, device=self.dev)
@@ -153,6 +153,8 @@ class DecodeEngine:
                 self.len_next = torch.empty_like(self.len_dev)
                 self.out_full = torch.empty((self.capacity, self.w.n_heads, self.w.head_dim),
                                             dtype=_TORCH_DT[self.out_dtype], device=self.dev)
+                # the library's scratch is sized here, once per batch capacity, so that no decode step allocates
+                s3.check(s3.s3_kv_reserve_scratch(self.arena, self.capacity), "s3_kv_reserve_scratch")
             self.slot_off_dev[:n].copy_(self._pinned(self.off), non_blocking=True)
             self.len_dev[:n].copy_(self._pinned(self.len), non_blocking=True)
             self._dirty = False
@@ -237,7 +239,8 @@ class DecodeEngine:
         drop, out = [], []
         for i in full.tolist():
             st, off, cap = self._grow(i)
-            if st == s3.S3_ERR_NOMEM and self.on_nomem == "swap" and self._compact_for(min(2 * int(self.cap[i]), self.w.max_len)):
+            if st == s3.S3_ERR_NOMEM and self.on_nomem == "swap" and self._compact_for(
+                    s3.s3_kv_grown_capacity(self.cfg, int(self.cap[i]))):
                 st, off, cap = self._grow(i)
             if st == s3.S3_OK:
                 self.off[i], self.cap[i] = off, cap
@@ -299,7 +302,7 @@ class DecodeEngine:
         self._evict_done.append(done)
         self._log("evict", int(self.serial[i]), sid, length)
         self.swapped.append(SimpleNamespace(serial=int(self.serial[i]), len=length, total=int(self.total[i]),
-                                            want=min(2 * int(self.cap[i]), self.w.max_len), host=host))
+                                            want=s3.s3_kv_grown_capacity(self.cfg, int(self.cap[i])), host=host))
         self.n_swapped_out += 1
 
     def _host_buffer(self, nbytes):

@@ -583,14 +583,16 @@ def test_shared_kv_heads_attention(H, Hkv, D, dtype):
     lens = [0, 1, 2, 3, 7, 8, 9, 31, 33, 64, 100, 255, 257, 600, 1, 5]
     rig = Rig(2, H, D, dtype, 64, 1024, [max(1, L) for L in lens], seed=70 + H + Hkv, Hkv=Hkv)
     rig.fill(lens, layer=1)
-    for out_dtype in (s3.S3_F32, s3.S3_F16 if dtype == s3.S3_F16 else s3.S3_BF16):
-        q, got = rig.attend(lens, layer=1, out_dtype=out_dtype)
-        want = rig.oracle_attend(q, lens, layer=1)
-        if out_dtype == s3.S3_F32:
-            assert_close(got, want, f"shared kv {H}/{Hkv} d{D}")
-            assert not got[0].any()  # empty context: zeros
-        else:
-            assert np.abs(got - want).max() <= 2e-2
+    q, got = rig.attend(lens, layer=1)
+    want = rig.oracle_attend(q, lens, layer=1)
+    assert_close(got, want, f"shared kv {H}/{Hkv} d{D}")
+    assert not got[0].any()  # empty context: zeros
+    # 16-bit outputs follow the same rule as the multi-head kernels: fp16 within the tolerance; a bf16 output
+    # cannot meet 2e-3 by rounding alone and must equal the fp32 result rounded once
+    _, got16 = rig.attend(lens, layer=1, out_dtype=s3.S3_F16, q=q)
+    assert_close(got16, want, f"shared kv {H}/{Hkv} d{D} fp16 output")
+    _, gotbf = rig.attend(lens, layer=1, out_dtype=s3.S3_BF16, q=q)
+    assert np.array_equal(gotbf, torch.from_numpy(got).to(torch.bfloat16).float().numpy())
     # every kernel shape; chunk sizes from contexts in up to 19 pieces (merged by the second kernel)
     # to all in one piece
     shapes = n_variants(rig.a) if Hkv < H else 1

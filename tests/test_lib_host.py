@@ -49,7 +49,7 @@ def meta_arena(n_layers, H, D, dtype, G, M, nbytes):
 def test_bytes_per_token_matches_the_paper_example():
     cfg = s3.make_config(44, 64, 64, s3.S3_F16, 64, 2048)  # hidden 4096: 4*44*4096
     assert s3.s3_kv_bytes_per_token(cfg) == 4 * 44 * 4096
-    bad = s3.make_config(44, 64, 96, s3.S3_F16, 64, 2048)  # head_dim 96 is not supported by the kernels
+    bad = s3.make_config(44, 64, 80, s3.S3_F16, 64, 2048)  # head_dim 80 is not supported by the kernels
     assert s3.s3_kv_bytes_per_token(bad) == s3.S3_ERR_INVALID
     gptj = s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048)
     assert s3.s3_kv_bytes_per_token(gptj) == 458752
@@ -57,6 +57,53 @@ def test_bytes_per_token_matches_the_paper_example():
     assert s3.s3_kv_bytes_per_token(s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048, 16)) == 458752
     assert s3.s3_kv_bytes_per_token(s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048, 4)) == 458752 // 4
     assert s3.s3_kv_bytes_per_token(s3.make_config(28, 16, 256, s3.S3_BF16, 64, 2048, 1)) == 458752 // 16
+
+
+def test_worked_example_of_the_paper_through_the_library():
+    """Sections 2.1 and 2.2: the 44-layer model with hidden size 6144 (64 heads x 96, table 1) holds
+    4 * l * d_h bytes per token, a maximum-length reservation of 2048 tokens takes about 2.2 GB, and the
+    memory that is left on a 40 GB card admits fewer than twenty of them (golden file)."""
+    g = {}
+    for line in open(os.path.join(ROOT, "tests", "golden", "kv_bytes_worked_example.txt")):
+        if line.strip() and not line.startswith("#"):
+            k, v = line.split()
+            g[k] = int(v)
+    cfg = s3.make_config(g["n_layers"], 64, 96, s3.S3_F16, 64, g["max_len"])
+    assert 64 * 96 == g["hidden"]
+    assert s3.s3_kv_bytes_per_token(cfg) == g["bytes_per_token"] == 1081344
+    assert s3.s3_kv_bytes_per_token(cfg) * g["max_len"] == g["bytes_per_max_reservation"]
+    for key_bytes, key_batch in (("free_bytes_decimal", "max_batch_decimal"), ("free_bytes_binary", "max_batch_binary")):
+        st, a = s3.s3_kv_arena_init(cfg, None, g[key_bytes])
+        assert st == s3.S3_OK
+        rc, ids, offs, caps = s3.s3_kv_alloc(a, [2048] * 25)
+        assert rc == g[key_batch] < 20
+        assert ids[:rc].tolist() == list(range(rc)) and (ids[rc:] == -1).all()
+        assert offs[:rc].tolist() == [2048 * i for i in range(rc)]
+        s3.s3_kv_arena_destroy(a)
+        # the same memory holds many more 50-token sequences when each reserves what is predicted
+        st, a = s3.s3_kv_arena_init(cfg, None, g[key_bytes])
+        many, *_ = s3.s3_kv_alloc(a, [50] * 1000)
+        assert many == min(1000, (g[key_bytes] // g["bytes_per_token"]) // 64) and many > 10 * rc
+        s3.s3_kv_arena_destroy(a)
+    # 96-wide heads are a multi-head 16-bit shape only
+    assert s3.s3_kv_bytes_per_token(s3.make_config(1, 64, 96, s3.S3_F16, 64, 2048, 8)) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_bytes_per_token(s3.make_config(1, 64, 96, s3.S3_E4M3, 64, 2048, 0, s3.S3_F16)) == s3.S3_ERR_INVALID
+
+
+def test_reservation_rules_equal_the_oracles():
+    """Capacity for a prediction (sections 1, 2.3) and the doubled reservation (section 3, supervisor
+    paragraph) as the library exports them, against the oracle's."""
+    for G, M in ((64, 2048), (128, 2048), (64, 320), (32, 16384)):
+        cfg = s3.make_config(1, 2, 64, s3.S3_F16, G, M)
+        o = orc.KVOracle(1, 2, 64, orc.F16, G, M, 10**6, store=False)
+        for p in list(range(0, 3 * G + 2)) + [M - 1, M, M + 1, 10**6, 2**31 - 1]:
+            assert s3.s3_kv_capacity_for(cfg, p) == o.capacity_for(p), (G, M, p)
+        for cap in range(0, M + G, G):
+            assert s3.s3_kv_grown_capacity(cfg, cap) == o.grown_capacity(cap), (G, M, cap)
+        assert s3.s3_kv_capacity_for(cfg, -1) == s3.S3_ERR_INVALID
+        assert s3.s3_kv_grown_capacity(cfg, -1) == s3.S3_ERR_INVALID
+    bad = s3.make_config(1, 2, 64, s3.S3_F16, 64, 100)
+    assert s3.s3_kv_capacity_for(bad, 1) == s3.S3_ERR_INVALID and s3.s3_kv_grown_capacity(bad, 64) == s3.S3_ERR_INVALID
 
 
 def test_config_validation():
@@ -220,3 +267,61 @@ def test_compact_validation():
     assert (st, new_off.tolist(), moved) == (0, [64], 2)
     assert s3.s3_kv_slot_info(a, 1) == (0, 0, 64) and s3.s3_kv_stats(a) == (0, 192, 832, 832, 1024)
     s3.s3_kv_arena_destroy(a)
+
+
+def test_write_through_partials_carry_the_cache_bits_the_in_kernel_merge_relies_on(tmp_path):
+    """Chunks of one context that meet inside one launch exchange their partial sums through memory between
+    workgroups on different XCDs (each with its own L2).  The default ordering relies on `volatile` vector
+    stores and loads being emitted as write-through / cache-bypassing accesses on gfx950 (cache bits sc0 sc1)
+    and on the fence-based ordering emitting an L2 write-back before and an invalidate after the counter.
+    This compiles the library's own helpers and reads the bits off the emitted code, so that a compiler
+    change shows up here and not as a rare wrong merge."""
+    import shutil
+    import subprocess
+
+    hipcc = shutil.which("hipcc") or "/opt/rocm/bin/hipcc"
+    if not os.path.exists(hipcc):
+        pytest.skip("no hipcc here")
+    src = tmp_path / "probe.hip"
+    src.write_text('''
+#include <hip/hip_runtime.h>
+#include "s3kv_device.h"
+__global__ void probe_put(float *p, float x) {
+    put_partial4<true>(p + 4 * threadIdx.x, (f32x4){x, x, x, x});
+    put_partial2<true>(p + 4096 + 2 * threadIdx.x, (f32x2){x, x});
+}
+__global__ void probe_get(const float *p, float *out) {
+    const f32x4 a = get_partial4<true>(p + 4 * threadIdx.x);
+    const f32x2 b = get_partial2<true>(p + 4096 + 2 * threadIdx.x);
+    out[threadIdx.x] = a[0] + a[1] + a[2] + a[3] + b[0] + b[1];
+}
+__global__ void probe_plain(float *p, float x) { put_partial4<false>(p + 4 * threadIdx.x, (f32x4){x, x, x, x}); }
+__global__ void probe_arrive(AttnArgs a, unsigned int *cnt, int *flag) {
+    if (chunk_arrived(a, cnt, 2)) flag[threadIdx.x] = 1;
+}
+''')
+    csrc = os.path.join(ROOT, "paper_2306_06000_amd", "csrc")
+    asm = tmp_path / "probe.s"
+    subprocess.run([hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "--cuda-device-only", "-S", "-I", csrc, "-I",
+                    os.path.join(ROOT, "include"), "-x", "hip", str(src), "-o", str(asm)], check=True,
+                   stdout=subprocess.PIPE, stderr=subprocess.STDOUT)
+    text = asm.read_text()
+
+    def body(kernel):
+        m = re.search(r"^_Z\d+" + kernel + r"\w*:[^\n]*\n(.*?)s_endpgm", text, flags=re.S | re.M)
+        assert m, kernel
+        return m.group(1)
+
+    put = body("probe_put")
+    assert re.search(r"(global|flat)_store_dwordx4 .*\bsc0\b.*\bsc1\b", put), put
+    assert re.search(r"(global|flat)_store_dwordx2 .*\bsc0\b.*\bsc1\b", put), put
+    get = body("probe_get")
+    assert re.search(r"(global|flat)_load_dwordx4 .*\bsc0\b.*\bsc1\b", get), get
+    assert re.search(r"(global|flat)_load_dwordx2 .*\bsc0\b.*\bsc1\b", get), get
+    plain = body("probe_plain")
+    assert "_store_dwordx4" in plain and "sc0" not in plain  # the bits come from `volatile`, not from every store
+    arrive = body("probe_arrive")
+    # both orderings are in the code (merge_sync picks one at run time): the fenced one writes the L2 back before
+    # the count and invalidates after it; the default drains the wave's memory counter before the count
+    assert "buffer_wbl2" in arrive and "buffer_inv" in arrive and "global_atomic_add" in arrive
+    assert re.search(r"s_waitcnt vmcnt\(0\).*global_atomic_add", arrive, flags=re.S)
