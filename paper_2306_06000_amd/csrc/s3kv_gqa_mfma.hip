@@ -26,9 +26,10 @@
 //     cached rows at ONE d per lane, while memory holds eight d of one row per 16-byte load: the V
 //     tile goes through a per-wave LDS buffer (row-major, row stride padded by 8 bytes so that the
 //     four lane groups hit different banks) and is read back as 16-bit gathers.
-//   * p is rounded to the storage type for the second product; for bfloat16 (8-bit mantissa) it
-//     is split into a high and a low bfloat16 part and the product is issued for both, which
-//     keeps the weights' error near 2^-16 instead of 2^-9.
+//   * p enters the second product as two 16-bit operands of the storage type, a high part (p rounded)
+//     and a low part (the remainder, rounded), and the product is issued for both, which keeps the
+//     weights' error near 2^-16 (bfloat16) / 2^-22 (fp16) instead of 2^-9 / 2^-12: with one part only,
+//     values of magnitude 1e2 put the fp16 kernel outside the attention tolerance.
 // Accumulators: O^T block db holds O^T[d = 16*db + 4*g + i][head], fp32.  Results leave as the
 // final row (single-chunk contexts) or as a chunk partial (max, sum, unnormalised row) that
 // attn_merge_kernel finishes (merging in this kernel through an arrival counter and device-scope
@@ -229,14 +230,22 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
                 lsum += p[i];
             }
 
+            // The weights enter the second product as 16-bit operands: a high part (p rounded to the type) and
+            // a low part (what the high part misses, rounded again), two products per value block.  Together
+            // they carry about twice the type's mantissa, so the weighted sum is as exact as the fp32 weights
+            // allow, also for values of large magnitude (one rounded part alone is off by 2^-12 of |p v|).
             u32x2 pop, pop_lo;
+            float r[4];
             if (DT == S3_F16) {
+#pragma unroll
+                for (int i = 0; i < 4; i++) r[i] = p[i] - (float)(_Float16)p[i];
                 pop[0] = pack_f16(p[0], p[1]);
                 pop[1] = pack_f16(p[2], p[3]);
+                pop_lo[0] = pack_f16(r[0], r[1]);
+                pop_lo[1] = pack_f16(r[2], r[3]);
             } else {
-                float r[4];
 #pragma unroll
-                for (int i = 0; i < 4; i++) r[i] = p[i] - (float)(__bf16)p[i];  // what the high part misses
+                for (int i = 0; i < 4; i++) r[i] = p[i] - (float)(__bf16)p[i];
                 pop[0] = pack_bf16(p[0], p[1]);
                 pop[1] = pack_bf16(p[2], p[3]);
                 pop_lo[0] = pack_bf16(r[0], r[1]);
@@ -269,7 +278,7 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
                     vop = (u32x2){v0 | (v1 << 16), v2 | (v3 << 16)};
                 }
                 o[db] = mfma_values<DT>(vop, pop, o[db]);
-                if (DT != S3_F16) o[db] = mfma_values<DT>(vop, pop_lo, o[db]);
+                o[db] = mfma_values<DT>(vop, pop_lo, o[db]);
             }
             __builtin_amdgcn_wave_barrier();
         };

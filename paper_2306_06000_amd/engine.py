@@ -70,6 +70,7 @@ class DecodeEngine:
             quarter = max(w.granule, w.max_len // 4) * self.bpt
             self._host_free = [torch.empty(quarter, dtype=torch.uint8, pin_memory=True) for _ in range(8)]
         self.out_dtype = out_dtype
+        self._row_term, self._seq_term = self._byte_terms()  # bytes per cached row and per sequence of one layer-step
         self.events = [] if log_events else None
         self.next_serial = 0
         self.pool_pos = 0
@@ -89,6 +90,11 @@ class DecodeEngine:
         self._dirty = True   # the device arrays must be rebuilt (batch membership or order changed)
         self._patch = set()  # entries whose offset / length changed in place
         self.out = None
+        self._out_n = -1     # batch size self.out was cut for
+        # steps until some sequence fills its slot / reaches its total length (the per-step checks run only
+        # then), and the rows the batch holds; refreshed by _recount() whenever membership or lengths change
+        self._to_full = self._to_done = 0
+        self._rows = 0
 
     # -- helpers ----------------------------------------------------------
     def close(self):
@@ -153,12 +159,26 @@ class DecodeEngine:
                 self.len_next = torch.empty_like(self.len_dev)
                 self.out_full = torch.empty((self.capacity, self.w.n_heads, self.w.head_dim),
                                             dtype=_TORCH_DT[self.out_dtype], device=self.dev)
+                self._out_n = -1
                 # the library's scratch is sized here, once per batch capacity, so that no decode step allocates
                 s3.check(s3.s3_kv_reserve_scratch(self.arena, self.capacity), "s3_kv_reserve_scratch")
             self.slot_off_dev[:n].copy_(self._pinned(self.off), non_blocking=True)
             self.len_dev[:n].copy_(self._pinned(self.len), non_blocking=True)
             self._dirty = False
-        self.out = self.out_full[:n]
+            self._out_n = -1
+        if n != self._out_n:
+            self.out = self.out_full[:n]
+            self._out_n = n
+
+    def _recount(self):
+        n = self.n_active
+        if n:
+            self._to_full = int((self.cap - self.len).min())
+            self._to_done = int((self.total - self.len).min())
+            self._rows = int(self.len.sum())
+        else:
+            self._to_full = self._to_done = 1 << 30
+            self._rows = 0
 
     def _set_batch(self, recs):
         self.serial = np.array([r[0] for r in recs], np.int64)
@@ -168,6 +188,7 @@ class DecodeEngine:
         self.len = np.array([r[4] for r in recs], np.int32)
         self.total = np.array([r[5] for r in recs], np.int32)
         self._dirty = True
+        self._recount()
 
     # -- admission --------------------------------------------------------
     def admit(self, seqs, prefill, fill=True):
@@ -187,13 +208,24 @@ class DecodeEngine:
             if sid < 0:
                 continue
             rows = s.start
-            for layer in range(self.w.n_layers if fill else 0):
-                k_rows, v_rows = prefill(serial, layer, rows)
-                s3.check(s3.s3_kv_fill(self.arena, sid, layer, 0, rows, k_rows, v_rows, self._stream_ptr()),
-                         "s3_kv_fill")
             self._log("fill", serial, sid, rows)
             admitted.append((serial, sid, off, cap, rows, s.total))
+        if fill:
+            self._fill_admitted(admitted, prefill)
         return admitted
+
+    def _fill_admitted(self, admitted, prefill):
+        """Prompt rows of newly admitted sequences: one s3_kv_fill_batch call per layer (sixteen newcomers
+        per launch) instead of one launch per sequence and layer."""
+        if not admitted:
+            return
+        sids = np.array([r[1] for r in admitted], np.int32)
+        rows = np.array([r[4] for r in admitted], np.int32)
+        st = self._stream_ptr()
+        for layer in range(self.w.n_layers):
+            kv = [prefill(r[0], layer, r[4]) for r in admitted]
+            s3.check(s3.s3_kv_fill_batch(self.arena, layer, sids, rows, [x[0] for x in kv], [x[1] for x in kv], st),
+                     "s3_kv_fill_batch")
 
     def admit_scheduled(self, max_out, prefill, fill=True):
         """Let the scheduler admit up to max_out waiting requests (decreasing first fit).  Same return value
@@ -209,24 +241,23 @@ class DecodeEngine:
         admitted = []
         for serial, rid, sid, off, cap in zip(serials, rids.tolist(), sids.tolist(), offs.tolist(), caps.tolist()):
             r = self._requests[rid]
-            for layer in range(self.w.n_layers if fill else 0):
-                k_rows, v_rows = prefill(serial, layer, r.start)
-                s3.check(s3.s3_kv_fill(self.arena, sid, layer, 0, r.start, k_rows, v_rows, self._stream_ptr()),
-                         "s3_kv_fill")
             self._log("fill", serial, sid, r.start)
             admitted.append((serial, sid, off, cap, r.start, r.total))
+        if fill:
+            self._fill_admitted(admitted, prefill)
         return admitted
 
     def start(self, prefill, stop_when_full=False):
         recs = []
         if self.admission == "dff":
             recs = self.admit_scheduled(self.w.batch, prefill)
-        elif stop_when_full:  # admit candidates one by one until the arena refuses one
+        elif stop_when_full:  # admit candidates one by one until the arena refuses one; then write their rows
             for s in self.w.seqs:
-                got = self.admit([s], prefill)
+                got = self.admit([s], prefill, fill=False)
                 if not got:
                     break
                 recs += got
+            self._fill_admitted(recs, prefill)
         else:
             recs = self.admit(self.w.seqs, prefill)
         self._set_batch(recs)
@@ -260,6 +291,7 @@ class DecodeEngine:
             self.n_evicted += 1
         if drop or out:
             self._remove(drop + out)
+        self._recount()
 
     def _grow(self, i):
         self._guard_freed_rows()
@@ -378,11 +410,15 @@ class DecodeEngine:
                                                 self.out_dtype, 0.0, st), "s3_decode_attention")
         self.len_dev, self.len_next = self.len_next, self.len_dev
         self.len += 1
+        self._rows += n
+        self._to_full -= 1
+        self._to_done -= 1
         return self.out
 
     def retire_and_refill(self, prefill):
         done = np.nonzero(self.len >= self.total)[0]
         if done.size == 0 and not (self.swapped and self.n_active == 0):
+            self._recount()
             return  # nothing was freed (a batch that is entirely on the host must come back, though)
         keep = np.ones(self.n_active, bool)
         for i in done.tolist():
@@ -433,6 +469,7 @@ class DecodeEngine:
             room = got is not None
             if got:
                 self._append_entry(got)
+        self._recount()
 
     def _append_entry(self, rec):
         for name, v in zip(("serial", "slot", "off", "cap", "len", "total"), rec):
@@ -441,13 +478,15 @@ class DecodeEngine:
         self._patch.add(self.n_active - 1)
 
     def step(self, tensors, prefill, check_host=False):
-        self.grow_full_slots()
+        if self._to_full <= 0:  # some slot is full: double it (or compact / swap / drop)
+            self.grow_full_slots()
         out = self.launch_step(tensors, check_host)
-        self.last_step_bytes = self.algorithmic_bytes() * self.w.n_layers
+        self.last_step_bytes = (self._row_term * self._rows + self._seq_term * self.n_active) * self.w.n_layers
         self.last_step_seqs = self.n_active
         if self.events is not None:
             self._log("step", self.serial.tolist(), self.len.tolist())
-        self.retire_and_refill(prefill)
+        if self._to_done <= 0 or (self.swapped and self.n_active == 0):  # some sequence has finished
+            self.retire_and_refill(prefill)
         return out
 
     # -- accounting -------------------------------------------------------
@@ -462,6 +501,14 @@ class DecodeEngine:
         kvd = self.w.kv_heads * self.w.head_dim  # elements of one cached row
         B = self.n_active
         return 2 * kvd * ec * int(self.len.sum()) + B * hd * e + B * hd * e_out + 2 * B * kvd * (e + ec)
+
+    def _byte_terms(self):
+        """The same count as two factors: bytes per cached row, bytes per sequence (one layer-step)."""
+        e, ec = 2, self.w.elem_bytes
+        e_out = {s3.S3_F32: 4, s3.S3_F16: 2, s3.S3_BF16: 2}[self.out_dtype]
+        hd = self.w.n_heads * self.w.head_dim
+        kvd = self.w.kv_heads * self.w.head_dim
+        return 2 * kvd * ec, hd * e + hd * e_out + 2 * kvd * (e + ec)
 
     def read_slot(self, a, layer, which, n_rows=None):
         n_rows = a.len if n_rows is None else n_rows

@@ -124,16 +124,31 @@ def errors(got, want):
     return float(np.abs(got - want).max()), float(np.linalg.norm((got - want).ravel()) / max(np.linalg.norm(want.ravel()), 1e-30))
 
 
-def check_cases(rig, q, tag, bad, chunks):
+def check_cases(rig, q, tag, bad, chunks, via_twin=False):
     """Attention of the rig's batch at several chunk sizes against the fp32 oracle; failures are collected
-    (with the oracle's own distance to its float64 twin) so that one run reports every case."""
+    (with the oracle's own distance to its float64 twin) so that one run reports every case.
+    via_twin: for outputs of magnitude 1e2 under a hard arg-max the fp32 definition itself is only determined
+    to about 2e-2 (near ties between scores of magnitude 1e2 turn one ulp of a score into 1e-5 of a weight,
+    times values of 1e2: measured as the fp32 oracle's distance to its float64 twin), so an absolute 2e-3
+    against the fp32 oracle would test the oracle's rounding, not the kernel.  There the kernel is held to the
+    float64 twin instead: no further from it than 2e-3 plus twice the fp32 oracle's own distance; the relative
+    L2 bound against the fp32 oracle stays as it is."""
     for chunk in chunks:
         assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
         qb, got = rig.attend(q)
         want = rig.want(qb)
         ma, rel = errors(got, want)
-        if not (np.isfinite(got).all() and ma <= MAX_ABS and rel <= REL_L2):
-            oa, orel = errors(want, rig.want(qb, precision="f64"))
+        ok = np.isfinite(got).all() and rel <= REL_L2
+        oa = orel = 0.0
+        if ok and via_twin:
+            twin = rig.want(qb, precision="f64")
+            oa, orel = errors(want, twin)
+            ok = errors(got, twin)[0] <= MAX_ABS + 2.0 * oa
+        elif ok:
+            ok = ma <= MAX_ABS
+        if not ok:
+            if not via_twin:
+                oa, orel = errors(want, rig.want(qb, precision="f64"))
             bad.append(f"{rig.name} / {tag} / chunk {chunk}: max-abs {ma:.3e} rel-L2 {rel:.3e} "
                        f"(fp32 oracle vs float64 twin: {oa:.3e} {orel:.3e})")
 
@@ -171,10 +186,15 @@ def test_peaked_softmax_dominant_keys_and_large_magnitudes(fam):
         check_cases(rig, q, f"dominant key {where}", bad, chunks)
         rig.close()
 
-    # 3. keys and values of magnitude 1e2 (scores of magnitude 1e2: a hard arg-max with near ties now and then)
+    # 3. keys of magnitude 1e2 (scores of magnitude 1e2: a hard arg-max with near ties now and then), values
+    # of magnitude 1; then both at 1e2 (held to the float64 twin, see check_cases)
+    rig = EdgeRig(fam, lens)
+    rig.put([100.0 * k for k in K], V)
+    check_cases(rig, q, "K x100", bad, chunks)
+    rig.close()
     rig = EdgeRig(fam, lens)
     rig.put([100.0 * k for k in K], [100.0 * v for v in V])
-    check_cases(rig, q, "K, V x100", bad, chunks)
+    check_cases(rig, q, "K, V x100", bad, chunks, via_twin=True)
     rig.close()
 
     # 4. values of magnitude 1e2 under a flat softmax (tiny queries): sums of large terms
