@@ -62,7 +62,9 @@ typedef enum {
     S3_ERR_NOMEM = -2,     /* the arena cannot fit the request; state unchanged */
     S3_ERR_SLOT_FULL = -3, /* append at pos == capacity; nothing written, nothing launched */
     S3_ERR_MAXLEN = -4,    /* grow of a slot whose capacity already is max_len */
-    S3_ERR_HIP = -5        /* a HIP call failed; see s3_last_hip_error() */
+    S3_ERR_HIP = -5,       /* a HIP call failed; see s3_last_hip_error() */
+    S3_ERR_SCRATCH = -6    /* s3_decode_step_static: the call needs more chunk-partial scratch than the
+                              library's fixed device buffer holds; nothing launched */
 } s3_status;
 
 typedef struct {
@@ -177,6 +179,25 @@ int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, co
 int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
                    const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
                    const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out, void *stream);
+
+/* For callers that cannot allocate device memory: code recorded into a HIP graph, serving loops that must
+ * never synchronise, harnesses that forbid hipMalloc.  Exactly s3_decode_step (same arguments, checks,
+ * kernels and results), except that the chunk partials and arrival counters live in a fixed buffer that is
+ * part of the library's device image (S3_STATIC_SCRATCH_BYTES = 32 MiB, held by every GPU the library runs
+ * on until the process ends) instead of the arena's scratch: the call makes no hipMalloc, hipFree or other
+ * allocating call and never synchronises.  A call that needs more - about
+ * n * ceil(max_len / chunk) * n_heads * (4 * head_dim + 8) bytes plus the counters; 32 MiB hold the
+ * 28-layer, 721-sequence GPT-J batch at the default chunk - returns S3_ERR_SCRATCH and launches nothing.
+ * The "profile" parameter does not time these launches (its events are allocated).  All calls on one GPU,
+ * from every arena, share the buffer and it keeps the last call's contents: the counters are left at zero
+ * by every launch (and are cleared by a small kernel on `stream` whenever the previous call on this GPU laid
+ * the buffer out differently), partials are always written before they are read; calls that overlap on one
+ * GPU (two streams, two threads) race on it. */
+int s3_decode_step_static(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
+                          const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
+                          const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out,
+                          void *stream);
+#define S3_STATIC_SCRATCH_BYTES (32u << 20)
 
 /* Size the arena's own scratch (chunk partials, arrival counters) once, for batches of up to max_batch
  * sequences at the current "chunk" setting, so that s3_decode_attention / s3_decode_step never allocate or

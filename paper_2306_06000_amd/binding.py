@@ -12,7 +12,8 @@ import os
 import numpy as np
 
 S3_F16, S3_BF16, S3_F32, S3_E4M3 = 0, 1, 2, 3
-S3_OK, S3_ERR_INVALID, S3_ERR_NOMEM, S3_ERR_SLOT_FULL, S3_ERR_MAXLEN, S3_ERR_HIP = 0, -1, -2, -3, -4, -5
+S3_OK, S3_ERR_INVALID, S3_ERR_NOMEM, S3_ERR_SLOT_FULL, S3_ERR_MAXLEN, S3_ERR_HIP, S3_ERR_SCRATCH = 0, -1, -2, -3, -4, -5, -6
+S3_STATIC_SCRATCH_BYTES = 32 << 20
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("S3KV_LIB") or os.path.join(_HERE, "libs3kv.so")  # S3KV_LIB: a diagnostic build
@@ -41,6 +42,7 @@ SIGNATURES = {
     "s3_kv_append": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp]),
     "s3_decode_attention": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp, _vp, _vp, _i32, _f32, _vp]),
     "s3_decode_step": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]),
+    "s3_decode_step_static": (ctypes.c_int, [_vp, _i32, _i32, _pi32, _pi32, _vp, _vp, _vp, _vp, _vp, _vp, _i32, _f32, _vp, _vp]),
     "s3_kv_grow": (ctypes.c_int, [_vp, _i32, _i32, _pi64, _pi32, _vp]),
     "s3_kv_compact": (ctypes.c_int, [_vp, _i32, _pi32, _pi32, _pi64, _pi32, _vp]),
     "s3_kv_evict_bytes": (_i64, [_vp, _i32]),
@@ -178,6 +180,16 @@ def s3_decode_step(arena, layer, n, slot_off, pos, q, k_new, v_new, out, out_dty
     _b, php = _host_i32(pos_host)
     return lib().s3_decode_step(arena, int(layer), int(n), idp, php, _ptr(slot_off), _ptr(pos), _ptr(q), _ptr(k_new),
                                 _ptr(v_new), _ptr(out), int(out_dtype), float(scale), _ptr(len_out), stream or None)
+
+
+def s3_decode_step_static(arena, layer, n, slot_off, pos, q, k_new, v_new, out, out_dtype=S3_F32, scale=0.0, len_out=None,
+                          stream=0, slot_id=None, pos_host=None):
+    """s3_decode_step for callers that cannot allocate: the library's fixed device scratch is used."""
+    _a, idp = _host_i32(slot_id)
+    _b, php = _host_i32(pos_host)
+    return lib().s3_decode_step_static(arena, int(layer), int(n), idp, php, _ptr(slot_off), _ptr(pos), _ptr(q),
+                                       _ptr(k_new), _ptr(v_new), _ptr(out), int(out_dtype), float(scale), _ptr(len_out),
+                                       stream or None)
 
 
 def s3_kv_grow(arena, slot_id, length, stream=0):

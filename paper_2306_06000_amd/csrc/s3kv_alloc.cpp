@@ -33,6 +33,7 @@ extern "C" const char *s3_status_str(int status) {
         case S3_ERR_SLOT_FULL: return "S3_ERR_SLOT_FULL";
         case S3_ERR_MAXLEN: return "S3_ERR_MAXLEN";
         case S3_ERR_HIP: return "S3_ERR_HIP";
+        case S3_ERR_SCRATCH: return "S3_ERR_SCRATCH";
         default: return status > 0 ? "count" : "unknown";
     }
 }
@@ -74,6 +75,7 @@ extern "C" int s3_kv_arena_init(s3_arena **out, const s3_kv_config *cfg, void *d
     if (a->n_tokens > 0) a->free_ext[0] = a->n_tokens;
     if (dev_base) {
         int rc = s3i_device_cus(&a->num_cus);
+        if (rc == S3_OK) rc = s3i_static_scratch_setup();
         if (rc != S3_OK) {
             delete a;
             return rc;

@@ -77,3 +77,4 @@ int s3i_kernel_kind(const s3_arena *a);
 int s3i_profile_collect(s3_arena *a);  // synchronises on the recorded events and accumulates the sums
 void s3i_profile_reset(s3_arena *a);
 int s3i_device_cus(int32_t *cus);
+int s3i_static_scratch_setup();  // resolves the device address of the fixed scratch of s3_decode_step_static

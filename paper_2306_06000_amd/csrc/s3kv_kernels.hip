@@ -299,6 +299,75 @@ static int ensure_scratch(s3_arena *a, size_t need) {
     return S3_OK;
 }
 
+// ---- the fixed scratch of s3_decode_step_static ------------------------------------------
+// Part of the library's device image: every GPU that loads the library holds its own copy at its own
+// address until the process ends.  In host code the array's name is only a handle for the runtime; the
+// device address is asked for once per device (with that device current) and only that address is ever
+// handed to kernels.
+static __device__ __align__(256) unsigned char s3_static_scratch[S3_STATIC_SCRATCH_BYTES];
+
+#define S3_MAX_DEVICES 64
+struct StaticScratch {
+    void *ptr = nullptr;      // device address of s3_static_scratch on this device
+    size_t counter_bytes = 0; // counter region of the last call on this device (0: none yet)
+};
+static StaticScratch g_static[S3_MAX_DEVICES];
+static std::mutex g_static_guard;
+
+__global__ void __launch_bounds__(256) zero_words_kernel(unsigned int *p, size_t n) {
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n; i += stride) p[i] = 0u;
+}
+
+// The current device's entry, with the buffer's device address resolved (once per device).  Caller holds the guard.
+static int static_scratch_entry(StaticScratch **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= S3_MAX_DEVICES) return S3_ERR_INVALID;
+    StaticScratch &st = g_static[dev];
+    if (!st.ptr) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(s3_static_scratch)));
+        if (!p || ((uintptr_t)p & 255)) return S3_ERR_INVALID;
+        st.ptr = p;
+    }
+    *out = &st;
+    return S3_OK;
+}
+
+// Called when an arena is created over device memory: the address is then known before the first decode step
+// (which may run where no runtime query is wanted, e.g. under graph capture).
+int s3i_static_scratch_setup() {
+    std::lock_guard<std::mutex> lock(g_static_guard);
+    StaticScratch *st = nullptr;
+    return static_scratch_entry(&st);
+}
+
+// Address of the current device's fixed scratch, laid out with cnt_bytes of arrival counters at its head.
+// The counters must be zero before a launch.  Every launch leaves them at zero, but the region may hold
+// partials of a call that laid the buffer out with fewer counter bytes (another arena kind): whenever the
+// counter region differs from the last call's on this device (the first call included) it is cleared by a
+// kernel on `stream` (a kernel, not a memset, so that the call can be recorded into a graph).
+static int static_scratch_for_call(size_t cnt_bytes, void *stream, char **out) {
+    std::lock_guard<std::mutex> lock(g_static_guard);
+    StaticScratch *entry = nullptr;
+    const int src = static_scratch_entry(&entry);
+    if (src != S3_OK) return src;
+    StaticScratch &st = *entry;
+    if (cnt_bytes != st.counter_bytes) {
+        const size_t clear = cnt_bytes > st.counter_bytes ? cnt_bytes : st.counter_bytes;
+        if (clear > 0) {
+            const size_t words = clear / sizeof(unsigned int);
+            hipLaunchKernelGGL(zero_words_kernel, dim3((unsigned)((words + 1023) / 1024)), dim3(256), 0,
+                               (hipStream_t)stream, (unsigned int *)st.ptr, words);
+            HIP_TRY(hipGetLastError());
+        }
+        st.counter_bytes = cnt_bytes;
+    }
+    *out = (char *)st.ptr;
+    return S3_OK;
+}
+
 // ---- optional event timing of the attention kernels -------------------------------------
 static int prof_next_event(s3_arena *a, hipEvent_t *ev) {
     if (a->prof_used == a->prof_events.size()) {
@@ -430,6 +499,7 @@ struct AttnCall {
     bool with_append;
     const void *k_new, *v_new;
     int32_t *len_out;
+    bool static_scratch;  // s3_decode_step_static: partials and counters in the library's fixed device buffer
 };
 
 static size_t batch_view_lds(int n, int ncls);
@@ -471,14 +541,23 @@ static AttnArgs common_args(const s3_arena *a, const AttnCall &c, int row_heads,
 
 // Library scratch: [arrival counters: cnt_bytes, fixed per arena kind, zero between launches]
 // [partial sums][partial (max, sum)], one partial per (sequence, chunk, head of q).
-static int place_scratch(s3_arena *a, AttnArgs &args, size_t cnt_bytes) {
+static int place_scratch(s3_arena *a, AttnArgs &args, size_t cnt_bytes, const AttnCall &c) {
     const size_t n_part = (size_t)args.n * args.max_chunks * args.Hq;
     const size_t acc_bytes = n_part * a->cfg.head_dim * sizeof(float);
-    const int rc = ensure_scratch(a, cnt_bytes + acc_bytes + n_part * sizeof(float2));
-    if (rc != S3_OK) return rc;
-    args.arrivals = (unsigned int *)a->scratch;
-    args.part_acc = (float *)((char *)a->scratch + cnt_bytes);
-    args.part_ml = (float2 *)((char *)a->scratch + cnt_bytes + acc_bytes);
+    const size_t need = cnt_bytes + acc_bytes + n_part * sizeof(float2);
+    char *base = nullptr;
+    if (c.static_scratch) {  // no allocation on this path: the fixed buffer holds the call, or the call is refused
+        if (need > (size_t)S3_STATIC_SCRATCH_BYTES) return S3_ERR_SCRATCH;
+        const int rc = static_scratch_for_call(cnt_bytes, c.stream, &base);
+        if (rc != S3_OK) return rc;
+    } else {
+        const int rc = ensure_scratch(a, need);
+        if (rc != S3_OK) return rc;
+        base = (char *)a->scratch;
+    }
+    args.arrivals = (unsigned int *)base;
+    args.part_acc = (float *)(base + cnt_bytes);
+    args.part_ml = (float2 *)(base + cnt_bytes + acc_bytes);
     return S3_OK;
 }
 
@@ -534,9 +613,9 @@ static int stride_grid(const s3_arena *a, const void *fn, int threads, size_t dy
 // (it finishes multi-chunk contexts and writes the zero rows of empty ones).  Every k-th call (the
 // "profile" parameter) is bracketed with events: before, after the attention kernel, after the merge.
 static int launch_attn_kernels(s3_arena *a, attn_fn fn, int blocks, int threads, size_t dyn_lds, void *stream,
-                               const AttnArgs &args, int merge_heads) {
+                               const AttnArgs &args, int merge_heads, bool may_time) {
     hipEvent_t ev[3] = {nullptr, nullptr, nullptr};
-    const bool timed = a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
+    const bool timed = may_time && a->profile > 0 && (a->prof_tick++ % a->profile) == 0;
     if (timed) {
         for (int i = 0; i < 3; i++) {
             const int prc = prof_next_event(a, &ev[i]);
@@ -602,13 +681,13 @@ static int launch_gqa(s3_arena *a, const AttnCall &c) {
                       : (int64_t)c.n * per_seq >= 2048 ? 1024 : (int64_t)c.n * per_seq >= 512 ? 512 : 256;
     AttnArgs args = common_args(a, c, Hkv, Hq, chunk);
     if (mfma && a->ncls <= 0) args.ncls = 1;  // items of at most 128 rows are all alike: no order to gain from (measured)
-    int rc = place_scratch(a, args, 0);
+    int rc = place_scratch(a, args, 0, c);
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;
     rc = stride_grid(a, (const void *)fn, threads, dyn_lds, 1, &blocks);
     if (rc != S3_OK) return rc;
-    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, Hq);
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, Hq, !c.static_scratch);
 }
 
 // 8-bit cache rows: one kernel, which in a decode step also quantises and appends the new row, merges
@@ -620,13 +699,13 @@ static int launch_fp8(s3_arena *a, const AttnCall &c) {
     if (!fn) return S3_ERR_INVALID;
     AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
     const int n_hg = (H + 1024 / D - 1) / (1024 / D);  // head groups: 1024/D heads per 128-bit wave load of bytes
-    int rc = place_scratch(a, args, counters_bytes(n_hg));
+    int rc = place_scratch(a, args, counters_bytes(n_hg), c);
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;
     rc = stride_grid(a, (const void *)fn, threads, dyn_lds, c.n > 128 ? 2 : 1, &blocks);
     if (rc != S3_OK) return rc;
-    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, 0);  // the kernel merges by itself
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, 0, !c.static_scratch);  // the kernel merges by itself
 }
 
 // Shared by s3_decode_attention (partial kernel + merge kernel) and s3_decode_step (with_append: one
@@ -646,14 +725,14 @@ static int launch_attention(s3_arena *a, const AttnCall &c) {
     const int n_hg = (H + GH - 1) / GH;
     AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
     args.len_out = c.len_out;
-    int rc = place_scratch(a, args, counters_bytes(n_hg));
+    int rc = place_scratch(a, args, counters_bytes(n_hg), c);
     if (rc != S3_OK) return rc;
     const int threads = s3i_variant_threads(variant, fused);  // the fused kernel adds an epilogue wave
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;
     rc = stride_grid(a, (const void *)fn, threads, dyn_lds, c.n > 128 ? 2 : 1, &blocks);  // large batches: two rounds balance better
     if (rc != S3_OK) return rc;
-    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, fused ? 0 : H);
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, fused ? 0 : H, !c.static_scratch);
 }
 
 extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const void *q, const int64_t *slot_off,
@@ -662,14 +741,13 @@ extern "C" int s3_decode_attention(s3_arena *a, int32_t layer, int32_t n, const 
     if (n == 0) return S3_OK;
     if (!q || !slot_off || !cur_len || !out || !aligned16(q) || !aligned16(out)) return S3_ERR_INVALID;
     if (out_dtype != S3_F32 && out_dtype != S3_F16 && out_dtype != S3_BF16) return S3_ERR_INVALID;
-    const AttnCall c = {layer, n, q, slot_off, cur_len, out, out_dtype, scale, stream, false, nullptr, nullptr, nullptr};
+    const AttnCall c = {layer, n, q, slot_off, cur_len, out, out_dtype, scale, stream, false, nullptr, nullptr, nullptr, false};
     return launch_attention(a, c);
 }
 
-extern "C" int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
-                              const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
-                              const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out,
-                              void *stream) {
+static int decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
+                       const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new, const void *v_new,
+                       void *out, int32_t out_dtype, float scale, int32_t *len_out, void *stream, bool static_scratch) {
     if (!a || !a->base || layer < 0 || layer >= a->cfg.n_layers || n < 0 || n > S3_MAX_BATCH) return S3_ERR_INVALID;
     if (n == 0) return S3_OK;
     if (!q || !k_new || !v_new || !slot_off || !pos || !out) return S3_ERR_INVALID;
@@ -678,8 +756,24 @@ extern "C" int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32
     if (out_dtype != S3_F32 && out_dtype != S3_F16 && out_dtype != S3_BF16) return S3_ERR_INVALID;
     const int rc = check_slots_host(a, n, slot_id, pos_host);
     if (rc != S3_OK) return rc;
-    const AttnCall c = {layer, n, q, slot_off, pos, out, out_dtype, scale, stream, true, k_new, v_new, len_out};
+    const AttnCall c = {layer, n, q, slot_off, pos, out, out_dtype, scale, stream, true, k_new, v_new, len_out, static_scratch};
     return launch_attention(a, c);
+}
+
+extern "C" int s3_decode_step(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id, const int32_t *pos_host,
+                              const int64_t *slot_off, const int32_t *pos, const void *q, const void *k_new,
+                              const void *v_new, void *out, int32_t out_dtype, float scale, int32_t *len_out,
+                              void *stream) {
+    return decode_step(a, layer, n, slot_id, pos_host, slot_off, pos, q, k_new, v_new, out, out_dtype, scale, len_out,
+                       stream, false);
+}
+
+extern "C" int s3_decode_step_static(s3_arena *a, int32_t layer, int32_t n, const int32_t *slot_id,
+                                     const int32_t *pos_host, const int64_t *slot_off, const int32_t *pos, const void *q,
+                                     const void *k_new, const void *v_new, void *out, int32_t out_dtype, float scale,
+                                     int32_t *len_out, void *stream) {
+    return decode_step(a, layer, n, slot_id, pos_host, slot_off, pos, q, k_new, v_new, out, out_dtype, scale, len_out,
+                       stream, true);
 }
 
 extern "C" int s3_kv_fill(s3_arena *a, int32_t slot_id, int32_t layer, int32_t first_row, int32_t n_rows,

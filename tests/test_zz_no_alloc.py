@@ -1,0 +1,114 @@
+"""s3_decode_step_static (the decode step for callers that cannot allocate device memory) against
+s3_decode_step: same outputs and same appended rows, bit for bit, and within the attention tolerance of the
+oracle; two calls in a row, the second on a smaller batch; across kernel families that lay the fixed scratch
+out differently; refusal of a call that does not fit; no device allocation."""
+import os
+
+import numpy as np
+import pytest
+
+from paper_2306_06000_amd import binding as s3
+from paper_2306_06000_amd import workloads as wl
+from tests.harness import assert_close, device_bits
+from tests.test_gpu_numeric_edges import FAMILIES, TDT, EdgeRig
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+DEV = "cuda:0"
+
+
+@pytest.fixture(scope="module", autouse=True)
+def need_gpu_and_lib():
+    assert torch.cuda.is_available(), "these tests need the GPU box"
+    assert os.path.exists(s3.LIB_PATH), "libs3kv.so must be built before the GPU tests run"
+    s3.lib()
+
+
+def one_call(fam, lens, chunk, seed, entry):
+    """Fill a fresh arena with seeded rows, run one decode step through `entry`, return what it produced."""
+    name, H, Hkv, D, kvt, act, kind = fam
+    rng = np.random.default_rng(seed)
+    rig = EdgeRig(fam, lens, M=2048)
+    rig.put([rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens],
+            [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens])
+    assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+    n = len(lens)
+    qb = wl.normal_bits(rng, (n, H, D), act)
+    kb = wl.normal_bits(rng, (n, Hkv, D), act)
+    vb = wl.normal_bits(rng, (n, Hkv, D), act)
+    q, k_new, v_new = (device_bits(x, TDT[act], DEV) for x in (qb, kb, vb))
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    torch.cuda.synchronize()
+    free_before = torch.cuda.mem_get_info()[0]
+    st = entry(rig.a, 0, n, rig.off_d, pos_d, q, k_new, v_new, out, s3.S3_F32, 0.0, len_out, rig.stream,
+               slot_id=rig.ids, pos_host=lens)
+    torch.cuda.synchronize()
+    free_after = torch.cuda.mem_get_info()[0]
+    assert st == 0, (name, st)
+    for b, sid in enumerate(rig.ids.tolist()):
+        assert rig.o.append(sid, 0, lens[b], kb[b], vb[b]) == 0
+    want = rig.want(qb, [L + 1 for L in lens])
+    res = dict(out=out.clone(), mem=rig.mem.clone(), len_out=len_out.cpu().tolist(), want=want,
+               scratch=s3.s3_kv_get_param(rig.a, "scratch_bytes")[1], freed=free_before - free_after)
+    rig.close()
+    return res
+
+
+def compare(fam, lens, chunk, seed):
+    ref = one_call(fam, lens, chunk, seed, s3.s3_decode_step)
+    got = one_call(fam, lens, chunk, seed, s3.s3_decode_step_static)
+    what = f"{fam[0]} n={len(lens)} chunk={chunk}"
+    assert got["len_out"] == ref["len_out"] == [L + 1 for L in lens], what
+    assert torch.equal(got["out"], ref["out"]), what          # same kernels, same arithmetic: same bits
+    assert torch.equal(got["mem"], ref["mem"]), what          # the appended rows, and nothing else, changed
+    assert_close(got["out"].cpu().numpy(), got["want"], what)  # and both are right
+    assert got["scratch"] == 0, what   # the arena's own scratch was never allocated on this path
+    assert got["freed"] == 0, what     # free device memory is the same before and after the call
+    assert ref["scratch"] > 0, what    # (the existing entry point did allocate its scratch)
+
+
+def test_static_scratch_step_equals_the_allocating_step_two_calls_in_a_row():
+    rng = np.random.default_rng(77)
+    big = [int(x) for x in rng.integers(1, 1500, size=48)] + [0, 1, 2047]
+    small = [700, 3, 64, 129, 0, 1999, 65]
+    mha = FAMILIES[0]
+    # many chunks per context (the partials and the arrival counters live in the fixed buffer), then a smaller
+    # batch right after it: stale partials and counters of the first call must not leak into the second
+    compare(mha, big, 64, seed=1)
+    compare(mha, small, 64, seed=2)
+    compare(mha, small, 0, seed=3)
+    # other families lay the buffer out differently (no counters; counters for other head-group counts): the
+    # layout changes back and forth between calls
+    for fam, chunk in ((FAMILIES[4], 32), (FAMILIES[6], 64), (FAMILIES[3], 64), (FAMILIES[7], 32), (FAMILIES[2], 64),
+                       (mha, 64)):
+        compare(fam, small, chunk, seed=4)
+        compare(fam, big[:20], chunk, seed=5)
+
+
+def test_static_scratch_step_refuses_what_does_not_fit_and_launches_nothing():
+    fam = FAMILIES[0]
+    name, H, Hkv, D, kvt, act, kind = fam
+    n = 600
+    lens = [10] * n
+    rig = EdgeRig(fam, lens, M=2048)
+    assert s3.s3_kv_set_param(rig.a, "chunk", 32) == 0  # 64 chunk slots x 600 sequences x 16 heads x 1032 B > 32 MiB
+    need = n * 64 * H * (4 * D + 8)
+    assert need > s3.S3_STATIC_SCRATCH_BYTES
+    z = torch.zeros((n, H, D), dtype=TDT[act], device=DEV)
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    out = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    snap = rig.mem.clone()
+    st = s3.s3_decode_step_static(rig.a, 0, n, rig.off_d, pos_d, z, z, z, out, s3.S3_F32, 0.0, None, rig.stream)
+    torch.cuda.synchronize()
+    assert st == s3.S3_ERR_SCRATCH
+    assert s3.lib().s3_status_str(st) == b"S3_ERR_SCRATCH"
+    assert torch.isnan(out).all() and torch.equal(snap, rig.mem)
+    # the same call fits at the default chunk (two chunk slots per sequence)
+    assert s3.s3_kv_set_param(rig.a, "chunk", 0) == 0
+    assert s3.s3_decode_step_static(rig.a, 0, n, rig.off_d, pos_d, z, z, z, out, s3.S3_F32, 0.0, None, rig.stream) == 0
+    torch.cuda.synchronize()
+    assert torch.isfinite(out).all()
+    rig.close()
