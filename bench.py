@@ -60,7 +60,7 @@ def parse():
     return ap.parse_args()
 
 
-DEFAULT_STEPS = {"c1": (128, 8), "c2": (256, 8), "c3": (8, 2), "c4": (56, 8), "c5": (128, 8), "c6": (128, 8)}  # (timed, warm-up)
+DEFAULT_STEPS = {"c1": (128, 8), "c2": (256, 8), "c3": (8, 2), "c4": (24, 8), "c5": (128, 8), "c6": (128, 8)}  # (timed, warm-up)
 
 
 class DeviceSources:

@@ -244,6 +244,19 @@ int s3_kv_restore(s3_arena *a, int32_t predicted_len, int32_t len, const void *h
                   int32_t *slot_id /*HOST out*/, int64_t *slot_off /*HOST out*/, int32_t *slot_cap /*HOST out*/,
                   void *stream);
 
+/* The device-side halves of the same eviction and re-admission (section 3, supervisor paragraph), for callers
+ * that keep the host link off the decode stream: the rows are first gathered into a contiguous DEVICE buffer
+ * (one kernel; the slot can be freed right behind it in stream order and its room reused at once), cross the
+ * link in one copy on another stream, and come back the same way.
+ *   s3_kv_gather_rows   rows [0, len) of K and V of every layer of a live slot -> dev_buf (DEVICE, 16-byte
+ *                       aligned, s3_kv_evict_bytes(len) bytes, layout [2*n_layers][len][H][D] as host_buf of
+ *                       s3_kv_evict); the slot stays live (free it with s3_kv_free)
+ *   s3_kv_scatter_rows  the inverse: dev_buf -> rows [0, len) of every plane of a live slot (reserve it with
+ *                       s3_kv_alloc for the reservation the sequence is owed, see s3_kv_grown_capacity)
+ * S3_ERR_INVALID for a dead id, len outside [0, cap] or a misaligned buffer. */
+int s3_kv_gather_rows(s3_arena *a, int32_t slot_id, int32_t len, void *dev_buf /*DEVICE*/, void *stream);
+int s3_kv_scatter_rows(s3_arena *a, int32_t slot_id, int32_t len, const void *dev_buf /*DEVICE*/, void *stream);
+
 /* The supervisor's report of available memory (section 3), in tokens.  Any out pointer may be NULL. */
 int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t *largest_free_tok,
                 int64_t *capacity_tok);

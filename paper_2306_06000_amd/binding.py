@@ -48,6 +48,8 @@ SIGNATURES = {
     "s3_kv_evict_bytes": (_i64, [_vp, _i32]),
     "s3_kv_evict": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
     "s3_kv_restore": (ctypes.c_int, [_vp, _i32, _i32, _vp, _pi32, _pi64, _pi32, _vp]),
+    "s3_kv_gather_rows": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
+    "s3_kv_scatter_rows": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
     "s3_sched_create": (ctypes.c_int, [ctypes.POINTER(_vp), _vp]),
     "s3_sched_destroy": (None, [_vp]),
     "s3_sched_submit": (ctypes.c_int, [_vp, _i64, _i32]),
@@ -225,6 +227,14 @@ def s3_kv_restore(arena, predicted_len, length, host_buf, stream=0):
     st = lib().s3_kv_restore(arena, int(predicted_len), int(length), _ptr(host_buf), ctypes.byref(sid),
                              ctypes.byref(off), ctypes.byref(cap), stream or None)
     return st, sid.value, off.value, cap.value
+
+
+def s3_kv_gather_rows(arena, slot_id, length, dev_buf, stream=0):
+    return lib().s3_kv_gather_rows(arena, int(slot_id), int(length), _ptr(dev_buf), stream or None)
+
+
+def s3_kv_scatter_rows(arena, slot_id, length, dev_buf, stream=0):
+    return lib().s3_kv_scatter_rows(arena, int(slot_id), int(length), _ptr(dev_buf), stream or None)
 
 
 def s3_sched_create(arena):

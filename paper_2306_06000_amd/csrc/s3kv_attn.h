@@ -145,15 +145,118 @@ __device__ __forceinline__ void wave_tokens(const AttnArgs &a, const Item &it, i
     }
 }
 
-// Merge TS token splits (rows first..first+TS-1 of comb) lane by lane.
+
+// ---- streaming through a per-wave LDS ring ------------------------------------------------------------------
+// The rows in flight do not sit in vector registers: every 128-bit load of a row piece goes from global memory
+// straight into the wave's ring in LDS (global_load_lds_dwordx4: lane l's 16 bytes land at base + 16*l, so one
+// load deposits the same 1 KiB the register path would hold), and the wave reads a row back with ds_read_b128
+// when its turn comes.  R rows of K and of V are kept in flight per wave (2 KiB per row) without a register per
+// byte, which is what limits the depth of the register path.  The memory counter is managed by hand: loads
+// return in issue order, so before rows [j, j+U) are read it is enough that at most the loads issued after
+// them - 2 per row - are still outstanding.
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void glb_void;
+
+__device__ __forceinline__ void dma16_nt(const char *src, char *lds_dst) {
+    // aux 2 = nt: the rows are read once (same hint as the register path's non-temporal loads)
+    __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)lds_dst, 16, 0, 2);
+}
+
+template <int N>
+__device__ __forceinline__ void wait_vm_then_read2(const char *s0, const char *s1, u32x4 &k0, u32x4 &v0, u32x4 &k1, u32x4 &v1) {
+    const unsigned a0 = (unsigned)(uintptr_t)(lds_void *)s0, a1 = (unsigned)(uintptr_t)(lds_void *)s1;
+    asm volatile(
+        "s_waitcnt vmcnt(%6)\n\t"
+        "ds_read_b128 %0, %4\n\t"
+        "ds_read_b128 %1, %4 offset:1024\n\t"
+        "ds_read_b128 %2, %5\n\t"
+        "ds_read_b128 %3, %5 offset:1024\n\t"
+        "s_waitcnt lgkmcnt(0)"
+        : "=&v"(k0), "=&v"(v0), "=&v"(k1), "=&v"(v1)
+        : "v"(a0), "v"(a1), "n"(N)
+        : "memory");
+}
+
+template <int DT, int D, int R, bool FUSED>
+__device__ __forceinline__ void wave_tokens_ring(const AttnArgs &a, const Item &it, int hg, int j0, int j1, char *ring,
+                                                 float &m, float &l, float (&acc)[8]) {
+    constexpr int U = 2;
+    typedef TokenStream<DT, D, U, true, FUSED> TS_t;
+    typedef HeadLanes<D> HL;
+    const int lane = threadIdx.x & 63;
+    const int g = lane / HL::LPH, dl = lane % HL::LPH;
+    const int h = hg * HL::GH + g;
+    const bool lane_ok = h < a.H && dl < HL::USED;
+    const int hc = h < a.H ? h : a.H - 1;
+    const int dc = dl < HL::USED ? dl : HL::USED - 1;
+    const int64_t rstride = (int64_t)a.H * D * 2;
+    const int64_t lane_byte = ((int64_t)hc * D + dc * 8) * 2;
+    const int64_t in_byte = ((int64_t)it.b * a.H * D) * 2 + lane_byte;
+    TS_t st;
+    st.kp = a.kplane + it.off * rstride + lane_byte;
+    st.vp = a.vplane + it.off * rstride + lane_byte;
+    st.knew = FUSED ? a.k_new + in_byte : nullptr;
+    st.vnew = FUSED ? a.v_new + in_byte : nullptr;
+    st.rstride = rstride;
+    st.jnew = FUSED ? it.len - 1 : -1;
+    st.j1 = j1;
+    st.scale_log2e = a.scale_log2e;
+    st.qv = *(const u32x4 *)(a.q + in_byte);
+    if (HL::USED < HL::LPH && dl >= HL::USED) st.qv = (u32x4){0u, 0u, 0u, 0u};
+
+    m = -INFINITY;
+    l = 0.f;
+#pragma unroll
+    for (int i = 0; i < 8; i++) acc[i] = 0.f;
+    if (j0 < j1) {
+        char *mine = ring + lane * 16;  // this lane's 16 bytes of every slot
+        int issued = j0, islot = 0;     // next row to load and the slot it goes to
+        auto issue = [&]() {
+            const char *ks = st.kp + (int64_t)issued * rstride, *vs = st.vp + (int64_t)issued * rstride;
+            if (FUSED && issued == st.jnew) {
+                ks = st.knew;
+                vs = st.vnew;
+            }
+            dma16_nt(ks, ring + islot * 2048);
+            dma16_nt(vs, ring + islot * 2048 + 1024);
+            issued++;
+            islot = islot + 1 == R ? 0 : islot + 1;
+        };
+        for (int r = 0; r < R && issued < j1; r++) issue();
+        int cslot = 0;
+        for (int j = j0; j < j1; j += U) {
+            // slots of rows j and j+1 (the tail batch of an odd share reads its one row twice; the second
+            // copy is masked in reduce)
+            const int s0 = cslot, s1 = (j + 1 < j1) ? (cslot + 1 == R ? 0 : cslot + 1) : cslot;
+            u32x4 kk[U], vv[U];
+            if (issued - j >= R) wait_vm_then_read2<2 * (R - U)>(mine + s0 * 2048, mine + s1 * 2048, kk[0], vv[0], kk[1], vv[1]);
+            else wait_vm_then_read2<0>(mine + s0 * 2048, mine + s1 * 2048, kk[0], vv[0], kk[1], vv[1]);
+            // the two slots are free again: refill them before the arithmetic
+            if (issued < j1) issue();
+            if (issued < j1) issue();
+            cslot = cslot + U >= R ? cslot + U - R : cslot + U;
+            st.reduce(j, kk, vv, m, l, acc);
+        }
+    }
+    if (FUSED && lane_ok && j0 <= st.jnew && st.jnew < j1) {
+        *(u32x4 *)(a.kplane + (it.off + st.jnew) * rstride + lane_byte) = *(const u32x4 *)(a.k_new + in_byte);
+        *(u32x4 *)(a.vplane + (it.off + st.jnew) * rstride + lane_byte) = *(const u32x4 *)(a.v_new + in_byte);
+    }
+}
+
+// Merge TS token splits (rows first..first+TS-1 of comb) lane by lane.  Two splits per round: unrolled over
+// all of them the eighty values of eight splits would sit in registers at once and set the kernel's register
+// count (which decides how many waves a SIMD holds) for the sake of the epilogue wave alone.
 template <int TS>
 __device__ __forceinline__ void combine_splits(const float (*comb)[10][64], int first, int lane, float &m, float &l,
                                                float (&acc)[8]) {
     m = comb[first][0][lane];
+#pragma unroll
     for (int t = 1; t < TS; t++) m = fmaxf(m, comb[first + t][0][lane]);
     l = 0.f;
 #pragma unroll
     for (int i = 0; i < 8; i++) acc[i] = 0.f;
+#pragma unroll 2
     for (int t = 0; t < TS; t++) {  // split 0 is never empty, so m is finite; empty splits weigh exp2(-inf) = 0
         const float wt = fast_exp2(comb[first + t][0][lane] - m);
         l += wt * comb[first + t][1][lane];
@@ -228,13 +331,19 @@ __global__ void __launch_bounds__(TS *HS * 64) attn_partial_kernel(const AttnArg
 // announces the chunk on the context's arrival counter and, if it delivered the last chunk, merges
 // the chunks; all its memory latencies overlap with the compute waves' next item.  len_out and the
 // zero rows of empty contexts are published by the workgroups in turn.
-template <int DT, int D, int TS, int HS, int U, bool NT, bool PF>
+// R > 0: the rows in flight go through a per-wave LDS ring of R rows (wave_tokens_ring) instead of registers.
+// DYN: the work list is not walked with a fixed stride; after its first item a workgroup takes the next
+// unclaimed position from a device-wide counter (fetched by the epilogue wave one item ahead, so that the
+// round trip hides behind the streaming), which keeps every compute unit busy to the end whatever else
+// occupies some of them, and makes the longest-first order of the list a longest-processing-time schedule.
+template <int DT, int D, int TS, int HS, int U, bool NT, bool PF, int R, bool DYN>
 __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const AttnArgs a) {
     constexpr int LPH = HeadLanes<D>::LPH, USED = HeadLanes<D>::USED, GH = HeadLanes<D>::GH;
     constexpr int NWC = TS * HS;  // compute waves
-    extern __shared__ __align__(16) char dyn_lds[];  // the batch view
+    extern __shared__ __align__(16) char dyn_lds[];  // the batch view, then the rings
     __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
     __shared__ float comb[2][NWC][10][64];
+    __shared__ long long next_pos[2];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const bool epilogue = wave == NWC;
@@ -243,6 +352,8 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
     const int n_hgb = (n_hg + HS - 1) / HS;
     const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
     const int64_t total = (int64_t)bv.total * n_hgb;
+    char *ring = R > 0 ? dyn_lds + ((batch_view_bytes(a.n, a.ncls) + 15) & ~(size_t)15) + (size_t)(epilogue ? 0 : wave) * (R * 2048)
+                       : nullptr;
 
     // Housekeeping that belongs to no item, spread over the workgroups (sequence b goes to workgroup
     // b mod grid) so that none of them starts its first item late: the new lengths, and a zero output
@@ -256,18 +367,29 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
         }
     }
 
+    // a work list no longer than the grid deals every position at launch: nothing to claim, no counter traffic
+    const bool dyn = DYN && total > (int64_t)gridDim.x;
     int parity = 0;
-    for (int64_t item = blockIdx.x; item < total; item += gridDim.x, parity ^= 1) {
+    int64_t item = blockIdx.x;
+    while (item < total) {
         const Item it = decode_item(a, bv, item, n_hgb);
         if (!epilogue) {
             int j0, j1;
             split_rows(it, ts, TS, j0, j1);
             float m, l, acc[8];
-            wave_tokens<DT, D, U, NT, true, PF>(a, it, it.hgb * HS + hs, j0, j1, m, l, acc);
+            if (R > 0) wave_tokens_ring<DT, D, R, true>(a, it, it.hgb * HS + hs, j0, j1, ring, m, l, acc);
+            else wave_tokens<DT, D, U, NT, true, PF>(a, it, it.hgb * HS + hs, j0, j1, m, l, acc);
             comb[parity][wave][0][lane] = m;
             comb[parity][wave][1][lane] = l;
 #pragma unroll
             for (int i = 0; i < 8; i++) comb[parity][wave][2 + i][lane] = acc[i];
+        } else if (dyn) {
+            // claim the position this workgroup works on after `item`; positions below gridDim.x were dealt
+            // at launch.  next_pos[parity] was last read after the barrier two items ago.
+            unsigned int got = 0;
+            if (lane == 0) got = atomicAdd(a.queue, 1u);
+            got = __builtin_amdgcn_readfirstlane(got);
+            if (lane == 0) next_pos[parity] = (long long)gridDim.x + got;
         }
         // The only barrier of an item.  Buffer `parity` is next written two items later, after the
         // barrier of item+1, which the epilogue wave reaches only when it is done reading it.
@@ -291,6 +413,17 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
                     }
                 }
             }
+        }
+        item = dyn ? (int64_t)next_pos[parity] : item + gridDim.x;
+        parity ^= 1;
+    }
+    if (dyn && threadIdx.x == 0) {
+        // the last workgroup to leave puts both counters back to zero for the next launch (nobody claims a
+        // position after it has announced its exit)
+        const unsigned int gone = atomicAdd(a.queue + 1, 1u);
+        if (gone == gridDim.x - 1) {
+            atomicExch(a.queue, 0u);
+            atomicExch(a.queue + 1, 0u);
         }
     }
 }
@@ -317,25 +450,35 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     store_out8(a.out, a.out_dtype, ((int64_t)b * a.H + h) * D + dl * 8, z);
 }
 
-// Kernel shapes: (index, TS token splits, HS head groups per workgroup, U rows per load batch, NT, PF).
-#define S3_VARIANTS(X)            \
-    X(0, 4, 1, 4, true, false)    \
-    X(1, 8, 1, 4, true, false)    \
-    X(2, 4, 2, 4, true, false)    \
-    X(3, 1, 4, 4, true, false)    \
-    X(4, 8, 1, 2, true, true)     \
-    X(5, 2, 4, 4, true, false)    \
-    X(6, 1, 8, 4, true, false)    \
-    X(7, 7, 1, 4, true, true)     \
-    X(8, 4, 1, 4, false, false)   \
-    X(9, 15, 1, 2, true, true)
+// Kernel shapes: (index, TS token splits, HS head groups per workgroup, U rows per load batch, NT, PF, R rows of
+// the LDS ring (0: rows in flight sit in registers), DYN dynamic work list); R and DYN concern the fused step
+// kernel only (the attention-only kernel of such a shape is the register / fixed-stride one).
+#define S3_VARIANTS(X)                     \
+    X(0, 4, 1, 4, true, false, 0, false)   \
+    X(1, 8, 1, 4, true, false, 0, false)   \
+    X(2, 4, 2, 4, true, false, 0, false)   \
+    X(3, 1, 4, 4, true, false, 0, false)   \
+    X(4, 8, 1, 2, true, true, 0, false)    \
+    X(5, 2, 4, 4, true, false, 0, false)   \
+    X(6, 1, 8, 4, true, false, 0, false)   \
+    X(7, 7, 1, 4, true, true, 0, false)    \
+    X(8, 4, 1, 4, false, false, 0, false)  \
+    X(9, 15, 1, 2, true, true, 0, false)   \
+    X(10, 8, 1, 2, true, true, 0, true)    \
+    X(11, 8, 1, 2, true, true, 6, false)   \
+    X(12, 8, 1, 2, true, true, 6, true)
+// Defaults (measured on MI355X): shape 4 with a fixed stride while the work list is about as long as the grid
+// (batches of up to 128 sequences), the same shape with the dynamic work list beyond (+4 % to +7 % on batches of
+// 512 and 700 sequences; -5 % on a batch of 128 long contexts).  The LDS-ring shapes stay selectable for
+// comparison: they measured 2-3 % behind the register path.
 #define S3_DEFAULT_VARIANT 4
+#define S3_DEFAULT_VARIANT_LARGE 10
 
 template <int DT, int D>
 static attn_fn pick_variant(int v, bool fused) {
     switch (v) {
-#define X(i, ts, hs, u, nt, pf) \
-    case i: return fused ? (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt, pf> : (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt, pf>;
+#define X(i, ts, hs, u, nt, pf, r, dyn) \
+    case i: return fused ? (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt, pf, r, dyn> : (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt, pf>;
         S3_VARIANTS(X)
 #undef X
         default: return nullptr;

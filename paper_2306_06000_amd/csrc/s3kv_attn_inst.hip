@@ -6,6 +6,12 @@
 
 #ifndef S3_INST_D
 #error "compile with -DS3_INST_D=<head dimension>"
+// Bytes of LDS rings a workgroup of the fused kernel of shape `variant` needs behind the batch view.
+int s3i_variant_ring_bytes(int variant) {
+    if (variant < 0 || variant >= s3i_num_variants()) return 0;
+    return kVariants[variant].ring * 2048 * kVariants[variant].ts * kVariants[variant].hs;
+}
+int s3i_variant_dynamic(int variant) { return variant >= 0 && variant < s3i_num_variants() ? kVariants[variant].dyn : 0; }
 #endif
 
 #define S3_CAT2(a, b) a##b
@@ -23,18 +29,25 @@ attn_fn S3_CAT(s3i_pick_merge_d, S3_INST_D)() { return (attn_fn)attn_merge_kerne
 
 #if S3_INST_D == 64
 struct VariantShape {
-    int ts, hs, u, nt, pf;
+    int ts, hs, u, nt, pf, ring, dyn;
 };
 static const VariantShape kVariants[] = {
-#define X(i, ts, hs, u, nt, pf) {ts, hs, u, nt, pf},
+#define X(i, ts, hs, u, nt, pf, r, dyn) {ts, hs, u, nt, pf, r, dyn},
     S3_VARIANTS(X)
 #undef X
 };
 int s3i_num_variants() { return (int)(sizeof(kVariants) / sizeof(kVariants[0])); }
 int s3i_default_variant() { return S3_DEFAULT_VARIANT; }
+int s3i_default_variant_large() { return S3_DEFAULT_VARIANT_LARGE; }  // batches of more than 128 sequences
 // Threads of a workgroup of shape `variant` (the fused kernel adds its epilogue wave).
 int s3i_variant_threads(int variant, bool fused) {
     if (variant < 0 || variant >= s3i_num_variants()) return 0;
     return (kVariants[variant].ts * kVariants[variant].hs + (fused ? 1 : 0)) * 64;
 }
+// Bytes of LDS rings a workgroup of the fused kernel of shape `variant` needs behind the batch view.
+int s3i_variant_ring_bytes(int variant) {
+    if (variant < 0 || variant >= s3i_num_variants()) return 0;
+    return kVariants[variant].ring * 2048 * kVariants[variant].ts * kVariants[variant].hs;
+}
+int s3i_variant_dynamic(int variant) { return variant >= 0 && variant < s3i_num_variants() ? kVariants[variant].dyn : 0; }
 #endif

@@ -264,7 +264,10 @@ attn_fn s3i_pick_merge_d96();
 attn_fn s3i_pick_merge_d128();
 attn_fn s3i_pick_merge_d256();
 int s3i_default_variant();
+int s3i_default_variant_large();
 int s3i_variant_threads(int variant, bool fused);
+int s3i_variant_ring_bytes(int variant);
+int s3i_variant_dynamic(int variant);
 
 static attn_fn pick_kernel(int dt, int d, int variant, bool fused) {
     switch (d) {
@@ -556,6 +559,7 @@ static int place_scratch(s3_arena *a, AttnArgs &args, size_t cnt_bytes, const At
         base = (char *)a->scratch;
     }
     args.arrivals = (unsigned int *)base;
+    args.queue = cnt_bytes >= 256 ? (unsigned int *)(base + cnt_bytes - 256) : nullptr;  // the last 256 bytes of the counter region
     args.part_acc = (float *)(base + cnt_bytes);
     args.part_ml = (float2 *)(base + cnt_bytes + acc_bytes);
     return S3_OK;
@@ -564,7 +568,7 @@ static int place_scratch(s3_arena *a, AttnArgs &args, size_t cnt_bytes, const At
 // Bytes of the arrival counters at the head of the scratch: one per (sequence, head group), for the largest
 // batch a call takes, so that the partials behind them never move with the batch size.
 static size_t counters_bytes(int n_hg) {
-    return (((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255;
+    return ((((size_t)(S3_MAX_BATCH + 1) * n_hg * sizeof(unsigned int)) + 255) & ~(size_t)255) + 256;  // + the work-list counters
 }
 
 // Scratch an attention call over n sequences needs at most: the launchers' layout with the smallest chunk
@@ -717,7 +721,7 @@ static int launch_attention(s3_arena *a, const AttnCall &c) {
     // Defaults from sweeps on MI355X: large chunks keep most contexts in one piece (no cross-workgroup
     // merge), eight waves share an item's rows evenly, each with two batches of two rows in flight
     // alternately (1 % ahead of one batch of four rows on the ragged batch of 64, level on the others).
-    const int variant = a->variant >= 0 ? a->variant : s3i_default_variant();
+    const int variant = a->variant >= 0 ? a->variant : c.n > 128 ? s3i_default_variant_large() : s3i_default_variant();
     const bool fused = c.with_append;
     attn_fn fn = pick_kernel(a->cfg.kv_dtype, D, variant, fused);
     if (!fn) return S3_ERR_INVALID;
@@ -725,12 +729,22 @@ static int launch_attention(s3_arena *a, const AttnCall &c) {
     const int n_hg = (H + GH - 1) / GH;
     AttnArgs args = common_args(a, c, H, H, a->chunk > 0 ? a->chunk : 1024);
     args.len_out = c.len_out;
+    // a dynamic work list is a longest-processing-time schedule only if the long items come first: four length
+    // classes whatever the batch size (with a fixed stride, large batches did better without the classes' prologue)
+    if (a->ncls <= 0 && fused && s3i_variant_dynamic(variant)) {
+        args.ncls = 4;
+        while (args.ncls > 1 && batch_view_lds(c.n, args.ncls) > (size_t)96 * 1024) args.ncls--;
+    }
     int rc = place_scratch(a, args, counters_bytes(n_hg), c);
     if (rc != S3_OK) return rc;
     const int threads = s3i_variant_threads(variant, fused);  // the fused kernel adds an epilogue wave
-    const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
+    const size_t view = batch_view_lds(c.n, args.ncls);
+    const size_t dyn_lds = fused && s3i_variant_ring_bytes(variant) ? ((view + 15) & ~(size_t)15) + s3i_variant_ring_bytes(variant) : view;
     int blocks = 0;
-    rc = stride_grid(a, (const void *)fn, threads, dyn_lds, c.n > 128 ? 2 : 1, &blocks);  // large batches: two rounds balance better
+    // fixed stride: large batches balance better over two rounds of resident workgroups; a dynamic work list
+    // needs exactly the resident ones
+    const int rounds = (fused && s3i_variant_dynamic(variant)) ? 1 : c.n > 128 ? 2 : 1;
+    rc = stride_grid(a, (const void *)fn, threads, dyn_lds, rounds, &blocks);
     if (rc != S3_OK) return rc;
     return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, fused ? 0 : H, !c.static_scratch);
 }
@@ -838,6 +852,25 @@ extern "C" int s3_kv_restore(s3_arena *a, int32_t predicted_len, int32_t len, co
     if (slot_off) *slot_off = off;
     if (slot_cap) *slot_cap = cap;
     return S3_OK;
+}
+
+// Rows [0, len) of every plane of a live slot to / from one contiguous device buffer laid out like the host
+// buffer of s3_kv_evict: the device-side halves of an eviction and of a re-admission that cross the host link
+// off the decode stream.  One launch each.
+extern "C" int s3_kv_gather_rows(s3_arena *a, int32_t slot_id, int32_t len, void *dev_buf, void *stream) {
+    const s3_slot *s = s3i_live_slot(a, slot_id);
+    if (!s || !a->base || len < 0 || len > s->cap || (len > 0 && (!dev_buf || ((uintptr_t)dev_buf & 15)))) return S3_ERR_INVALID;
+    const size_t piece = (size_t)len * (size_t)a->row_bytes;
+    return s3i_launch_copy_planes(a->base + s->off * a->row_bytes, (char *)dev_buf, piece, (size_t)a->plane_bytes, piece,
+                                  2 * a->cfg.n_layers, stream);
+}
+
+extern "C" int s3_kv_scatter_rows(s3_arena *a, int32_t slot_id, int32_t len, const void *dev_buf, void *stream) {
+    const s3_slot *s = s3i_live_slot(a, slot_id);
+    if (!s || !a->base || len < 0 || len > s->cap || (len > 0 && (!dev_buf || ((uintptr_t)dev_buf & 15)))) return S3_ERR_INVALID;
+    const size_t piece = (size_t)len * (size_t)a->row_bytes;
+    return s3i_launch_copy_planes((const char *)dev_buf, a->base + s->off * a->row_bytes, piece, piece, (size_t)a->plane_bytes,
+                                  2 * a->cfg.n_layers, stream);
 }
 
 extern "C" int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,

@@ -11,7 +11,11 @@ Per decode step (iteration-level scheduling, section 3 of the S3 paper):
 When a reservation cannot be doubled because no extent is large enough (supervisor paragraph of
 section 3): if the free space is merely fragmented the arena is compacted and the doubling repeated;
 otherwise the sequence's rows go to pinned host memory, its slot is freed, and it comes back with the
-doubled reservation as soon as a finished sequence has made room (before any newcomer).
+doubled reservation as soon as a finished sequence has made room (before any newcomer).  The host link never
+sits on the decode stream: an eviction gathers the rows into a device staging buffer with one kernel on the
+decode stream (the slot is free right behind it), the buffer crosses to the host in one copy on a side stream;
+a re-admission reserves its slot at once, brings the rows into a staging buffer on the side stream, and the
+sequence joins the batch at the first step that finds that copy complete (one scatter kernel).
 The event log lets a test replay the same decisions on the CPU oracle and compare every id,
 offset and capacity bit for bit.  Host-side state is kept in numpy arrays so that a step costs
 a few vector operations however large the batch is.
@@ -40,10 +44,11 @@ class DecodeEngine:
         # "swap": compact, else evict to the host and re-admit later (the paper's supervisor); "drop": free
         self.on_nomem = on_nomem
         self.swapped = []     # evicted sequences waiting for room, oldest first
-        self._host_keep = []  # (event, pinned buffer): buffers of restores the stream may still be reading
+        self._restoring = []  # re-admitted sequences whose rows are still on their way back, oldest first
         self._host_free = []  # pinned buffers ready for reuse
-        self._side = None     # stream the evictions copy on, beside the decode steps
-        self._evict_done = [] # events of evictions whose freed rows the main stream must not overwrite yet
+        self._stage = []      # [event or None, device staging buffer, held]: free once the event has passed and no
+                              # returning sequence holds it
+        self._side = None     # stream on which evicted rows cross the host link, beside the decode steps
         self.n_swapped_out = self.n_swapped_in = self.n_compactions = 0
         self.capacity = 0     # entries the device arrays can hold (the largest batch so far)
         self.dev = torch.device(device)
@@ -69,6 +74,9 @@ class DecodeEngine:
             self._side = torch.cuda.Stream(self.dev)
             quarter = max(w.granule, w.max_len // 4) * self.bpt
             self._host_free = [torch.empty(quarter, dtype=torch.uint8, pin_memory=True) for _ in range(8)]
+            # device staging: four buffers that hold the longest sequence (allocating one mid-run would synchronise)
+            self._stage = [[None, torch.empty(w.max_len * self.bpt, dtype=torch.uint8, device=self.dev), False]
+                           for _ in range(4)]
         self.out_dtype = out_dtype
         self._row_term, self._seq_term = self._byte_terms()  # bytes per cached row and per sequence of one layer-step
         self.events = [] if log_events else None
@@ -100,6 +108,7 @@ class DecodeEngine:
     def close(self):
         if self.arena is not None:
             torch.cuda.synchronize(self.dev)
+            self._restoring.clear()
             if self.sched is not None:
                 s3.s3_sched_destroy(self.sched)
                 self.sched = None
@@ -113,12 +122,20 @@ class DecodeEngine:
     def _stream_ptr(self):
         return torch.cuda.current_stream(self.dev).cuda_stream
 
-    def _guard_freed_rows(self):
-        """Before anything on the main stream may write into space an eviction has freed (a fill, the copy of
-        a doubling, a compaction, a reload): wait until the eviction's copies to the host have read it."""
-        for ev in self._evict_done:
-            torch.cuda.current_stream(self.dev).wait_event(ev)
-        self._evict_done.clear()
+    MAX_RETURNING = 2  # sequences on their way back at once; each holds a staging buffer until it has joined
+
+    def _stage_buffer(self):
+        """A device staging buffer that no returning sequence holds and whose last use has completed (blocks on
+        one if all that are not held are busy; at least two never are held)."""
+        idle = [e for e in self._stage if not e[2]]
+        for entry in idle:
+            if entry[0] is None or entry[0].query():
+                entry[0] = None
+                return entry
+        entry = idle[0]
+        entry[0].synchronize()
+        entry[0] = None
+        return entry
 
     def kv_dtype_torch(self):
         """torch type of cache rows handed to fill (8-bit caches: raw codes)."""
@@ -197,7 +214,6 @@ class DecodeEngine:
         prefill(serial, layer, rows) -> (k_rows, v_rows) device tensors [rows][H][D].
         Returns (serial, slot, off, cap, len, total) of the admitted ones."""
         preds = [s.predicted for s in seqs]
-        self._guard_freed_rows()
         rc, ids, offs, caps = s3.s3_kv_alloc(self.arena, preds)
         s3.check(rc, "s3_kv_alloc")
         admitted = []
@@ -232,7 +248,6 @@ class DecodeEngine:
         as admit()."""
         if max_out <= 0 or s3.s3_sched_pool_size(self.sched) == 0:
             return []
-        self._guard_freed_rows()
         rc, rids, sids, offs, caps = s3.s3_sched_admit(self.sched, max_out)
         s3.check(rc, "s3_sched_admit")
         serials = list(range(self.next_serial, self.next_serial + len(rids)))
@@ -294,7 +309,6 @@ class DecodeEngine:
         self._recount()
 
     def _grow(self, i):
-        self._guard_freed_rows()
         st, off, cap = s3.s3_kv_grow(self.arena, int(self.slot[i]), int(self.len[i]), self._stream_ptr())
         self._log("grow", int(self.serial[i]), int(self.slot[i]), int(self.len[i]), st, off, cap)
         return st, off, cap
@@ -310,7 +324,6 @@ class DecodeEngine:
         # host link twice, some fifty times slower per byte: compact only while that is the cheaper of the two.
         if used > self.COMPACT_RATIO * want:
             return False
-        self._guard_freed_rows()
         st, new_off, moved = s3.s3_kv_compact(self.arena, self.slot, self.len, self._stream_ptr())
         s3.check(st, "s3_kv_compact")
         self._log("compact", self.slot.tolist(), new_off.tolist(), moved)
@@ -320,54 +333,96 @@ class DecodeEngine:
         return True
 
     def _evict(self, i):
-        """Rows of batch entry i to pinned host memory; the slot is freed (the entry is removed by the caller)."""
+        """Rows of batch entry i to pinned host memory; the slot is freed (the entry is removed by the caller).
+        One gather kernel on the decode stream puts the rows into a device staging buffer, after which the slot's
+        room can be reused in stream order; the staging buffer crosses the host link in one copy on the side
+        stream, beside the decode steps that follow."""
         length, sid = int(self.len[i]), int(self.slot[i])
-        host = self._host_buffer(s3.s3_kv_evict_bytes(self.arena, length))
-        # the copies run on a side stream, after everything the main stream has enqueued so far, and overlap
-        # with the decode steps that follow (those touch live slots only)
+        nbytes = s3.s3_kv_evict_bytes(self.arena, length)
+        host = self._host_buffer(nbytes)
+        entry = self._stage_buffer()
         main = torch.cuda.current_stream(self.dev)
+        s3.check(s3.s3_kv_gather_rows(self.arena, sid, length, entry[1], main.cuda_stream), "s3_kv_gather_rows")
+        s3.check(s3.s3_kv_free(self.arena, sid), "s3_kv_free")
         ready, done = torch.cuda.Event(), torch.cuda.Event()
         ready.record(main)
         self._side.wait_event(ready)
-        s3.check(s3.s3_kv_evict(self.arena, sid, length, host, self._side.cuda_stream), "s3_kv_evict")
+        with torch.cuda.stream(self._side):
+            host[:nbytes].copy_(entry[1][:nbytes], non_blocking=True)
         done.record(self._side)
-        self._evict_done.append(done)
+        entry[0] = done
         self._log("evict", int(self.serial[i]), sid, length)
-        self.swapped.append(SimpleNamespace(serial=int(self.serial[i]), len=length, total=int(self.total[i]),
+        self.swapped.append(SimpleNamespace(serial=int(self.serial[i]), len=length, total=int(self.total[i]), nbytes=nbytes,
                                             want=s3.s3_kv_grown_capacity(self.cfg, int(self.cap[i])), host=host))
         self.n_swapped_out += 1
 
     def _host_buffer(self, nbytes):
-        """Pinned staging memory for one evicted sequence: a buffer whose reload has completed is reused
-        (pinning memory costs far more than the copy it serves)."""
-        still = []
-        for e, h in self._host_keep:
-            if e.query():
-                self._host_free.append(h)
-            else:
-                still.append((e, h))
-        self._host_keep = still
+        """Pinned staging memory for one evicted sequence (pinning memory costs far more than the copy it serves:
+        buffers are reused once their sequence is back on the device)."""
         fits = [k for k, h in enumerate(self._host_free) if h.numel() >= nbytes]
         if fits:  # the smallest that fits
             return self._host_free.pop(min(fits, key=lambda k: self._host_free[k].numel()))
         return torch.empty(nbytes, dtype=torch.uint8, pin_memory=True)
 
     def _restore_oldest(self):
-        """Try to bring the longest-waiting evicted sequence back with its doubled reservation.
-        -> (serial, slot, off, cap, len, total) or None (no room yet)."""
+        """Start bringing the longest-waiting evicted sequence back: its slot (the doubled reservation) is
+        reserved now, its rows start their way into a device staging buffer on the side stream, and it joins the
+        batch at the first step that finds them there (_join_restored).  -> True, or False (no room yet)."""
+        if len(self._restoring) >= self.MAX_RETURNING:
+            return False
         rec = self.swapped[0]
-        self._guard_freed_rows()  # also: the rows of `rec` have reached its host buffer
-        st, sid, off, cap = s3.s3_kv_restore(self.arena, rec.want, rec.len, rec.host, self._stream_ptr())
-        self._log("restore", rec.serial, rec.want, rec.len, st, sid, off, cap)
+        rc, ids, offs, caps = s3.s3_kv_alloc(self.arena, [rec.want])
+        s3.check(rc, "s3_kv_alloc")
+        st = s3.S3_OK if rc == 1 else s3.S3_ERR_NOMEM
+        self._log("restore", rec.serial, rec.want, rec.len, st, int(ids[0]), int(offs[0]), int(caps[0]))
         if st == s3.S3_ERR_NOMEM:
-            return None
-        s3.check(st, "s3_kv_restore")
+            return False
         self.swapped.pop(0)
-        ev = torch.cuda.Event()
-        ev.record(torch.cuda.current_stream(self.dev))
-        self._host_keep.append((ev, rec.host))
+        entry = self._stage_buffer()
+        entry[2] = True  # held until the rows have been scattered into the slot
+        with torch.cuda.stream(self._side):  # behind this sequence's own copy to the host, which ran on this stream
+            entry[1][:rec.nbytes].copy_(rec.host[:rec.nbytes], non_blocking=True)
+        back = torch.cuda.Event()
+        back.record(self._side)
+        entry[0] = back
+        self._restoring.append(SimpleNamespace(event=back, entry=entry, host=rec.host, nbytes=rec.nbytes,
+                                               rec=(rec.serial, int(ids[0]), int(offs[0]), int(caps[0]), rec.len, rec.total)))
         self.n_swapped_in += 1
-        return (rec.serial, sid, off, cap, rec.len, rec.total)
+        return True
+
+    @property
+    def n_returning(self):
+        """Re-admitted sequences whose rows are still on their way back from the host."""
+        return len(self._restoring)
+
+    def finish_restores(self):
+        """Block until every re-admitted sequence has its rows and is part of the batch again."""
+        while self._restoring and self.n_active < max(self.capacity, 1):
+            self._join_restored(wait=True)
+
+    def _join_restored(self, wait=False):
+        """Sequences whose rows have arrived in their staging buffer: scatter them into the reserved slot (one
+        kernel on the decode stream) and append them to the batch."""
+        joined = False
+        while self._restoring and self.n_active < max(self.capacity, 1):
+            r = self._restoring[0]
+            if not r.event.query():
+                if not wait:
+                    break
+                r.event.synchronize()
+            self._restoring.pop(0)
+            serial, sid, off, cap, length, total = r.rec
+            main = torch.cuda.current_stream(self.dev)
+            s3.check(s3.s3_kv_scatter_rows(self.arena, sid, length, r.entry[1], main.cuda_stream), "s3_kv_scatter_rows")
+            used = torch.cuda.Event()
+            used.record(main)
+            r.entry[0], r.entry[2] = used, False
+            self._host_free.append(r.host)
+            self._append_entry(r.rec)
+            joined = True
+            wait = False
+        if joined:
+            self._recount()
 
     def _remove(self, gone):
         """Take entries out of the batch without re-uploading it: the last entry moves into each hole
@@ -430,13 +485,9 @@ class DecodeEngine:
         room = True  # an evicted sequence comes back before any newcomer; one refusal ends the attempts of this step
         for i in done.tolist():
             if self.swapped and room:
-                got = self._restore_oldest()
-                room = got is not None
-                if got:
-                    (self.serial[i], self.slot[i], self.off[i], self.cap[i], self.len[i], self.total[i]) = got
-                    keep[i] = True
-                    self._patch.add(i)
-                    continue
+                room = self._restore_oldest()
+                if room:
+                    continue  # the entry stays open for the returning sequence, which joins when its rows are back
             if self.admission == "fifo" and self.w.refill and self.pool_pos < len(self.w.pool):
                 got = self.admit([self.w.pool[self.pool_pos]], prefill, fill=False)
                 self.pool_pos += 1
@@ -464,11 +515,8 @@ class DecodeEngine:
                 self._patch.update(new)
         if not keep.all():
             self._remove(np.nonzero(~keep)[0].tolist())
-        while self.swapped and room and self.n_active < self.capacity:
-            got = self._restore_oldest()
-            room = got is not None
-            if got:
-                self._append_entry(got)
+        while self.swapped and room and self.n_active + len(self._restoring) < self.capacity:
+            room = self._restore_oldest()
         self._recount()
 
     def _append_entry(self, rec):
@@ -478,6 +526,8 @@ class DecodeEngine:
         self._patch.add(self.n_active - 1)
 
     def step(self, tensors, prefill, check_host=False):
+        if self._restoring:
+            self._join_restored(wait=self.n_active == 0)
         if self._to_full <= 0:  # some slot is full: double it (or compact / swap / drop)
             self.grow_full_slots()
         out = self.launch_step(tensors, check_host)

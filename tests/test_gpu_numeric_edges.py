@@ -363,12 +363,14 @@ def test_worked_example_model_shape_runs_through_the_library():
 
 
 # ---------------------------------------------------------------- the merge inside one launch, many times
-@pytest.mark.parametrize("sync,launches", [(0, 200), (1, 40)])
-def test_soak_of_the_in_kernel_merge_equals_the_two_kernel_path(sync, launches):
+@pytest.mark.parametrize("sync,launches,variant", [(0, 200, -1), (1, 40, -1), (0, 120, 10), (1, 20, 10), (0, 40, 12)])
+def test_soak_of_the_in_kernel_merge_equals_the_two_kernel_path(sync, launches, variant):
     """Many contexts of many chunks, a grid that covers every compute unit (all XCDs), the same step
     launched again and again: the output of the fused step (chunks meet through arrival counters and
     write-through partials inside the launch) must equal, bit for bit, the two-kernel path (partials with
-    plain stores, merged by a second launch) every time.  Stops at the first mismatch."""
+    plain stores, merged by a second launch) every time.  Stops at the first mismatch.  Also with the dynamic
+    work list (variant 10: positions claimed from a device-wide counter that every launch must leave at zero)
+    and with rows staged through the LDS ring (variant 12), on grids smaller and larger than the list."""
     H, D, dtype = 16, 256, s3.S3_F16
     rng = np.random.default_rng(800)
     lens = [int(x) for x in rng.integers(200, 1000, size=96)]
@@ -379,6 +381,7 @@ def test_soak_of_the_in_kernel_merge_equals_the_two_kernel_path(sync, launches):
             [rng.standard_normal((L, H, D), dtype=np.float32) for L in lens])
     assert s3.s3_kv_set_param(rig.a, "chunk", 64) == 0  # 4 to 16 chunks per context, about 9000 items
     assert s3.s3_kv_set_param(rig.a, "merge_sync", sync) == 0
+    assert s3.s3_kv_set_param(rig.a, "variant", variant) == 0
     cus = s3.s3_kv_get_param(rig.a, "num_cus")[1]
     assert cus >= 8
     q, k_new, v_new = (device_bits(wl.normal_bits(rng, (n, H, D), dtype), TDT[dtype], DEV) for _ in range(3))
@@ -391,9 +394,9 @@ def test_soak_of_the_in_kernel_merge_equals_the_two_kernel_path(sync, launches):
     assert s3.s3_decode_attention(rig.a, 0, n, q, rig.off_d, len1_d, ref, s3.S3_F32, 0.0, rig.stream) == 0
     torch.cuda.synchronize()
     out = torch.empty_like(ref)
-    for grid in (0, 2 * cus, 8 * cus):
+    for grid in (0, 2 * cus, 8 * cus, 7, 100000):
         assert s3.s3_kv_set_param(rig.a, "grid_blocks", grid) == 0
-        for i in range(launches // 2 if grid else launches):
+        for i in range(launches if grid == 0 else launches // 2 if grid in (2 * cus, 8 * cus) else 6):
             out.fill_(float("nan"))
             assert s3.s3_decode_step(rig.a, 0, n, rig.off_d, pos_d, q, k_new, v_new, out, s3.S3_F32, 0.0, len_out,
                                      rig.stream) == 0

@@ -464,6 +464,53 @@ def test_evict_to_host_and_restore_with_doubled_reservation(pinned):
     rig.close()
 
 
+def test_gather_and_scatter_rows_are_the_device_side_halves_of_evict_and_restore():
+    """An eviction staged through device memory: gather into a contiguous buffer (same layout and bits as the
+    host buffer of s3_kv_evict, i.e. the oracle's evicted rows), free, reserve the doubled slot, scatter back;
+    nothing else in the arena changes."""
+    preds = [300, 128, 64]
+    lens = [257, 128, 40]
+    rig = Rig(2, 12, 128, s3.S3_BF16, 64, 512, preds, seed=34, arena_tokens=896)
+    for layer in range(2):
+        rig.fill(lens, layer)
+    sid = int(rig.ids[1])
+    nbytes = s3.s3_kv_evict_bytes(rig.a, 128)
+    stage = torch.full((nbytes + 64,), 0xAB, dtype=torch.uint8, device=DEV)
+    assert s3.s3_kv_gather_rows(rig.a, sid, 129, stage, rig.stream) == s3.S3_ERR_INVALID  # more rows than the slot holds
+    assert s3.s3_kv_gather_rows(rig.a, 7, 1, stage, rig.stream) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_gather_rows(rig.a, sid, 128, stage[8:], rig.stream) == s3.S3_ERR_INVALID  # misaligned
+    assert s3.s3_kv_gather_rows(rig.a, sid, 128, stage, rig.stream) == 0
+    assert s3.s3_kv_free(rig.a, sid) == 0
+    st_o, blob = rig.o.evict(sid, 128)
+    assert st_o == 0 and s3.s3_kv_stats(rig.a) == (0, *rig.o.stats())
+    torch.cuda.synchronize()
+    assert np.array_equal(stage[:nbytes].cpu().numpy().view(np.uint16).reshape(2, 2, 128, 12, 128), blob)
+    assert (stage[nbytes:] == 0xAB).all()  # nothing beyond the rows was written
+    # the freed room is overwritten by a newcomer before the sequence returns
+    rc, ids, offs, caps = s3.s3_kv_alloc(rig.a, [128])
+    assert (rc, int(ids[0]), int(offs[0]), int(caps[0])) == (1, *rig.o.alloc_one(128))
+    other = wl.normal_bits(rig.rng, (128, 12, 128), 1)
+    for layer in range(2):
+        assert rig.o.fill(int(ids[0]), layer, other, other) == 0
+        assert s3.s3_kv_fill(rig.a, int(ids[0]), layer, 0, 128, device_bits(other, torch.bfloat16, DEV),
+                             device_bits(other, torch.bfloat16, DEV), rig.stream) == 0
+    want_cap = s3.s3_kv_grown_capacity(rig.cfg, 128)
+    rc, ids2, offs2, caps2 = s3.s3_kv_alloc(rig.a, [want_cap])
+    got_o = rig.o.restore(want_cap, blob)
+    assert (0 if rc == 1 else -2, int(ids2[0]), int(offs2[0]), int(caps2[0])) == got_o and caps2[0] == 256
+    snap = rig.mem.clone()
+    assert s3.s3_kv_scatter_rows(rig.a, int(ids2[0]), 257, stage, rig.stream) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_scatter_rows(rig.a, int(ids2[0]), 128, stage, rig.stream) == 0
+    torch.cuda.synchronize()
+    changed = (rig.mem != snap).sum().item()
+    assert 0 < changed <= nbytes
+    for slot, rows in ((int(ids2[0]), 128), (int(ids[0]), 128), (int(rig.ids[0]), 257), (int(rig.ids[2]), 40)):
+        for layer in range(2):
+            for which in (0, 1):
+                assert np.array_equal(rig_read(rig, slot, layer, which, rows), rig.o.rows(slot, layer, which, rows))
+    rig.close()
+
+
 def test_fill_batch_equals_fills_plus_patch():
     """s3_kv_fill_batch = the s3_kv_fill of every newcomer + the s3_kv_batch_patch of their batch entries,
     in one launch (more than 16 newcomers: several); arguments are checked before anything is enqueued."""
@@ -716,11 +763,12 @@ def test_supervisor_path_compacts_evicts_and_readmits(seed, arena_tokens, admiss
     attend = sorted({0, 60, 130, 200, w.steps - 1})
     got = {}
     for t in range(w.steps):
-        if eng.n_active == 0 and not eng.swapped:
+        if eng.n_active == 0 and not eng.swapped and not eng.n_returning:
             break
         out = eng.step(tensors_for(t), prefill, check_host=True)
         if t in attend and out is not None:
             got[t] = out.float().cpu().numpy()
+    eng.finish_restores()  # sequences whose rows are still on their way back join the batch: their rows are checked too
     kinds = [e[0] for e in eng.events]
     print(f"tight {seed}: grows {eng.n_grown} compactions {eng.n_compactions} out {eng.n_swapped_out} in {eng.n_swapped_in} "
           f"still on host {len(eng.swapped)} batch {eng.n_active}")
