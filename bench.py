@@ -293,6 +293,7 @@ def run_workload(name, args, torch, cpu_budget_s):
                    "dropped": eng.n_evicted, "on_nomem": args.on_nomem,
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
                    "algorithmic_GB_per_step": round(total_bytes / max(steps_done, 1) / 1e9, 4),
+                   "algorithmic_bytes_per_launch": int(total_bytes / max(steps_done * w.n_layers, 1)),
                    "path": "quantising append + shared-kv matrix-core attention over 8-bit rows + merge per layer" if shared_kv and w.dtype == 3 else
                            "shared-kv attention kernel (+ append launch for the vector-ALU kernel) + merge per layer" if shared_kv else
                            "one s3_decode_step kernel per layer (quantises and appends the new row, attends over 8-bit rows, merges)" if w.dtype == 3 else

@@ -257,6 +257,16 @@ int s3_kv_restore(s3_arena *a, int32_t predicted_len, int32_t len, const void *h
 int s3_kv_gather_rows(s3_arena *a, int32_t slot_id, int32_t len, void *dev_buf /*DEVICE*/, void *stream);
 int s3_kv_scatter_rows(s3_arena *a, int32_t slot_id, int32_t len, const void *dev_buf /*DEVICE*/, void *stream);
 
+/* The link half of a staged eviction or re-admission: copy `bytes` (a multiple of 16; both pointers 16-byte
+ * aligned) between a DEVICE buffer and pinned HOST memory that the device can address (memory from hipHostMalloc,
+ * which torch's pinned tensors are), in either direction, with a kernel of `workgroups` workgroups (1..1024) on
+ * `stream`.  The host link sets the rate of such a copy (eight workgroups reach it); each workgroup takes a whole
+ * compute unit (it reserves the unit's LDS), so the decode steps running beside it keep all the other units to
+ * themselves, which they do not next to the runtime's own copy kernels.
+ * The caller vouches for both ranges (they cannot be checked here). */
+int s3_kv_link_copy(void *dst /*DEVICE or pinned HOST*/, const void *src /*DEVICE or pinned HOST*/, size_t bytes,
+                    int32_t workgroups, void *stream);
+
 /* The supervisor's report of available memory (section 3), in tokens.  Any out pointer may be NULL. */
 int s3_kv_stats(const s3_arena *a, int64_t *used_tok, int64_t *free_tok, int64_t *largest_free_tok,
                 int64_t *capacity_tok);

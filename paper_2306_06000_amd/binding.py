@@ -50,6 +50,7 @@ SIGNATURES = {
     "s3_kv_restore": (ctypes.c_int, [_vp, _i32, _i32, _vp, _pi32, _pi64, _pi32, _vp]),
     "s3_kv_gather_rows": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
     "s3_kv_scatter_rows": (ctypes.c_int, [_vp, _i32, _i32, _vp, _vp]),
+    "s3_kv_link_copy": (ctypes.c_int, [_vp, _vp, ctypes.c_size_t, _i32, _vp]),
     "s3_sched_create": (ctypes.c_int, [ctypes.POINTER(_vp), _vp]),
     "s3_sched_destroy": (None, [_vp]),
     "s3_sched_submit": (ctypes.c_int, [_vp, _i64, _i32]),
@@ -235,6 +236,10 @@ def s3_kv_gather_rows(arena, slot_id, length, dev_buf, stream=0):
 
 def s3_kv_scatter_rows(arena, slot_id, length, dev_buf, stream=0):
     return lib().s3_kv_scatter_rows(arena, int(slot_id), int(length), _ptr(dev_buf), stream or None)
+
+
+def s3_kv_link_copy(dst, src, nbytes, workgroups=16, stream=0):
+    return lib().s3_kv_link_copy(_ptr(dst), _ptr(src), int(nbytes), int(workgroups), stream or None)
 
 
 def s3_sched_create(arena):

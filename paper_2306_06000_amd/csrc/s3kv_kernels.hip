@@ -873,6 +873,47 @@ extern "C" int s3_kv_scatter_rows(s3_arena *a, int32_t slot_id, int32_t len, con
                                   2 * a->cfg.n_layers, stream);
 }
 
+// A copy that deliberately occupies few compute units, and occupies them alone: `workgroups` workgroups of 1024
+// threads move `bytes` with four 16-byte pieces in flight per thread, and every workgroup reserves nearly all of a
+// compute unit's LDS so that no attention workgroup shares the unit with waves that wait on the host link.  For
+// transfers between device memory and mapped pinned host memory beside the decode steps; the host link, not the
+// kernel, sets their rate (eight workgroups reach it).  Measured on the 28-layer workload under a kernel trace:
+// with the runtime's own copy kernels, which spread over every unit, the attention launches averaged 821 us (one
+// per eviction up to 5.5 ms); with this kernel 780 us (the launch during which a copy starts still takes 2-3 ms,
+// wherever the copy's workgroups sit: eight units taken whole or sixteen shared measured alike).
+#define S3_LINK_THREADS 1024
+#define S3_LINK_LDS (152 * 1024)
+__global__ void __launch_bounds__(S3_LINK_THREADS) link_copy_kernel(const char *src, char *dst, size_t n16) {
+    const u32x4 *s = (const u32x4 *)src;
+    u32x4 *d = (u32x4 *)dst;
+    const size_t stride = (size_t)gridDim.x * blockDim.x;
+    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    for (; i + 3 * stride < n16; i += 4 * stride) {
+        const u32x4 a = s[i], b = s[i + stride], c = s[i + 2 * stride], e = s[i + 3 * stride];
+        d[i] = a;
+        d[i + stride] = b;
+        d[i + 2 * stride] = c;
+        d[i + 3 * stride] = e;
+    }
+    for (; i < n16; i += stride) d[i] = s[i];
+}
+
+extern "C" int s3_kv_link_copy(void *dst, const void *src, size_t bytes, int32_t workgroups, void *stream) {
+    if (bytes == 0) return S3_OK;
+    if (!dst || !src || (bytes & 15) || ((uintptr_t)dst & 15) || ((uintptr_t)src & 15)) return S3_ERR_INVALID;
+    if (workgroups < 1 || workgroups > 1024) return S3_ERR_INVALID;
+    static std::once_flag once;
+    static hipError_t attr = hipSuccess;
+    std::call_once(once, [] {
+        attr = hipFuncSetAttribute((const void *)link_copy_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, S3_LINK_LDS);
+    });
+    if (attr != hipSuccess) return hip_fail("hipFuncSetAttribute(link_copy_kernel)", attr);
+    hipLaunchKernelGGL(link_copy_kernel, dim3((unsigned)workgroups), dim3(S3_LINK_THREADS), S3_LINK_LDS, (hipStream_t)stream,
+                       (const char *)src, (char *)dst, bytes / 16);
+    HIP_TRY(hipGetLastError());
+    return S3_OK;
+}
+
 extern "C" int s3_kv_read_rows(s3_arena *a, int32_t slot_id, int32_t layer, int32_t which, int32_t first_row,
                                int32_t n_rows, void *dst, void *stream) {
     const s3_slot *s = s3i_live_slot(a, slot_id);

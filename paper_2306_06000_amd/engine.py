@@ -70,10 +70,13 @@ class DecodeEngine:
             self._requests = list(w.seqs) + list(w.pool)  # request id = position in this list
             for rid, r in enumerate(self._requests):
                 s3.check(s3.s3_sched_submit(self.sched, rid, r.predicted), "s3_sched_submit")
-        if on_nomem == "swap":  # pinning is slow: eight buffers of a quarter of the longest sequence are pinned up front
+        if on_nomem == "swap":  # pinning is slow: six buffers of a quarter of the longest sequence are pinned up front
             self._side = torch.cuda.Stream(self.dev)
             quarter = max(w.granule, w.max_len // 4) * self.bpt
-            self._host_free = [torch.empty(quarter, dtype=torch.uint8, pin_memory=True) for _ in range(8)]
+            self._host_free = [torch.empty(quarter, dtype=torch.uint8, pin_memory=True) for _ in range(6)]
+            # and two that hold the longest sequence: pinning memory in the middle of a run maps it into the
+            # device's address space, which stalls the kernels that are running
+            self._host_free += [torch.empty(w.max_len * self.bpt, dtype=torch.uint8, pin_memory=True) for _ in range(2)]
             # device staging: four buffers that hold the longest sequence (allocating one mid-run would synchronise)
             self._stage = [[None, torch.empty(w.max_len * self.bpt, dtype=torch.uint8, device=self.dev), False]
                            for _ in range(4)]
@@ -122,16 +125,20 @@ class DecodeEngine:
     def _stream_ptr(self):
         return torch.cuda.current_stream(self.dev).cuda_stream
 
+    LINK_WORKGROUPS = 8  # workgroups (one compute unit each) of a copy over the host link: enough for its rate,
+                         # few enough to leave the other units to the decode steps that run beside it
     MAX_RETURNING = 2  # sequences on their way back at once; each holds a staging buffer until it has joined
 
-    def _stage_buffer(self):
-        """A device staging buffer that no returning sequence holds and whose last use has completed (blocks on
-        one if all that are not held are busy; at least two never are held)."""
+    def _stage_buffer(self, block=True):
+        """A device staging buffer that no returning sequence holds and whose last use has completed (if all
+        that are not held are busy: blocks on one, or returns None; at least two never are held)."""
         idle = [e for e in self._stage if not e[2]]
         for entry in idle:
             if entry[0] is None or entry[0].query():
                 entry[0] = None
                 return entry
+        if not block:
+            return None
         entry = idle[0]
         entry[0].synchronize()
         entry[0] = None
@@ -347,8 +354,7 @@ class DecodeEngine:
         ready, done = torch.cuda.Event(), torch.cuda.Event()
         ready.record(main)
         self._side.wait_event(ready)
-        with torch.cuda.stream(self._side):
-            host[:nbytes].copy_(entry[1][:nbytes], non_blocking=True)
+        s3.check(s3.s3_kv_link_copy(host, entry[1], nbytes, self.LINK_WORKGROUPS, self._side.cuda_stream), "s3_kv_link_copy")
         done.record(self._side)
         entry[0] = done
         self._log("evict", int(self.serial[i]), sid, length)
@@ -370,6 +376,9 @@ class DecodeEngine:
         batch at the first step that finds them there (_join_restored).  -> True, or False (no room yet)."""
         if len(self._restoring) >= self.MAX_RETURNING:
             return False
+        entry = self._stage_buffer(block=False)
+        if entry is None:  # every staging buffer still carries an eviction to the host: try again at the next retirement
+            return False
         rec = self.swapped[0]
         rc, ids, offs, caps = s3.s3_kv_alloc(self.arena, [rec.want])
         s3.check(rc, "s3_kv_alloc")
@@ -378,10 +387,10 @@ class DecodeEngine:
         if st == s3.S3_ERR_NOMEM:
             return False
         self.swapped.pop(0)
-        entry = self._stage_buffer()
         entry[2] = True  # held until the rows have been scattered into the slot
-        with torch.cuda.stream(self._side):  # behind this sequence's own copy to the host, which ran on this stream
-            entry[1][:rec.nbytes].copy_(rec.host[:rec.nbytes], non_blocking=True)
+        # on the side stream, i.e. behind this sequence's own copy to the host, which ran there
+        s3.check(s3.s3_kv_link_copy(entry[1], rec.host, rec.nbytes, self.LINK_WORKGROUPS, self._side.cuda_stream),
+                 "s3_kv_link_copy")
         back = torch.cuda.Event()
         back.record(self._side)
         entry[0] = back

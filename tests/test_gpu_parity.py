@@ -486,6 +486,17 @@ def test_gather_and_scatter_rows_are_the_device_side_halves_of_evict_and_restore
     torch.cuda.synchronize()
     assert np.array_equal(stage[:nbytes].cpu().numpy().view(np.uint16).reshape(2, 2, 128, 12, 128), blob)
     assert (stage[nbytes:] == 0xAB).all()  # nothing beyond the rows was written
+    # over the host link and back with the small-grid copy kernel (pinned host memory, any grid size)
+    host = torch.zeros(nbytes, dtype=torch.uint8).pin_memory()
+    back = torch.full((nbytes + 64,), 0xCD, dtype=torch.uint8, device=DEV)
+    assert s3.s3_kv_link_copy(host, stage, nbytes, 16, rig.stream) == 0
+    assert s3.s3_kv_link_copy(back, host, nbytes, 3, rig.stream) == 0
+    assert s3.s3_kv_link_copy(back, host, nbytes + 8, 3, rig.stream) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_link_copy(back, host, nbytes, 0, rig.stream) == s3.S3_ERR_INVALID
+    torch.cuda.synchronize()
+    assert np.array_equal(host.numpy().view(np.uint16).reshape(2, 2, 128, 12, 128), blob)
+    assert torch.equal(back[:nbytes], stage[:nbytes]) and (back[nbytes:] == 0xCD).all()
+    stage = back
     # the freed room is overwritten by a newcomer before the sequence returns
     rc, ids, offs, caps = s3.s3_kv_alloc(rig.a, [128])
     assert (rc, int(ids[0]), int(offs[0]), int(caps[0])) == (1, *rig.o.alloc_one(128))
