@@ -257,6 +257,12 @@ def run_workload(name, args, torch, cpu_budget_s):
         # tens of milliseconds here and would land on whichever step triggers it): collect now, resume after.
         gc.collect()
         gc.disable()
+        # the collection above left the device idle for tens of milliseconds, long enough for its clocks to fall
+        # back; a serving loop never pauses like that, so the device is kept streaming (the library's read probe,
+        # about 10 ms) right up to the synchronisation that opens the timed region
+        tail = torch.cuda.Event()
+        tail.record()  # created and used once before the region: an event's first use costs tens of microseconds
+        s3.check(s3.s3_kv_probe_bandwidth(eng.arena, probe_bytes, 0, max(2, int(0.01 * 5e12 / probe_bytes)))[0], "probe")
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
@@ -270,6 +276,12 @@ def run_workload(name, args, torch, cpu_budget_s):
             seq_steps += eng.last_step_seqs
             launch_bytes.append(eng.last_step_bytes)
         t_enqueue = time.perf_counter() - t0  # host time to enqueue every step (no device wait in it)
+        # the closing synchronisation is awaited by polling an event recorded behind the last step: a blocking wait
+        # puts the host thread to sleep, and its wake-up (tens of microseconds) would be charged to a region that
+        # at the driver's 20 steps of C1 lasts little more than a millisecond
+        tail.record()
+        while not tail.query():
+            pass
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         gc.enable()
