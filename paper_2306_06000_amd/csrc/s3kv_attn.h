@@ -466,13 +466,17 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
     X(9, 15, 1, 2, true, true, 0, false)   \
     X(10, 8, 1, 2, true, true, 0, true)    \
     X(11, 8, 1, 2, true, true, 6, false)   \
-    X(12, 8, 1, 2, true, true, 6, true)
+    X(12, 8, 1, 2, true, true, 6, true)    \
+    X(13, 8, 1, 3, true, true, 0, true)
 // Defaults (measured on MI355X): shape 4 with a fixed stride while the work list is about as long as the grid
-// (batches of up to 128 sequences), the same shape with the dynamic work list beyond (+4 % to +7 % on batches of
-// 512 and 700 sequences; -5 % on a batch of 128 long contexts).  The LDS-ring shapes stay selectable for
-// comparison: they measured 2-3 % behind the register path.
+// (batches of up to 128 sequences); beyond, the dynamic work list (+4 % to +7 % on batches of 512 and 700
+// sequences; -5 % on a batch of 128 long contexts) with three rows per register set (shape 13: +1.5 % / +0.5 % over
+// two rows there; on the small batches three or four rows per set are 1-5 % behind two).  The LDS-ring shapes stay
+// selectable for comparison: they measured 2-3 % behind the register path.  Shapes that were tried with the
+// dynamic list and dropped: two or four head groups per workgroup with four or two waves each (0.756 / 0.745 of
+// peak on the batch of 512 against 0.762), one workgroup per whole row (eight head groups, one wave each: 0.655).
 #define S3_DEFAULT_VARIANT 4
-#define S3_DEFAULT_VARIANT_LARGE 10
+#define S3_DEFAULT_VARIANT_LARGE 13
 
 template <int DT, int D>
 static attn_fn pick_variant(int v, bool fused) {
