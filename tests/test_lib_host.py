@@ -325,3 +325,33 @@ __global__ void probe_arrive(AttnArgs a, unsigned int *cnt, int *flag) {
     # the count and invalidates after it; the default drains the wave's memory counter before the count
     assert "buffer_wbl2" in arrive and "buffer_inv" in arrive and "global_atomic_add" in arrive
     assert re.search(r"s_waitcnt vmcnt\(0\).*global_atomic_add", arrive, flags=re.S)
+
+
+def test_calls_that_touch_rows_refuse_a_metadata_only_arena_without_any_device_call():
+    """The entry points added beside the core path make no HIP call before their argument checks: on an arena
+    without device memory they answer S3_ERR_INVALID (this runs where no GPU exists)."""
+    cfg, a = meta_arena(2, 4, 128, s3.S3_BF16, 64, 512, 1 << 24)
+    rc, ids, offs, caps = s3.s3_kv_alloc(a, [100])
+    assert rc == 1
+    sid = int(ids[0])
+    fake = 1 << 20  # an aligned address that is never dereferenced
+    assert s3.s3_kv_gather_rows(a, sid, 10, fake) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_scatter_rows(a, sid, 10, fake) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_reserve_scratch(a, 64) == s3.S3_ERR_INVALID
+    assert s3.s3_decode_step_static(a, 0, 1, fake, fake, fake, fake, fake, fake) == s3.S3_ERR_INVALID
+    assert s3.s3_decode_step(a, 0, 1, fake, fake, fake, fake, fake, fake) == s3.S3_ERR_INVALID
+    # the link copy checks sizes, alignment and the grid before it launches anything
+    assert s3.s3_kv_link_copy(fake, fake + 4096, 0, 8) == s3.S3_OK  # nothing to copy
+    assert s3.s3_kv_link_copy(fake, fake + 4096, 24, 8) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_link_copy(fake + 8, fake + 4096, 32, 8) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_link_copy(fake, fake + 4096, 32, 0) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_link_copy(fake, fake + 4096, 32, 1025) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_link_copy(None, fake, 32, 8) == s3.S3_ERR_INVALID
+    # parameters of the new knobs
+    assert s3.s3_kv_set_param(a, "merge_sync", 1) == s3.S3_OK and s3.s3_kv_get_param(a, "merge_sync") == (0, 1)
+    assert s3.s3_kv_set_param(a, "merge_sync", 2) == s3.S3_ERR_INVALID
+    st, dv = s3.s3_kv_get_param(a, "default_variant")
+    st2, nv = s3.s3_kv_get_param(a, "n_variants")
+    assert st == 0 and st2 == 0 and 0 <= dv < nv
+    assert s3.lib().s3_status_str(s3.S3_ERR_SCRATCH) == b"S3_ERR_SCRATCH"
+    s3.s3_kv_arena_destroy(a)
