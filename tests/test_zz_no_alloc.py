@@ -112,3 +112,52 @@ def test_static_scratch_step_refuses_what_does_not_fit_and_launches_nothing():
     torch.cuda.synchronize()
     assert torch.isfinite(out).all()
     rig.close()
+
+
+def test_static_scratch_step_recorded_in_a_graph_replays_exactly_with_the_dynamic_work_list():
+    """What the entry point is for: the step is recorded into a HIP graph (nothing in it allocates) and replayed,
+    with eager work on the same arena in between.  The kernel shape with the dynamic work list on a grid much
+    smaller than the list: the list's counters and the arrival counters of the chunk merge, which live in the fixed
+    buffer, must be back at zero after every launch, replayed or not."""
+    fam = FAMILIES[0]
+    name, H, Hkv, D, kvt, act, kind = fam
+    rng = np.random.default_rng(91)
+    lens = [0, 1, 63, 200, 511, 700, 64, 5, 999, 130]
+    rig = EdgeRig(fam, lens, M=2048)
+    rig.put([rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens],
+            [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens])
+    assert s3.s3_kv_set_param(rig.a, "chunk", 64) == 0
+    assert s3.s3_kv_set_param(rig.a, "variant", 13) == 0
+    assert s3.s3_kv_set_param(rig.a, "grid_blocks", 16) == 0
+    n = len(lens)
+    q, k, v = (device_bits(wl.normal_bits(rng, (n, H, D), act), TDT[act], DEV) for _ in range(3))
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    want = torch.full((n, H, D), float("nan"), dtype=torch.float32, device=DEV)
+    assert s3.s3_decode_step(rig.a, 0, n, rig.off_d, pos_d, q, k, v, want, s3.S3_F32, 0.0, len_out, rig.stream) == 0
+    first = torch.full_like(want, float("nan"))
+    assert s3.s3_decode_step_static(rig.a, 0, n, rig.off_d, pos_d, q, k, v, first, s3.S3_F32, 0.0, len_out, rig.stream) == 0
+    torch.cuda.synchronize()
+    assert torch.equal(first, want)
+    out = torch.full_like(want, float("nan"))
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        st = s3.s3_decode_step_static(rig.a, 0, n, rig.off_d, pos_d, q, k, v, out, s3.S3_F32, 0.0, len_out,
+                                      torch.cuda.current_stream().cuda_stream)
+    assert st == 0
+    for rep in range(4):
+        out.fill_(float("nan"))
+        len_out.zero_()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
+        assert len_out.cpu().tolist() == [L + 1 for L in lens]
+        again = torch.full_like(want, float("nan"))
+        assert s3.s3_decode_step_static(rig.a, 0, n, rig.off_d, pos_d, q, k, v, again, s3.S3_F32, 0.0, len_out,
+                                        rig.stream) == 0
+        torch.cuda.synchronize()
+        assert torch.equal(again, want)
+    assert s3.s3_kv_get_param(rig.a, "scratch_bytes")[1] > 0  # (from the allocating reference call only)
+    rig.close()
