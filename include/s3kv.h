@@ -260,9 +260,10 @@ int s3_kv_scatter_rows(s3_arena *a, int32_t slot_id, int32_t len, const void *de
 /* The link half of a staged eviction or re-admission: copy `bytes` (a multiple of 16; both pointers 16-byte
  * aligned) between a DEVICE buffer and pinned HOST memory that the device can address (memory from hipHostMalloc,
  * which torch's pinned tensors are), in either direction, with a kernel of `workgroups` workgroups (1..1024) on
- * `stream`.  The host link sets the rate of such a copy (eight workgroups reach it); each workgroup takes a whole
- * compute unit (it reserves the unit's LDS), so the decode steps running beside it keep all the other units to
- * themselves, which they do not next to the runtime's own copy kernels.
+ * `stream`.  Each workgroup takes a whole compute unit (it reserves the unit's LDS).  Few workgroups keep few
+ * writes queued for the link at once, which is what lets decode steps run beside the copy undisturbed: two reach
+ * about 30 GB/s and leave an attention kernel at full speed, eight reach the link's 55 GB/s and slow whatever runs
+ * beside the copy's first milliseconds several times over (as the runtime's own copy kernels do).
  * The caller vouches for both ranges (they cannot be checked here). */
 int s3_kv_link_copy(void *dst /*DEVICE or pinned HOST*/, const void *src /*DEVICE or pinned HOST*/, size_t bytes,
                     int32_t workgroups, void *stream);

@@ -876,11 +876,14 @@ extern "C" int s3_kv_scatter_rows(s3_arena *a, int32_t slot_id, int32_t len, con
 // A copy that deliberately occupies few compute units, and occupies them alone: `workgroups` workgroups of 1024
 // threads move `bytes` with four 16-byte pieces in flight per thread, and every workgroup reserves nearly all of a
 // compute unit's LDS so that no attention workgroup shares the unit with waves that wait on the host link.  For
-// transfers between device memory and mapped pinned host memory beside the decode steps; the host link, not the
-// kernel, sets their rate (eight workgroups reach it).  Measured on the 28-layer workload under a kernel trace:
-// with the runtime's own copy kernels, which spread over every unit, the attention launches averaged 821 us (one
-// per eviction up to 5.5 ms); with this kernel 780 us (the launch during which a copy starts still takes 2-3 ms,
-// wherever the copy's workgroups sit: eight units taken whole or sixteen shared measured alike).
+// transfers between device memory and mapped pinned host memory beside the decode steps.  How many workgroups
+// is the caller's trade: the copy's rate grows with them (measured device -> host: 1: 17 GB/s, 2: 31, 4: 43,
+// 8: 55 = the link's rate), but so does the number of writes queued for the link at once, and beyond four the
+// queue hurts everything else that runs - with eight, whatever kernel was running when a copy started (an
+// attention launch, a doubling's copy) took 3-5 times as long for the copy's first milliseconds (attention
+// launches of the 28-layer workload under a kernel trace: average 769-780 us, up to 3.5 ms; the runtime's own
+// copy kernels, which spread over every unit: 821 us, up to 5.5 ms), with one, two or four: 746-748 us, none above
+// 1.0 ms.  The decode loop uses two.
 #define S3_LINK_THREADS 1024
 #define S3_LINK_LDS (152 * 1024)
 __global__ void __launch_bounds__(S3_LINK_THREADS) link_copy_kernel(const char *src, char *dst, size_t n16) {

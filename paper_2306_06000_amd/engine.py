@@ -125,8 +125,8 @@ class DecodeEngine:
     def _stream_ptr(self):
         return torch.cuda.current_stream(self.dev).cuda_stream
 
-    LINK_WORKGROUPS = 8  # workgroups (one compute unit each) of a copy over the host link: enough for its rate,
-                         # few enough to leave the other units to the decode steps that run beside it
+    LINK_WORKGROUPS = 2  # workgroups (one compute unit each) of a copy over the host link: about 30 GB/s, and few
+                         # enough writes queued for the link at once that the decode steps beside it run at full speed
     MAX_RETURNING = 2  # sequences on their way back at once; each holds a staging buffer until it has joined
 
     def _stage_buffer(self, block=True):
