@@ -339,6 +339,9 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *                  caches, 8-bit rows) are ordered across workgroups: 0 (default) write-through partial
  *                  stores, a drained memory counter and a relaxed counter increment; 1 device-scope
  *                  release / acquire fences around the increment (slower; same results)
+ *   "gqa_merge"    shared key/value heads, matrix-core kernel: 1 = multi-chunk contexts are finished inside the
+ *                  attention launch (arrival counters, write-through partials), 0 (default) = by a merge launch;
+ *                  same results; the launch-saving form measured slower (its partials bypass the caches)
  *   "profile"      k > 0: every k-th attention launch (counted from this call) carries HIP events that
  *                  take the kernel's own start and end times (hipExtLaunchKernel); 0: off; both reset the sums
  * get names: the above plus "default_variant", "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,

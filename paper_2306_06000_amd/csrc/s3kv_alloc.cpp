@@ -318,6 +318,11 @@ extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
         a->variant = (int32_t)value;
         return S3_OK;
     }
+    if (!strcmp(name, "gqa_merge")) {
+        if (value != 0 && value != 1) return S3_ERR_INVALID;
+        a->gqa_merge = (int32_t)value;
+        return S3_OK;
+    }
     if (!strcmp(name, "merge_sync")) {
         if (value != 0 && value != 1) return S3_ERR_INVALID;
         a->merge_sync = (int32_t)value;
@@ -341,6 +346,7 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
     else if (!strcmp(name, "classes")) *value = a->ncls;
     else if (!strcmp(name, "variant")) *value = a->variant;
     else if (!strcmp(name, "merge_sync")) *value = a->merge_sync;
+    else if (!strcmp(name, "gqa_merge")) *value = a->gqa_merge;
     else if (!strcmp(name, "n_variants")) *value = s3i_variants_of(a);
     else if (!strcmp(name, "default_variant")) *value = s3i_kernel_kind(a) == 0 ? s3i_default_variant() : -1;
     else if (!strcmp(name, "kernel_kind")) *value = s3i_kernel_kind(a);

@@ -36,6 +36,7 @@ struct AttnArgs {
     int32_t *len_out;        // may be null
     unsigned int *arrivals;  // [n][n_hgb] chunk-arrival counters, zero between launches
     int32_t merge_sync;      // how chunks that meet inside one launch are ordered: see chunk_arrived()
+    int32_t merge_in_kernel; // matrix-core kernel for shared heads: chunks meet inside the launch (no merge launch follows)
     unsigned int *queue;     // [2] kernels with a dynamic work list: positions claimed, workgroups gone; zero between launches
 };
 

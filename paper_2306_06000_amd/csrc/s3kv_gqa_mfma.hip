@@ -31,12 +31,19 @@
 //     weights' error near 2^-16 (bfloat16) / 2^-22 (fp16) instead of 2^-9 / 2^-12: with one part only,
 //     values of magnitude 1e2 put the fp16 kernel outside the attention tolerance.
 // Accumulators: O^T block db holds O^T[d = 16*db + 4*g + i][head], fp32.  Results leave as the
-// final row (single-chunk contexts) or as a chunk partial (max, sum, unnormalised row) that
-// attn_merge_kernel finishes (merging in this kernel through an arrival counter and device-scope
-// partials, as the fused multi-head step does in its epilogue wave, tripled the kernel's time here:
-// with one wave per item nothing hides the write-through and the counter's round trip).  In a decode
-// step the new row is read from k_new / v_new and appended by the wave that owns it, so the step is
-// this launch plus the merge.
+// final row (single-chunk contexts) or as a chunk partial (max, sum, unnormalised row).  Partials are
+// finished either by attn_merge_kernel (a second launch) or, with merge_in_kernel, inside this launch:
+// an arrival counter per (sequence, K/V head, query block), write-through partials, the wave that
+// delivers the last chunk merges.  Done at once after every item this tripled the kernel's time (with
+// one wave per item nothing hides the write-through and the counter's round trip); here the
+// publication of an item trails the wave's work by two items - the counter is bumped at the end of the
+// NEXT item, when the partial's stores have long completed, and its answer is looked at one item
+// later still - so a wave never waits for either.  It still loses to the merge launch and is not the
+// default: with 128-row chunks nearly every item leaves an 8 KiB partial, and written through to memory
+// (as partials that cross XCDs inside one launch must be) they cost more than the launch they save -
+// 32 query / 8 cached heads x 128, 256 sequences: kernel 74 -> 101 us, whole step 72 -> 89 us;
+// multi-query 16/1 x 256: 29 -> 65 us.  In a decode step the new row is read from k_new / v_new and
+// appended by the wave that owns it.
 #include "s3kv_device.h"
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -94,6 +101,23 @@ __device__ __forceinline__ unsigned widen2_e4m3(const unsigned w, const bool upp
     return DT == S3_F16 ? pack_f16(f[0], f[1]) : pack_bf16(f[0], f[1]);
 }
 
+// A chunk whose partial this wave has written and whose arrival is still to be counted / answered.
+struct PendingChunk {
+    unsigned int *cnt;  // the context's arrival counter; null: nothing pending
+    int b, hq0, nheads, nchunks;
+};
+
+// The wave that delivered the last chunk of (sequence b, query heads hq0 .. hq0+nheads-1) merges their chunk
+// partials: 64/(D/8) heads per pass, each lane its 8-element slice.
+template <int D>
+__device__ __forceinline__ void merge_pending(const AttnArgs &a, const PendingChunk &p, int lane) {
+    constexpr int LPH = D / 8, HPP = 64 / LPH;
+    for (int h0 = 0; h0 < p.nheads; h0 += HPP) {
+        const int h = h0 + lane / LPH;
+        if (h < p.nheads) merge_chunks<D, true>(a, a.Hq, p.b, p.hq0 + h, lane % LPH, p.nchunks);
+    }
+}
+
 // KV8: the cache rows are e4m3 codes (one byte per element) and DT is the type of q; a 16-byte load then
 // holds 16 elements, which are widened (exactly) to DT in registers and feed two contraction steps.
 template <int DT, int D, bool KV8>
@@ -121,6 +145,42 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
         if (a.len_out)
             for (int b = threadIdx.x; b < a.n; b += 256) a.len_out[b] = a.cur_len[b] + 1;
     }
+    const bool ink = a.merge_in_kernel != 0;
+    if (ink) {  // no merge launch follows: the zero rows of empty or refused contexts are written here, by the workgroups in turn
+        for (int b = blockIdx.x; b < a.n; b += gridDim.x) {
+            if (bv.len[b] == 0) {
+                const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                for (int e = threadIdx.x; e < a.Hq * D / 8; e += 256) store_out8(a.out, a.out_dtype, ((int64_t)b * a.Hq * D / 8 + e) * 8, z);
+            }
+        }
+    }
+    // Chunks published by this wave whose bookkeeping is still due (wave-uniform): `told` has its partial in
+    // flight to memory, `counted` has been counted on its context's arrival counter and awaits the answer.
+    PendingChunk told, counted;
+    told.cnt = counted.cnt = nullptr;
+    unsigned int counted_old = 0;
+    auto settle = [&](bool drain) {
+        if (!told.cnt && !counted.cnt) return;
+        // everything this wave stored or loaded before the current item's results has completed: the loads were
+        // consumed, and the stores are older than they
+        __builtin_amdgcn_s_waitcnt(0);
+        for (int round = 0; round < (drain ? 2 : 1); round++) {
+            if (counted.cnt) {
+                if (__builtin_amdgcn_readfirstlane(counted_old) == (unsigned int)(counted.nchunks - 1)) {
+                    if (lane == 0) atomicExch(counted.cnt, 0u);  // leave the counter clean for the next launch
+                    if (a.merge_sync) __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "agent");
+                    merge_pending<D>(a, counted, lane);
+                }
+                counted.cnt = nullptr;
+            }
+            if (told.cnt) {
+                if (a.merge_sync) __builtin_amdgcn_fence(__ATOMIC_RELEASE, "agent");
+                if (lane == 0) counted_old = atomicAdd(told.cnt, 1u);
+                counted = told;
+                told.cnt = nullptr;
+            }
+        }
+    };
 
     char *vt = vtile[wave];
     const int64_t rstride = (int64_t)a.H * D * EB;
@@ -298,6 +358,7 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
 
         lsum += __shfl_xor(lsum, 16);
         lsum += __shfl_xor(lsum, 32);
+        if (ink) settle(false);
         if (head_ok) {
             if (it.nchunks == 1) {
                 const float inv = 1.f / lsum;
@@ -306,12 +367,26 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
                     store_out4(a.out, a.out_dtype, ((int64_t)it.b * a.Hq + hq) * D + db * 16 + 4 * g, o[db] * inv);
             } else {
                 const int64_t pi = ((int64_t)it.b * a.max_chunks + it.c) * a.Hq + hq;
-                if (g == 0) a.part_ml[pi] = make_float2(m, lsum);
+                if (ink) {
+                    if (g == 0) put_partial2<true>((float *)a.part_ml + 2 * pi, (f32x2){m, lsum});
 #pragma unroll
-                for (int db = 0; db < DB; db++) *(f32x4 *)(a.part_acc + pi * D + db * 16 + 4 * g) = o[db];
+                    for (int db = 0; db < DB; db++) put_partial4<true>(a.part_acc + pi * D + db * 16 + 4 * g, o[db]);
+                } else {
+                    if (g == 0) a.part_ml[pi] = make_float2(m, lsum);
+#pragma unroll
+                    for (int db = 0; db < DB; db++) *(f32x4 *)(a.part_acc + pi * D + db * 16 + 4 * g) = o[db];
+                }
             }
         }
+        if (ink && it.nchunks > 1) {
+            told.cnt = a.arrivals + (int64_t)it.b * per_seq + it.hgb;
+            told.b = it.b;
+            told.hq0 = hk * group + qb * 16;
+            told.nheads = min(16, group - qb * 16);
+            told.nchunks = it.nchunks;
+        }
     }
+    if (ink) settle(true);  // the last one or two chunks of this wave
 }
 
 attn_fn s3i_pick_gqa_mfma(int dt, int d) {

@@ -582,8 +582,10 @@ static size_t scratch_need(const s3_arena *a, int n) {
         if (chunk <= 0) chunk = 1024;
         const int gh = kind == 3 ? 1024 / D : heads_per_load(D);
         cnt_bytes = counters_bytes((Hq + gh - 1) / gh);
-    } else if (chunk <= 0) {
-        chunk = (kind == 2 || kind == 4) ? 128 : 256;
+    } else {
+        if (chunk <= 0) chunk = (kind == 2 || kind == 4) ? 128 : 256;
+        if ((kind == 2 || kind == 4) && a->gqa_merge)
+            cnt_bytes = counters_bytes(a->cfg.n_kv_heads * ((Hq / a->cfg.n_kv_heads + 15) / 16));
     }
     const size_t max_chunks = (size_t)(a->cfg.max_len + chunk - 1) / chunk;
     const size_t n_part = (size_t)n * max_chunks * Hq;
@@ -685,13 +687,16 @@ static int launch_gqa(s3_arena *a, const AttnCall &c) {
                       : (int64_t)c.n * per_seq >= 2048 ? 1024 : (int64_t)c.n * per_seq >= 512 ? 512 : 256;
     AttnArgs args = common_args(a, c, Hkv, Hq, chunk);
     if (mfma && a->ncls <= 0) args.ncls = 1;  // items of at most 128 rows are all alike: no order to gain from (measured)
-    int rc = place_scratch(a, args, 0, c);
+    // matrix-core kernel: chunks of a context may meet inside the launch (one counter per sequence and item slot)
+    const bool ink = mfma && a->gqa_merge != 0;
+    args.merge_in_kernel = ink ? 1 : 0;
+    int rc = place_scratch(a, args, ink ? counters_bytes(per_seq) : 0, c);
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;
     rc = stride_grid(a, (const void *)fn, threads, dyn_lds, 1, &blocks);
     if (rc != S3_OK) return rc;
-    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, Hq, !c.static_scratch);
+    return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, ink ? 0 : Hq, !c.static_scratch);
 }
 
 // 8-bit cache rows: one kernel, which in a decode step also quantises and appends the new row, merges

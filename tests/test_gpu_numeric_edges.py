@@ -402,3 +402,44 @@ def test_soak_of_the_in_kernel_merge_equals_the_two_kernel_path(sync, launches, 
                                      rig.stream) == 0
             assert torch.equal(out, ref), f"merge_sync {sync} grid {grid}: launch {i} differs from the two-kernel path"
     rig.close()
+
+
+@pytest.mark.parametrize("fam", [FAMILIES[4], FAMILIES[5], FAMILIES[7]], ids=[FAMILIES[i][0] for i in (4, 5, 7)])
+def test_matrix_core_kernel_merging_chunks_inside_the_launch_equals_the_merge_launch(fam):
+    """The matrix-core kernel for shared heads can finish multi-chunk contexts itself (arrival counters, the
+    publication of a chunk trailing the wave's work by two items) instead of leaving them to a merge launch:
+    same bits as the two-launch path, for attention and for the decode step, on a dominant-key batch (chunks with
+    very different maxima), launch after launch (the counters must come back to zero), and within the tolerance
+    of the oracle."""
+    name, H, Hkv, D, kvt, act, kind = fam
+    rng = np.random.default_rng(900 + D + kind)
+    lens = [300, 0, 301, 64, 1, 517, 129, 1000, 33]
+    n, g = len(lens), H // Hkv
+    K = [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens]
+    V = [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens]
+    q = rng.standard_normal((n, H, D), dtype=np.float32)
+    for b, L in enumerate(lens):
+        if L:
+            K[b][max(L - 3, 0)] = 4.0 * q[b, ::g]
+    k_new = rng.standard_normal((n, Hkv, D), dtype=np.float32)
+    v_new = rng.standard_normal((n, Hkv, D), dtype=np.float32)
+    for chunk in (32, 64, 0, 512):
+        outs = {}
+        for merge in (0, 1):
+            rig = EdgeRig(fam, lens, M=2048)
+            rig.put(K, V)
+            assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+            assert s3.s3_kv_set_param(rig.a, "gqa_merge", merge) == 0
+            assert s3.s3_kv_get_param(rig.a, "gqa_merge") == (0, merge)
+            got = []
+            for rep in range(6 if merge else 1):  # again and again on the same counters
+                qb, o = rig.attend(q)
+                got.append(o)
+            assert all(np.array_equal(got[0], x) for x in got[1:]), (name, chunk)
+            assert_close(got[0], rig.want(qb), f"{name} chunk {chunk} gqa_merge {merge}")
+            assert not got[0][1].any()  # the empty context: zeros, written by whoever finishes the contexts
+            qb, step = rig.step(q, k_new, v_new)
+            assert_close(step, rig.want(qb, [L + 1 for L in lens]), f"{name} step chunk {chunk} gqa_merge {merge}")
+            outs[merge] = (got[0], step)
+            rig.close()
+        assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]), (name, chunk)
