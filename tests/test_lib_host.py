@@ -355,3 +355,16 @@ def test_calls_that_touch_rows_refuse_a_metadata_only_arena_without_any_device_c
     assert st == 0 and st2 == 0 and 0 <= dv < nv
     assert s3.lib().s3_status_str(s3.S3_ERR_SCRATCH) == b"S3_ERR_SCRATCH"
     s3.s3_kv_arena_destroy(a)
+
+
+def test_committed_counter_summaries_carry_same_run_traffic_and_algorithmic_bytes():
+    """bench.py prints `roofline.traffic` from the committed rocprofv3 counter summary of each target workload
+    together with THAT run's own algorithmic bytes: both must be present, and every cached byte is read once
+    (traffic within a few per cent of the algorithmic bytes)."""
+    import bench
+
+    for wl_name in ("c1", "c2", "c3", "c4"):
+        traffic, algorithmic = bench.read_traffic("attn_step_kernel", wl_name)
+        assert traffic and algorithmic, wl_name
+        assert 0.97 <= traffic / algorithmic <= 1.03, (wl_name, traffic, algorithmic)
+    assert bench.read_traffic("attn_step_kernel", "c9") == (None, None)
