@@ -242,16 +242,12 @@ def run_workload(name, args, torch, cpu_budget_s):
     probe_bytes = min(eng.arena_mem.numel(), 1 << 30) & ~0xFFFF
     st, probe_gbps = s3.s3_kv_probe_bandwidth(eng.arena, probe_bytes, 0, max(4, int(0.04 * 5e12 / probe_bytes)))
     s3.check(st, "s3_kv_probe_bandwidth")
-    for _ in range(warmup):
-        eng.step(src.tensors, src.prefill)
-    torch.cuda.synchronize()
     setup_s = time.perf_counter() - t_setup
-    lens_at_start = eng.len.copy()
     flush = torch.empty(args.flush_mb << 20, dtype=torch.uint8, device=eng.dev) if args.flush_mb else None
-    grown0, retired0 = eng.n_grown, eng.n_retired
 
-    def timed_pass(evented):
-        """`steps` decode steps; -> (bytes, sequence-steps, per-launch bytes, steps done, wall s, host enqueue s)."""
+    def timed_pass(evented, warm):
+        """`warm` untimed steps, then `steps` timed decode steps; -> (bytes, sequence-steps, per-launch bytes, steps
+        done, wall s, host enqueue s, lengths at the start of the timed steps)."""
         if evented:
             s3.check(s3.s3_kv_set_param(eng.arena, "profile", 1))
         total_bytes, seq_steps, launch_bytes, done = 0, 0, [], 0
@@ -265,6 +261,14 @@ def run_workload(name, args, torch, cpu_budget_s):
         tail = torch.cuda.Event()
         tail.record()  # created and used once before the region: an event's first use costs tens of microseconds
         s3.check(s3.s3_kv_probe_bandwidth(eng.arena, probe_bytes, 0, max(2, int(0.01 * 5e12 / probe_bytes)))[0], "probe")
+        # the warm-up steps come last, right before the synchronisation that opens the region: they leave the
+        # interpreter's and the library's step path hot in the host's caches and the device at its working clocks
+        for _ in range(warm):
+            if eng.n_active:
+                eng.step(src.tensors, src.prefill)
+        if evented:  # warm-up launches are not part of the evented sample
+            s3.check(s3.s3_kv_set_param(eng.arena, "profile", 1))
+        lens0 = (eng.len.copy(), eng.n_grown, eng.n_retired)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
         for _ in range(steps):
@@ -287,9 +291,10 @@ def run_workload(name, args, torch, cpu_budget_s):
         torch.cuda.synchronize()
         dt = time.perf_counter() - t0
         gc.enable()
-        return total_bytes, seq_steps, launch_bytes, done, dt, t_enqueue
+        return total_bytes, seq_steps, launch_bytes, done, dt, t_enqueue, lens0
 
-    total_bytes, seq_steps, _lb, steps_done, dt, t_enqueue = timed_pass(False)
+    total_bytes, seq_steps, _lb, steps_done, dt, t_enqueue, (lens_at_start, grown0, retired0) = timed_pass(False, warmup)
+    grown1, retired1 = eng.n_grown, eng.n_retired
     res = {
         "workload": w.name, "value": round(total_bytes / dt / 1e9, 2), "unit": "GB/s",
         "pct_of_peak_hbm": round(100 * total_bytes / dt / 1e9 / PEAK_HBM_GBPS, 2),
@@ -302,7 +307,7 @@ def run_workload(name, args, torch, cpu_budget_s):
                    "n_heads": w.n_heads, "n_kv_heads": w.kv_heads, "head_dim": w.head_dim,
                    "mean_context_at_start": round(float(lens_at_start.mean()), 1) if lens_at_start.size else 0.0,
                    "batch_at_end": int(eng.n_active), "refill": bool(w.refill),
-                   "grows": eng.n_grown - grown0, "retired": eng.n_retired - retired0,
+                   "grows": grown1 - grown0, "retired": retired1 - retired0,
                    "swapped_out": eng.n_swapped_out, "swapped_in": eng.n_swapped_in, "compactions": eng.n_compactions,
                    "dropped": eng.n_evicted, "on_nomem": args.on_nomem,
                    "arena_GB": round(eng.arena_mem.numel() / 1e9, 3),
@@ -316,7 +321,7 @@ def run_workload(name, args, torch, cpu_budget_s):
                    "chunk": s3.s3_kv_get_param(eng.arena, "chunk")[1]},
     }
     if not args.no_kernel_events and eng.n_active > 0:
-        ev_bytes, _ss, step_bytes, ev_steps, ev_dt, _te = timed_pass(True)
+        ev_bytes, _ss, step_bytes, ev_steps, ev_dt, _te, _l0 = timed_pass(True, 0)
         launches = s3.s3_kv_get_param(eng.arena, "profile_launches")[1]
         part_ns = s3.s3_kv_get_param(eng.arena, "profile_partial_ns")[1]
         merge_ns = s3.s3_kv_get_param(eng.arena, "profile_merge_ns")[1]
