@@ -428,6 +428,261 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
     }
 }
 
+// ---- the fused step with the row stream carried across items ------------------------------------------------
+// In attn_step_kernel a compute wave drains its loads at the end of every item (last rows, LDS hand-over,
+// barrier, look-up of the next item, query load) before the first rows of the next item leave: with one
+// workgroup per compute unit all eight waves of the unit do so at once and the unit has nothing in flight for
+// about one memory round trip per item.  Here a wave keeps two cursors over the workgroup's item sequence: a
+// LOADER that issues the row batches (U rows of K and of V into one of two register sets, alternately) and runs
+// up to one item ahead, and a REDUCER that consumes the sets in the same order.  When the loader has issued the
+// last batch of its share of an item it opens the next item at once (position, rows, query), so the first rows
+// of item k+1 are already on their way while the last rows of item k are reduced, handed over and merged.
+// Every set load is unconditional (a wave without further work re-reads its query row) so that the memory
+// counter the compiler waits on always means the same thing: the other set stays in flight.
+// All cursor state is wave-uniform and lives in scalar registers; a row address is a scalar base plus one
+// per-lane 32-bit offset.  A share without rows (fewer rows than waves) still takes one batch, whose loads
+// point at the query row and whose reduction is skipped.  The new row is stored from the registers it was
+// streamed into.  With a dynamic list the epilogue wave claims positions two items ahead: position k+1 is read
+// by the loaders between the barriers of items k-1 and k, and was published before the barrier of item k-1.
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ Item uniform_item(const Item &i) {
+    Item o;
+    o.b = __builtin_amdgcn_readfirstlane(i.b);
+    o.c = __builtin_amdgcn_readfirstlane(i.c);
+    o.nchunks = __builtin_amdgcn_readfirstlane(i.nchunks);
+    o.len = __builtin_amdgcn_readfirstlane(i.len);
+    o.hgb = __builtin_amdgcn_readfirstlane(i.hgb);
+    o.clen = __builtin_amdgcn_readfirstlane(i.clen);
+    o.off = uniform64(i.off);
+    return o;
+}
+
+template <int DT, int D, int TS, int U, bool DYN>
+__global__ void __launch_bounds__((TS + 1) * 64) attn_step_stream_kernel(const AttnArgs a) {
+    typedef HeadLanes<D> HL;
+    typedef TokenStream<DT, D, U, true, true> TS_t;
+    constexpr int LPH = HL::LPH, USED = HL::USED, GH = HL::GH;
+    constexpr int NO_ROW = -0x40000000;  // "no new row in this share": equal to no row index
+    extern __shared__ __align__(16) char dyn_lds[];  // the batch view
+    __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
+    __shared__ float comb[2][TS][10][64];
+    __shared__ long long next_pos[2];
+
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const bool epilogue = wave == TS;
+    const int n_hgb = (a.H + GH - 1) / GH;
+    // position 0 of a workgroup is its index, position 1 its first claim (visible behind the view's barrier)
+    if (DYN && threadIdx.x == TS * 64) next_pos[1] = (long long)gridDim.x + atomicAdd(a.queue, 1u);
+    const BatchView bv = build_batch_view(a, dyn_lds, wave_sums);
+    // (scalar on purpose: every branch of the cursors below must be provably uniform)
+    const int64_t total = uniform64((int64_t)bv.total * n_hgb);
+    const int64_t grid = gridDim.x;
+
+    for (int b = blockIdx.x; b < a.n; b += gridDim.x) {  // the new lengths; zero rows of empty or refused contexts
+        if (a.len_out && threadIdx.x == 0) a.len_out[b] = a.cur_len[b] + 1;
+        if (bv.len[b] == 0) {
+            const int per_row = a.H * D / 8;
+            const float z[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+            for (int e = threadIdx.x; e < per_row; e += (TS + 1) * 64) store_out8(a.out, a.out_dtype, ((int64_t)b * per_row + e) * 8, z);
+        }
+    }
+
+    if ((int64_t)blockIdx.x < total) {
+        if (!epilogue) {
+            const int g = lane / LPH, dl = lane % LPH;
+            const int dc = dl < USED ? dl : USED - 1;
+            const int64_t rstride = (int64_t)a.H * D * 2;
+
+            // ---- loader cursor (wave-uniform except lane_l, ok_l, q_l)
+            int seq_l = 0;
+            int64_t pos_l = blockIdx.x;
+            bool exhausted = false, fresh = false;
+            Item it_l;
+            int j0_l = 0, j_l = 0, j1_l = 0, jnew_l = NO_ROW;
+            int64_t stride_l = 0;
+            const char *kb_l = a.q, *vb_l = a.q, *kn_l = a.q, *vn_l = a.q;
+            unsigned lane_l = 0;
+            bool ok_l = false;
+            u32x4 q_l = (u32x4){0u, 0u, 0u, 0u};
+            auto open_item = [&]() {
+                it_l = uniform_item(decode_item(a, bv, pos_l, n_hgb));
+                split_rows(it_l, wave, TS, j0_l, j1_l);
+                j_l = j0_l;
+                fresh = true;
+                const int h = it_l.hgb * GH + g;
+                ok_l = h < a.H && dl < USED;
+                const int hc = h < a.H ? h : a.H - 1;
+                lane_l = (unsigned)((hc * D + dc * 8) * 2);
+                const int64_t in_row = (int64_t)it_l.b * a.H * D * 2;  // row b of q / k_new / v_new
+                q_l = *(const u32x4 *)(a.q + in_row + lane_l);
+                if (USED < LPH && dl >= USED) q_l = (u32x4){0u, 0u, 0u, 0u};
+                if (j0_l < j1_l) {
+                    kb_l = a.kplane + it_l.off * rstride;
+                    vb_l = a.vplane + it_l.off * rstride;
+                    kn_l = a.k_new + in_row;
+                    vn_l = a.v_new + in_row;
+                    stride_l = rstride;
+                    jnew_l = it_l.len - 1;
+                } else {  // no rows for this wave: its one batch reads the query row and is not reduced
+                    kb_l = vb_l = kn_l = vn_l = a.q + in_row;
+                    stride_l = 0;
+                    jnew_l = NO_ROW;
+                }
+            };
+            auto issue = [&](u32x4(&kk)[U], u32x4(&vv)[U]) {
+                if (!exhausted && !fresh && j_l >= j1_l) {  // this share is on its way: on to the next item
+                    const int64_t nxt = DYN ? uniform64(next_pos[(seq_l + 1) & 1]) : pos_l + grid;
+                    if (nxt < total) {
+                        pos_l = nxt;
+                        seq_l++;
+                        open_item();
+                    } else {
+                        exhausted = true;
+                        stride_l = 0;  // whatever is still issued re-reads one valid row
+                        jnew_l = NO_ROW;
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const int jj = min(j_l + u, j1_l - 1);
+                    const char *row = (jj == jnew_l) ? kn_l : kb_l + (int64_t)jj * stride_l;
+                    kk[u] = load16<true>(row + (size_t)lane_l);
+                }
+#pragma unroll
+                for (int u = 0; u < U; u++) {
+                    const int jj = min(j_l + u, j1_l - 1);
+                    const char *row = (jj == jnew_l) ? vn_l : vb_l + (int64_t)jj * stride_l;
+                    vv[u] = load16<true>(row + (size_t)lane_l);
+                }
+                j_l += U;
+                fresh = false;
+            };
+
+            // ---- reducer cursor
+            TS_t st;
+            st.scale_log2e = a.scale_log2e;
+            int seq_r = 0, j_r = 0, jnew_r = NO_ROW, parity = 0;
+            int64_t off_r = 0;
+            unsigned lane_r = 0;
+            bool ok_r = false;
+            float m = -INFINITY, l = 0.f, acc[8];
+            auto adopt = [&]() {  // the reducer enters the item the loader has open
+                j_r = j0_l;
+                st.j1 = j1_l;
+                jnew_r = j0_l < j1_l ? it_l.len - 1 : NO_ROW;
+                off_r = it_l.off;
+                st.qv = q_l;
+                lane_r = lane_l;
+                ok_r = ok_l;
+                m = -INFINITY;
+                l = 0.f;
+#pragma unroll
+                for (int i = 0; i < 8; i++) acc[i] = 0.f;
+            };
+            // One set: reduce it, close the item if that was its last batch, refill the set.  The loop below has ONE
+            // exit, at its bottom, and every trip through it issues the same loads in the same order (after the last
+            // item a half only waits for its set and refills it with the query row): the compiler derives how many
+            // loads may stay in flight at each wait from ALL paths that reach it, and a path that skipped a refill
+            // would make it wait for the other set as well, i.e. drain the pipeline this kernel exists to keep full.
+            bool done = false;
+            auto half = [&](u32x4(&kk)[U], u32x4(&vv)[U]) {
+                if (!done && j_r < st.j1) {
+                    st.reduce(j_r, kk, vv, m, l, acc);
+                    if (jnew_r >= j_r && jnew_r < j_r + U && jnew_r < st.j1 && ok_r) {  // the append
+                        char *kd = a.kplane + (off_r + jnew_r) * rstride + (size_t)lane_r;
+                        char *vd = a.vplane + (off_r + jnew_r) * rstride + (size_t)lane_r;
+#pragma unroll
+                        for (int u = 0; u < U; u++) {
+                            if (j_r + u == jnew_r) {
+                                *(u32x4 *)kd = kk[u];
+                                *(u32x4 *)vd = vv[u];
+                            }
+                        }
+                    }
+                } else {
+                    // a batch without rows: wait for its loads all the same, so that a set is never refilled
+                    // with loads into it still pending
+#pragma unroll
+                    for (int u = 0; u < U; u++) asm volatile("" ::"v"(kk[u]), "v"(vv[u]));
+                }
+                j_r += U;
+                if (!done && j_r >= st.j1) {
+                    comb[parity][wave][0][lane] = m;
+                    comb[parity][wave][1][lane] = l;
+#pragma unroll
+                    for (int i = 0; i < 8; i++) comb[parity][wave][2 + i][lane] = acc[i];
+                    __syncthreads();  // the item's only barrier; buffer `parity` is written again two items later
+                    parity ^= 1;
+                    if (seq_l == seq_r) {
+                        done = true;  // the loader opened nothing further: the list is exhausted
+                    } else {
+                        seq_r++;
+                        adopt();
+                    }
+                }
+                issue(kk, vv);
+            };
+
+            u32x4 ka[U], va[U], kb[U], vb[U];
+            open_item();
+            issue(ka, va);
+            adopt();
+            issue(kb, vb);
+            do {
+                half(ka, va);
+                half(kb, vb);
+            } while (!done);
+        } else {
+            const bool dl_ok = lane % LPH < USED;
+            int64_t pos = blockIdx.x;
+            int64_t pos1 = DYN ? uniform64(next_pos[1]) : pos + grid;
+            int parity = 0;
+            while (pos < total) {
+                const Item it = decode_item(a, bv, pos, n_hgb);
+                int64_t pos2 = pos1 + grid;
+                if (DYN && pos1 < total) {  // the position after next; next_pos[parity] was last read before the previous barrier
+                    unsigned int got = 0;
+                    if (lane == 0) got = atomicAdd(a.queue, 1u);
+                    got = __builtin_amdgcn_readfirstlane(got);
+                    pos2 = grid + got;
+                    if (lane == 0) next_pos[parity] = pos2;
+                }
+                __syncthreads();
+                const int h = it.hgb * GH + lane / LPH;
+                if (h < a.H && dl_ok) {
+                    float m, l, acc[8];
+                    combine_splits<TS>(comb[parity], 0, lane, m, l, acc);
+                    emit_chunk<D, true>(a, it, h, lane % LPH, m, l, acc);
+                }
+                if (it.nchunks > 1) {
+                    unsigned int *cnt = a.arrivals + (int64_t)it.b * n_hgb + it.hgb;
+                    if (chunk_arrived(a, cnt, it.nchunks)) {  // every chunk of this context has arrived
+                        if (h < a.H && dl_ok) merge_chunks<D, true>(a, a.H, it.b, h, lane % LPH, it.nchunks);
+                    }
+                }
+                pos = pos1;
+                pos1 = pos2;
+                parity ^= 1;
+            }
+        }
+    }
+    if (DYN && threadIdx.x == 0) {
+        // the last workgroup to leave puts both counters back to zero for the next launch (a workgroup has made
+        // all its claims before the barrier of its last item)
+        const unsigned int gone = atomicAdd(a.queue + 1, 1u);
+        if (gone == gridDim.x - 1) {
+            atomicExch(a.queue, 0u);
+            atomicExch(a.queue + 1, 0u);
+        }
+    }
+}
+
 // One wave per (sequence, head group): merge the chunk partials of contexts longer than one
 // chunk; write zeros for empty contexts; leave single-chunk contexts (already final) alone.
 template <int D>
@@ -451,28 +706,37 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
 }
 
 // Kernel shapes: (index, TS token splits, HS head groups per workgroup, U rows per load batch, NT, PF, R rows of
-// the LDS ring (0: rows in flight sit in registers), DYN dynamic work list); R and DYN concern the fused step
-// kernel only (the attention-only kernel of such a shape is the register / fixed-stride one).
-#define S3_VARIANTS(X)                     \
-    X(0, 4, 1, 4, true, false, 0, false)   \
-    X(1, 8, 1, 4, true, false, 0, false)   \
-    X(2, 4, 2, 4, true, false, 0, false)   \
-    X(3, 1, 4, 4, true, false, 0, false)   \
-    X(4, 8, 1, 2, true, true, 0, false)    \
-    X(5, 2, 4, 4, true, false, 0, false)   \
-    X(6, 1, 8, 4, true, false, 0, false)   \
-    X(7, 7, 1, 4, true, true, 0, false)    \
-    X(8, 4, 1, 4, false, false, 0, false)  \
-    X(9, 15, 1, 2, true, true, 0, false)   \
-    X(10, 8, 1, 2, true, true, 0, true)    \
-    X(11, 8, 1, 2, true, true, 6, false)   \
-    X(12, 8, 1, 2, true, true, 6, true)    \
-    X(13, 8, 1, 3, true, true, 0, true)
+// the LDS ring (0: rows in flight sit in registers), DYN dynamic work list, XS row stream carried across items);
+// R, DYN and XS concern the fused step kernel only (the attention-only kernel of such a shape is the register /
+// fixed-stride one).
+#define S3_VARIANTS(X)                            \
+    X(0, 4, 1, 4, true, false, 0, false, false)   \
+    X(1, 8, 1, 4, true, false, 0, false, false)   \
+    X(2, 4, 2, 4, true, false, 0, false, false)   \
+    X(3, 1, 4, 4, true, false, 0, false, false)   \
+    X(4, 8, 1, 2, true, true, 0, false, false)    \
+    X(5, 2, 4, 4, true, false, 0, false, false)   \
+    X(6, 1, 8, 4, true, false, 0, false, false)   \
+    X(7, 7, 1, 4, true, true, 0, false, false)    \
+    X(8, 4, 1, 4, false, false, 0, false, false)  \
+    X(9, 15, 1, 2, true, true, 0, false, false)   \
+    X(10, 8, 1, 2, true, true, 0, true, false)    \
+    X(11, 8, 1, 2, true, true, 6, false, false)   \
+    X(12, 8, 1, 2, true, true, 6, true, false)    \
+    X(13, 8, 1, 3, true, true, 0, true, false)    \
+    X(14, 8, 1, 3, true, true, 0, true, true)     \
+    X(15, 8, 1, 2, true, true, 0, true, true)     \
+    X(16, 8, 1, 2, true, true, 0, false, true)    \
+    X(17, 8, 1, 3, true, true, 0, false, true)
 // Defaults (measured on MI355X): shape 4 with a fixed stride while the work list is about as long as the grid
 // (batches of up to 128 sequences); beyond, the dynamic work list (+4 % to +7 % on batches of 512 and 700
 // sequences; -5 % on a batch of 128 long contexts) with three rows per register set (shape 13: +1.5 % / +0.5 % over
 // two rows there; on the small batches three or four rows per set are 1-5 % behind two).  The LDS-ring shapes stay
-// selectable for comparison: they measured 2-3 % behind the register path.  Shapes that were tried with the
+// selectable for comparison: they measured 2-3 % behind the register path.  So do the shapes that carry the row
+// stream across items (14-17): with one workgroup per compute unit they measured level with shape 13 on the
+// batch of 512 (0.770-0.775 of peak against 0.7725; two resident workgroups, which their lower register count
+// allows, 0.750-0.757) and 1-3 % behind shape 4 on the small batches - the pause of a compute unit's loads at an
+// item's end is not what bounds the kernel.  Shapes that were tried with the
 // dynamic list and dropped: two or four head groups per workgroup with four or two waves each (0.756 / 0.745 of
 // peak on the batch of 512 against 0.762), one workgroup per whole row (eight head groups, one wave each: 0.655).
 #define S3_DEFAULT_VARIANT 4
@@ -481,8 +745,11 @@ __global__ void __launch_bounds__(256) attn_merge_kernel(const AttnArgs a) {
 template <int DT, int D>
 static attn_fn pick_variant(int v, bool fused) {
     switch (v) {
-#define X(i, ts, hs, u, nt, pf, r, dyn) \
-    case i: return fused ? (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt, pf, r, dyn> : (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt, pf>;
+#define X(i, ts, hs, u, nt, pf, r, dyn, xs)                                                                       \
+    case i:                                                                                                       \
+        if (!fused) return (attn_fn)attn_partial_kernel<DT, D, ts, hs, u, nt, pf>;                                  \
+        if constexpr (xs) return (attn_fn)attn_step_stream_kernel<DT, D, ts * hs, u, dyn>; /* XS shapes: hs = 1 */ \
+        else return (attn_fn)attn_step_kernel<DT, D, ts, hs, u, nt, pf, r, dyn>;
         S3_VARIANTS(X)
 #undef X
         default: return nullptr;

@@ -6,12 +6,6 @@
 
 #ifndef S3_INST_D
 #error "compile with -DS3_INST_D=<head dimension>"
-// Bytes of LDS rings a workgroup of the fused kernel of shape `variant` needs behind the batch view.
-int s3i_variant_ring_bytes(int variant) {
-    if (variant < 0 || variant >= s3i_num_variants()) return 0;
-    return kVariants[variant].ring * 2048 * kVariants[variant].ts * kVariants[variant].hs;
-}
-int s3i_variant_dynamic(int variant) { return variant >= 0 && variant < s3i_num_variants() ? kVariants[variant].dyn : 0; }
 #endif
 
 #define S3_CAT2(a, b) a##b
@@ -29,10 +23,10 @@ attn_fn S3_CAT(s3i_pick_merge_d, S3_INST_D)() { return (attn_fn)attn_merge_kerne
 
 #if S3_INST_D == 64
 struct VariantShape {
-    int ts, hs, u, nt, pf, ring, dyn;
+    int ts, hs, u, nt, pf, ring, dyn, xs;
 };
 static const VariantShape kVariants[] = {
-#define X(i, ts, hs, u, nt, pf, r, dyn) {ts, hs, u, nt, pf, r, dyn},
+#define X(i, ts, hs, u, nt, pf, r, dyn, xs) {ts, hs, u, nt, pf, r, dyn, xs},
     S3_VARIANTS(X)
 #undef X
 };
@@ -50,4 +44,6 @@ int s3i_variant_ring_bytes(int variant) {
     return kVariants[variant].ring * 2048 * kVariants[variant].ts * kVariants[variant].hs;
 }
 int s3i_variant_dynamic(int variant) { return variant >= 0 && variant < s3i_num_variants() ? kVariants[variant].dyn : 0; }
+// Whether the fused kernel of shape `variant` carries its row stream across items.
+int s3i_variant_stream(int variant) { return variant >= 0 && variant < s3i_num_variants() ? kVariants[variant].xs : 0; }
 #endif

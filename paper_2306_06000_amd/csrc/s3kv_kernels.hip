@@ -268,6 +268,7 @@ int s3i_default_variant_large();
 int s3i_variant_threads(int variant, bool fused);
 int s3i_variant_ring_bytes(int variant);
 int s3i_variant_dynamic(int variant);
+int s3i_variant_stream(int variant);
 
 static attn_fn pick_kernel(int dt, int d, int variant, bool fused) {
     switch (d) {
@@ -603,7 +604,8 @@ static size_t batch_view_lds(int n, int ncls) {
 
 // Grid of a kernel that walks the work list with a stride: the workgroups that are resident at once
 // (every workgroup pays the batch-view prologue once), times `rounds`; or what the caller set.
-static int stride_grid(const s3_arena *a, const void *fn, int threads, size_t dyn_lds, int rounds, int *blocks) {
+static int stride_grid(const s3_arena *a, const void *fn, int threads, size_t dyn_lds, int rounds, int *blocks,
+                       int max_per_cu = 0) {
     if (a->grid_blocks > 0) {
         *blocks = a->grid_blocks;
         return S3_OK;
@@ -611,6 +613,7 @@ static int stride_grid(const s3_arena *a, const void *fn, int threads, size_t dy
     int per_cu = 0;
     const int rc = resident_per_cu(fn, threads, dyn_lds, &per_cu);
     if (rc != S3_OK) return rc;
+    if (max_per_cu > 0 && per_cu > max_per_cu) per_cu = max_per_cu;
     *blocks = (a->num_cus > 0 ? a->num_cus : 256) * per_cu * rounds;
     return S3_OK;
 }
@@ -749,7 +752,9 @@ static int launch_attention(s3_arena *a, const AttnCall &c) {
     // fixed stride: large batches balance better over two rounds of resident workgroups; a dynamic work list
     // needs exactly the resident ones
     const int rounds = (fused && s3i_variant_dynamic(variant)) ? 1 : c.n > 128 ? 2 : 1;
-    rc = stride_grid(a, (const void *)fn, threads, dyn_lds, rounds, &blocks);
+    // the shapes that carry the row stream across items keep a compute unit's memory pipeline full from one
+    // workgroup; a second resident one (their register count admits it) measured 2 % slower
+    rc = stride_grid(a, (const void *)fn, threads, dyn_lds, rounds, &blocks, fused && s3i_variant_stream(variant) ? 1 : 0);
     if (rc != S3_OK) return rc;
     return launch_attn_kernels(a, fn, blocks, threads, dyn_lds, c.stream, args, fused ? 0 : H, !c.static_scratch);
 }

@@ -363,14 +363,16 @@ def test_worked_example_model_shape_runs_through_the_library():
 
 
 # ---------------------------------------------------------------- the merge inside one launch, many times
-@pytest.mark.parametrize("sync,launches,variant", [(0, 200, -1), (1, 40, -1), (0, 120, 10), (1, 20, 10), (0, 40, 12)])
+@pytest.mark.parametrize("sync,launches,variant", [(0, 200, -1), (1, 40, -1), (0, 120, 10), (1, 20, 10), (0, 40, 12),
+                                                   (0, 120, 14), (1, 20, 14), (0, 40, 16)])
 def test_soak_of_the_in_kernel_merge_equals_the_two_kernel_path(sync, launches, variant):
     """Many contexts of many chunks, a grid that covers every compute unit (all XCDs), the same step
     launched again and again: the output of the fused step (chunks meet through arrival counters and
     write-through partials inside the launch) must equal, bit for bit, the two-kernel path (partials with
     plain stores, merged by a second launch) every time.  Stops at the first mismatch.  Also with the dynamic
     work list (variant 10: positions claimed from a device-wide counter that every launch must leave at zero)
-    and with rows staged through the LDS ring (variant 12), on grids smaller and larger than the list."""
+    and with rows staged through the LDS ring (variant 12), on grids smaller and larger than the list; and with
+    the row stream carried from one item into the next (variants 14, 16: positions claimed two items ahead)."""
     H, D, dtype = 16, 256, s3.S3_F16
     rng = np.random.default_rng(800)
     lens = [int(x) for x in rng.integers(200, 1000, size=96)]
@@ -401,6 +403,45 @@ def test_soak_of_the_in_kernel_merge_equals_the_two_kernel_path(sync, launches, 
             assert s3.s3_decode_step(rig.a, 0, n, rig.off_d, pos_d, q, k_new, v_new, out, s3.S3_F32, 0.0, len_out,
                                      rig.stream) == 0
             assert torch.equal(out, ref), f"merge_sync {sync} grid {grid}: launch {i} differs from the two-kernel path"
+    rig.close()
+
+
+@pytest.mark.parametrize("variant", [14, 15, 16, 17])
+@pytest.mark.parametrize("H,D,dtype", [(16, 256, s3.S3_F16), (12, 128, s3.S3_BF16), (8, 96, s3.S3_F16), (3, 64, s3.S3_BF16)])
+def test_row_stream_carried_across_items_equals_the_two_kernel_path(variant, H, D, dtype):
+    """Kernel shapes whose waves start loading the rows of their next item while the current one is still being
+    reduced.  Grids far smaller than the work list, so that every workgroup walks many items; contexts from one row
+    up, so that the list holds items whose trailing waves have no rows at all, shares of a single load batch and
+    shares of many; chunk sizes from the smallest.  The fused step must leave the same rows and the same output
+    bits as append + attention + merge, launch after launch (the claim counters must come back to zero)."""
+    rng = np.random.default_rng(900 + variant)
+    lens = [1, 2, 3, 5, 7, 8, 9, 15, 16, 17, 31, 32, 33, 63, 64, 65, 100, 129, 255, 256, 257, 300, 511, 640, 777, 1000,
+            4, 1, 66, 12]
+    n = len(lens)
+    rig = EdgeRig(("stream", H, H, D, dtype, dtype, 0), lens)
+    rig.put([rng.standard_normal((L, H, D), dtype=np.float32) for L in lens],
+            [rng.standard_normal((L, H, D), dtype=np.float32) for L in lens])
+    assert s3.s3_kv_set_param(rig.a, "variant", variant) == 0
+    q, k_new, v_new = (device_bits(wl.normal_bits(rng, (n, H, D), dtype), TDT[dtype], DEV) for _ in range(3))
+    pos_d = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    len_out = torch.zeros(n, dtype=torch.int32, device=DEV)
+    assert s3.s3_kv_append(rig.a, 0, n, rig.off_d, pos_d, k_new, v_new, rig.stream) == 0
+    ref = torch.empty((n, H, D), dtype=torch.float32, device=DEV)
+    out = torch.empty_like(ref)
+    for chunk in (32, 64, 256):
+        assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+        assert s3.s3_kv_set_param(rig.a, "grid_blocks", 0) == 0
+        assert s3.s3_decode_attention(rig.a, 0, n, q, rig.off_d, pos_d + 1, ref, s3.S3_F32, 0.0, rig.stream) == 0
+        torch.cuda.synchronize()
+        for grid in (1, 2, 5, 64, 0):
+            assert s3.s3_kv_set_param(rig.a, "grid_blocks", grid) == 0
+            for i in range(3):
+                out.fill_(float("nan"))
+                len_out.zero_()
+                assert s3.s3_decode_step(rig.a, 0, n, rig.off_d, pos_d, q, k_new, v_new, out, s3.S3_F32, 0.0, len_out,
+                                         rig.stream) == 0
+                assert torch.equal(out, ref), f"chunk {chunk} grid {grid} launch {i}"
+                assert len_out.cpu().tolist() == [L + 1 for L in lens]
     rig.close()
 
 
