@@ -444,24 +444,6 @@ __global__ void __launch_bounds__((TS *HS + 1) * 64) attn_step_kernel(const Attn
 // point at the query row and whose reduction is skipped.  The new row is stored from the registers it was
 // streamed into.  With a dynamic list the epilogue wave claims positions two items ahead: position k+1 is read
 // by the loaders between the barriers of items k-1 and k, and was published before the barrier of item k-1.
-__device__ __forceinline__ int64_t uniform64(int64_t v) {
-    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
-    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uint64_t)v >> 32));
-    return (int64_t)(((uint64_t)hi << 32) | lo);
-}
-
-__device__ __forceinline__ Item uniform_item(const Item &i) {
-    Item o;
-    o.b = __builtin_amdgcn_readfirstlane(i.b);
-    o.c = __builtin_amdgcn_readfirstlane(i.c);
-    o.nchunks = __builtin_amdgcn_readfirstlane(i.nchunks);
-    o.len = __builtin_amdgcn_readfirstlane(i.len);
-    o.hgb = __builtin_amdgcn_readfirstlane(i.hgb);
-    o.clen = __builtin_amdgcn_readfirstlane(i.clen);
-    o.off = uniform64(i.off);
-    return o;
-}
-
 template <int DT, int D, int TS, int U, bool DYN>
 __global__ void __launch_bounds__((TS + 1) * 64) attn_step_stream_kernel(const AttnArgs a) {
     typedef HeadLanes<D> HL;

@@ -514,6 +514,26 @@ __device__ __forceinline__ Item decode_item(const AttnArgs &a, const BatchView &
     return it;
 }
 
+// A wave-uniform value as the compiler should see it: in scalar registers, so that addresses and branches
+// derived from it are scalar too.
+__device__ __forceinline__ int64_t uniform64(int64_t v) {
+    const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v);
+    const unsigned hi = __builtin_amdgcn_readfirstlane((unsigned)((uint64_t)v >> 32));
+    return (int64_t)(((uint64_t)hi << 32) | lo);
+}
+
+__device__ __forceinline__ Item uniform_item(const Item &i) {
+    Item o;
+    o.b = __builtin_amdgcn_readfirstlane(i.b);
+    o.c = __builtin_amdgcn_readfirstlane(i.c);
+    o.nchunks = __builtin_amdgcn_readfirstlane(i.nchunks);
+    o.len = __builtin_amdgcn_readfirstlane(i.len);
+    o.hgb = __builtin_amdgcn_readfirstlane(i.hgb);
+    o.clen = __builtin_amdgcn_readfirstlane(i.clen);
+    o.off = uniform64(i.off);
+    return o;
+}
+
 typedef void (*attn_fn)(const AttnArgs);
 
 // Kernel for shared key/value heads (defined in s3kv_gqa.hip): gq query heads per K/V head and

@@ -25,7 +25,10 @@
 //     operand V^T (row of the product = output element d, contraction = cached rows) needs four
 //     cached rows at ONE d per lane, while memory holds eight d of one row per 16-byte load: the V
 //     tile goes through a per-wave LDS buffer (row-major, row stride padded by 8 bytes so that the
-//     four lane groups hit different banks) and is read back as 16-bit gathers.
+//     four lane groups hit different banks) and is read back as 16-bit gathers.  With 8-bit rows a
+//     lane reads one 32-bit word (four consecutive d) from each of its four rows and transposes the
+//     4 x 4 codes in registers (eight v_perm_b32), which feeds four products at once; the products'
+//     operand rows are numbered accordingly (d = 64q + 4n + j) and the results leave in that order.
 //   * p enters the second product as two 16-bit operands of the storage type, a high part (p rounded)
 //     and a low part (the remainder, rounded), and the product is issued for both, which keeps the
 //     weights' error near 2^-16 (bfloat16) / 2^-22 (fp16) instead of 2^-9 / 2^-12: with one part only,
@@ -92,13 +95,31 @@ __device__ __forceinline__ void store_out4(void *out, int out_dtype, int64_t e, 
     }
 }
 
-typedef float f32x2w __attribute__((ext_vector_type(2)));
-
-// Two e4m3 codes (bytes 2*half, 2*half+1 of w) -> one 32-bit word of two DT elements, exact.
+// Two e4m3 codes (bytes 2*half, 2*half+1 of w) -> one 32-bit word of two DT elements, exact: every e4m3 value
+// is an fp16 and a bfloat16 number, and gfx950 converts a pair of codes to either type in one instruction
+// (v_cvt_scalef32_pk_{f16,bf16}_fp8 with scale 1).
 template <int DT>
 __device__ __forceinline__ unsigned widen2_e4m3(const unsigned w, const bool upper) {
-    const f32x2w f = upper ? __builtin_amdgcn_cvt_pk_f32_fp8((int)w, true) : __builtin_amdgcn_cvt_pk_f32_fp8((int)w, false);
-    return DT == S3_F16 ? pack_f16(f[0], f[1]) : pack_bf16(f[0], f[1]);
+    if (DT == S3_F16) {
+        const f16x2 h = upper ? __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_f16_fp8(w, 1.0f, false);
+        return __builtin_bit_cast(unsigned, h);
+    }
+    const bf16x2 h = upper ? __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, true) : __builtin_amdgcn_cvt_scalef32_pk_bf16_fp8(w, 1.0f, false);
+    return __builtin_bit_cast(unsigned, h);
+}
+
+// Bytes j of four words -> one word, j = 0..3 (a 4 x 4 byte transpose in eight v_perm_b32; selector bytes 0-3
+// pick from the second operand, 4-7 from the first).
+__device__ __forceinline__ void transpose4x4_bytes(const unsigned w0, const unsigned w1, const unsigned w2, const unsigned w3,
+                                                   unsigned (&t)[4]) {
+    const unsigned a_lo = __builtin_amdgcn_perm(w1, w0, 0x05010400u);  // w0.0 w1.0 w0.1 w1.1
+    const unsigned a_hi = __builtin_amdgcn_perm(w1, w0, 0x07030602u);  // w0.2 w1.2 w0.3 w1.3
+    const unsigned b_lo = __builtin_amdgcn_perm(w3, w2, 0x05010400u);  // w2.0 w3.0 w2.1 w3.1
+    const unsigned b_hi = __builtin_amdgcn_perm(w3, w2, 0x07030602u);
+    t[0] = __builtin_amdgcn_perm(b_lo, a_lo, 0x05040100u);  // w0.0 w1.0 w2.0 w3.0
+    t[1] = __builtin_amdgcn_perm(b_lo, a_lo, 0x07060302u);
+    t[2] = __builtin_amdgcn_perm(b_hi, a_hi, 0x05040100u);
+    t[3] = __builtin_amdgcn_perm(b_hi, a_hi, 0x07060302u);
 }
 
 // A chunk whose partial this wave has written and whose arrival is still to be counted / answered.
@@ -128,7 +149,10 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
     constexpr int DB = D / 16;            // 16-element blocks of an output row
     constexpr int PPR = D * EB / 16;      // 16-byte pieces per cached row of one head
     constexpr int VL = 16 * PPR / 64;     // 16-byte loads per lane for a 16-row V tile
-    constexpr int VSTRIDE = D * EB + 8;   // LDS row stride of the V tile, bytes
+    // LDS row stride of the V tile, bytes.  16-bit rows: 8 bytes of padding, so that the four lane groups' 16-bit
+    // gathers hit different banks.  8-bit rows: 16 bytes, so that rows stay 16-byte aligned and the four lane
+    // groups' 32-bit reads (rows 4g .. 4g+3, sixteen consecutive words each) cover the banks evenly.
+    constexpr int VSTRIDE = KV8 ? D + 16 : D * 2 + 8;
     constexpr float RESCALE_LOG2 = 8.f;   // see the softmax step
     extern __shared__ __align__(16) char dyn_lds[];  // the batch view
     __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
@@ -320,25 +344,39 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
                 const int idx = i * 64 + lane;
                 char *dst = vt + (idx / PPR) * VSTRIDE + (idx % PPR) * 16;
                 const u32x4 w = vv[i];
-                *(u32x2 *)dst = (u32x2){w[0], w[1]};
-                *(u32x2 *)(dst + 8) = (u32x2){w[2], w[3]};
+                if (KV8) {
+                    *(u32x4 *)dst = w;
+                } else {
+                    *(u32x2 *)dst = (u32x2){w[0], w[1]};
+                    *(u32x2 *)(dst + 8) = (u32x2){w[2], w[3]};
+                }
             }
             __builtin_amdgcn_wave_barrier();
+            if (KV8) {
+                // Four products at a time: this lane's operand row m = n of products 4q .. 4q+3 is output element
+                // d = 64q + 4n + j (j = 0..3), four consecutive codes = ONE 32-bit word per cached row; the words of
+                // rows 4g .. 4g+3 are transposed in registers into the four operands (codes of four rows at one d).
 #pragma unroll
-            for (int db = 0; db < DB; db++) {
-                u32x2 vop;
-                if (KV8) {
-                    const unsigned char *src = (const unsigned char *)(vt + (4 * g) * VSTRIDE) + db * 16 + n;
-                    const unsigned b0 = src[0], b1 = src[VSTRIDE], b2 = src[2 * VSTRIDE], b3 = src[3 * VSTRIDE];
-                    const unsigned codes = b0 | (b1 << 8) | (b2 << 16) | (b3 << 24);
-                    vop = (u32x2){widen2_e4m3<DT>(codes, false), widen2_e4m3<DT>(codes, true)};
-                } else {
+                for (int q4 = 0; q4 < DB / 4; q4++) {
+                    const unsigned *src = (const unsigned *)(vt + (4 * g) * VSTRIDE + q4 * 64) + n;
+                    unsigned t[4];
+                    transpose4x4_bytes(src[0], src[VSTRIDE / 4], src[2 * (VSTRIDE / 4)], src[3 * (VSTRIDE / 4)], t);
+#pragma unroll
+                    for (int j = 0; j < 4; j++) {
+                        const u32x2 vop = (u32x2){widen2_e4m3<DT>(t[j], false), widen2_e4m3<DT>(t[j], true)};
+                        o[4 * q4 + j] = mfma_values<DT>(vop, pop, o[4 * q4 + j]);
+                        o[4 * q4 + j] = mfma_values<DT>(vop, pop_lo, o[4 * q4 + j]);
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int db = 0; db < DB; db++) {
                     const unsigned short *src = (const unsigned short *)(vt + (4 * g) * VSTRIDE) + db * 16 + n;
                     const unsigned v0 = src[0], v1 = src[VSTRIDE / 2], v2 = src[2 * (VSTRIDE / 2)], v3 = src[3 * (VSTRIDE / 2)];
-                    vop = (u32x2){v0 | (v1 << 16), v2 | (v3 << 16)};
+                    const u32x2 vop = (u32x2){v0 | (v1 << 16), v2 | (v3 << 16)};
+                    o[db] = mfma_values<DT>(vop, pop, o[db]);
+                    o[db] = mfma_values<DT>(vop, pop_lo, o[db]);
                 }
-                o[db] = mfma_values<DT>(vop, pop, o[db]);
-                o[db] = mfma_values<DT>(vop, pop_lo, o[db]);
             }
             __builtin_amdgcn_wave_barrier();
         };
@@ -360,21 +398,39 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
         lsum += __shfl_xor(lsum, 32);
         if (ink) settle(false);
         if (head_ok) {
+            // Four consecutive output elements per store.  16-bit rows: accumulator block t holds elements
+            // 16t + 4g + i (i = 0..3).  8-bit rows (see the V product): register i of blocks 4q .. 4q+3 holds
+            // elements 64q + 16g + 4i + j.
+            auto piece = [&](int t, int &d0) -> f32x4 {
+                if (!KV8) {
+                    d0 = t * 16 + 4 * g;
+                    return o[t];
+                }
+                const int q4 = t / 4, i = t % 4;
+                d0 = q4 * 64 + 16 * g + 4 * i;
+                return (f32x4){o[4 * q4][i], o[4 * q4 + 1][i], o[4 * q4 + 2][i], o[4 * q4 + 3][i]};
+            };
             if (it.nchunks == 1) {
                 const float inv = 1.f / lsum;
 #pragma unroll
-                for (int db = 0; db < DB; db++)
-                    store_out4(a.out, a.out_dtype, ((int64_t)it.b * a.Hq + hq) * D + db * 16 + 4 * g, o[db] * inv);
+                for (int t = 0; t < DB; t++) {
+                    int d0;
+                    const f32x4 v = piece(t, d0);
+                    store_out4(a.out, a.out_dtype, ((int64_t)it.b * a.Hq + hq) * D + d0, v * inv);
+                }
             } else {
                 const int64_t pi = ((int64_t)it.b * a.max_chunks + it.c) * a.Hq + hq;
                 if (ink) {
                     if (g == 0) put_partial2<true>((float *)a.part_ml + 2 * pi, (f32x2){m, lsum});
-#pragma unroll
-                    for (int db = 0; db < DB; db++) put_partial4<true>(a.part_acc + pi * D + db * 16 + 4 * g, o[db]);
                 } else {
                     if (g == 0) a.part_ml[pi] = make_float2(m, lsum);
+                }
 #pragma unroll
-                    for (int db = 0; db < DB; db++) *(f32x4 *)(a.part_acc + pi * D + db * 16 + 4 * g) = o[db];
+                for (int t = 0; t < DB; t++) {
+                    int d0;
+                    const f32x4 v = piece(t, d0);
+                    if (ink) put_partial4<true>(a.part_acc + pi * D + d0, v);
+                    else *(f32x4 *)(a.part_acc + pi * D + d0) = v;
                 }
             }
         }
