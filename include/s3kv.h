@@ -322,8 +322,9 @@ int s3_sched_admit(s3_sched *s, int32_t max_out, int64_t *request_id, int32_t *s
 int s3_sched_pool_size(const s3_sched *s);
 
 /* Measurement aid: the rate a plain streaming kernel reaches over the first `bytes` of the arena
- * (mode 0: 128-bit reads only; mode 1: copy of the first `bytes` onto the next `bytes`, counted as
- * 2*bytes moved), averaged over `reps` back-to-back launches on the default stream, in GB/s.
+ * (mode 0: 128-bit reads only, in the attention kernels' pattern - 1 KiB pieces of 8 KiB rows -, `bytes`
+ * rounded down to a multiple of 1 MiB and at least that; mode 1: copy of the first `bytes` onto the next
+ * `bytes`, counted as 2*bytes moved), averaged over `reps` back-to-back launches on the default stream, in GB/s.
  * DESTROYS arena contents in mode 1.  Synchronises the device.  Says what fraction of the nominal
  * HBM peak is attainable at all, next to the attention kernel's own figure. */
 int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps, double *gbps /*HOST*/);

@@ -187,24 +187,32 @@ int s3i_launch_copy_planes(const char *src, char *dst, size_t nbytes, size_t src
 // ------------------------------------------------------------------------------------------
 static int ensure_scratch(s3_arena *a, size_t need);
 
-__global__ void __launch_bounds__(256) read_probe_kernel(const char *src, size_t n16, unsigned int *sink) {
-    const u32x4 *s = (const u32x4 *)src;
-    const size_t stride = (size_t)gridDim.x * blockDim.x;
+// The buffer is read as the attention kernels read a cache: rows of 8 KiB, a wave streams one 1 KiB piece of 128
+// consecutive rows, eight non-temporal 128-bit loads per lane in flight; neighbouring waves take neighbouring pieces
+// of the same rows.  (A grid-stride loop over the whole buffer, four loads in flight, read 20 % slower here.)
+#define S3_PROBE_ROW 8192
+#define S3_PROBE_ROWS 128
+__global__ void __launch_bounds__(256) read_probe_kernel(const char *src, size_t n_items, unsigned int *sink) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     u32x4 acc = {0u, 0u, 0u, 0u};
-    size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    for (; i + 3 * stride < n16; i += 4 * stride) {
-        const u32x4 a = __builtin_nontemporal_load(s + i), b = __builtin_nontemporal_load(s + i + stride),
-                    c = __builtin_nontemporal_load(s + i + 2 * stride), d = __builtin_nontemporal_load(s + i + 3 * stride);
-        acc ^= a ^ b ^ c ^ d;
+    for (size_t item = (size_t)blockIdx.x * 4 + wave; item < n_items; item += (size_t)gridDim.x * 4) {
+        const char *base = src + (item / 8) * ((size_t)S3_PROBE_ROWS * S3_PROBE_ROW) + (item % 8) * 1024 + lane * 16;
+        for (int r = 0; r < S3_PROBE_ROWS; r += 8) {
+            u32x4 v[8];
+#pragma unroll
+            for (int i = 0; i < 8; i++) v[i] = __builtin_nontemporal_load((const u32x4 *)(base + (size_t)(r + i) * S3_PROBE_ROW));
+#pragma unroll
+            for (int i = 0; i < 8; i++) acc ^= v[i];
+        }
     }
-    for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(s + i);
     const unsigned int x = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
     if (x == 0x9E3779B9u) *sink = x;  // practically never: keeps the loads alive
 }
 
 extern "C" int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps, double *gbps) {
     if (!a || !a->base || !gbps || reps <= 0 || (mode != 0 && mode != 1)) return S3_ERR_INVALID;
-    bytes &= ~(size_t)15;
+    // mode 0 reads whole blocks of 128 rows of 8 KiB (1 MiB); a smaller request reads nothing and is refused
+    bytes = mode == 0 ? bytes / ((size_t)S3_PROBE_ROWS * S3_PROBE_ROW) * ((size_t)S3_PROBE_ROWS * S3_PROBE_ROW) : bytes & ~(size_t)15;
     if (bytes == 0 || (mode == 0 ? bytes : 2 * bytes) > a->dev_bytes) return S3_ERR_INVALID;
     const int rc = ensure_scratch(a, 256);
     if (rc != S3_OK) return rc;
@@ -216,8 +224,8 @@ extern "C" int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, in
     for (int r = -2; r < reps; r++) {  // two untimed warm-up passes
         if (r == 0) HIP_TRY(hipEventRecord(e0, nullptr));
         if (mode == 0) {
-            hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)(cus * 8)), dim3(256), 0, nullptr, a->base, n16,
-                               (unsigned int *)((char *)a->scratch + 128));
+            hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)(cus * 2)), dim3(256), 0, nullptr, a->base,
+                               bytes / ((size_t)S3_PROBE_ROWS * 1024), (unsigned int *)((char *)a->scratch + 128));
         } else {
             hipLaunchKernelGGL(copy_planes_kernel, dim3((unsigned)(cus * 8), 1), dim3(256), 0, nullptr, a->base,
                                a->base + bytes, n16, (size_t)0, (size_t)0);
