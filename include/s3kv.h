@@ -343,6 +343,9 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *   "gqa_merge"    shared key/value heads, matrix-core kernel: 1 = multi-chunk contexts are finished inside the
  *                  attention launch (arrival counters, write-through partials), 0 (default) = by a merge launch;
  *                  same results; the launch-saving form measured slower (its partials bypass the caches)
+ *   "gqa_stream"   shared key/value heads, matrix-core kernel: how K rows are read: 1 = with the streaming hint
+ *                  (whole rows per load, operand layout through LDS), 0 = plain loads straight into operand layout,
+ *                  -1 (default) = 1 if the launch's K rows exceed the 256 MB memory-side cache, else 0; same results
  *   "profile"      k > 0: every k-th attention launch (counted from this call) carries HIP events that
  *                  take the kernel's own start and end times (hipExtLaunchKernel); 0: off; both reset the sums
  * get names: the above plus "default_variant", "kernel_kind" (0 multi-head kernels, 1 shared-K/V vector-ALU kernel,

@@ -38,6 +38,7 @@ struct AttnArgs {
     int32_t merge_sync;      // how chunks that meet inside one launch are ordered: see chunk_arrived()
     int32_t merge_in_kernel; // matrix-core kernel for shared heads: chunks meet inside the launch (no merge launch follows)
     unsigned int *queue;     // [2] kernels with a dynamic work list: positions claimed, workgroups gone; zero between launches
+    int32_t stream_k;        // matrix-core kernel for shared heads: K rows with the streaming hint (1), plain (0), by launch size (< 0)
 };
 
 __device__ __forceinline__ int checked_len(const AttnArgs &a, int b) {

@@ -12,11 +12,14 @@
 // One wave = one work item = (sequence, chunk of its context, K/V head, block of 16 query heads);
 // the four waves of a workgroup are independent (no barrier after the batch-view prologue).  Per
 // tile of 16 cached rows:
-//   * K: lane (r = lane % 16, g = lane / 16) loads 16 bytes (8 elements) of row r at element offset
-//     32*ks + 8*g, ks = 0 .. D/32-1: that is the A operand of v_mfma_f32_16x16x32 directly (row r,
-//     contraction slots of lane group g); Q^T is the B operand, loaded once per item with the same
-//     slot assignment (head = lane % 16), so whichever way the instruction numbers its contraction
-//     slots, both operands agree.  The accumulator holds S^T[row 4*g + i][head lane % 16], i < 4.
+//   * K: lane (r = lane % 16, g = lane / 16) holds 16 bytes (8 elements) of row r at element offset
+//     32*ks + 8*g, ks = 0 .. D/32-1 - loaded so directly with plain loads, or, in launches whose K rows
+//     exceed the memory-side cache, loaded in whole rows with the streaming hint and brought into that
+//     layout through a per-wave LDS buffer - : the A operand of
+//     v_mfma_f32_16x16x32 (row r, contraction slots of lane group g); Q^T is the B operand, loaded
+//     once per item with the same slot assignment (head = lane % 16), so whichever way the
+//     instruction numbers its contraction slots, both operands agree.  The accumulator holds
+//     S^T[row 4*g + i][head lane % 16], i < 4.
 //   * softmax: scale into log2 units, mask rows past the end, tile maximum per head (over the four
 //     registers, then across the four lane groups); the exponent reference m follows the maximum
 //     lazily (see the loop), p = exp2(s - m), running sum.
@@ -47,6 +50,8 @@
 // 32 query / 8 cached heads x 128, 256 sequences: kernel 74 -> 101 us, whole step 72 -> 89 us;
 // multi-query 16/1 x 256: 29 -> 65 us.  In a decode step the new row is read from k_new / v_new and
 // appended by the wave that owns it.
+#include <type_traits>
+
 #include "s3kv_device.h"
 
 typedef _Float16 f16x4 __attribute__((ext_vector_type(4)));
@@ -156,7 +161,10 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
     constexpr float RESCALE_LOG2 = 8.f;   // see the softmax step
     extern __shared__ __align__(16) char dyn_lds[];  // the batch view
     __shared__ int wave_sums[S3_MAX_CLASSES * S3_MAX_WAVES];
+    // LDS row stride of the K tile: with 16 bytes of padding the 128-bit reads of sixteen rows cover every bank once
+    constexpr int KSTRIDE = D * EB + 16;
     __shared__ __align__(16) char vtile[4][16 * VSTRIDE];
+    __shared__ __align__(16) char ktile[4][16 * KSTRIDE];
 
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int n = lane & 15, g = lane >> 4;
@@ -207,8 +215,15 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
     };
 
     char *vt = vtile[wave];
+    char *kt = ktile[wave];
     const int64_t rstride = (int64_t)a.H * D * EB;
     const unsigned rs32 = (unsigned)rstride;  // a cached row of all K/V heads: below 2^32 bytes
+    // SK: the K rows of this launch are more than the memory-side cache holds, so none of them survives until
+    // the next step and they are read with the streaming hint like the V rows; otherwise with plain loads (a batch
+    // whose K rows fit - 256 sequences of 32q/8kv x 128 - finds most of them still cached one step later: 0.76 of
+    // peak against 0.63 with the hint; a batch of 1024 the other way round, 0.66 against 0.63).
+    auto run_items = [&](auto stream_k_tag) {
+    constexpr bool SK = decltype(stream_k_tag)::value;
     for (int64_t item = (int64_t)blockIdx.x * 4 + wave; item < total; item += (int64_t)gridDim.x * 4) {
         const Item it = decode_item(a, bv, item, per_seq);
         const int hk = it.hgb / nqb, qb = it.hgb - hk * nqb;
@@ -241,11 +256,23 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
         float m = -INFINITY, lsum = 0.f;
 
         // Loads of one 16-row tile (rows past the chunk's end are clamped to its last row and masked later).
-        auto load_tile = [&](int r0, u32x4 (&kop)[KL], u32x4 (&vv)[VL]) {
-            const int rk = min(r0 + n, end - 1);
-            const char *krow = (rk == jnew ? knew : kbase + (uint64_t)(unsigned)rk * rs32) + g * 16;
+        // V, and K when it streams (SK): whole rows per load instruction (16 bytes per lane, PPR lanes per row).
+        // K otherwise: the operand layout directly (row n, 16 bytes at 64 ks + 16 g).
+        auto load_tile = [&](int r0, u32x4 (&kld)[KL], u32x4 (&vv)[VL]) {
+            static_assert(KL == VL, "K and V tiles are loaded with the same pattern");
+            if (SK) {
 #pragma unroll
-            for (int ks = 0; ks < KL; ks++) kop[ks] = load16<false>(krow + ks * 64);
+                for (int i = 0; i < KL; i++) {
+                    const int idx = i * 64 + lane;
+                    const int rv = min(r0 + idx / PPR, end - 1);
+                    kld[i] = load16<true>((rv == jnew ? knew : kbase + (uint64_t)(unsigned)rv * rs32) + (idx % PPR) * 16);
+                }
+            } else {
+                const int rk = min(r0 + n, end - 1);
+                const char *krow = (rk == jnew ? knew : kbase + (uint64_t)(unsigned)rk * rs32) + g * 16;
+#pragma unroll
+                for (int ks = 0; ks < KL; ks++) kld[ks] = load16<false>(krow + ks * 64);
+            }
 #pragma unroll
             for (int i = 0; i < VL; i++) {
                 const int idx = i * 64 + lane;
@@ -253,18 +280,40 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
                 vv[i] = load16<true>((rv == jnew ? vnew : vbase + (uint64_t)(unsigned)rv * rs32) + (idx % PPR) * 16);
             }
         };
-        auto reduce_tile = [&](int r0, const u32x4 (&kop)[KL], const u32x4 (&vv)[VL]) {
+        auto reduce_tile = [&](int r0, const u32x4 (&kld)[KL], const u32x4 (&vv)[VL]) {
             if (qb == 0 && jnew >= r0 && jnew < r0 + 16 && jnew < end) {  // this tile holds the new row: append it
-                if (r0 + n == jnew) {
+                if (!SK && r0 + n == jnew) {
 #pragma unroll
                     for (int ks = 0; ks < KL; ks++)
-                        *(u32x4 *)(kbase + (uint64_t)(unsigned)jnew * rs32 + g * 16 + ks * 64) = kop[ks];
+                        *(u32x4 *)(kbase + (uint64_t)(unsigned)jnew * rs32 + g * 16 + ks * 64) = kld[ks];
                 }
 #pragma unroll
                 for (int i = 0; i < VL; i++) {
                     const int idx = i * 64 + lane;
-                    if (r0 + idx / PPR == jnew) *(u32x4 *)(vbase + (uint64_t)(unsigned)jnew * rs32 + (idx % PPR) * 16) = vv[i];
+                    if (r0 + idx / PPR == jnew) {
+                        if (SK) *(u32x4 *)(kbase + (uint64_t)(unsigned)jnew * rs32 + (idx % PPR) * 16) = kld[i];
+                        *(u32x4 *)(vbase + (uint64_t)(unsigned)jnew * rs32 + (idx % PPR) * 16) = vv[i];
+                    }
                 }
+            }
+            u32x4 kop[KL];
+            if (SK) {
+                // K tile through this wave's LDS buffer into operand layout, one 128-bit read per contraction load.
+                // (Loading the operand layout directly is 64 separate 16-byte cache accesses per instruction and
+                // fetches every 128-byte line twice, the second time from the L1 - which the streaming hint forgoes.)
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int i = 0; i < KL; i++) {
+                    const int idx = i * 64 + lane;
+                    *(u32x4 *)(kt + (idx / PPR) * KSTRIDE + (idx % PPR) * 16) = kld[i];
+                }
+                __builtin_amdgcn_wave_barrier();
+#pragma unroll
+                for (int ks = 0; ks < KL; ks++) kop[ks] = *(const u32x4 *)(kt + n * KSTRIDE + ks * 64 + g * 16);
+                __builtin_amdgcn_wave_barrier();
+            } else {
+#pragma unroll
+                for (int ks = 0; ks < KL; ks++) kop[ks] = kld[ks];
             }
             f32x4 s = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
@@ -442,6 +491,11 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
             told.nchunks = it.nchunks;
         }
     }
+    };
+    // chunk counts bound the rows: (chunks - 1) * chunk < rows of a context <= chunks * chunk
+    const int64_t k_bytes = (int64_t)bv.total * a.chunk * rstride;
+    if (a.stream_k < 0 ? k_bytes > ((int64_t)256 << 20) : a.stream_k != 0) run_items(std::true_type{});
+    else run_items(std::false_type{});
     if (ink) settle(true);  // the last one or two chunks of this wave
 }
 

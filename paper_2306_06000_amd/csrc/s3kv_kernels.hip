@@ -538,7 +538,7 @@ static AttnArgs common_args(const s3_arena *a, const AttnCall &c, int row_heads,
     // short, the tail matters); for large batches the extra prologue work per class costs more than
     // the order gains.  Measured on MI355X.
     args.ncls = a->ncls > 0 ? a->ncls : c.n <= 128 ? 4 : c.n <= 256 ? 2 : 1;
-    // the view must fit LDS beside the kernels' own buffers (up to 41 KiB) whatever the caller asked for:
+    // the view must fit LDS beside the kernels' own buffers (up to 67 KiB) whatever the caller asked for:
     // a batch of thousands keeps fewer classes
     while (args.ncls > 1 && batch_view_lds(c.n, args.ncls) > (size_t)96 * 1024) args.ncls--;
     args.out_dtype = c.out_dtype;
@@ -694,13 +694,14 @@ static int launch_gqa(s3_arena *a, const AttnCall &c) {
     const int per_seq = mfma ? Hkv * ((group + 15) / 16) : ((Hkv + GH - 1) / GH) * (group / gq);
     // Few (sequence, head group) pairs: cut contexts finer so that the chip still has work everywhere.
     const int chunk = a->chunk > 0 ? a->chunk
-                      : mfma     ? 128  // one wave per item: short items keep every SIMD busy
+                      : mfma     ? ((int64_t)c.n * per_seq >= 4096 ? 256 : 128)  // one wave per item: short items keep every SIMD busy
                       : (int64_t)c.n * per_seq >= 2048 ? 1024 : (int64_t)c.n * per_seq >= 512 ? 512 : 256;
     AttnArgs args = common_args(a, c, Hkv, Hq, chunk);
     if (mfma && a->ncls <= 0) args.ncls = 1;  // items of at most 128 rows are all alike: no order to gain from (measured)
     // matrix-core kernel: chunks of a context may meet inside the launch (one counter per sequence and item slot)
     const bool ink = mfma && a->gqa_merge != 0;
     args.merge_in_kernel = ink ? 1 : 0;
+    args.stream_k = a->gqa_stream;
     int rc = place_scratch(a, args, ink ? counters_bytes(per_seq) : 0, c);
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);

@@ -484,3 +484,49 @@ def test_matrix_core_kernel_merging_chunks_inside_the_launch_equals_the_merge_la
             outs[merge] = (got[0], step)
             rig.close()
         assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]), (name, chunk)
+
+
+STREAM_FAMILIES = [FAMILIES[4], FAMILIES[5], FAMILIES[7],
+                   ("shared heads, matrix cores d64", 16, 4, 64, s3.S3_F16, s3.S3_F16, 2),
+                   ("multi-query, matrix cores d256", 16, 1, 256, s3.S3_BF16, s3.S3_BF16, 2),
+                   ("8-bit rows, shared heads d256", 8, 2, 256, s3.S3_E4M3, s3.S3_F16, 4)]
+
+
+@pytest.mark.parametrize("fam", STREAM_FAMILIES, ids=[f[0] for f in STREAM_FAMILIES])
+def test_matrix_core_kernel_streaming_k_rows_equals_plain_loads(fam):
+    """The matrix-core kernel reads K either straight into operand layout with plain loads or, when a launch's K
+    rows exceed the memory-side cache, in whole rows with the streaming hint and through LDS (`gqa_stream`): the
+    operands hold the same bits either way, so attention and the decode step (whose append takes the new row from
+    differently laid out registers) must give the same output bits, the appended row must read back the same, and
+    both must meet the oracle's tolerance."""
+    name, H, Hkv, D, kvt, act, kind = fam
+    rng = np.random.default_rng(950 + D + kind)
+    lens = [300, 0, 301, 64, 1, 517, 129, 1000, 33, 15, 16, 17]
+    n = len(lens)
+    K = [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens]
+    V = [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens]
+    q = rng.standard_normal((n, H, D), dtype=np.float32)
+    k_new = rng.standard_normal((n, Hkv, D), dtype=np.float32)
+    v_new = rng.standard_normal((n, Hkv, D), dtype=np.float32)
+    for chunk in (32, 0, 512):
+        outs = {}
+        for stream in (0, 1):
+            rig = EdgeRig(fam, lens, M=2048)
+            rig.put(K, V)
+            assert s3.s3_kv_set_param(rig.a, "chunk", chunk) == 0
+            assert s3.s3_kv_set_param(rig.a, "gqa_stream", stream) == 0
+            assert s3.s3_kv_get_param(rig.a, "gqa_stream") == (0, stream)
+            qb, att = rig.attend(q)
+            assert_close(att, rig.want(qb), f"{name} chunk {chunk} gqa_stream {stream}")
+            qb, step = rig.step(q, k_new, v_new)
+            longer = [L + 1 for L in lens]
+            assert_close(step, rig.want(qb, longer), f"{name} step chunk {chunk} gqa_stream {stream}")
+            _, again = rig.attend(q, lens=longer)  # the appended rows, now read from the arena
+            assert np.array_equal(again, step), (name, chunk, stream)
+            outs[stream] = (att, step)
+            rig.close()
+        assert np.array_equal(outs[0][0], outs[1][0]) and np.array_equal(outs[0][1], outs[1][1]), (name, chunk)
+    a_rig = EdgeRig(fam, [4])
+    assert s3.s3_kv_set_param(a_rig.a, "gqa_stream", 2) == s3.S3_ERR_INVALID
+    assert s3.s3_kv_set_param(a_rig.a, "gqa_stream", -1) == 0
+    a_rig.close()
