@@ -147,7 +147,7 @@ __device__ __forceinline__ void merge_pending(const AttnArgs &a, const PendingCh
 // KV8: the cache rows are e4m3 codes (one byte per element) and DT is the type of q; a 16-byte load then
 // holds 16 elements, which are widened (exactly) to DT in registers and feed two contraction steps.
 template <int DT, int D, bool KV8>
-__global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
+__global__ void __launch_bounds__(256, D <= 128 ? 2 : 1) attn_gqa_mfma_kernel(const AttnArgs a) {
     constexpr int EB = KV8 ? 1 : 2;       // bytes per cached element
     constexpr int KS = D / 32;            // contraction steps of the score product
     constexpr int KL = KV8 ? D / 64 : KS; // 16-byte K loads per lane and tile
@@ -430,17 +430,25 @@ __global__ void __launch_bounds__(256) attn_gqa_mfma_kernel(const AttnArgs a) {
             __builtin_amdgcn_wave_barrier();
         };
         // Two register sets used alternately: the next tile's loads are in flight while this one is reduced.
+        // The loop takes tiles in pairs for as long as a further tile follows the pair, so that every load in it is
+        // unconditional (the compiler then lets the other set's loads stay in flight at each wait); the last one
+        // or two tiles follow outside, and no tile beyond the chunk's end is ever loaded.
         u32x4 k0[KL], v0[VL], k1[KL], v1[VL];
         load_tile(start, k0, v0);
-        for (int r0 = start;;) {
+        int r0 = start;
+        while (r0 + 32 < end) {
             load_tile(r0 + 16, k1, v1);
             reduce_tile(r0, k0, v0);
-            r0 += 16;
-            if (r0 >= end) break;
-            load_tile(r0 + 16, k0, v0);
-            reduce_tile(r0, k1, v1);
-            r0 += 16;
-            if (r0 >= end) break;
+            load_tile(r0 + 32, k0, v0);
+            reduce_tile(r0 + 16, k1, v1);
+            r0 += 32;
+        }
+        if (r0 + 16 < end) {
+            load_tile(r0 + 16, k1, v1);
+            reduce_tile(r0, k0, v0);
+            reduce_tile(r0 + 16, k1, v1);
+        } else {
+            reduce_tile(r0, k0, v0);
         }
 
         lsum += __shfl_xor(lsum, 16);
