@@ -48,6 +48,8 @@ def parse():
                     "the attention launch, 0 = merge launch (-1: library default)")
     ap.add_argument("--gqa-stream", type=int, default=-1, help="shared heads, matrix-core kernel: K rows read with the "
                     "streaming hint (1), with plain loads (0), by launch size (-1, the library's default)")
+    ap.add_argument("--gqa-dynamic", type=int, default=-1, help="shared heads, matrix-core kernel: per cent of the work "
+                    "list dealt by stride before waves claim positions (0 or -1, the default: all by stride)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-kernel-events", action="store_true", help="skip pass 2 (no events anywhere: for counter runs)")
     ap.add_argument("--c3-bytes", type=float, default=200e9)
@@ -234,7 +236,8 @@ def run_workload(name, args, torch, cpu_budget_s):
     for pname, val in (("variant", args.variant if args.variant >= 0 else None), ("chunk", args.chunk or None),
                        ("grid_blocks", args.grid_blocks or None), ("classes", args.classes or None),
                        ("merge_sync", args.merge_sync or None), ("gqa_merge", args.gqa_merge if args.gqa_merge >= 0 else None),
-                       ("gqa_stream", args.gqa_stream if args.gqa_stream >= 0 else None)):
+                       ("gqa_stream", args.gqa_stream if args.gqa_stream >= 0 else None),
+                       ("gqa_dynamic", args.gqa_dynamic if args.gqa_dynamic >= 0 else None)):
         if val is not None:
             s3.check(s3.s3_kv_set_param(eng.arena, pname, val), pname)
     src = DeviceSources(w, eng, torch)

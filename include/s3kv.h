@@ -343,6 +343,9 @@ int s3_kv_probe_bandwidth(s3_arena *a, size_t bytes, int32_t mode, int32_t reps,
  *   "gqa_merge"    shared key/value heads, matrix-core kernel: 1 = multi-chunk contexts are finished inside the
  *                  attention launch (arrival counters, write-through partials), 0 (default) = by a merge launch;
  *                  same results; the launch-saving form measured slower (its partials bypass the caches)
+ *   "gqa_dynamic"  shared key/value heads, matrix-core kernel: per cent of the work list that is dealt by stride
+ *                  before the waves claim the remaining positions from a device-wide counter (1..99; 0, 100 or -1,
+ *                  the default = all by stride: claims pay only on very long lists of long items); same results
  *   "gqa_stream"   shared key/value heads, matrix-core kernel: how K rows are read: 1 = with the streaming hint
  *                  (whole rows per load, operand layout through LDS), 0 = plain loads straight into operand layout,
  *                  -1 (default) = 1 if the launch's K rows exceed the 256 MB memory-side cache, else 0; same results

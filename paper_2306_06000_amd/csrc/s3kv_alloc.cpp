@@ -323,6 +323,11 @@ extern "C" int s3_kv_set_param(s3_arena *a, const char *name, int64_t value) {
         a->gqa_merge = (int32_t)value;
         return S3_OK;
     }
+    if (!strcmp(name, "gqa_dynamic")) {
+        if (value < -1 || value > 100) return S3_ERR_INVALID;
+        a->gqa_dynamic = (int32_t)value;
+        return S3_OK;
+    }
     if (!strcmp(name, "gqa_stream")) {
         if (value < -1 || value > 1) return S3_ERR_INVALID;
         a->gqa_stream = (int32_t)value;
@@ -353,6 +358,7 @@ extern "C" int s3_kv_get_param(const s3_arena *a, const char *name, int64_t *val
     else if (!strcmp(name, "merge_sync")) *value = a->merge_sync;
     else if (!strcmp(name, "gqa_merge")) *value = a->gqa_merge;
     else if (!strcmp(name, "gqa_stream")) *value = a->gqa_stream;
+    else if (!strcmp(name, "gqa_dynamic")) *value = a->gqa_dynamic;
     else if (!strcmp(name, "n_variants")) *value = s3i_variants_of(a);
     else if (!strcmp(name, "default_variant")) *value = s3i_kernel_kind(a) == 0 ? s3i_default_variant() : -1;
     else if (!strcmp(name, "kernel_kind")) *value = s3i_kernel_kind(a);

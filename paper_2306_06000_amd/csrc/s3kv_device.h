@@ -39,6 +39,7 @@ struct AttnArgs {
     int32_t merge_in_kernel; // matrix-core kernel for shared heads: chunks meet inside the launch (no merge launch follows)
     unsigned int *queue;     // [2] kernels with a dynamic work list: positions claimed, workgroups gone; zero between launches
     int32_t stream_k;        // matrix-core kernel for shared heads: K rows with the streaming hint (1), plain (0), by launch size (< 0)
+    int32_t dyn_list;        // matrix-core kernel for shared heads: per cent of the list dealt by stride before waves claim positions from `queue` (0: all by stride)
 };
 
 __device__ __forceinline__ int checked_len(const AttnArgs &a, int b) {

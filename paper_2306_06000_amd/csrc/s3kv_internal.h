@@ -49,6 +49,7 @@ struct s3_arena {
     int32_t variant = -1;
     int32_t gqa_merge = 0;   // matrix-core kernel for shared heads: 1 = chunks merge inside the launch, 0 = merge launch
     int32_t gqa_stream = -1; // matrix-core kernel: K rows read with the streaming hint (1), with plain loads (0), by launch size (-1)
+    int32_t gqa_dynamic = -1; // matrix-core kernel: per cent of the work list dealt by stride before waves claim positions (0, 100 or -1, the default: all by stride)
     int32_t merge_sync = 0;  // ordering of chunks that meet inside one launch (0: write-through partials, 1: fences)
     int32_t num_cus = 0;
 

@@ -593,7 +593,7 @@ static size_t scratch_need(const s3_arena *a, int n) {
         cnt_bytes = counters_bytes((Hq + gh - 1) / gh);
     } else {
         if (chunk <= 0) chunk = (kind == 2 || kind == 4) ? 128 : 256;
-        if ((kind == 2 || kind == 4) && a->gqa_merge)
+        if (kind == 2 || kind == 4)  // arrival counters (if chunks merge inside the launch) and the work-list counters
             cnt_bytes = counters_bytes(a->cfg.n_kv_heads * ((Hq / a->cfg.n_kv_heads + 15) / 16));
     }
     const size_t max_chunks = (size_t)(a->cfg.max_len + chunk - 1) / chunk;
@@ -702,7 +702,8 @@ static int launch_gqa(s3_arena *a, const AttnCall &c) {
     const bool ink = mfma && a->gqa_merge != 0;
     args.merge_in_kernel = ink ? 1 : 0;
     args.stream_k = a->gqa_stream;
-    int rc = place_scratch(a, args, ink ? counters_bytes(per_seq) : 0, c);
+    args.dyn_list = mfma && a->gqa_dynamic > 0 ? a->gqa_dynamic : 0;
+    int rc = place_scratch(a, args, mfma ? counters_bytes(per_seq) : 0, c);
     if (rc != S3_OK) return rc;
     const size_t dyn_lds = batch_view_lds(c.n, args.ncls);
     int blocks = 0;

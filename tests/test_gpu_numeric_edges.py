@@ -530,3 +530,46 @@ def test_matrix_core_kernel_streaming_k_rows_equals_plain_loads(fam):
     assert s3.s3_kv_set_param(a_rig.a, "gqa_stream", 2) == s3.S3_ERR_INVALID
     assert s3.s3_kv_set_param(a_rig.a, "gqa_stream", -1) == 0
     a_rig.close()
+
+
+@pytest.mark.parametrize("fam", STREAM_FAMILIES[:3], ids=[f[0] for f in STREAM_FAMILIES[:3]])
+def test_matrix_core_kernel_claiming_the_end_of_its_work_list_equals_the_fixed_stride(fam):
+    """`gqa_dynamic`: the waves of the matrix-core kernel take the first part of the work list by stride and claim
+    the rest from a device-wide counter that every launch must leave at zero.  Grids far smaller than the list, so
+    that most positions are claimed; launch after launch; attention and decode step; same bits as the fixed
+    stride."""
+    name, H, Hkv, D, kvt, act, kind = fam
+    rng = np.random.default_rng(970 + D + kind)
+    lens = [300, 0, 301, 64, 1, 517, 129, 1000, 33, 15, 16, 17, 700, 45]
+    n = len(lens)
+    K = [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens]
+    V = [rng.standard_normal((L, Hkv, D), dtype=np.float32) for L in lens]
+    q = rng.standard_normal((n, H, D), dtype=np.float32)
+    rig = EdgeRig(fam, lens, M=2048)
+    rig.put(K, V)
+    assert s3.s3_kv_set_param(rig.a, "chunk", 64) == 0
+    assert s3.s3_kv_set_param(rig.a, "gqa_dynamic", 0) == 0
+    qb, ref = rig.attend(q)
+    assert_close(ref, rig.want(qb), name)
+    for grid in (1, 3, 0):
+        assert s3.s3_kv_set_param(rig.a, "grid_blocks", grid) == 0
+        for pct in (1, 50, 99, -1):
+            assert s3.s3_kv_set_param(rig.a, "gqa_dynamic", pct) == 0
+            for rep in range(3):
+                _, got = rig.attend(q)
+                assert np.array_equal(got, ref), (name, grid, pct, rep)
+    assert s3.s3_kv_set_param(rig.a, "gqa_dynamic", 101) == s3.S3_ERR_INVALID
+    # the decode step, half of the list claimed, against the step by stride on a twin arena
+    k_new = rng.standard_normal((n, Hkv, D), dtype=np.float32)
+    v_new = rng.standard_normal((n, Hkv, D), dtype=np.float32)
+    twin = EdgeRig(fam, lens, M=2048)
+    twin.put(K, V)
+    steps = []
+    for r, pct in ((rig, 50), (twin, 0)):
+        assert s3.s3_kv_set_param(r.a, "chunk", 64) == 0
+        assert s3.s3_kv_set_param(r.a, "grid_blocks", 2) == 0
+        assert s3.s3_kv_set_param(r.a, "gqa_dynamic", pct) == 0
+        steps.append(r.step(q, k_new, v_new)[1])
+    assert np.array_equal(steps[0], steps[1]), name
+    rig.close()
+    twin.close()
